@@ -1,0 +1,360 @@
+/*
+ * repquant.h -- C ABI of librepquant.so: the inference path of a transformer block after
+ * RepQuant's scale reparameterization (arXiv 2402.05628), hand-written HIP for gfx950 (MI355X).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Plain C: no C++ types, no exceptions cross this boundary.
+ *  - Every data pointer is a DEVICE pointer unless a field says "host".  Scalars travel by value.
+ *  - The caller owns every buffer; the library never allocates outputs and never frees inputs.
+ *    Scratch memory comes from a caller-provided workspace (rq_block_workspace_bytes).
+ *  - Calls are asynchronous on the context's stream; nothing here synchronizes unless stated.
+ *  - Arguments are validated before any GPU work is issued.  A context created with device < 0 is a
+ *    "host-only" context: validation runs as usual and a valid call then returns RQ_ERR_UNSUPPORTED.
+ *  - Matrices are row-major.  Leading dimensions (ld*) are in elements.  Weights are [out, in] with
+ *    `in` contiguous, so every GEMM here is C[m, n] = sum_k A[m, k] * B[n, k].
+ *  - Returns rq_status; rq_last_error() gives the text of the last failure on that context (or of the
+ *    last failure of a call that had no context).
+ *
+ * Integer codes and their storage
+ * -------------------------------
+ *  The uniform quantizer (Section "Efficient quantizers") produces unsigned codes in [0, 2^b - 1] with
+ *  an integer zero-point z.  The matrix cores multiply signed 8-bit integers, so an activation tensor is
+ *  stored as int8 `code - off`, where the storage offset `off` is chosen by the producer so that the
+ *  value fits (off = z whenever -128 <= -z and 2^b - 1 - z <= 127; off = 128 for 8-bit codes).  Every
+ *  descriptor carries both z and off.  The contract of an integer matmul is the TRUE accumulator
+ *      acc[m, n] = sum_k (qa[m, k] - z_a) * (qb[n, k] - z_b[n]),
+ *  bit-exact; the kernels reach it from the stored operands with rank-1 corrections.
+ *
+ *  Weight formats (per-output-channel scale s_w[n] and zero-point z_w[n]):
+ *    RQ_W_I8_BAKED     int8 [N, K], stored = code - z_w[n]          (b <= 7)
+ *    RQ_W_I8_CENTERED  int8 [N, K], stored = code - 128             (b == 8); needs rowsum_a
+ *    RQ_W_U4           uint8 [N, K/2], two raw 4-bit codes per byte, in the interleaved order
+ *                      produced by rq_weight_quant_pack (see there); z_w[n] is subtracted while the
+ *                      nibbles are unpacked in LDS.
+ *  colsum_w[n] = sum_k (code[n, k] - z_w[n]) accompanies every format.
+ */
+#ifndef REPQUANT_H
+#define REPQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rq_ctx rq_ctx;
+
+typedef enum {
+  RQ_OK = 0,
+  RQ_ERR_INVALID_ARG = 1, /* null pointer, bad enum, bad bit-width, non-positive scale, misalignment */
+  RQ_ERR_SHAPE = 2,       /* sizes or leading dimensions inconsistent or beyond what the kernels support */
+  RQ_ERR_UNSUPPORTED = 3, /* valid request that this build cannot run (e.g. host-only context) */
+  RQ_ERR_WORKSPACE = 4,   /* workspace too small */
+  RQ_ERR_HIP = 5          /* a HIP runtime call failed; text in rq_last_error */
+} rq_status;
+
+enum { RQ_NORM_LAYERNORM = 0, RQ_NORM_RMSNORM = 1 };
+enum { RQ_ACT_NONE = 0, RQ_ACT_GELU = 1, RQ_ACT_SILU_GATED = 2 };
+enum { RQ_MASK_NONE = 0, RQ_MASK_CAUSAL = 1 };
+enum { RQ_W_I8_BAKED = 0, RQ_W_I8_CENTERED = 1, RQ_W_U4 = 2, RQ_B_ACT_I8 = 3 };
+
+/* ---- context ---------------------------------------------------------------------------------- */
+
+/* Creates a context bound to HIP device `device` and stream `hip_stream` (a hipStream_t, or NULL for
+ * the default stream).  device < 0 creates a host-only context (validation only).  Host call. */
+rq_status rq_create(rq_ctx** ctx, int device, void* hip_stream);
+void rq_destroy(rq_ctx* ctx);
+/* Host string owned by the library; valid until the next failing call on the same context/thread. */
+const char* rq_last_error(const rq_ctx* ctx);
+/* Storage offset the library's own producers use for codes with zero-point z at `bits` bits. */
+int32_t rq_store_offset(int32_t bits, int32_t z);
+
+/* ---- rq_reparam_fold ---------------------------------------------------------------------------
+ * Section "Scale reparameterization for LayerNorm activations": channel-wise (s, z) of a LayerNorm
+ * activation become ONE layer-wise pair, with the difference folded into the LayerNorm affine and
+ * the next Linear:
+ *    s~ = mean(s),  z~ = round(mean(z))  (an integer, so r2 is integral),  r1 = s / s~,  r2 = z - z~,
+ *    gamma~ = gamma / r1,  beta~ = (beta + s.r2) / r1,
+ *    W~[j, d] = r1[d] W[j, d],  b~[j] = b[j] - sum_d s[d] r2[d] W[j, d].
+ * Section "Scale reparameterization for Softmax activations", Eq. (3.3-2): the log-sqrt2 scale s_log
+ * becomes the pair {s_log (even codes), s_log*sqrt2 (odd codes)}.
+ * All arithmetic is float64; outputs are rounded once to float32.  In-place (W_t == W etc.) is allowed.
+ */
+typedef struct {
+  int32_t D;             /* channels of the LayerNorm activation (= K of the next Linear) */
+  int32_t D_out;         /* output channels of the next Linear */
+  const float* s_ch;     /* [D] channel scales, > 0 */
+  const int32_t* z_ch;   /* [D] channel zero-points */
+  const float* gamma;    /* [D] */
+  const float* beta;     /* [D] or NULL (= 0) */
+  const float* W;        /* [D_out, D] */
+  const float* b;        /* [D_out] or NULL (= 0) */
+  float s_log;           /* log-sqrt2 scale, > 0 (ignored when s_log_pair is NULL) */
+  float* s_tilde;        /* [1] out */
+  int32_t* z_tilde;      /* [1] out */
+  float* gamma_t;        /* [D] out */
+  float* beta_t;         /* [D] out */
+  float* W_t;            /* [D_out, D] out */
+  float* b_t;            /* [D_out] out */
+  float* s_log_pair;     /* [2] out {s_log, s_log*sqrt2} or NULL */
+} rq_fold_desc;
+rq_status rq_reparam_fold(rq_ctx* ctx, const rq_fold_desc* d);
+
+/* ---- rq_weight_quant_pack (helper) ---------------------------------------------------------------
+ * Channel-wise (per output channel) min/max uniform quantization of a float weight matrix
+ * (Section "Efficient quantizers", Eq. for s and z; granularity paragraph):
+ *    s_w[n] = float32((max_n - min_n) / (2^b - 1)),  z_w[n] = round(-min_n / s_w[n]),
+ *    code = clip(round(W / s_w[n]) + z_w[n], 0, 2^b - 1).
+ * bits = 8 -> RQ_W_I8_CENTERED, bits in 2..7 with format RQ_W_I8_BAKED, bits = 4 with RQ_W_U4.
+ * RQ_W_U4 layout: row n holds K/2 bytes; within each aligned group of 8 codes k0..k7 the four bytes
+ * are (k0 | k4<<4), (k1 | k5<<4), (k2 | k6<<4), (k3 | k7<<4), so that `dword & 0x0F0F0F0F` yields
+ * k0..k3 and `(dword >> 4) & 0x0F0F0F0F` yields k4..k7 as bytes.  K must be a multiple of 8.
+ * If gate_up_rows > 0 the input rows are [gate(0..Dm-1) ; up(0..Dm-1)] with Dm = gate_up_rows and the
+ * output rows are interleaved in groups of 16 (16 gate rows, then the 16 matching up rows), the order
+ * the fused SiLU(gate)*up epilogue of rq_qgemm expects; Dm must be a multiple of 16.
+ */
+typedef struct {
+  int32_t N, K;
+  int32_t bits;
+  int32_t format;        /* RQ_W_* */
+  int32_t gate_up_rows;  /* 0, or Dm for the gated-MLP interleave */
+  const float* W;        /* [N, K] */
+  const float* bias;     /* [N] or NULL; only permuted along with the rows into bias_out */
+  void* w_out;           /* int8 [N, K] or uint8 [N, K/2] */
+  float* s_w;            /* [N] out */
+  int32_t* z_w;          /* [N] out */
+  int32_t* colsum_w;     /* [N] out, sum_k (code - z_w) */
+  float* bias_out;       /* [N] out or NULL */
+} rq_wq_desc;
+rq_status rq_weight_quant_pack(rq_ctx* ctx, const rq_wq_desc* d);
+
+/* ---- rq_ln_quant ---------------------------------------------------------------------------------
+ * LayerNorm (Eq. for X'_{n,:}) with the folded affine, fused with the layer-wise uniform quantizer:
+ *    code = clip(round((xhat * gamma~ + beta~) / s~) + z~, 0, 2^b - 1),  stored as int8 code - store_off.
+ * xhat = (x - mean) / sqrt(var + eps) (population variance) or x / sqrt(mean(x^2) + eps) for RMSNorm.
+ * Statistics and the affine are evaluated in float64.  rowsum[t] = sum_d stored[t, d] (optional).
+ * x and q must be 16-byte aligned, D a multiple of 4, ldx a multiple of 4, ldq a multiple of 4.
+ */
+typedef struct {
+  int64_t T;
+  int32_t D;
+  int32_t norm_kind;
+  double eps;
+  const float* x;
+  int64_t ldx;
+  const float* gamma_t;  /* [D] */
+  const float* beta_t;   /* [D] or NULL */
+  float s_tilde;
+  int32_t z_tilde;
+  int32_t bits;          /* 2..8 */
+  int32_t store_off;
+  int8_t* q;             /* [T, D] out */
+  int64_t ldq;
+  int32_t* rowsum;       /* [T] out or NULL */
+} rq_ln_desc;
+rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d);
+
+/* ---- rq_qgemm --------------------------------------------------------------------------------------
+ * Integer matmul with both operands quantized (Section "Transformer blocks", last paragraph; uniform
+ * de-quantizer of Section "Efficient quantizers" applied to both operands):
+ *    acc[m, n] = sum_k (qa[m, k] - z_a)(qb[n, k] - z_b[n])            exact, int32
+ *    y[m, n]   = s_a * s_b[n] * acc[m, n] + bias[n]                   float32
+ *    y = act(y);  y += residual[m, n];  out_f32 = y;
+ *    out_q = clip(round(y / s_o) + z_o, 0, 2^bits_o - 1) - off_o     (requantized for the next matmul)
+ * Weight mode (b_format = RQ_W_*): batch fields must be 1/0.  s_b, z_b, colsum_b are [N] arrays.
+ * Activation mode (b_format = RQ_B_ACT_I8, used for Q.K^T): B is int8 `code - b_off` with the scalar
+ * pair (*s_b_scalar, z_b_scalar); problems are batched over (outer, inner) with element strides; only
+ * out_acc is produced (the Softmax kernel consumes exact accumulators); K <= 256, K % 16 == 0;
+ * with causal != 0 tiles entirely above the diagonal are not written.
+ * RQ_ACT_SILU_GATED: B rows are interleaved gate/up (see rq_weight_quant_pack), N = 2*Dm, outputs
+ * have N/2 columns: SiLU(y_gate) * y_up.
+ * Requant segments: column n (output column) uses entry n / seg_len of s_o/z_o/off_o (n_seg <= 4);
+ * this is how one GEMM emits Q, K and V with their own static scales.
+ * rowsum_a[m] = sum_k stored_a[m, k] is required for RQ_W_I8_CENTERED.
+ * A, B 16-byte aligned; lda % 16 == 0; K % 16 == 0 (RQ_W_U4: K % 64 == 0).
+ */
+typedef struct {
+  int64_t M;
+  int32_t N, K;
+  const int8_t* A;
+  int64_t lda;
+  int32_t a_off, z_a;
+  float s_a;
+  const void* B;
+  int64_t ldb;               /* elements (bytes for RQ_W_U4 rows: K/2) */
+  int32_t b_format;
+  const float* s_b;          /* [N] (weight mode) */
+  const int32_t* z_b;        /* [N] (weight mode; may be NULL for RQ_W_I8_BAKED) */
+  const int32_t* colsum_b;   /* [N] (weight mode; required when a_off != z_a) */
+  const int32_t* rowsum_a;   /* [M] (required for RQ_W_I8_CENTERED) */
+  int32_t b_off, z_b_scalar; /* activation mode */
+  const float* bias;         /* [N] or NULL */
+  int32_t act;               /* RQ_ACT_* */
+  const float* residual;     /* [M, N] or NULL */
+  int64_t ldr;
+  int32_t* out_acc;          /* [M, N] true accumulators, or NULL */
+  int64_t ldacc;
+  float* out_f32;            /* or NULL */
+  int64_t ldf;
+  int8_t* out_q;             /* or NULL */
+  int64_t ldq;
+  int32_t bits_o, n_seg, seg_len;
+  float s_o[4];
+  int32_t z_o[4];
+  int32_t off_o[4];
+  /* batching (activation mode) */
+  int64_t batch_outer;       /* >= 1 */
+  int32_t batch_inner;       /* >= 1 */
+  int64_t a_stride_outer, a_stride_inner;
+  int64_t b_stride_outer, b_stride_inner;
+  int64_t acc_stride_group;  /* elements between consecutive groups (outer*batch_inner + inner) */
+  int32_t causal;
+} rq_gemm_desc;
+rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
+
+/* ---- rq_softmax_log2_quant --------------------------------------------------------------------------
+ * Softmax fused with the log-sqrt2 quantizer in its base-2 form (Eq. (3.3-1), second line):
+ *    l[j]  = logit_scale * acc[j] (+ bias[g % H, i, j]);  masked j (causal: j > i) are excluded;
+ *    code[j] = clip(round(-2 * log2(softmax(l)[j] / s_log)), 0, 2^b - 1),
+ * evaluated as round(2 * (log2(sum_j 2^(l_j log2 e)) - l_j log2 e + log2 s_log)) in one pass over the
+ * row held in registers: the probability itself is never formed.  Masked and padding positions
+ * (j >= Nk up to ld) receive the largest code.  ld % 4 == 0, acc 16-byte aligned, codes 4-byte aligned.
+ */
+typedef struct {
+  int64_t G;              /* number of (batch, head) groups */
+  int32_t H;              /* heads: bias plane = g % H */
+  int32_t Nq, Nk;
+  int64_t ld;             /* row pitch (elements) of acc and of codes */
+  const int32_t* acc;     /* [G, Nq, ld] exact accumulators of Q.K^T */
+  double logit_scale;     /* s_q * s_k / sqrt(d_head) */
+  const float* bias;      /* [H, Nq, Nk] dense, or NULL */
+  int32_t mask;
+  float s_log;
+  int32_t bits;           /* 2..8 */
+  uint8_t* codes;         /* [G, Nq, ld] out */
+} rq_softmax_desc;
+rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d);
+
+/* ---- rq_attn_pv -----------------------------------------------------------------------------------------
+ * P.V with shift de-quantized probabilities (case analysis before Eq. (3.3-2) and Eq. (3.3-2)):
+ *    A^[i, j] = s~(code) * 2^floor(-code / 2),   s~ = s_log (even code) or s_log * sqrt2 (odd code),
+ *    out[i, c] = sum_j A^[i, j] * s_v * (qv[j, c] - z_v),     masked j excluded.
+ * The power of two is applied as an integer shift: each probability becomes -(128 >> k) in int8
+ * (k = code >> 1 within a window of 8 shifts), the two parities accumulate separately in exact int32
+ * on the matrix cores, and the two sums are combined once per output with s_log and s_log/sqrt2.
+ * codes [batch*H, Nq, ld]; V is token-major int8 (row b*Nk + j, column h*d_head + c) stored code - v_off.
+ * Outputs are token-major [batch*Nq, H*d_head].  d_head in {32, 64, 128}; ld % 4 == 0.
+ */
+typedef struct {
+  int64_t batch;
+  int32_t H, Nq, Nk, d_head;
+  int64_t ld;
+  const uint8_t* codes;
+  const int8_t* V;
+  int64_t ldv;
+  float s_log, s_v;
+  int32_t z_v, v_off;
+  int32_t bits_p;
+  int32_t mask;
+  float* out_f32;         /* or NULL */
+  int64_t ldf;
+  int8_t* out_q;          /* or NULL */
+  int64_t ldq;
+  float s_o;
+  int32_t z_o, off_o, bits_o;
+} rq_pv_desc;
+rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d);
+
+/* ---- rq_block_forward -------------------------------------------------------------------------------------
+ * One transformer block (Eqs. for X-bar and Y, attention Eq.), every matmul operand quantized:
+ *    a1 = ln_quant(x);  q,k,v = requant(qgemm(a1, W_qkv));  acc = q.k^T;  codes = softmax_log2_quant(acc);
+ *    o = requant(attn_pv(codes, v));  xbar = qgemm(o, W_proj) + x;
+ *    a2 = ln_quant(xbar);  h = requant(act(qgemm(a2, W_fc1)));  y = qgemm(h, W_fc2) + xbar.
+ * x, y: float32 [batch*seq, D].  Attention groups are (batch item, head); for windowed attention pass
+ * batch = images * windows and seq = tokens per window.
+ */
+typedef struct {
+  int32_t N, K, bits, format;
+  const void* w;
+  const float* s_w;
+  const int32_t* z_w;
+  const int32_t* colsum_w;
+  const float* bias;      /* [N] or NULL */
+} rq_qlinear;
+
+typedef struct {
+  int32_t D, H, Dm;
+  int32_t norm_kind, act, mask;
+  int32_t bits_a, bits_p;
+  double eps;
+  const float *ln1_gamma_t, *ln1_beta_t;
+  float ln1_s; int32_t ln1_z;
+  rq_qlinear qkv;         /* N = 3D */
+  float s_q, s_k, s_v; int32_t z_q, z_k, z_v;
+  const float* rel_bias;  /* [H, seq, seq] or NULL */
+  float s_log;
+  float s_o; int32_t z_o;
+  rq_qlinear proj;        /* N = D, K = D */
+  const float *ln2_gamma_t, *ln2_beta_t;
+  float ln2_s; int32_t ln2_z;
+  rq_qlinear fc1;         /* N = Dm (GELU) or 2*Dm interleaved gate/up (SiLU gated) */
+  float s_h; int32_t z_h;
+  rq_qlinear fc2;         /* N = D, K = Dm */
+} rq_block_params;
+
+size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
+rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
+                           int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);
+
+/* Per-kernel timing of rq_block_forward: when enabled, every kernel launch inside rq_block_forward is
+ * bracketed by HIP events on the context's stream.  rq_profile_read synchronizes the stream, writes up to
+ * `cap` records (host arrays) accumulated since the last rq_profile_reset and returns their number.
+ * step ids: see RQ_STEP_*. */
+enum {
+  RQ_STEP_LN1 = 0, RQ_STEP_QKV, RQ_STEP_QK, RQ_STEP_SOFTMAX, RQ_STEP_PV, RQ_STEP_PROJ,
+  RQ_STEP_LN2, RQ_STEP_FC1, RQ_STEP_FC2, RQ_STEP_AUX, RQ_STEP_COUNT
+};
+rq_status rq_profile_enable(rq_ctx* ctx, int32_t on);
+rq_status rq_profile_reset(rq_ctx* ctx);
+int32_t rq_profile_read(rq_ctx* ctx, double* ms_total /* [RQ_STEP_COUNT] */, int64_t* launches /* [RQ_STEP_COUNT] */);
+
+/* ---- calibration helpers (the step before the path; untimed preparation) -----------------------------------
+ * rq_rowsum_i8:        rowsum[m] = sum_k A[m, k].
+ * rq_ln_channel_minmax: per-channel min and max over all T tokens of LayerNorm(x) * gamma + beta
+ *                      (the channel extremes of the Eqs. for X'_up and X'_low), float64 math, float32 out.
+ * rq_minmax_f32:       min and max of a [rows, cols] float32 region -> out[0], out[1].
+ * rq_block_calibrate:  Algorithm 1 restricted to one block and to min/max bounds: walks the block on one
+ *                      calibration batch, layer by layer, each layer seeing the quantized layers before it;
+ *                      fills the caller-allocated arrays named in rq_block_params and writes the scalar
+ *                      fields.  Weight quantization is round-to-nearest (GPTQ is not part of this library).
+ */
+rq_status rq_rowsum_i8(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum);
+rq_status rq_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
+                               double eps, const float* gamma, const float* beta, float* cmin, float* cmax);
+rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, float* out2);
+
+typedef struct {
+  int32_t D, H, Dm;
+  int32_t norm_kind, act, mask;
+  int32_t bits_w, bits_a, bits_p;
+  double eps;
+  const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;     /* [D]; beta may be NULL */
+  const float *w_qkv, *b_qkv, *w_proj, *b_proj, *w_fc1, *b_fc1, *w_fc2, *b_fc2; /* biases may be NULL */
+  const float *ln1_clip_up, *ln1_clip_lo, *ln2_clip_up, *ln2_clip_lo;           /* [D] or NULL (= 1) */
+  const float* rel_bias;
+  float s_log;
+} rq_block_raw;
+
+size_t rq_block_calibrate_workspace_bytes(const rq_block_raw* raw, int64_t batch, int64_t seq);
+/* `out` arrives with every array pointer set to caller-allocated device memory of the documented size
+ * (ln*_gamma_t/beta_t [D]; each rq_qlinear: w, s_w, z_w, colsum_w, bias); scalar fields are written.
+ * Synchronizes the stream (scalars are read back to the host). */
+rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* x, int64_t batch, int64_t seq,
+                             rq_block_params* out, void* workspace, size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REPQUANT_H */

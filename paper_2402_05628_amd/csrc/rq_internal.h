@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of librepquant.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include <string>
+#include <vector>
+
+#include "repquant.h"
+
+struct rq_ctx {
+  int device = -1;            // < 0: host-only (validation) context
+  hipStream_t stream = nullptr;
+  int num_cu = 256;
+  std::string err;
+  // per-kernel profiling of rq_block_forward
+  bool profiling = false;
+  struct EvPair { hipEvent_t a, b; int step; };
+  std::vector<EvPair>* pending = nullptr;
+  std::vector<hipEvent_t>* pool = nullptr;
+  double prof_ms[RQ_STEP_COUNT] = {0};
+  int64_t prof_n[RQ_STEP_COUNT] = {0};
+};
+
+rq_status rq_fail(rq_ctx* ctx, rq_status st, const char* fmt, ...);
+
+#define RQ_REQUIRE(cond, st, ...)                         \
+  do {                                                    \
+    if (!(cond)) return rq_fail(ctx, st, __VA_ARGS__);    \
+  } while (0)
+
+#define RQ_HIP(call)                                                                          \
+  do {                                                                                        \
+    hipError_t e__ = (call);                                                                  \
+    if (e__ != hipSuccess)                                                                    \
+      return rq_fail(ctx, RQ_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e__));        \
+  } while (0)
+
+static inline bool rq_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Returns RQ_ERR_UNSUPPORTED for a host-only context (after validation has passed).
+#define RQ_NEED_DEVICE()                                                                              \
+  do {                                                                                                \
+    if (ctx->device < 0) return rq_fail(ctx, RQ_ERR_UNSUPPORTED, "host-only context: no GPU work");   \
+  } while (0)
+
+// kernel launchers (defined next to their kernels); all arguments already validated
+rq_status rq_launch_ln_quant(rq_ctx* ctx, const rq_ln_desc* d);
+rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d);
+rq_status rq_launch_qgemm_act(rq_ctx* ctx, const rq_gemm_desc* d);
+rq_status rq_launch_softmax(rq_ctx* ctx, const rq_softmax_desc* d);
+rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d);
+rq_status rq_launch_fold(rq_ctx* ctx, const rq_fold_desc* d);
+rq_status rq_launch_weight_quant(rq_ctx* ctx, const rq_wq_desc* d);
+rq_status rq_launch_rowsum(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum);
+rq_status rq_launch_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
+                                      double eps, const float* gamma, const float* beta, float* cmin, float* cmax,
+                                      void* scratch /* 2*D*ROWBLOCKS floats */, size_t scratch_bytes);
+rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, float* out2);
+
+// profiling hooks used by rq_block_forward
+void rq_prof_begin(rq_ctx* ctx, int step);
+void rq_prof_end(rq_ctx* ctx);
+
+// ---- device helpers ---------------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ double rq_wave_sum_xor(double v, int width) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1)
+    if (m < width) v += __shfl_xor(v, m, 64);
+  return v;
+}
+__device__ __forceinline__ int rq_pack4(int c0, int c1, int c2, int c3) {
+  return (c0 & 0xFF) | ((c1 & 0xFF) << 8) | ((c2 & 0xFF) << 16) | (c3 << 24);
+}
+#endif
