@@ -112,8 +112,8 @@ rq_status rq_reparam_fold(rq_ctx* ctx, const rq_fold_desc* d);
  * are (k0 | k4<<4), (k1 | k5<<4), (k2 | k6<<4), (k3 | k7<<4), so that `dword & 0x0F0F0F0F` yields
  * k0..k3 and `(dword >> 4) & 0x0F0F0F0F` yields k4..k7 as bytes.  K must be a multiple of 8.
  * If gate_up_rows > 0 the input rows are [gate(0..Dm-1) ; up(0..Dm-1)] with Dm = gate_up_rows and the
- * output rows are interleaved in groups of 16 (16 gate rows, then the 16 matching up rows), the order
- * the fused SiLU(gate)*up epilogue of rq_qgemm expects; Dm must be a multiple of 16.
+ * output rows are interleaved in groups of 32 (32 gate rows, then the 32 matching up rows), the order
+ * the fused SiLU(gate)*up epilogue of rq_qgemm expects; Dm must be a multiple of 32.
  */
 typedef struct {
   int32_t N, K;
@@ -166,14 +166,14 @@ rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d);
  * Weight mode (b_format = RQ_W_*): batch fields must be 1/0.  s_b, z_b, colsum_b are [N] arrays.
  * Activation mode (b_format = RQ_B_ACT_I8, used for Q.K^T): B is int8 `code - b_off` with the scalar
  * pair (*s_b_scalar, z_b_scalar); problems are batched over (outer, inner) with element strides; only
- * out_acc is produced (the Softmax kernel consumes exact accumulators); K <= 256, K % 16 == 0;
+ * out_acc is produced (the Softmax kernel consumes exact accumulators); K in {32, 64, 128, 256};
  * with causal != 0 tiles entirely above the diagonal are not written.
  * RQ_ACT_SILU_GATED: B rows are interleaved gate/up (see rq_weight_quant_pack), N = 2*Dm, outputs
  * have N/2 columns: SiLU(y_gate) * y_up.
  * Requant segments: column n (output column) uses entry n / seg_len of s_o/z_o/off_o (n_seg <= 4);
  * this is how one GEMM emits Q, K and V with their own static scales.
  * rowsum_a[m] = sum_k stored_a[m, k] is required for RQ_W_I8_CENTERED.
- * A, B 16-byte aligned; lda % 16 == 0; K % 16 == 0 (RQ_W_U4: K % 64 == 0).
+ * A, B 16-byte aligned; lda % 16 == 0; weight mode: K % 64 == 0, N % 4 == 0.
  */
 typedef struct {
   int64_t M;
@@ -213,6 +213,8 @@ typedef struct {
   int32_t causal;
 } rq_gemm_desc;
 rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
+/* Tuning knob (process-wide): output tile of the weight-mode kernel. 0 = choose by shape, 1 = 128x128, 2 = 256x128. */
+rq_status rq_set_gemm_tile(int32_t tile);
 
 /* ---- rq_softmax_log2_quant --------------------------------------------------------------------------
  * Softmax fused with the log-sqrt2 quantizer in its base-2 form (Eq. (3.3-1), second line):
@@ -245,7 +247,7 @@ rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d);
  * (k = code >> 1 within a window of 8 shifts), the two parities accumulate separately in exact int32
  * on the matrix cores, and the two sums are combined once per output with s_log and s_log/sqrt2.
  * codes [batch*H, Nq, ld]; V is token-major int8 (row b*Nk + j, column h*d_head + c) stored code - v_off.
- * Outputs are token-major [batch*Nq, H*d_head].  d_head in {32, 64, 128}; ld % 4 == 0.
+ * Outputs are token-major [batch*Nq, H*d_head].  d_head in {32, 64, 128}; ld % 16 == 0, codes 16-byte aligned.
  */
 typedef struct {
   int64_t batch;
@@ -304,6 +306,10 @@ typedef struct {
   rq_qlinear fc2;         /* N = D, K = Dm */
 } rq_block_params;
 
+/* Attention runs in chunks of batch items so that the int32 logits and the codes of one chunk stay in the
+ * last-level cache between Q.K^T, Softmax and P.V.  Sets the chunk budget in bytes (process-wide, default
+ * 64 MiB); call before rq_block_workspace_bytes. */
+rq_status rq_set_attn_chunk_bytes(int64_t bytes);
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);
@@ -323,8 +329,9 @@ int32_t rq_profile_read(rq_ctx* ctx, double* ms_total /* [RQ_STEP_COUNT] */, int
 /* ---- calibration helpers (the step before the path; untimed preparation) -----------------------------------
  * rq_rowsum_i8:        rowsum[m] = sum_k A[m, k].
  * rq_ln_channel_minmax: per-channel min and max over all T tokens of LayerNorm(x) * gamma + beta
- *                      (the channel extremes of the Eqs. for X'_up and X'_low), float64 math, float32 out.
- * rq_minmax_f32:       min and max of a [rows, cols] float32 region -> out[0], out[1].
+ *                      (the channel extremes of the Eqs. for X'_up and X'_low), float64 math and output
+ *                      (cmin, cmax: device double [D]).
+ * rq_minmax_f32:       min and max of a [rows, cols] float32 region -> out2[0], out2[1] (device double).
  * rq_block_calibrate:  Algorithm 1 restricted to one block and to min/max bounds: walks the block on one
  *                      calibration batch, layer by layer, each layer seeing the quantized layers before it;
  *                      fills the caller-allocated arrays named in rq_block_params and writes the scalar
@@ -332,8 +339,8 @@ int32_t rq_profile_read(rq_ctx* ctx, double* ms_total /* [RQ_STEP_COUNT] */, int
  */
 rq_status rq_rowsum_i8(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum);
 rq_status rq_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
-                               double eps, const float* gamma, const float* beta, float* cmin, float* cmax);
-rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, float* out2);
+                               double eps, const float* gamma, const float* beta, double* cmin, double* cmax);
+rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, double* out2);
 
 typedef struct {
   int32_t D, H, Dm;

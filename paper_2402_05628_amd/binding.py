@@ -172,3 +172,210 @@ def rq_ln_quant(ctx: Context, x: torch.Tensor, gamma_t: torch.Tensor, beta_t: Op
                q=_p(q), ldq=q.stride(0), rowsum=_p(rowsum))
     ctx.check(_rq_ln_quant(ctx.handle, C.byref(d)))
     return off
+
+
+_rq_reparam_fold = _sig("rq_reparam_fold", i32, [vp, C.POINTER(FoldDesc)])
+_rq_weight_quant_pack = _sig("rq_weight_quant_pack", i32, [vp, C.POINTER(WqDesc)])
+_rq_qgemm = _sig("rq_qgemm", i32, [vp, C.POINTER(GemmDesc)])
+_rq_softmax = _sig("rq_softmax_log2_quant", i32, [vp, C.POINTER(SoftmaxDesc)])
+_rq_attn_pv = _sig("rq_attn_pv", i32, [vp, C.POINTER(PvDesc)])
+_rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
+_rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
+_rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
+_rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
+_rq_profile_reset = _sig("rq_profile_reset", i32, [vp])
+_rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i64)])
+_rq_rowsum = _sig("rq_rowsum_i8", i32, [vp, vp, i64, i32, i64, vp])
+_rq_ln_cmm = _sig("rq_ln_channel_minmax", i32, [vp, vp, i64, i32, i64, i32, f64, vp, vp, vp, vp])
+_rq_minmax = _sig("rq_minmax_f32", i32, [vp, vp, i64, i64, i64, vp])
+
+
+def rq_reparam_fold(ctx, s_ch, z_ch, gamma, beta, W, b, s_log=1.0):
+    """Allocates the outputs (torch) and calls rq_reparam_fold; returns a dict of device tensors."""
+    D, D_out = s_ch.numel(), (0 if W is None else W.shape[0])
+    dev = s_ch.device
+    out = dict(s_tilde=torch.empty(1, dtype=torch.float32, device=dev), z_tilde=torch.empty(1, dtype=torch.int32, device=dev),
+               gamma_t=torch.empty(D, dtype=torch.float32, device=dev), beta_t=torch.empty(D, dtype=torch.float32, device=dev),
+               W_t=torch.empty((D_out, D), dtype=torch.float32, device=dev),
+               b_t=torch.empty(D_out, dtype=torch.float32, device=dev),
+               s_log_pair=torch.empty(2, dtype=torch.float32, device=dev))
+    d = FoldDesc(D=D, D_out=D_out, s_ch=_p(s_ch), z_ch=_p(z_ch), gamma=_p(gamma), beta=_p(beta), W=_p(W), b=_p(b),
+                 s_log=s_log, s_tilde=_p(out["s_tilde"]), z_tilde=_p(out["z_tilde"]), gamma_t=_p(out["gamma_t"]),
+                 beta_t=_p(out["beta_t"]), W_t=_p(out["W_t"]), b_t=_p(out["b_t"]), s_log_pair=_p(out["s_log_pair"]))
+    ctx.check(_rq_reparam_fold(ctx.handle, C.byref(d)))
+    return out
+
+
+def weight_format(bits: int) -> int:
+    return W_U4 if bits == 4 else (W_I8_CENTERED if bits == 8 else W_I8_BAKED)
+
+
+def rq_weight_quant_pack(ctx, W, bias, bits, fmt=None, gate_up_rows=0):
+    """Quantizes and packs a float weight matrix on the GPU; returns a dict usable as a QLinear source."""
+    N, K = W.shape
+    fmt = weight_format(bits) if fmt is None else fmt
+    dev = W.device
+    w_out = (torch.empty((N, K // 2), dtype=torch.uint8, device=dev) if fmt == W_U4
+             else torch.empty((N, K), dtype=torch.int8, device=dev))
+    out = dict(w=w_out, s_w=torch.empty(N, dtype=torch.float32, device=dev), z_w=torch.empty(N, dtype=torch.int32, device=dev),
+               colsum_w=torch.empty(N, dtype=torch.int32, device=dev), bias=torch.empty(N, dtype=torch.float32, device=dev),
+               N=N, K=K, bits=bits, format=fmt)
+    d = WqDesc(N=N, K=K, bits=bits, format=fmt, gate_up_rows=gate_up_rows, W=_p(W), bias=_p(bias), w_out=_p(w_out),
+               s_w=_p(out["s_w"]), z_w=_p(out["z_w"]), colsum_w=_p(out["colsum_w"]), bias_out=_p(out["bias"]))
+    ctx.check(_rq_weight_quant_pack(ctx.handle, C.byref(d)))
+    return out
+
+
+def rq_qgemm(ctx, A, a_off, z_a, s_a, lin, *, act=ACT_NONE, residual=None, out_acc=None, out_f32=None, out_q=None,
+             bits_o=8, s_o=(), z_o=(), off_o=(), seg_len=0, rowsum_a=None):
+    """Weight-mode rq_qgemm.  `lin` is a dict with w, s_w, z_w, colsum_w, bias, N, K, format."""
+    d = GemmDesc()
+    d.M, d.N, d.K = A.shape[0], lin["N"], lin["K"]
+    d.A, d.lda, d.a_off, d.z_a, d.s_a = _p(A), A.stride(0), a_off, z_a, s_a
+    d.B, d.ldb, d.b_format = _p(lin["w"]), lin["w"].stride(0), lin["format"]
+    d.s_b, d.z_b, d.colsum_b, d.rowsum_a, d.bias = _p(lin["s_w"]), _p(lin["z_w"]), _p(lin["colsum_w"]), _p(rowsum_a), _p(lin.get("bias"))
+    d.act = act
+    if residual is not None:
+        d.residual, d.ldr = _p(residual), residual.stride(0)
+    if out_acc is not None:
+        d.out_acc, d.ldacc = _p(out_acc), out_acc.stride(0)
+    if out_f32 is not None:
+        d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
+    if out_q is not None:
+        d.out_q, d.ldq, d.bits_o = _p(out_q), out_q.stride(0), bits_o
+        d.n_seg, d.seg_len = len(s_o), seg_len
+        for i in range(len(s_o)):
+            d.s_o[i], d.z_o[i], d.off_o[i] = s_o[i], z_o[i], off_o[i]
+    d.batch_outer, d.batch_inner = 1, 1
+    ctx.check(_rq_qgemm(ctx.handle, C.byref(d)))
+
+
+def rq_qk(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_off, z_q, k_off, z_k, acc, ld, causal=False):
+    """Activation-mode rq_qgemm: acc[b*H+h, i, j] = sum_c (q - z_q)(k - z_k) from a token-major int8 tensor."""
+    d = GemmDesc()
+    ldt = qkv.stride(0)
+    d.M, d.N, d.K = seq, seq, d_head
+    base = qkv.data_ptr()
+    d.A, d.lda, d.a_off, d.z_a, d.s_a = base + q_col, ldt, q_off, z_q, 1.0
+    d.B, d.ldb, d.b_format, d.b_off, d.z_b_scalar = base + k_col, ldt, B_ACT_I8, k_off, z_k
+    d.out_acc, d.ldacc, d.acc_stride_group = _p(acc), ld, seq * ld
+    d.batch_outer, d.batch_inner = batch, H
+    d.a_stride_outer, d.a_stride_inner = seq * ldt, d_head
+    d.b_stride_outer, d.b_stride_inner = seq * ldt, d_head
+    d.causal = 1 if causal else 0
+    ctx.check(_rq_qgemm(ctx.handle, C.byref(d)))
+
+
+def rq_softmax_log2_quant(ctx, acc, G, H, Nq, Nk, ld, logit_scale, codes, bits, s_log=1.0, bias=None, mask=MASK_NONE):
+    d = SoftmaxDesc(G=G, H=H, Nq=Nq, Nk=Nk, ld=ld, acc=_p(acc), logit_scale=logit_scale, bias=_p(bias), mask=mask,
+                    s_log=s_log, bits=bits, codes=_p(codes))
+    ctx.check(_rq_softmax(ctx.handle, C.byref(d)))
+
+
+def rq_attn_pv(ctx, codes, ld, V_ptr, ldv, batch, H, Nq, Nk, d_head, s_log, s_v, z_v, v_off, bits_p, *, mask=MASK_NONE,
+               out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
+    d = PvDesc(batch=batch, H=H, Nq=Nq, Nk=Nk, d_head=d_head, ld=ld, codes=_p(codes), V=V_ptr, ldv=ldv, s_log=s_log,
+               s_v=s_v, z_v=z_v, v_off=v_off, bits_p=bits_p, mask=mask)
+    if out_f32 is not None:
+        d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
+    if out_q is not None:
+        d.out_q, d.ldq, d.s_o, d.z_o, d.off_o, d.bits_o = _p(out_q), out_q.stride(0), s_o, z_o, off_o, bits_o
+    ctx.check(_rq_attn_pv(ctx.handle, C.byref(d)))
+
+
+def rq_rowsum_i8(ctx, A, rowsum):
+    ctx.check(_rq_rowsum(ctx.handle, _p(A), A.shape[0], A.shape[1], A.stride(0), _p(rowsum)))
+
+
+def rq_ln_channel_minmax(ctx, x, gamma, beta, norm_kind=NORM_LAYERNORM, eps=1e-6):
+    D = x.shape[1]
+    cmin = torch.empty(D, dtype=torch.float64, device=x.device)
+    cmax = torch.empty(D, dtype=torch.float64, device=x.device)
+    ctx.check(_rq_ln_cmm(ctx.handle, _p(x), x.shape[0], D, x.stride(0), norm_kind, eps, _p(gamma), _p(beta), _p(cmin), _p(cmax)))
+    return cmin, cmax
+
+
+def rq_minmax_f32(ctx, v):
+    out = torch.empty(2, dtype=torch.float64, device=v.device)
+    ctx.check(_rq_minmax(ctx.handle, _p(v), v.shape[0], v.shape[1], v.stride(0), _p(out)))
+    return out
+
+
+def set_attn_chunk_bytes(nbytes: int):
+    rc = _rq_set_chunk(nbytes)
+    if rc != RQ_OK:
+        raise RqError(rc, _rq_last_error(None).decode())
+
+
+def _qlinear_struct(lin) -> QLinear:
+    return QLinear(N=lin["N"], K=lin["K"], bits=lin["bits"], format=lin["format"], w=_p(lin["w"]), s_w=_p(lin["s_w"]),
+                   z_w=_p(lin["z_w"]), colsum_w=_p(lin["colsum_w"]), bias=_p(lin.get("bias")))
+
+
+class Block:
+    """Device-resident quantized block parameters + workspace; forward() calls rq_block_forward."""
+
+    def __init__(self, ctx: Context, cfg, P):
+        """cfg: object with D, H, Dm, norm, act, mask, bits_a, bits_p, eps.  P: dict of device tensors / scalars:
+        ln1/ln2 {gamma_t, beta_t, s, z}; qkv/proj/fc1/fc2 dicts as produced by rq_weight_quant_pack;
+        s_q.., z_q.., s_o, z_o, s_h, z_h, s_log, rel_bias."""
+        self.ctx, self.cfg, self.P = ctx, cfg, P
+        bp = BlockParams()
+        bp.D, bp.H, bp.Dm = cfg.D, cfg.H, cfg.Dm
+        bp.norm_kind, bp.mask = cfg.norm, cfg.mask
+        bp.act = ACT_GELU if cfg.act == 0 else ACT_SILU_GATED
+        bp.bits_a, bp.bits_p, bp.eps = cfg.bits_a, cfg.bits_p, cfg.eps
+        for k in ("ln1", "ln2"):
+            setattr(bp, k + "_gamma_t", _p(P[k]["gamma_t"]))
+            setattr(bp, k + "_beta_t", _p(P[k]["beta_t"]))
+            setattr(bp, k + "_s", float(P[k]["s"]))
+            setattr(bp, k + "_z", int(P[k]["z"]))
+        for k in ("qkv", "proj", "fc1", "fc2"):
+            setattr(bp, k, _qlinear_struct(P[k]))
+        for k in ("s_q", "s_k", "s_v", "s_o", "s_h", "s_log"):
+            setattr(bp, k, float(P[k]))
+        for k in ("z_q", "z_k", "z_v", "z_o", "z_h"):
+            setattr(bp, k, int(P[k]))
+        bp.rel_bias = _p(P.get("rel_bias"))
+        self.bp = bp
+        self._ws = None
+        self._ws_key = None
+
+    def workspace(self, batch, seq):
+        key = (batch, seq)
+        if self._ws_key != key:
+            n = int(_rq_block_ws(C.byref(self.bp), batch, seq))
+            self._ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+            self._ws_key = key
+            self._ws_n = n
+        off = (-self._ws.data_ptr()) % 256
+        return self._ws.data_ptr() + off, self._ws_n
+
+    def forward(self, x: torch.Tensor, y: torch.Tensor, batch: int, seq: int):
+        ptr, n = self.workspace(batch, seq)
+        self.ctx.check(_rq_block_forward(self.ctx.handle, C.byref(self.bp), _p(x), _p(y), batch, seq, ptr, n))
+        return y
+
+
+def profile_enable(ctx: Context, on: bool):
+    ctx.check(_rq_profile_enable(ctx.handle, 1 if on else 0))
+
+
+def profile_reset(ctx: Context):
+    ctx.check(_rq_profile_reset(ctx.handle))
+
+
+def profile_read(ctx: Context):
+    ms = (f64 * len(STEP_NAMES))()
+    n = (i64 * len(STEP_NAMES))()
+    _rq_profile_read(ctx.handle, ms, n)
+    return {STEP_NAMES[i]: (ms[i], n[i]) for i in range(len(STEP_NAMES))}
+
+
+_rq_set_tile = _sig("rq_set_gemm_tile", i32, [i32])
+
+
+def set_gemm_tile(tile: int):
+    rc = _rq_set_tile(tile)
+    if rc != RQ_OK:
+        raise RqError(rc, _rq_last_error(None).decode())

@@ -1,0 +1,265 @@
+// rq_attn_pv: P.V with shift de-quantized log-sqrt2 probabilities
+// (Section "Scale reparameterization for Softmax activations": case analysis before Eq. (3.3-2), Eq. (3.3-2)).
+//
+//   A^[i, j] = s~(code) * 2^floor(-code/2),  s~ = s (even code) | s*sqrt2 (odd code)
+//            = s * 2^-k            (even, k = code >> 1)
+//            = (s / sqrt2) * 2^-k  (odd,  k = code >> 1)
+// The power of two is an integer shift: inside a window of 8 shifts the probability is the int8 value
+// -(128 >> (k & 7)) = -2^(7 - k%8), looked up with one byte-permute per 4 codes.  Even and odd codes go to
+// separate exact int32 accumulators on the int8 matrix cores (v_mfma_i32_32x32x32_i8); the parity scale is
+// applied once per output.  Codes wider than 4 bits span several windows (k >= 8); those are visited one
+// window at a time, only if present, each contributing 2^(-8 w) times its exact integer sum.
+// V^T is staged per 256 keys in LDS (transposed on the way in) as the ROW operand; the codes go straight from
+// global memory into the COLUMN operand (each lane owns 16 consecutive keys of one query row), so a lane ends up
+// with 4 consecutive channels of one token.
+#include "rq_internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct PvParams {
+  const uint8_t* codes;
+  const int8_t* V;
+  int64_t ld, ldv;
+  int H, Nq, Nk;
+  int causal;
+  int wmax;            // last window index: (2^bits - 1) >> 4
+  double a_even, a_odd;   // s_log*s_v*(-1/128), s_log*s_v/sqrt2*(-1/128)
+  int dv;              // v_off - z_v
+  float* out_f32;
+  int64_t ldf;
+  int8_t* out_q;
+  int64_t ldq;
+  double inv_so;
+  int zo, lo, hi;      // z_o - off_o, clamp bounds of the stored code
+  int tiles_i;
+};
+
+constexpr int JB = 256;          // keys staged per LDS block
+constexpr int VT_PITCH = JB + 16;  // bytes per V^T row (skewed: 68 dwords -> conflict-free 16-byte reads)
+
+// table of -(128 >> k), k = 0..7, as the 8 bytes {lo dword, hi dword} for v_perm_b32
+constexpr unsigned TAB_LO = 0xF0E0C080u, TAB_HI = 0xFFFEFCF8u;
+
+__device__ __forceinline__ unsigned byte_eq_mask(unsigned x, unsigned ref4) {
+  // 0xFF in every byte of x equal to the matching byte of ref4 (bytes are < 0x80)
+  const unsigned d = x ^ ref4;
+  const unsigned nz = ((d + 0x7F7F7F7Fu) | d) & 0x80808080u;   // 0x80 where byte != 0
+  const unsigned z = (~nz) & 0x80808080u;                      // 0x80 where byte == 0
+  return (z >> 7) * 0xFFu;
+}
+
+template <int DH, bool WIDE>
+__global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
+  constexpr int TC = DH / 32;
+  __shared__ __align__(16) int8_t vt[DH * VT_PITCH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int blocks_per_group = (p.tiles_i + 3) / 4;
+  const int64_t g = blockIdx.x / blocks_per_group;
+  const int it = (blockIdx.x % blocks_per_group) * 4 + wave;
+  const bool wave_live = it < p.tiles_i;
+  const int64_t b = g / p.H;
+  const int h = (int)(g % p.H);
+  const int8_t* Vg = p.V + b * p.Nk * p.ldv + h * DH;
+  const uint8_t* Cg = p.codes + g * p.Nq * p.ld;
+  const int qi = it * 32 + l32;
+  const int qi_ld = qi < p.Nq ? (wave_live ? qi : 0) : p.Nq - 1;
+  const uint8_t* crow = Cg + (int64_t)qi_ld * p.ld;
+  const int limit = p.causal ? (qi_ld + 1 < p.Nk ? qi_ld + 1 : p.Nk) : p.Nk;
+  // keys this workgroup needs: up to the last row of its last tile when causal
+  int blk_rows_end = ((blockIdx.x % blocks_per_group) * 4 + 4) * 32;
+  blk_rows_end = blk_rows_end < p.Nq ? blk_rows_end : p.Nq;
+  const int nk_block = p.causal ? (blk_rows_end < p.Nk ? blk_rows_end : p.Nk) : p.Nk;
+  int wave_rows_end = (it + 1) * 32;
+  wave_rows_end = wave_rows_end < p.Nq ? wave_rows_end : p.Nq;
+  const int nk_wave = wave_live ? (p.causal ? (wave_rows_end < p.Nk ? wave_rows_end : p.Nk) : p.Nk) : 0;
+
+  // windows present in this wavefront's rows (WIDE only): bit w set if some valid code has code >> 4 == w
+  unsigned present = 1u;
+  if (WIDE && wave_live) {
+    unsigned pm = 0;
+    for (int j0 = half * 16; j0 < nk_wave; j0 += 32) {
+      const v4i cw = *reinterpret_cast<const v4i*>(crow + j0);
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = j0 + d4 * 4 + e;
+          const unsigned code = ((unsigned)cw[d4] >> (8 * e)) & 0xFFu;
+          pm |= (j < limit) ? (1u << (code >> 4)) : 0u;
+        }
+      }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) pm |= __shfl_xor(pm, m, 64);
+    present = pm;
+  }
+  present = __builtin_amdgcn_readfirstlane(present);
+
+  // WIDE: per-window exact integer sums are folded into float64 running sums (each window has its own power of
+  // two); otherwise one window, and the int32 accumulators simply run over all keys.
+  double outE[WIDE ? TC : 1][16], outO[WIDE ? TC : 1][16];
+  double psE = 0.0, psO = 0.0;
+  v16i E[TC], O[TC];
+  int se = 0, so = 0;
+#pragma unroll
+  for (int c = 0; c < TC; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      E[c][e] = 0; O[c][e] = 0;
+      if (WIDE) { outE[c][e] = 0.0; outO[c][e] = 0.0; }
+    }
+
+  for (int jb = 0; jb < nk_block; jb += JB) {
+    __syncthreads();
+    // ---- stage V^T for keys jb .. jb+JB-1: thread -> (4 keys, 4 channels), byte transpose in registers ----
+    for (int id = tid; id < (JB / 4) * (DH / 4); id += 256) {
+      const int j4 = id % (JB / 4), c4 = id / (JB / 4);
+      unsigned r[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = jb + j4 * 4 + e;
+        r[e] = j < p.Nk ? *reinterpret_cast<const unsigned*>(Vg + (int64_t)j * p.ldv + c4 * 4) : 0u;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const unsigned o = ((r[0] >> (8 * e)) & 0xFFu) | (((r[1] >> (8 * e)) & 0xFFu) << 8) |
+                           (((r[2] >> (8 * e)) & 0xFFu) << 16) | (((r[3] >> (8 * e)) & 0xFFu) << 24);
+        *reinterpret_cast<unsigned*>(vt + (c4 * 4 + e) * VT_PITCH + j4 * 4) = o;
+      }
+    }
+    __syncthreads();
+    if (jb >= nk_wave) continue;
+    int jend = nk_wave - jb;
+    jend = jend < JB ? jend : JB;
+    for (int w = 0; w <= (WIDE ? p.wmax : 0); ++w) {
+      if (WIDE && !((present >> w) & 1u)) continue;
+      if (WIDE) {
+#pragma unroll
+        for (int c = 0; c < TC; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
+        se = 0; so = 0;
+      }
+      const unsigned wref = (unsigned)w * 0x01010101u;
+      for (int js = 0; js < jend; js += 32) {
+        const int j0 = jb + js + half * 16;
+        const v4i cw = j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
+        v4i pe, po;
+#pragma unroll
+        for (int d4 = 0; d4 < 4; ++d4) {
+          const unsigned c = (unsigned)cw[d4];
+          const unsigned sel = (c >> 1) & 0x07070707u;
+          unsigned pall = __builtin_amdgcn_perm(TAB_HI, TAB_LO, sel);
+          if (WIDE) pall &= byte_eq_mask((c >> 4) & 0x0F0F0F0Fu, wref);
+          // validity of the 4 keys j0+4*d4 .. +3 (padding and causal mask)
+          int nv = limit - (j0 + d4 * 4);
+          nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+          const unsigned vm = nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
+          pall &= vm;
+          const unsigned odd = (c & 0x01010101u) * 0xFFu;
+          po[d4] = (int)(pall & odd);
+          pe[d4] = (int)(pall & ~odd);
+        }
+        if (p.dv != 0) {
+#pragma unroll
+          for (int d4 = 0; d4 < 4; ++d4) {
+            se = __builtin_amdgcn_sdot4(pe[d4], 0x01010101, se, false);
+            so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < TC; ++c) {
+          const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VT_PITCH + js + half * 16);
+          E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
+          O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
+        }
+      }
+      if (WIDE) {
+        const double wsc = __builtin_ldexp(1.0, -8 * w);
+#pragma unroll
+        for (int c = 0; c < TC; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            outE[c][e] = fma((double)E[c][e], wsc, outE[c][e]);
+            outO[c][e] = fma((double)O[c][e], wsc, outO[c][e]);
+          }
+        psE = fma((double)se, wsc, psE);
+        psO = fma((double)so, wsc, psO);
+      }
+    }
+  }
+  if (!WIDE) { psE = (double)se; psO = (double)so; }
+  if (!wave_live) return;
+  if (p.dv != 0) {   // the two halves of the wavefront saw different keys of the same row
+    psE += __shfl_xor(psE, 32, 64);
+    psO += __shfl_xor(psO, 32, 64);
+  }
+  if (qi >= p.Nq) return;
+  const int64_t tok = b * p.Nq + qi;
+  const double corr = (double)p.dv * (p.a_even * psE + p.a_odd * psO);
+#pragma unroll
+  for (int c = 0; c < TC; ++c) {
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      const int col = h * DH + c * 32 + 8 * gq + half * 4;
+      double y[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const double ve = WIDE ? outE[WIDE ? c : 0][4 * gq + e] : (double)E[c][4 * gq + e];
+        const double vo = WIDE ? outO[WIDE ? c : 0][4 * gq + e] : (double)O[c][4 * gq + e];
+        y[e] = p.a_even * ve + p.a_odd * vo + corr;
+      }
+      if (p.out_f32)
+        *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4((float)y[0], (float)y[1], (float)y[2], (float)y[3]);
+      if (p.out_q) {
+        int k[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int q = (int)rint(y[e] * p.inv_so) + p.zo;
+          k[e] = q < p.lo ? p.lo : (q > p.hi ? p.hi : q);
+        }
+        *reinterpret_cast<int*>(p.out_q + tok * p.ldq + col) = rq_pack4(k[0], k[1], k[2], k[3]);
+      }
+    }
+  }
+}
+
+template <int DH>
+void launch(rq_ctx* ctx, const PvParams& p, int64_t groups, bool wide) {
+  const int blocks_per_group = (p.tiles_i + 3) / 4;
+  const dim3 grid((unsigned)(groups * blocks_per_group));
+  if (wide) hipLaunchKernelGGL((pv_kernel<DH, true>), grid, dim3(256), 0, ctx->stream, p);
+  else hipLaunchKernelGGL((pv_kernel<DH, false>), grid, dim3(256), 0, ctx->stream, p);
+}
+
+}  // namespace
+
+rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d) {
+  PvParams p;
+  p.codes = d->codes; p.V = d->V; p.ld = d->ld; p.ldv = d->ldv;
+  p.H = d->H; p.Nq = d->Nq; p.Nk = d->Nk;
+  p.causal = d->mask == RQ_MASK_CAUSAL;
+  p.wmax = ((1 << d->bits_p) - 1) >> 4;
+  const double ss = (double)d->s_log * (double)d->s_v;
+  p.a_even = -ss / 128.0;
+  p.a_odd = -ss / (128.0 * 1.4142135623730951);
+  p.dv = d->v_off - d->z_v;
+  p.out_f32 = d->out_f32; p.ldf = d->ldf; p.out_q = d->out_q; p.ldq = d->ldq;
+  p.inv_so = d->out_q ? 1.0 / (double)d->s_o : 0.0;
+  p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
+  p.tiles_i = (d->Nq + 31) / 32;
+  const bool wide = d->bits_p > 4;
+  const int64_t groups = d->batch * d->H;
+  switch (d->d_head) {
+    case 32: launch<32>(ctx, p, groups, wide); break;
+    case 64: launch<64>(ctx, p, groups, wide); break;
+    case 128: launch<128>(ctx, p, groups, wide); break;
+    default: return rq_fail(ctx, RQ_ERR_SHAPE, "rq_attn_pv: d_head = %d must be 32, 64 or 128", d->d_head);
+  }
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}

@@ -164,4 +164,195 @@ rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
   return rq_launch_ln_quant(ctx, d);
 }
 
+
+rq_status rq_reparam_fold(rq_ctx* ctx, const rq_fold_desc* d) {
+  RQ_CHECK_CTX("rq_reparam_fold");
+  RQ_REQUIRE(d->D > 0 && d->D_out >= 0, RQ_ERR_SHAPE, "rq_reparam_fold: D = %d, D_out = %d", d->D, d->D_out);
+  RQ_REQUIRE(d->s_ch && d->z_ch && d->gamma, RQ_ERR_INVALID_ARG, "rq_reparam_fold: s_ch, z_ch, gamma must be non-NULL");
+  RQ_REQUIRE(d->s_tilde && d->z_tilde && d->gamma_t && d->beta_t, RQ_ERR_INVALID_ARG,
+             "rq_reparam_fold: s_tilde, z_tilde, gamma_t, beta_t must be non-NULL");
+  RQ_REQUIRE(d->D_out == 0 || (d->W && d->W_t && d->b_t), RQ_ERR_INVALID_ARG, "rq_reparam_fold: W, W_t, b_t must be non-NULL");
+  RQ_REQUIRE(!d->s_log_pair || (d->s_log > 0.f && std::isfinite(d->s_log)), RQ_ERR_INVALID_ARG,
+             "rq_reparam_fold: s_log must be > 0");
+  RQ_NEED_DEVICE();
+  return rq_launch_fold(ctx, d);
+}
+
+rq_status rq_weight_quant_pack(rq_ctx* ctx, const rq_wq_desc* d) {
+  RQ_CHECK_CTX("rq_weight_quant_pack");
+  RQ_REQUIRE(d->W && d->w_out && d->s_w && d->z_w && d->colsum_w, RQ_ERR_INVALID_ARG,
+             "rq_weight_quant_pack: W, w_out, s_w, z_w, colsum_w must be non-NULL");
+  RQ_REQUIRE(d->N > 0 && d->K > 0, RQ_ERR_SHAPE, "rq_weight_quant_pack: N = %d, K = %d", d->N, d->K);
+  switch (d->format) {
+    case RQ_W_U4:
+      RQ_REQUIRE(d->bits == 4, RQ_ERR_INVALID_ARG, "rq_weight_quant_pack: RQ_W_U4 needs bits = 4, got %d", d->bits);
+      RQ_REQUIRE(d->K % 8 == 0, RQ_ERR_SHAPE, "rq_weight_quant_pack: RQ_W_U4 needs K %% 8 == 0, got %d", d->K);
+      break;
+    case RQ_W_I8_CENTERED:
+      RQ_REQUIRE(d->bits >= 2 && d->bits <= 8, RQ_ERR_INVALID_ARG, "rq_weight_quant_pack: bits = %d not in 2..8", d->bits);
+      break;
+    case RQ_W_I8_BAKED:
+      RQ_REQUIRE(d->bits >= 2 && d->bits <= 7, RQ_ERR_INVALID_ARG,
+                 "rq_weight_quant_pack: RQ_W_I8_BAKED needs bits in 2..7, got %d", d->bits);
+      break;
+    default:
+      return rq_fail(ctx, RQ_ERR_INVALID_ARG, "rq_weight_quant_pack: format %d", d->format);
+  }
+  if (d->gate_up_rows != 0)
+    RQ_REQUIRE(d->gate_up_rows > 0 && d->N == 2 * d->gate_up_rows && d->gate_up_rows % 32 == 0, RQ_ERR_SHAPE,
+               "rq_weight_quant_pack: gate_up_rows = %d needs N = 2*gate_up_rows and a multiple of 32", d->gate_up_rows);
+  RQ_REQUIRE(d->w_out != (const void*)d->W, RQ_ERR_INVALID_ARG, "rq_weight_quant_pack: w_out must not alias W");
+  RQ_NEED_DEVICE();
+  return rq_launch_weight_quant(ctx, d);
+}
+
+rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d) {
+  RQ_CHECK_CTX("rq_qgemm");
+  RQ_REQUIRE(d->A && d->B, RQ_ERR_INVALID_ARG, "rq_qgemm: A and B must be non-NULL");
+  RQ_REQUIRE(d->M >= 0 && d->N > 0 && d->K > 0, RQ_ERR_SHAPE, "rq_qgemm: M = %lld, N = %d, K = %d", (long long)d->M, d->N, d->K);
+  RQ_REQUIRE(rq_aligned(d->A, 16) && rq_aligned(d->B, 16), RQ_ERR_INVALID_ARG, "rq_qgemm: A and B need 16-byte alignment");
+  RQ_REQUIRE(d->lda >= d->K && d->lda % 16 == 0, RQ_ERR_SHAPE, "rq_qgemm: lda = %lld must be >= K and a multiple of 16",
+             (long long)d->lda);
+  if (d->b_format == RQ_B_ACT_I8) {
+    RQ_REQUIRE(d->K == 32 || d->K == 64 || d->K == 128 || d->K == 256, RQ_ERR_SHAPE,
+               "rq_qgemm (activation mode): K = %d must be 32, 64, 128 or 256", d->K);
+    RQ_REQUIRE(d->ldb >= d->K && d->ldb % 16 == 0, RQ_ERR_SHAPE, "rq_qgemm: ldb must be >= K and a multiple of 16");
+    RQ_REQUIRE(d->out_acc && !d->out_f32 && !d->out_q, RQ_ERR_INVALID_ARG,
+               "rq_qgemm (activation mode): out_acc is the only output");
+    RQ_REQUIRE(rq_aligned(d->out_acc, 16) && d->ldacc >= d->N && d->ldacc % 4 == 0 && d->acc_stride_group % 4 == 0, RQ_ERR_SHAPE,
+               "rq_qgemm (activation mode): out_acc needs 16-byte alignment, ldacc >= N, ldacc and group stride multiples of 4");
+    RQ_REQUIRE(d->batch_outer >= 1 && d->batch_inner >= 1, RQ_ERR_SHAPE, "rq_qgemm: batch counts must be >= 1");
+    RQ_REQUIRE(d->a_stride_outer % 16 == 0 && d->a_stride_inner % 16 == 0 && d->b_stride_outer % 16 == 0 &&
+                   d->b_stride_inner % 16 == 0, RQ_ERR_SHAPE, "rq_qgemm: batch strides must be multiples of 16");
+    RQ_REQUIRE(d->M < (1ll << 31), RQ_ERR_SHAPE, "rq_qgemm (activation mode): M too large");
+    RQ_REQUIRE(!d->causal || d->M == d->N, RQ_ERR_SHAPE, "rq_qgemm: causal needs M == N");
+    RQ_NEED_DEVICE();
+    if (d->M == 0) return RQ_OK;
+    return rq_launch_qgemm_act(ctx, d);
+  }
+  RQ_REQUIRE(d->b_format == RQ_W_I8_BAKED || d->b_format == RQ_W_I8_CENTERED || d->b_format == RQ_W_U4, RQ_ERR_INVALID_ARG,
+             "rq_qgemm: b_format %d", d->b_format);
+  RQ_REQUIRE(d->K % 64 == 0, RQ_ERR_SHAPE, "rq_qgemm: K = %d must be a multiple of 64", d->K);
+  RQ_REQUIRE(d->N % 4 == 0, RQ_ERR_SHAPE, "rq_qgemm: N = %d must be a multiple of 4", d->N);
+  const int64_t ldb_min = d->b_format == RQ_W_U4 ? d->K / 2 : d->K;
+  RQ_REQUIRE(d->ldb >= ldb_min && d->ldb % 16 == 0, RQ_ERR_SHAPE, "rq_qgemm: ldb = %lld must be >= %lld and a multiple of 16",
+             (long long)d->ldb, (long long)ldb_min);
+  RQ_REQUIRE(d->s_b, RQ_ERR_INVALID_ARG, "rq_qgemm: s_b must be non-NULL");
+  RQ_REQUIRE(d->s_a > 0.f && std::isfinite(d->s_a), RQ_ERR_INVALID_ARG, "rq_qgemm: s_a must be > 0");
+  RQ_REQUIRE(d->b_format == RQ_W_I8_BAKED || d->z_b, RQ_ERR_INVALID_ARG, "rq_qgemm: z_b is required for this weight format");
+  RQ_REQUIRE(d->b_format != RQ_W_I8_CENTERED || d->rowsum_a, RQ_ERR_INVALID_ARG,
+             "rq_qgemm: rowsum_a is required for RQ_W_I8_CENTERED");
+  RQ_REQUIRE(d->a_off == d->z_a || d->colsum_b, RQ_ERR_INVALID_ARG, "rq_qgemm: colsum_b is required when a_off != z_a");
+  RQ_REQUIRE(d->act == RQ_ACT_NONE || d->act == RQ_ACT_GELU || d->act == RQ_ACT_SILU_GATED, RQ_ERR_INVALID_ARG,
+             "rq_qgemm: act %d", d->act);
+  RQ_REQUIRE(d->out_acc || d->out_f32 || d->out_q, RQ_ERR_INVALID_ARG, "rq_qgemm: no output requested");
+  const bool gated = d->act == RQ_ACT_SILU_GATED;
+  if (gated) {
+    RQ_REQUIRE(d->N % 64 == 0, RQ_ERR_SHAPE, "rq_qgemm: gated activation needs N %% 64 == 0");
+    RQ_REQUIRE(!d->out_acc, RQ_ERR_INVALID_ARG, "rq_qgemm: out_acc is not available with the gated activation");
+  }
+  const int n_out = gated ? d->N / 2 : d->N;
+  RQ_REQUIRE(!d->out_acc || (rq_aligned(d->out_acc, 16) && d->ldacc >= d->N && d->ldacc % 4 == 0), RQ_ERR_SHAPE,
+             "rq_qgemm: out_acc alignment / ldacc");
+  RQ_REQUIRE(!d->out_f32 || (rq_aligned(d->out_f32, 16) && d->ldf >= n_out && d->ldf % 4 == 0), RQ_ERR_SHAPE,
+             "rq_qgemm: out_f32 alignment / ldf");
+  RQ_REQUIRE(!d->residual || (rq_aligned(d->residual, 16) && d->ldr >= n_out && d->ldr % 4 == 0), RQ_ERR_SHAPE,
+             "rq_qgemm: residual alignment / ldr");
+  if (d->out_q) {
+    RQ_REQUIRE(rq_aligned(d->out_q, 4) && d->ldq >= n_out && d->ldq % 4 == 0, RQ_ERR_SHAPE, "rq_qgemm: out_q alignment / ldq");
+    RQ_REQUIRE(d->bits_o >= 2 && d->bits_o <= 8, RQ_ERR_INVALID_ARG, "rq_qgemm: bits_o = %d not in 2..8", d->bits_o);
+    const int ns = d->n_seg > 0 ? d->n_seg : 1;
+    RQ_REQUIRE(ns <= 4, RQ_ERR_INVALID_ARG, "rq_qgemm: n_seg = %d > 4", ns);
+    RQ_REQUIRE(ns == 1 || (d->seg_len > 0 && d->seg_len % 4 == 0 && (int64_t)d->seg_len * ns >= n_out), RQ_ERR_SHAPE,
+               "rq_qgemm: seg_len = %d must be a multiple of 4 and cover N", d->seg_len);
+    for (int i = 0; i < ns; ++i) {
+      RQ_REQUIRE(d->s_o[i] > 0.f && std::isfinite(d->s_o[i]), RQ_ERR_INVALID_ARG, "rq_qgemm: s_o[%d] must be > 0", i);
+      RQ_REQUIRE(fits_i8(d->bits_o, d->off_o[i]), RQ_ERR_INVALID_ARG, "rq_qgemm: off_o[%d] = %d does not fit int8 at %d bits", i,
+                 d->off_o[i], d->bits_o);
+    }
+  }
+  RQ_REQUIRE(d->batch_outer <= 1 && d->batch_inner <= 1, RQ_ERR_UNSUPPORTED, "rq_qgemm: weight mode is not batched");
+  RQ_NEED_DEVICE();
+  if (d->M == 0) return RQ_OK;
+  return rq_launch_qgemm_weight(ctx, d);
+}
+
+rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d) {
+  RQ_CHECK_CTX("rq_softmax_log2_quant");
+  RQ_REQUIRE(d->acc && d->codes, RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: acc and codes must be non-NULL");
+  RQ_REQUIRE(d->G >= 0 && d->Nq > 0 && d->Nk > 0 && d->H > 0, RQ_ERR_SHAPE, "rq_softmax_log2_quant: G = %lld, H = %d, Nq = %d, Nk = %d",
+             (long long)d->G, d->H, d->Nq, d->Nk);
+  RQ_REQUIRE(d->ld >= d->Nk && d->ld % 4 == 0 && d->ld <= 4096, RQ_ERR_SHAPE,
+             "rq_softmax_log2_quant: ld = %lld must be >= Nk, a multiple of 4 and at most 4096", (long long)d->ld);
+  RQ_REQUIRE(rq_aligned(d->acc, 16) && rq_aligned(d->codes, 4), RQ_ERR_INVALID_ARG,
+             "rq_softmax_log2_quant: acc needs 16-byte, codes 4-byte alignment");
+  RQ_REQUIRE(d->bits >= 2 && d->bits <= 8, RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: bits = %d not in 2..8", d->bits);
+  RQ_REQUIRE(d->s_log > 0.f && std::isfinite(d->s_log), RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: s_log must be > 0");
+  RQ_REQUIRE(d->logit_scale > 0.0 && std::isfinite(d->logit_scale), RQ_ERR_INVALID_ARG,
+             "rq_softmax_log2_quant: logit_scale must be > 0");
+  RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: mask %d", d->mask);
+  RQ_REQUIRE(d->mask != RQ_MASK_CAUSAL || d->Nq == d->Nk, RQ_ERR_SHAPE, "rq_softmax_log2_quant: causal needs Nq == Nk");
+  RQ_NEED_DEVICE();
+  if (d->G == 0) return RQ_OK;
+  return rq_launch_softmax(ctx, d);
+}
+
+rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d) {
+  RQ_CHECK_CTX("rq_attn_pv");
+  RQ_REQUIRE(d->codes && d->V, RQ_ERR_INVALID_ARG, "rq_attn_pv: codes and V must be non-NULL");
+  RQ_REQUIRE(d->out_f32 || d->out_q, RQ_ERR_INVALID_ARG, "rq_attn_pv: no output requested");
+  RQ_REQUIRE(d->batch >= 0 && d->H > 0 && d->Nq > 0 && d->Nk > 0, RQ_ERR_SHAPE, "rq_attn_pv: batch = %lld, H = %d, Nq = %d, Nk = %d",
+             (long long)d->batch, d->H, d->Nq, d->Nk);
+  RQ_REQUIRE(d->d_head == 32 || d->d_head == 64 || d->d_head == 128, RQ_ERR_SHAPE, "rq_attn_pv: d_head = %d must be 32, 64 or 128",
+             d->d_head);
+  RQ_REQUIRE(d->ld >= d->Nk && d->ld % 16 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ld = %lld must be >= Nk and a multiple of 16",
+             (long long)d->ld);
+  RQ_REQUIRE(rq_aligned(d->codes, 16) && rq_aligned(d->V, 4), RQ_ERR_INVALID_ARG, "rq_attn_pv: codes need 16-byte, V 4-byte alignment");
+  RQ_REQUIRE(d->ldv >= (int64_t)d->H * d->d_head && d->ldv % 4 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ldv must be >= H*d_head and a multiple of 4");
+  RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_pv: bits_p = %d not in 2..8", d->bits_p);
+  RQ_REQUIRE(d->s_log > 0.f && d->s_v > 0.f, RQ_ERR_INVALID_ARG, "rq_attn_pv: s_log and s_v must be > 0");
+  RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_attn_pv: mask %d", d->mask);
+  RQ_REQUIRE(d->mask != RQ_MASK_CAUSAL || d->Nq == d->Nk, RQ_ERR_SHAPE, "rq_attn_pv: causal needs Nq == Nk");
+  const int64_t width = (int64_t)d->H * d->d_head;
+  RQ_REQUIRE(!d->out_f32 || (rq_aligned(d->out_f32, 16) && d->ldf >= width && d->ldf % 4 == 0), RQ_ERR_SHAPE,
+             "rq_attn_pv: out_f32 alignment / ldf");
+  if (d->out_q) {
+    RQ_REQUIRE(rq_aligned(d->out_q, 4) && d->ldq >= width && d->ldq % 4 == 0, RQ_ERR_SHAPE, "rq_attn_pv: out_q alignment / ldq");
+    RQ_REQUIRE(d->bits_o >= 2 && d->bits_o <= 8 && d->s_o > 0.f && fits_i8(d->bits_o, d->off_o), RQ_ERR_INVALID_ARG,
+               "rq_attn_pv: bad output quantizer (bits_o = %d, s_o = %g, off_o = %d)", d->bits_o, (double)d->s_o, d->off_o);
+  }
+  RQ_NEED_DEVICE();
+  if (d->batch == 0) return RQ_OK;
+  return rq_launch_pv(ctx, d);
+}
+
+rq_status rq_rowsum_i8(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_rowsum_i8: ctx is NULL");
+  RQ_REQUIRE(A && rowsum, RQ_ERR_INVALID_ARG, "rq_rowsum_i8: A and rowsum must be non-NULL");
+  RQ_REQUIRE(M >= 0 && K > 0 && K % 4 == 0 && lda >= K && lda % 4 == 0 && rq_aligned(A, 4), RQ_ERR_SHAPE,
+             "rq_rowsum_i8: K and lda must be multiples of 4, A 4-byte aligned");
+  RQ_NEED_DEVICE();
+  if (M == 0) return RQ_OK;
+  return rq_launch_rowsum(ctx, A, M, K, lda, rowsum);
+}
+
+rq_status rq_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind, double eps,
+                               const float* gamma, const float* beta, double* cmin, double* cmax) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_ln_channel_minmax: ctx is NULL");
+  RQ_REQUIRE(x && gamma && cmin && cmax, RQ_ERR_INVALID_ARG, "rq_ln_channel_minmax: x, gamma, cmin, cmax must be non-NULL");
+  RQ_REQUIRE(T > 0 && D > 0 && D % 4 == 0 && D <= 8192 && ldx >= D && ldx % 4 == 0 && rq_aligned(x, 16), RQ_ERR_SHAPE,
+             "rq_ln_channel_minmax: T > 0, D a multiple of 4 and <= 8192, ldx a multiple of 4, x 16-byte aligned");
+  RQ_REQUIRE(norm_kind == RQ_NORM_LAYERNORM || norm_kind == RQ_NORM_RMSNORM, RQ_ERR_INVALID_ARG, "rq_ln_channel_minmax: norm_kind");
+  RQ_NEED_DEVICE();
+  return rq_launch_ln_channel_minmax(ctx, x, T, D, ldx, norm_kind, eps, gamma, beta, cmin, cmax);
+}
+
+rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, double* out2) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_minmax_f32: ctx is NULL");
+  RQ_REQUIRE(v && out2, RQ_ERR_INVALID_ARG, "rq_minmax_f32: v and out2 must be non-NULL");
+  RQ_REQUIRE(rows > 0 && cols > 0 && ld >= cols, RQ_ERR_SHAPE, "rq_minmax_f32: rows, cols > 0 and ld >= cols");
+  RQ_NEED_DEVICE();
+  return rq_launch_minmax_f32(ctx, v, rows, cols, ld, out2);
+}
+
 }  // extern "C"

@@ -56,9 +56,8 @@ rq_status rq_launch_fold(rq_ctx* ctx, const rq_fold_desc* d);
 rq_status rq_launch_weight_quant(rq_ctx* ctx, const rq_wq_desc* d);
 rq_status rq_launch_rowsum(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum);
 rq_status rq_launch_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
-                                      double eps, const float* gamma, const float* beta, float* cmin, float* cmax,
-                                      void* scratch /* 2*D*ROWBLOCKS floats */, size_t scratch_bytes);
-rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, float* out2);
+                                      double eps, const float* gamma, const float* beta, double* cmin, double* cmax);
+rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, double* out2);
 
 // profiling hooks used by rq_block_forward
 void rq_prof_begin(rq_ctx* ctx, int step);

@@ -61,3 +61,62 @@ def assert_float_close(got, want, what, rtol=1e-3):
 
 def cfg_dict(cfg):
     return dataclasses.asdict(cfg)
+
+
+# ---- numpy-side packing of oracle weight codes into the library's storage formats (independent of the product's
+#      own packer, so it also checks the layout the header documents) --------------------------------------------
+W_I8_BAKED, W_I8_CENTERED, W_U4 = 0, 1, 2
+
+
+def pack_u4(codes):
+    """[N, K] codes 0..15 -> [N, K/2] bytes: in each group of 8 codes, byte i = code[i] | code[i+4] << 4."""
+    N, K = codes.shape
+    g = codes.reshape(N, K // 8, 8).astype(np.uint8)
+    return (g[:, :, 0:4] | (g[:, :, 4:8] << 4)).reshape(N, K // 2)
+
+
+def gate_up_interleave(arr, Dm):
+    """rows [gate(0..Dm-1); up(0..Dm-1)] -> groups of 32 gate rows followed by the matching 32 up rows."""
+    gate, upp = arr[:Dm], arr[Dm:2 * Dm]
+    sh = (Dm // 32, 32) + arr.shape[1:]
+    return np.stack([gate.reshape(sh), upp.reshape(sh)], axis=1).reshape(arr.shape)
+
+
+def lin_to_device(lin, bits, gated_Dm=0):
+    """Oracle linear dict (codes, s_w, z_w, bias) -> dict of device tensors in the library's format."""
+    codes, s_w, z_w = np.asarray(lin["codes"]), np.asarray(lin["s_w"], np.float32), np.asarray(lin["z_w"], np.int64)
+    bias = lin.get("bias")
+    bias = np.zeros(codes.shape[0], np.float32) if bias is None else np.asarray(bias, np.float32)
+    if gated_Dm:
+        codes, s_w, z_w, bias = (gate_up_interleave(a, gated_Dm) for a in (codes, s_w, z_w, bias))
+    colsum = (codes - z_w[:, None]).sum(1)
+    if bits == 4:
+        fmt, w = W_U4, pack_u4(codes)
+    elif bits == 8:
+        fmt, w = W_I8_CENTERED, (codes - 128).astype(np.int8)
+    else:
+        fmt, w = W_I8_BAKED, (codes - z_w[:, None]).astype(np.int8)
+    return dict(w=dev(w), s_w=dev(s_w), z_w=dev(z_w.astype(np.int32)), colsum_w=dev(colsum.astype(np.int32)),
+                bias=dev(bias), N=codes.shape[0], K=codes.shape[1], bits=bits, format=fmt)
+
+
+def block_to_device(P):
+    """Oracle block parameters -> the dict paper_2402_05628_amd.binding.Block consumes."""
+    c = P["cfg"]
+    gated = c["act"] == orc.ACT_SILU_GATED
+    out = {}
+    for k in ("ln1", "ln2"):
+        out[k] = dict(gamma_t=dev(P[k]["gamma_t"]), beta_t=dev(P[k]["beta_t"]), s=float(P[k]["s"]), z=int(P[k]["z"]))
+    for k in ("qkv", "proj", "fc2"):
+        out[k] = lin_to_device(P[k], c["bits_w"])
+    out["fc1"] = lin_to_device(P["fc1"], c["bits_w"], c["Dm"] if gated else 0)
+    for k in ("s_q", "s_k", "s_v", "s_o", "s_h", "s_log", "z_q", "z_k", "z_v", "z_o", "z_h"):
+        out[k] = P[k]
+    out["rel_bias"] = None if P.get("rel_bias") is None else dev(P["rel_bias"])
+    return out
+
+
+def random_linear(g, N, K, bits):
+    """Random weight codes with per-channel scale / zero-point, as an oracle linear dict."""
+    return dict(codes=g.integers(0, 2 ** bits, size=(N, K)), s_w=g.uniform(1e-3, 5e-3, size=N).astype(np.float32),
+                z_w=g.integers(0, 2 ** bits, size=N), bias=g.normal(0, 0.5, size=N).astype(np.float32))

@@ -1,0 +1,125 @@
+"""Q.K^T accumulators (bit-exact), Softmax-log2 codes and shift-dequantized P.V against the oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import repquant_oracle as orc
+from tests.helpers import assert_codes_close, assert_float_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rq():
+    from paper_2402_05628_amd import binding
+    return binding, binding.Context(0)
+
+
+def _ld(n):
+    return (n + 15) // 16 * 16
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits,causal", [(2, 3, 197, 64, 4, False), (1, 2, 49, 32, 6, False), (3, 2, 257, 64, 4, False),
+                                                        (1, 2, 300, 128, 8, True), (2, 2, 64, 64, 8, False), (1, 1, 1, 32, 8, False),
+                                                        (1, 2, 33, 64, 8, True)])
+def test_qk_accumulators_bit_exact(rq, batch, H, seq, dh, bits, causal):
+    b, ctx = rq
+    print("case", batch, H, seq, dh, bits, causal, flush=True)
+    g = np.random.default_rng(seq + dh + bits)
+    D = H * dh
+    codes = g.integers(0, 2 ** bits, size=(batch * seq, 3 * D))
+    z_q, z_k = int(g.integers(0, 2 ** bits)), int(g.integers(0, 2 ** bits))
+    offq, offk = b.store_offset(bits, z_q), b.store_offset(bits, z_k)
+    st = codes.copy()
+    st[:, :D] -= offq
+    st[:, D:2 * D] -= offk
+    st[:, 2 * D:] -= 128 if bits == 8 else 0
+    qkv = dev(st.astype(np.int8))
+    ld = _ld(seq)
+    acc = torch.full((batch * H, seq, ld), 12345, dtype=torch.int32, device="cuda")
+    b.rq_qk(ctx, qkv, batch, seq, H, dh, 0, D, offq, z_q, offk, z_k, acc, ld, causal=causal)
+    got = acc.cpu().numpy()
+    for bi in range(batch):
+        r = slice(bi * seq, (bi + 1) * seq)
+        for h in range(H):
+            want = orc.int_matmul_nt(codes[r, h * dh:(h + 1) * dh] - z_q, codes[r, D + h * dh:D + (h + 1) * dh] - z_k)
+            sub = got[bi * H + h, :, :seq]
+            if causal:
+                m = np.tril(np.ones((seq, seq), bool))
+                assert np.array_equal(sub[m], want[m])
+            else:
+                assert np.array_equal(sub, want)
+
+
+@pytest.mark.parametrize("G,H,N,bits,bias,causal", [(6, 3, 197, 4, False, False), (8, 4, 49, 6, True, False), (4, 2, 257, 4, False, False),
+                                                    (2, 2, 2048, 8, False, True), (3, 3, 64, 8, False, False), (2, 1, 1, 4, False, False),
+                                                    (2, 2, 1000, 6, True, True), (2, 2, 4096, 8, False, False), (5, 5, 20, 8, True, True)])
+def test_softmax_log2_codes(rq, G, H, N, bits, bias, causal):
+    b, ctx = rq
+    print("case", G, H, N, bits, bias, causal, flush=True)
+    g = np.random.default_rng(G + N + bits)
+    dh = 64
+    # accumulators of 4..8-bit q, k whose de-quantized values are ~N(0,1): heavy-tailed probabilities
+    sq = 8.0 / 2 ** 8
+    acc = np.rint(g.normal(size=(G, N, N)) * math.sqrt(dh) / (sq * sq)).astype(np.int64)
+    ld = _ld(N)
+    accp = np.full((G, N, ld), 7777, np.int32)
+    accp[:, :, :N] = acc
+    scale = sq * sq / math.sqrt(dh)
+    bias_a = (g.normal(0, 0.5, size=(H, N, N)).astype(np.float32)) if bias else None
+    s_log = np.float32(0.8)
+    want = np.empty((G, N, N), np.int64)
+    for gi in range(G):
+        L = acc[gi].astype(np.float64) * scale
+        if bias:
+            L = L + bias_a[gi % H].astype(np.float64)
+        if causal:
+            L = np.where(np.arange(N)[None, :] > np.arange(N)[:, None], -np.inf, L)
+        want[gi] = orc.softmax_log_quant(L, s_log, bits)
+    codes = torch.full((G, N, ld), 99, dtype=torch.uint8, device="cuda")
+    b.rq_softmax_log2_quant(ctx, dev(accp), G, H, N, N, ld, scale, codes, bits, s_log=float(s_log),
+                            bias=None if bias_a is None else dev(bias_a), mask=b.MASK_CAUSAL if causal else b.MASK_NONE)
+    got = codes.cpu().numpy()
+    assert_codes_close(got[:, :, :N], want, "softmax codes N=%d b=%d" % (N, bits))
+    assert np.all(got[:, :, N:] == 2 ** bits - 1)
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits_p,bits_v,causal", [(2, 3, 197, 64, 4, 4, False), (2, 2, 49, 32, 6, 6, False),
+                                                                 (1, 2, 257, 64, 4, 4, False), (1, 2, 600, 128, 8, 8, True),
+                                                                 (2, 2, 64, 64, 8, 8, False), (1, 1, 1, 32, 4, 8, False),
+                                                                 (1, 2, 300, 64, 4, 8, True)])
+def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
+    b, ctx = rq
+    print("case", batch, H, seq, dh, bits_p, bits_v, causal, flush=True)
+    g = np.random.default_rng(seq + dh + bits_p)
+    D = H * dh
+    ld = _ld(seq)
+    # codes with a realistic spread: most mass on large codes, a few small ones
+    A = orc.softmax_rows(g.normal(size=(batch * H, seq, seq)) * 3)
+    codes = orc.logsqrt2_quant_base2(A, 1.0, bits_p)
+    cp = np.full((batch * H, seq, ld), 3, np.uint8)      # padding holds a small code on purpose: it must be ignored
+    cp[:, :, :seq] = codes
+    qv = g.integers(0, 2 ** bits_v, size=(batch * seq, D))
+    z_v = int(g.integers(0, 2 ** bits_v))
+    offv = b.store_offset(bits_v, z_v)
+    qkv = np.zeros((batch * seq, 3 * D), np.int8)
+    qkv[:, 2 * D:] = (qv - offv).astype(np.int8)
+    s_log, s_v = np.float32(0.9), np.float32(0.043)
+    want = np.empty((batch * seq, D))
+    for bi in range(batch):
+        r = slice(bi * seq, (bi + 1) * seq)
+        for h in range(H):
+            want[r, h * dh:(h + 1) * dh] = orc.attn_pv(codes[bi * H + h], qv[r, h * dh:(h + 1) * dh], s_log, s_v, z_v, causal)
+    s_o = np.float32((want.max() - want.min()) / (2 ** bits_v - 1))
+    z_o = int(np.rint(-want.min() / np.float64(s_o)))
+    off_o = b.store_offset(bits_v, z_o)
+    qd = dev(qkv)
+    outf = torch.zeros((batch * seq, D), dtype=torch.float32, device="cuda")
+    outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
+    b.rq_attn_pv(ctx, dev(cp), ld, qd.data_ptr() + 2 * D, 3 * D, batch, H, seq, seq, dh, float(s_log), float(s_v), z_v, offv, bits_p,
+                 mask=b.MASK_CAUSAL if causal else b.MASK_NONE, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o,
+                 bits_o=bits_v)
+    assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-5)
+    assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits_v), "attn_pv codes")

@@ -1,0 +1,133 @@
+"""rq_qgemm (weight mode) against the oracle: accumulators bit-exact; float outputs within 1e-3;
+re-quantized codes equal except at ties."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import repquant_oracle as orc
+from tests.helpers import assert_codes_close, assert_float_close, dev, lin_to_device, random_linear
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rq():
+    from paper_2402_05628_amd import binding
+    return binding, binding.Context(0)
+
+
+def _act_codes(g, M, K, bits):
+    qa = g.integers(0, 2 ** bits, size=(M, K))
+    z_a = int(g.integers(0, 2 ** bits))
+    return qa, z_a
+
+
+@pytest.mark.parametrize("M,N,K", [(333, 192, 128), (128, 128, 64), (1000, 768, 768), (2049, 1536, 384), (77, 2304, 768),
+                                   (513, 260, 3072)])
+@pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4), (6, 6)])
+@pytest.mark.parametrize("tile", [1, 2])
+def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
+    b, ctx = rq
+    print("case", M, N, K, bits_a, bits_w, tile, flush=True)
+    b.set_gemm_tile(tile)
+    try:
+        g = np.random.default_rng(M + N + K + bits_a)
+        qa, z_a = _act_codes(g, M, K, bits_a)
+        lin = random_linear(g, N, K, bits_w)
+        want = orc.qlinear_acc(qa, z_a, lin["codes"], lin["z_w"])
+        a_off = b.store_offset(bits_a, z_a)
+        A = dev((qa - a_off).astype(np.int8))
+        rs = torch.empty(M, dtype=torch.int32, device="cuda")
+        b.rq_rowsum_i8(ctx, A, rs)
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        b.rq_qgemm(ctx, A, a_off, z_a, 0.01, lin_to_device(lin, bits_w), out_acc=acc, rowsum_a=rs)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
+    finally:
+        b.set_gemm_tile(0)
+
+
+def test_accumulator_extremes(rq):
+    """All-max codes against all-min weights at K = 11008: the largest magnitudes the int32 contract allows."""
+    b, ctx = rq
+    M, N, K = 130, 128, 11008
+    qa = np.full((M, K), 255)
+    lin = dict(codes=np.zeros((N, K), np.int64), s_w=np.full(N, 1e-3, np.float32), z_w=np.full(N, 255), bias=None)
+    lin["codes"][::2] = 255
+    lin["z_w"][::2] = 0
+    want = orc.qlinear_acc(qa, 0, lin["codes"], lin["z_w"])
+    a_off = b.store_offset(8, 0)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    acc = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+    b.rq_qgemm(ctx, A, a_off, 0, 0.01, lin_to_device(lin, 8), out_acc=acc, rowsum_a=rs)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
+    assert np.abs(want).max() == 255 * 255 * K
+
+
+@pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4)])
+def test_float_output_bias_residual(rq, bits_a, bits_w):
+    b, ctx = rq
+    M, N, K = 515, 384, 256
+    g = np.random.default_rng(11 + bits_a)
+    qa, z_a = _act_codes(g, M, K, bits_a)
+    lin = random_linear(g, N, K, bits_w)
+    res = g.normal(size=(M, N)).astype(np.float32) * 3
+    s_a = np.float32(0.037)
+    want = orc.qlinear(qa, s_a, z_a, lin) + res
+    a_off = b.store_offset(bits_a, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), residual=dev(res), out_f32=out, rowsum_a=rs)
+    assert_float_close(out.cpu().numpy(), want, "qgemm f32")
+
+
+@pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
+@pytest.mark.parametrize("act", ["none3", "gelu", "gated"])
+def test_requantized_output(rq, bits_a, bits_w, bits_o, act):
+    b, ctx = rq
+    M, K = 301, 256
+    N = 384 if act != "gated" else 512
+    g = np.random.default_rng(5 + bits_a + len(act))
+    qa, z_a = _act_codes(g, M, K, bits_a)
+    lin = random_linear(g, N, K, bits_w)
+    s_a = np.float32(1.5 / (np.sqrt(K) * (2 ** bits_a / 3.46) * (2 ** bits_w / 3.46) * 3e-3))   # y of order 1
+    y = orc.qlinear(qa, s_a, z_a, lin)
+    a_off = b.store_offset(bits_a, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    if act == "none3":
+        seg = N // 3
+        s_o, z_o, want = [], [], np.empty((M, N), np.int64)
+        for i in range(3):
+            part = y[:, i * seg:(i + 1) * seg]
+            s = np.float32((part.max() - part.min()) / (2 ** bits_o - 1))
+            z = int(np.rint(-part.min() / np.float64(s)))
+            s_o.append(float(s)); z_o.append(z)
+            want[:, i * seg:(i + 1) * seg] = orc.uniform_quant(part, s, z, bits_o)
+        off_o = [b.store_offset(bits_o, z) for z in z_o]
+        out = torch.zeros((M, N), dtype=torch.int8, device="cuda")
+        b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), out_q=out, bits_o=bits_o, s_o=s_o, z_o=z_o,
+                   off_o=off_o, seg_len=seg, rowsum_a=rs)
+        got = out.cpu().numpy().astype(np.int64)
+        for i in range(3):
+            got[:, i * seg:(i + 1) * seg] += off_o[i]
+    else:
+        Dm = N // 2
+        hid = orc.mlp_activation(y, orc.ACT_GELU if act == "gelu" else orc.ACT_SILU_GATED, Dm)
+        s = np.float32((hid.max() - hid.min()) / (2 ** bits_o - 1))
+        z = int(np.rint(-hid.min() / np.float64(s)))
+        want = orc.uniform_quant(hid, s, z, bits_o)
+        off = b.store_offset(bits_o, z)
+        out = torch.zeros(want.shape, dtype=torch.int8, device="cuda")
+        outf = torch.zeros(want.shape, dtype=torch.float32, device="cuda")
+        b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w, Dm if act == "gated" else 0),
+                   act=b.ACT_GELU if act == "gelu" else b.ACT_SILU_GATED, out_q=out, out_f32=outf, bits_o=bits_o, s_o=[float(s)],
+                   z_o=[z], off_o=[off], seg_len=want.shape[1], rowsum_a=rs)
+        assert_float_close(outf.cpu().numpy(), hid, "activation " + act)
+        got = out.cpu().numpy().astype(np.int64) + off
+    assert_codes_close(got, want, "requant %s b%d" % (act, bits_o))
