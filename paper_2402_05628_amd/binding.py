@@ -379,3 +379,52 @@ def set_gemm_tile(tile: int):
     rc = _rq_set_tile(tile)
     if rc != RQ_OK:
         raise RqError(rc, _rq_last_error(None).decode())
+
+
+_rq_cal_ws = _sig("rq_block_calibrate_workspace_bytes", C.c_size_t, [C.POINTER(BlockRaw), i64, i64])
+_rq_calibrate = _sig("rq_block_calibrate", i32, [vp, C.POINTER(BlockRaw), vp, i64, i64, C.POINTER(BlockParams), vp, C.c_size_t])
+
+
+def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: int) -> "Block":
+    """Allocates the quantized-parameter arrays, runs rq_block_calibrate on the batch x and returns a Block.
+    raw: dict of device float32 tensors named as in synth.make_block (None allowed where the C struct allows NULL)."""
+    D, Dm = cfg.D, cfg.Dm
+    gated = cfg.act != 0
+    n1 = 2 * Dm if gated else Dm
+    dev = x.device
+    br = BlockRaw()
+    br.D, br.H, br.Dm, br.norm_kind, br.mask = cfg.D, cfg.H, cfg.Dm, cfg.norm, cfg.mask
+    br.act = ACT_SILU_GATED if gated else ACT_GELU
+    br.bits_w, br.bits_a, br.bits_p, br.eps, br.s_log = cfg.bits_w, cfg.bits_a, cfg.bits_p, cfg.eps, 1.0
+    for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta", "w_qkv", "b_qkv", "w_proj", "b_proj", "w_fc1", "b_fc1",
+              "w_fc2", "b_fc2", "ln1_clip_up", "ln1_clip_lo", "ln2_clip_up", "ln2_clip_lo", "rel_bias"):
+        setattr(br, k, _p(raw.get(k)))
+    fmt = weight_format(cfg.bits_w)
+
+    def lin(N, K):
+        w = (torch.empty((N, K // 2), dtype=torch.uint8, device=dev) if fmt == W_U4
+             else torch.empty((N, K), dtype=torch.int8, device=dev))
+        return dict(w=w, s_w=torch.empty(N, dtype=torch.float32, device=dev), z_w=torch.empty(N, dtype=torch.int32, device=dev),
+                    colsum_w=torch.empty(N, dtype=torch.int32, device=dev), bias=torch.empty(N, dtype=torch.float32, device=dev),
+                    N=N, K=K, bits=cfg.bits_w, format=fmt)
+
+    P = dict(qkv=lin(3 * D, D), proj=lin(D, D), fc1=lin(n1, D), fc2=lin(D, Dm), rel_bias=raw.get("rel_bias"))
+    for k in ("ln1", "ln2"):
+        P[k] = dict(gamma_t=torch.empty(D, dtype=torch.float32, device=dev), beta_t=torch.empty(D, dtype=torch.float32, device=dev),
+                    s=1.0, z=0)
+    for k in ("s_q", "s_k", "s_v", "s_o", "s_h", "s_log"):
+        P[k] = 1.0
+    for k in ("z_q", "z_k", "z_v", "z_o", "z_h"):
+        P[k] = 0
+    blk = Block(ctx, cfg, P)
+    n = int(_rq_cal_ws(C.byref(br), batch, seq))
+    ws = torch.empty(n + 256, dtype=torch.uint8, device=dev)
+    ptr = ws.data_ptr() + (-ws.data_ptr()) % 256
+    ctx.check(_rq_calibrate(ctx.handle, C.byref(br), _p(x), batch, seq, C.byref(blk.bp), ptr, n))
+    bp = blk.bp
+    for k in ("ln1", "ln2"):
+        P[k]["s"], P[k]["z"] = getattr(bp, k + "_s"), getattr(bp, k + "_z")
+    for k in ("s_q", "s_k", "s_v", "s_o", "s_h", "s_log", "z_q", "z_k", "z_v", "z_o", "z_h"):
+        P[k] = getattr(bp, k)
+    del ws
+    return blk

@@ -248,3 +248,238 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
 }
 
 }  // extern "C"
+
+// ---- rq_block_calibrate ---------------------------------------------------------------------------------------
+// Algorithm 1 restricted to one block and to min/max bounds: activation quantizer -> scale reparameterization ->
+// weight quantization, layer by layer, each layer fed by the already-quantized layers before it.  Every tensor
+// operation is one of the library's kernels; the host only turns min/max pairs into (s, z) scalars.
+namespace {
+
+struct CalPlan {
+  Plan fwd;
+  size_t o_cmin, o_cmax, o_sch, o_zch, o_wt, o_bt, o_f32, o_scal, total;
+};
+
+CalPlan make_cal_plan(const rq_block_raw* raw, int64_t batch, int64_t seq) {
+  rq_block_params tmp;
+  std::memset(&tmp, 0, sizeof tmp);
+  tmp.D = raw->D; tmp.H = raw->H; tmp.Dm = raw->Dm;
+  CalPlan c;
+  c.fwd = make_plan(&tmp, batch, seq);
+  const int D = raw->D, Dm = raw->Dm;
+  const int n1 = raw->act == RQ_ACT_SILU_GATED ? 2 * Dm : Dm;
+  const int nmax = 3 * D > n1 ? 3 * D : n1;
+  size_t o = c.fwd.total;
+  c.o_cmin = o; o += up((size_t)D * 8);
+  c.o_cmax = o; o += up((size_t)D * 8);
+  c.o_sch = o; o += up((size_t)D * 4);
+  c.o_zch = o; o += up((size_t)D * 4);
+  c.o_wt = o; o += up((size_t)nmax * D * 4);
+  c.o_bt = o; o += up((size_t)nmax * 4);
+  c.o_f32 = o; o += up((size_t)c.fwd.T * nmax * 4);
+  c.o_scal = o; o += up(256);
+  c.total = o;
+  return c;
+}
+
+void qparams_from_minmax(double lo, double hi, int bits, float* s, int32_t* z) {
+  *s = (float)((hi - lo) / (double)((1 << bits) - 1));
+  *z = (int32_t)std::nearbyint(-lo / (double)*s);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rq_block_calibrate_workspace_bytes(const rq_block_raw* raw, int64_t batch, int64_t seq) {
+  if (!raw || batch <= 0 || seq <= 0 || raw->D <= 0 || raw->H <= 0 || raw->Dm <= 0) return 0;
+  return make_cal_plan(raw, batch, seq).total;
+}
+
+rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* x, int64_t batch, int64_t seq,
+                             rq_block_params* out, void* workspace, size_t workspace_bytes) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_block_calibrate: ctx is NULL");
+  RQ_REQUIRE(raw && x && out && workspace, RQ_ERR_INVALID_ARG, "rq_block_calibrate: raw, x, out, workspace must be non-NULL");
+  RQ_REQUIRE(batch > 0 && seq > 0, RQ_ERR_SHAPE, "rq_block_calibrate: batch, seq must be > 0");
+  RQ_REQUIRE(raw->D > 0 && raw->H > 0 && raw->Dm > 0 && raw->D % raw->H == 0, RQ_ERR_SHAPE, "rq_block_calibrate: D, H, Dm");
+  RQ_REQUIRE(raw->bits_w == 4 || (raw->bits_w >= 2 && raw->bits_w <= 8), RQ_ERR_INVALID_ARG, "rq_block_calibrate: bits_w");
+  RQ_REQUIRE(raw->ln1_gamma && raw->ln2_gamma && raw->w_qkv && raw->w_proj && raw->w_fc1 && raw->w_fc2, RQ_ERR_INVALID_ARG,
+             "rq_block_calibrate: gammas and weights must be non-NULL");
+  RQ_REQUIRE(raw->s_log > 0.f, RQ_ERR_INVALID_ARG, "rq_block_calibrate: s_log must be > 0");
+  RQ_REQUIRE(out->ln1_gamma_t && out->ln1_beta_t && out->ln2_gamma_t && out->ln2_beta_t, RQ_ERR_INVALID_ARG,
+             "rq_block_calibrate: out->ln*_gamma_t / beta_t must point to caller-allocated [D] arrays");
+  const rq_qlinear* lins[4] = {&out->qkv, &out->proj, &out->fc1, &out->fc2};
+  for (const rq_qlinear* l : lins)
+    RQ_REQUIRE(l->w && l->s_w && l->z_w && l->colsum_w && l->bias, RQ_ERR_INVALID_ARG,
+               "rq_block_calibrate: every rq_qlinear of out needs w, s_w, z_w, colsum_w, bias allocated by the caller");
+  RQ_REQUIRE(rq_aligned(workspace, ALIGN), RQ_ERR_INVALID_ARG, "rq_block_calibrate: workspace needs 256-byte alignment");
+  const CalPlan cp = make_cal_plan(raw, batch, seq);
+  RQ_REQUIRE(workspace_bytes >= cp.total, RQ_ERR_WORKSPACE, "rq_block_calibrate: workspace has %zu bytes, %zu needed",
+             workspace_bytes, cp.total);
+  RQ_NEED_DEVICE();
+
+  const int D = raw->D, H = raw->H, Dm = raw->Dm, dh = D / H;
+  const bool gated = raw->act == RQ_ACT_SILU_GATED;
+  const int n1 = gated ? 2 * Dm : Dm;
+  const int ba = raw->bits_a, bw = raw->bits_w;
+  const int wfmt = bw == 4 ? RQ_W_U4 : (bw == 8 ? RQ_W_I8_CENTERED : RQ_W_I8_BAKED);
+  const int64_t T = batch * seq;
+  char* ws = static_cast<char*>(workspace);
+  double* cmin = reinterpret_cast<double*>(ws + cp.o_cmin);
+  double* cmax = reinterpret_cast<double*>(ws + cp.o_cmax);
+  float* s_ch = reinterpret_cast<float*>(ws + cp.o_sch);
+  int32_t* z_ch = reinterpret_cast<int32_t*>(ws + cp.o_zch);
+  float* wt = reinterpret_cast<float*>(ws + cp.o_wt);
+  float* bt = reinterpret_cast<float*>(ws + cp.o_bt);
+  float* f32 = reinterpret_cast<float*>(ws + cp.o_f32);
+  char* scal = ws + cp.o_scal;   // device scalars: s_tilde (float), z_tilde (int32), min/max (2 doubles at +16)
+  const Plan& pl = cp.fwd;
+  int8_t* a = reinterpret_cast<int8_t*>(ws + pl.o_a);
+  int32_t* rowsum = reinterpret_cast<int32_t*>(ws + pl.o_rowsum);
+  int8_t* qkv = reinterpret_cast<int8_t*>(ws + pl.o_qkv);
+  int32_t* acc = reinterpret_cast<int32_t*>(ws + pl.o_acc);
+  uint8_t* codes = reinterpret_cast<uint8_t*>(ws + pl.o_codes);
+  int8_t* o = reinterpret_cast<int8_t*>(ws + pl.o_o);
+  float* xbar = reinterpret_cast<float*>(ws + pl.o_xbar);
+  rq_status st;
+
+  out->D = D; out->H = H; out->Dm = Dm; out->norm_kind = raw->norm_kind; out->act = raw->act; out->mask = raw->mask;
+  out->bits_a = ba; out->bits_p = raw->bits_p; out->eps = raw->eps; out->rel_bias = raw->rel_bias; out->s_log = raw->s_log;
+
+  auto minmax_host = [&](const float* v, int64_t rows, int64_t cols, int64_t ld, double* lo, double* hi) -> rq_status {
+    double* d2 = reinterpret_cast<double*>(scal + 16);
+    rq_status s2 = rq_minmax_f32(ctx, v, rows, cols, ld, d2);
+    if (s2 != RQ_OK) return s2;
+    double h2[2];
+    RQ_HIP(hipMemcpyAsync(h2, d2, 16, hipMemcpyDeviceToHost, ctx->stream));
+    RQ_HIP(hipStreamSynchronize(ctx->stream));
+    *lo = h2[0]; *hi = h2[1];
+    return RQ_OK;
+  };
+  auto quant_linear = [&](rq_qlinear* l, const float* W, const float* b, int N, int K, int gate_rows) -> rq_status {
+    rq_wq_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.N = N; d.K = K; d.bits = bw; d.format = wfmt; d.gate_up_rows = gate_rows; d.W = W; d.bias = b;
+    d.w_out = const_cast<void*>(l->w); d.s_w = const_cast<float*>(l->s_w); d.z_w = const_cast<int32_t*>(l->z_w);
+    d.colsum_w = const_cast<int32_t*>(l->colsum_w); d.bias_out = const_cast<float*>(l->bias);
+    l->N = N; l->K = K; l->bits = bw; l->format = wfmt;
+    return rq_weight_quant_pack(ctx, &d);
+  };
+  // LayerNorm activation: channel-wise (s, z) -> fold into the affine and the next Linear -> quantize that Linear
+  auto fold_ln = [&](const float* xin, const float* gamma, const float* beta, const float* cu, const float* cl, const float* W,
+                     const float* b, int N, int gate_rows, float* gamma_t, float* beta_t, float* s_out, int32_t* z_out,
+                     rq_qlinear* lin) -> rq_status {
+    rq_status s2 = rq_ln_channel_minmax(ctx, xin, T, D, D, raw->norm_kind, raw->eps, gamma, beta, cmin, cmax);
+    if (s2 != RQ_OK) return s2;
+    if ((s2 = rq_launch_channel_qparams(ctx, cmin, cmax, cu, cl, D, ba, s_ch, z_ch)) != RQ_OK) return s2;
+    rq_fold_desc f;
+    std::memset(&f, 0, sizeof f);
+    f.D = D; f.D_out = N; f.s_ch = s_ch; f.z_ch = z_ch; f.gamma = gamma; f.beta = beta; f.W = W; f.b = b;
+    f.s_tilde = reinterpret_cast<float*>(scal); f.z_tilde = reinterpret_cast<int32_t*>(scal + 4);
+    f.gamma_t = gamma_t; f.beta_t = beta_t; f.W_t = wt; f.b_t = bt;
+    if ((s2 = rq_reparam_fold(ctx, &f)) != RQ_OK) return s2;
+    char h8[8];
+    RQ_HIP(hipMemcpyAsync(h8, scal, 8, hipMemcpyDeviceToHost, ctx->stream));
+    RQ_HIP(hipStreamSynchronize(ctx->stream));
+    std::memcpy(s_out, h8, 4);
+    std::memcpy(z_out, h8 + 4, 4);
+    return quant_linear(lin, wt, bt, N, D, gate_rows);
+  };
+  auto ln_q = [&](const float* xin, const float* gt, const float* btl, float s, int z, const rq_qlinear& next) -> rq_status {
+    rq_ln_desc d;
+    std::memset(&d, 0, sizeof d);
+    d.T = T; d.D = D; d.norm_kind = raw->norm_kind; d.eps = raw->eps; d.x = xin; d.ldx = D; d.gamma_t = gt; d.beta_t = btl;
+    d.s_tilde = s; d.z_tilde = z; d.bits = ba; d.store_off = rq_store_offset(ba, z); d.q = a; d.ldq = D;
+    d.rowsum = next.format == RQ_W_I8_CENTERED ? rowsum : nullptr;
+    return rq_ln_quant(ctx, &d);
+  };
+
+  // ---- LN1 -> QKV ----
+  if ((st = fold_ln(x, raw->ln1_gamma, raw->ln1_beta, raw->ln1_clip_up, raw->ln1_clip_lo, raw->w_qkv, raw->b_qkv, 3 * D, 0,
+                    const_cast<float*>(out->ln1_gamma_t), const_cast<float*>(out->ln1_beta_t), &out->ln1_s, &out->ln1_z,
+                    &out->qkv)) != RQ_OK)
+    return st;
+  if ((st = ln_q(x, out->ln1_gamma_t, out->ln1_beta_t, out->ln1_s, out->ln1_z, out->qkv)) != RQ_OK) return st;
+  const int off1 = rq_store_offset(ba, out->ln1_z);
+  rq_gemm_desc g;
+  fill_linear(g, out->qkv, a, T, D, out->ln1_s, out->ln1_z, off1, rowsum);
+  g.out_f32 = f32; g.ldf = 3 * D;
+  if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
+  float* s3[3] = {&out->s_q, &out->s_k, &out->s_v};
+  int32_t* z3[3] = {&out->z_q, &out->z_k, &out->z_v};
+  for (int i = 0; i < 3; ++i) {
+    double lo, hi;
+    if ((st = minmax_host(f32 + (int64_t)i * D, T, D, 3 * D, &lo, &hi)) != RQ_OK) return st;
+    qparams_from_minmax(lo, hi, ba, s3[i], z3[i]);
+  }
+  const int offq = rq_store_offset(ba, out->z_q), offk = rq_store_offset(ba, out->z_k), offv = rq_store_offset(ba, out->z_v);
+  g.out_f32 = nullptr; g.out_q = qkv; g.ldq = 3 * D; g.bits_o = ba; g.n_seg = 3; g.seg_len = D;
+  g.s_o[0] = out->s_q; g.s_o[1] = out->s_k; g.s_o[2] = out->s_v;
+  g.z_o[0] = out->z_q; g.z_o[1] = out->z_k; g.z_o[2] = out->z_v;
+  g.off_o[0] = offq; g.off_o[1] = offk; g.off_o[2] = offv;
+  if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
+
+  // ---- attention: first pass float output for the static scale of its activation, second pass quantized ----
+  int offo = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
+      const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
+      const int8_t* qkv_c = qkv + b0 * seq * 3 * D;
+      rq_gemm_desc q;
+      std::memset(&q, 0, sizeof q);
+      q.M = seq; q.N = (int)seq; q.K = dh; q.A = qkv_c; q.lda = 3 * D; q.a_off = offq; q.z_a = out->z_q; q.s_a = out->s_q;
+      q.B = qkv_c + D; q.ldb = 3 * D; q.b_format = RQ_B_ACT_I8; q.b_off = offk; q.z_b_scalar = out->z_k;
+      q.out_acc = acc; q.ldacc = pl.ld; q.acc_stride_group = seq * pl.ld; q.batch_outer = nb; q.batch_inner = H;
+      q.a_stride_outer = seq * 3 * D; q.a_stride_inner = dh; q.b_stride_outer = seq * 3 * D; q.b_stride_inner = dh;
+      q.causal = raw->mask == RQ_MASK_CAUSAL;
+      if ((st = rq_qgemm(ctx, &q)) != RQ_OK) return st;
+      rq_softmax_desc sd;
+      std::memset(&sd, 0, sizeof sd);
+      sd.G = nb * H; sd.H = H; sd.Nq = (int)seq; sd.Nk = (int)seq; sd.ld = pl.ld; sd.acc = acc;
+      sd.logit_scale = (double)out->s_q * (double)out->s_k / std::sqrt((double)dh);
+      sd.bias = raw->rel_bias; sd.mask = raw->mask; sd.s_log = raw->s_log; sd.bits = raw->bits_p; sd.codes = codes;
+      if ((st = rq_softmax_log2_quant(ctx, &sd)) != RQ_OK) return st;
+      rq_pv_desc pd;
+      std::memset(&pd, 0, sizeof pd);
+      pd.batch = nb; pd.H = H; pd.Nq = (int)seq; pd.Nk = (int)seq; pd.d_head = dh; pd.ld = pl.ld; pd.codes = codes;
+      pd.V = qkv_c + 2 * D; pd.ldv = 3 * D; pd.s_log = raw->s_log; pd.s_v = out->s_v; pd.z_v = out->z_v; pd.v_off = offv;
+      pd.bits_p = raw->bits_p; pd.mask = raw->mask;
+      if (pass == 0) {
+        pd.out_f32 = f32 + b0 * seq * D; pd.ldf = D;
+      } else {
+        pd.out_q = o + b0 * seq * D; pd.ldq = D; pd.s_o = out->s_o; pd.z_o = out->z_o; pd.off_o = offo; pd.bits_o = ba;
+      }
+      if ((st = rq_attn_pv(ctx, &pd)) != RQ_OK) return st;
+    }
+    if (pass == 0) {
+      double lo, hi;
+      if ((st = minmax_host(f32, T, D, D, &lo, &hi)) != RQ_OK) return st;
+      qparams_from_minmax(lo, hi, ba, &out->s_o, &out->z_o);
+      offo = rq_store_offset(ba, out->z_o);
+    }
+  }
+  // ---- proj (plain channel-wise weight quantization), residual ----
+  if ((st = quant_linear(&out->proj, raw->w_proj, raw->b_proj, D, D, 0)) != RQ_OK) return st;
+  if (out->proj.format == RQ_W_I8_CENTERED && (st = rq_rowsum_i8(ctx, o, T, D, D, rowsum)) != RQ_OK) return st;
+  fill_linear(g, out->proj, o, T, D, out->s_o, out->z_o, offo, rowsum);
+  g.residual = x; g.ldr = D; g.out_f32 = xbar; g.ldf = D;
+  if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
+  // ---- LN2 -> FC1 ----
+  if ((st = fold_ln(xbar, raw->ln2_gamma, raw->ln2_beta, raw->ln2_clip_up, raw->ln2_clip_lo, raw->w_fc1, raw->b_fc1, n1,
+                    gated ? Dm : 0, const_cast<float*>(out->ln2_gamma_t), const_cast<float*>(out->ln2_beta_t), &out->ln2_s,
+                    &out->ln2_z, &out->fc1)) != RQ_OK)
+    return st;
+  if ((st = ln_q(xbar, out->ln2_gamma_t, out->ln2_beta_t, out->ln2_s, out->ln2_z, out->fc1)) != RQ_OK) return st;
+  fill_linear(g, out->fc1, a, T, D, out->ln2_s, out->ln2_z, rq_store_offset(ba, out->ln2_z), rowsum);
+  g.act = raw->act; g.out_f32 = f32; g.ldf = Dm;
+  if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
+  {
+    double lo, hi;
+    if ((st = minmax_host(f32, T, Dm, Dm, &lo, &hi)) != RQ_OK) return st;
+    qparams_from_minmax(lo, hi, ba, &out->s_h, &out->z_h);
+  }
+  // ---- FC2 ----
+  return quant_linear(&out->fc2, raw->w_fc2, raw->b_fc2, D, Dm, 0);
+}
+
+}  // extern "C"

@@ -266,7 +266,28 @@ __global__ __launch_bounds__(256) void minmax_f32_kernel(const float* __restrict
   }
 }
 
+// Channel-wise (s, z) from the channel extremes, with the optional dual-clipping contraction factors
+// (Eqs. for X'_up, X'_low, then the Eq. for s and z per channel); the scale is stored float32 and z follows it.
+__global__ void channel_qparams_kernel(const double* cmin, const double* cmax, const float* clip_up, const float* clip_lo,
+                                       int D, int bits, float* s_ch, int32_t* z_ch) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= D) return;
+  const double up = cmax[i] * (clip_up ? (double)clip_up[i] : 1.0);
+  const double lo = cmin[i] * (clip_lo ? (double)clip_lo[i] : 1.0);
+  const float s = (float)((up - lo) / (double)((1 << bits) - 1));
+  s_ch[i] = s;
+  z_ch[i] = (int)rint(-lo / (double)s);
+}
+
 }  // namespace
+
+rq_status rq_launch_channel_qparams(rq_ctx* ctx, const double* cmin, const double* cmax, const float* clip_up,
+                                    const float* clip_lo, int D, int bits, float* s_ch, int32_t* z_ch) {
+  hipLaunchKernelGGL(channel_qparams_kernel, dim3((D + 255) / 256), dim3(256), 0, ctx->stream, cmin, cmax, clip_up, clip_lo, D, bits,
+                     s_ch, z_ch);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}
 
 rq_status rq_launch_fold(rq_ctx* ctx, const rq_fold_desc* d) {
   int blocks = d->D_out < 1 ? 1 : d->D_out;

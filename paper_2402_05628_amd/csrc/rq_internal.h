@@ -59,6 +59,9 @@ rq_status rq_launch_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, in
                                       double eps, const float* gamma, const float* beta, double* cmin, double* cmax);
 rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, double* out2);
 
+rq_status rq_launch_channel_qparams(rq_ctx* ctx, const double* cmin, const double* cmax, const float* clip_up,
+                                    const float* clip_lo, int D, int bits, float* s_ch, int32_t* z_ch);
+
 // profiling hooks used by rq_block_forward
 void rq_prof_begin(rq_ctx* ctx, int step);
 void rq_prof_end(rq_ctx* ctx);

@@ -55,3 +55,46 @@ def test_block_forward_matches_oracle(rq, name, chunk_mb):
     frac = float(np.mean(np.abs(got - want) > bar))
     print("  elements beyond the element-wise bar: %.3g" % frac, flush=True)
     assert frac < 0.02
+
+
+def _raw_to_device(raw):
+    return {k: (None if v is None else dev(v)) for k, v in raw.items() if k != "x"}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_block_calibrate_matches_oracle(rq, name):
+    """The library's own calibration (min/max bounds, fold, weight packing) reproduces the oracle's parameters."""
+    b, ctx = rq
+    cfg = SMALL[name]
+    print("case", name, flush=True)
+    raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
+    P = orc.calibrate_block(raw, cfg_dict(cfg))
+    x = dev(raw["x"])
+    blk = b.calibrate_block(ctx, cfg, _raw_to_device(raw), x, cfg.batch, cfg.seq)
+    Q = blk.P
+    # the LayerNorm folds see the same float inputs on both sides: equal up to the last float32 place
+    for k in ("ln1",):
+        assert Q[k]["z"] == P[k]["z"]
+        assert abs(Q[k]["s"] - float(P[k]["s"])) <= 1e-6 * float(P[k]["s"])
+        assert np.allclose(Q[k]["gamma_t"].cpu().numpy(), P[k]["gamma_t"], rtol=1e-6, atol=0)
+        assert np.allclose(Q[k]["beta_t"].cpu().numpy(), P[k]["beta_t"], rtol=1e-5, atol=1e-6)
+    gated = cfg.act == synth.ACT_SILU_GATED
+    from tests.helpers import lin_to_device
+    want = lin_to_device(P["qkv"], cfg.bits_w)
+    assert np.mean(Q["qkv"]["w"].cpu().numpy() != want["w"].cpu().numpy()) < 1e-4
+    assert np.allclose(Q["qkv"]["s_w"].cpu().numpy(), want["s_w"].cpu().numpy(), rtol=1e-6)
+    # static scales downstream depend on min/max of tensors that may contain a few tie flips: tight but not bit-tight
+    for k in ("s_q", "s_k", "s_v", "s_o", "s_h"):
+        assert abs(Q[k] - float(P[k])) <= 2e-3 * float(P[k]), (k, Q[k], float(P[k]))
+    for k in ("z_q", "z_k", "z_v", "z_o", "z_h"):
+        assert abs(Q[k] - P[k]) <= 1, (k, Q[k], P[k])
+    assert abs(Q["ln2"]["z"] - P["ln2"]["z"]) <= 1
+    assert abs(Q["ln2"]["s"] - float(P["ln2"]["s"])) <= 1e-3 * float(P["ln2"]["s"])
+    # and the block it produces tracks the oracle block built from the oracle's own calibration
+    want_y = orc.block_forward(P, raw["x"])
+    y = torch.zeros_like(x)
+    blk.forward(x, y, cfg.batch, cfg.seq)
+    got = y.cpu().numpy().astype(np.float64)
+    rel = np.abs(got - want_y).max() / np.abs(want_y).max()
+    print("  calibrated-on-GPU block vs oracle block: max|d|/max|ref| = %.3g" % rel, flush=True)
+    assert rel < 2e-2
