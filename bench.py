@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the reparameterized quantized transformer block on one MI355X.
+
+A step is one rq_block_forward over one synthetic batch (all kernels of the hot path: LN-quant, QKV GEMM,
+Q.K^T, softmax-log2, P.V, proj GEMM, LN-quant, FC1 GEMM, FC2 GEMM), inputs and parameters resident in HBM.
+Prints ONE JSON line: tokens/s, the roofline of the dominant kernel (measured live with HIP events on the
+library's stream in a second, instrumented pass of the same length) and the CPU oracle timed on a bounded
+sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
+
+
+def algorithmic_work(cfg, ld):
+    """Per-step algorithmic ops / bytes of every kernel family ('Measurement')."""
+    T, D, Dm, H, N = cfg.tokens, cfg.D, cfg.Dm, cfg.H, cfg.seq
+    G = cfg.batch * H
+    dh = D // H
+    n1 = 2 * Dm if cfg.act != 0 else Dm
+    wb = cfg.bits_w / 8.0 if cfg.bits_w == 4 else 1.0
+    causal = cfg.mask != 0
+    nn = N * (N + 1) // 2 if causal else N * N
+    gemm = {
+        "qkv": (T, 3 * D, D, 1), "proj": (T, D, D, 4), "fc1": (T, n1, D, 1), "fc2": (T, D, Dm, 4),
+    }
+    w = {}
+    for k, (M, Nn, K, ob) in gemm.items():
+        n_out = Nn // 2 if (k == "fc1" and cfg.act != 0) else Nn
+        w[k] = dict(ops=2.0 * M * Nn * K, bytes=M * K + Nn * K * wb + M * n_out * ob + (M * n_out * 4 if ob == 4 else 0))
+    w["ln1"] = w["ln2"] = dict(ops=0.0, bytes=5.0 * T * D)
+    w["qk"] = dict(ops=2.0 * G * nn * dh, bytes=G * (2 * N * dh + 4.0 * nn))
+    w["softmax"] = dict(ops=0.0, bytes=5.0 * G * nn)
+    w["pv"] = dict(ops=2.0 * G * nn * dh, bytes=G * (1.0 * nn + N * dh) + T * D)
+    return w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="index into the synthetic workloads (default: ViT-B W4/A4)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch of the workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-mb", type=int, default=0)
+    ap.add_argument("--tile", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every box here has one); --gpus %d is not supported. "
+              "DESIGN.md describes how the path would shard." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_05628_amd import binding as rq
+    from paper_2402_05628_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    if args.batch:
+        cfg = cfg.with_batch(args.batch)
+    if args.chunk_mb:
+        rq.set_attn_chunk_bytes(args.chunk_mb << 20)
+    if args.tile:
+        rq.set_gemm_tile(args.tile)
+    torch.cuda.set_device(0)
+    ctx = rq.Context(0)
+    raw = synth.make_block(cfg, args.config, 0)
+    x = torch.from_numpy(raw["x"]).cuda()
+    rawd = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in raw.items() if k != "x"}
+    blk = rq.calibrate_block(ctx, cfg, rawd, x, cfg.batch, cfg.seq)       # untimed preparation, on the GPU
+    y = torch.empty_like(x)
+
+    for _ in range(args.warmup):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
+
+    # second pass of the same length with HIP events around every kernel launch (on the library's stream)
+    rq.profile_enable(ctx, True)
+    rq.profile_reset(ctx)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    prof = rq.profile_read(ctx)
+    t3 = time.perf_counter()
+    rq.profile_enable(ctx, False)
+    ld = (cfg.seq + 15) // 16 * 16
+    work = algorithmic_work(cfg, ld)
+    kern = {}
+    for name, (ms, n) in prof.items():
+        if n == 0 or name not in work:
+            continue
+        per_step_ms = ms / args.steps
+        kern[name] = dict(ms_per_step=per_step_ms, launches_per_step=n / args.steps,
+                          tops=work[name]["ops"] / (per_step_ms * 1e-3) / 1e12,
+                          gbs=work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9)
+    # dominant kernel: the weight-mode int8 MFMA GEMM (four launches per step, one kernel family)
+    gemm_ms = sum(kern[k]["ms_per_step"] for k in ("qkv", "proj", "fc1", "fc2"))
+    gemm_ops = sum(work[k]["ops"] for k in ("qkv", "proj", "fc1", "fc2"))
+    other = {k: v["ms_per_step"] for k, v in kern.items() if k not in ("qkv", "proj", "fc1", "fc2")}
+    achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="qgemm_kernel (qkv+proj+fc1+fc2)", achieved=achieved, peak=PEAK_INT8_TOPS,
+                    unit="TFLOP/s", frac=achieved / PEAK_INT8_TOPS, traffic=None,
+                    avg_launch_ms=gemm_ms / 4.0, ops_per_launch=gemm_ops / 4.0,
+                    share_of_step=gemm_ms / sum(v["ms_per_step"] for v in kern.values()))
+    hbm = {}
+    for k in ("ln1", "ln2", "softmax"):
+        if k in kern:
+            hbm[k] = dict(achieved=kern[k]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=kern[k]["gbs"] / PEAK_HBM_GBS,
+                          ms_per_step=kern[k]["ms_per_step"])
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import repquant_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        cal_cfg = cfg.with_batch(min(cfg.batch, 4))
+        run_cfg = cfg.with_batch(min(cfg.batch, 32 if cfg.seq <= 512 else 1))
+        raw_c = synth.make_block(cal_cfg, args.config, 1)
+        P = orc.calibrate_block(raw_c, dataclasses.asdict(cal_cfg))
+        P["cfg"] = dataclasses.asdict(run_cfg)
+        xs = synth.make_block(run_cfg, args.config, 2)["x"]
+        c0 = time.perf_counter()
+        orc.block_forward(P, xs)
+        c1 = time.perf_counter()
+        cpu = dict(value=run_cfg.tokens / (c1 - c0), unit="tokens/s", cores=cores, kind="oracle",
+                   sample="%d of %d sequences of the same workload (%d tokens), oracle calibrated on %d sequences; %.1f s"
+                          % (run_cfg.batch, cfg.batch, run_cfg.tokens, cal_cfg.batch, c1 - c0))
+
+    out = dict(metric="quantized-block tokens/s on 1 MI355X", value=tokens_per_s, unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="int8", data="synthetic",
+               config=dict(workload=cfg.name, batch=cfg.batch, seq=cfg.seq, hidden=cfg.D, heads=cfg.H, mlp=cfg.Dm,
+                           bits_w=cfg.bits_w, bits_a=cfg.bits_a, bits_softmax=cfg.bits_p, tokens=cfg.tokens),
+               roofline=roofline, hbm_kernels=hbm,
+               kernels_ms_per_step={k: round(v["ms_per_step"], 5) for k, v in kern.items()},
+               ms_per_step_instrumented=(t3 - t2) * 1e3 / args.steps, cpu_baseline=cpu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
