@@ -213,7 +213,8 @@ typedef struct {
   int32_t causal;
 } rq_gemm_desc;
 rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
-/* Tuning knob (process-wide): output tile of the weight-mode kernel. 0 = choose by shape, 1 = 128x128, 2 = 256x128. */
+/* Tuning knob (process-wide): kernel of the weight mode. 0 = choose by shape (the pipelined 256x128 kernel whenever
+ * N % 32 == 0), 1 = simple 128x128, 2 = simple 256x128, 3 = pipelined 256x128. */
 rq_status rq_set_gemm_tile(int32_t tile);
 
 /* ---- rq_softmax_log2_quant --------------------------------------------------------------------------

@@ -1,0 +1,187 @@
+// Device code shared by the translation units of the weight-mode integer GEMM (rq_qgemm).
+#pragma once
+
+#include "rq_internal.h"
+
+namespace rqg {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct GemmParams {
+  int64_t M;
+  int N, K;
+  const int8_t* A;
+  int64_t lda;
+  const uint8_t* B;
+  int64_t ldb;
+  const float* s_b;
+  const int32_t* z_b;
+  const int32_t* colsum_b;
+  const int32_t* rowsum_a;
+  const float* bias;
+  float s_a;
+  int da;        // a_off - z_a
+  int centered;  // weights stored code - 128: needs (128 - z_b[n]) * rowsum_a[m]
+  int act;
+  const float* residual;
+  int64_t ldr;
+  int32_t* out_acc;
+  int64_t ldacc;
+  float* out_f32;
+  int64_t ldf;
+  int8_t* out_q;
+  int64_t ldq;
+  int n_seg, seg_len;
+  float inv_so[4];
+  float zo[4];   // z_o - off_o
+  float zcode[4];   // z_o
+  float qmaxf;
+  int off4[4];   // off_o replicated in the four bytes
+  int lo[4], hi[4];
+  int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ int swz(int row, int c) {
+  return (row >> 1) * 128 + (((((row & 1) << 2) | c) ^ ((row >> 1) & 7)) << 4);
+}
+
+// erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7), enough for
+// 8-bit re-quantization of GELU outputs; GELU(y) = y * Phi(y), Phi(y) = 1 - r/2 (y >= 0) or r/2 (y < 0).
+__device__ __forceinline__ float gelu_f(float y) {
+  const float ax = fabsf(y) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
+  const float hr = 0.5f * p * e;
+  const float phi = y >= 0.f ? 1.0f - hr : hr;
+  return y * phi;
+}
+
+__device__ __forceinline__ float silu_f(float y) {
+  return y * __frcp_rn(1.0f + __builtin_amdgcn_exp2f(y * -1.4426950408889634f));
+}
+
+// Accumulators start at the zero-point corrections:
+//   true = sum a'w' + (a_off - z_a) * colsum_w[n] + (128 - z_w[n]) * rowsum_a'[m]   (second term only for centered weights)
+template <int TM, int TN>
+__device__ __forceinline__ void init_acc(const GemmParams& p, v16i (&acc)[TN][TM], int64_t m0, int n0, int wm0, int wn0, int lane) {
+  const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
+  const bool need_cs = p.da != 0 && p.colsum_b;
+  if (!need_cs && !p.centered) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][i][e] = 0;
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int n = n0 + wn0 + j * 32 + 8 * (e >> 2) + lrow4 + (e & 3);
+      n = n < p.N ? n : p.N - 1;
+      const int cs = need_cs ? p.da * p.colsum_b[n] : 0;
+      const int dw = p.centered ? 128 - p.z_b[n] : 0;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        int64_t m = m0 + wm0 + i * 32 + lcol;
+        m = m < p.M ? m : p.M - 1;
+        acc[j][i][e] = cs + (p.centered ? dw * p.rowsum_a[m] : 0);
+      }
+    }
+  }
+}
+
+// Epilogue: for MFMA tile (j, i) and e-group g the lane holds output channels n..n+3 of token m.
+template <int TM, int TN>
+__device__ __forceinline__ void epilogue(const GemmParams& p, v16i (&acc)[TN][TM], int64_t m0, int n0, int wm0, int wn0, int lane) {
+  const int lcol = lane & 31, lrow4 = (lane >> 5) * 4;
+  const bool gated = p.act == RQ_ACT_SILU_GATED;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    if (gated && (j & 1)) continue;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = n0 + wn0 + j * 32 + 8 * g + lrow4;
+      if (n >= p.N) continue;
+      float4 sc = *reinterpret_cast<const float4*>(p.s_b + n);
+      sc.x *= p.s_a; sc.y *= p.s_a; sc.z *= p.s_a; sc.w *= p.s_a;
+      const float4 bi = p.bias ? *reinterpret_cast<const float4*>(p.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 sc2 = sc, bi2 = bi;
+      int no = n;   // output column
+      if (gated) {
+        sc2 = *reinterpret_cast<const float4*>(p.s_b + n + 32);
+        sc2.x *= p.s_a; sc2.y *= p.s_a; sc2.z *= p.s_a; sc2.w *= p.s_a;
+        bi2 = p.bias ? *reinterpret_cast<const float4*>(p.bias + n + 32) : make_float4(0.f, 0.f, 0.f, 0.f);
+        no = (n0 + wn0 + j * 32) / 2 + 8 * g + lrow4;
+      }
+      const int sg = (p.out_q && p.n_seg > 1) ? no / p.seg_len : 0;
+      const float is = p.inv_so[sg], zz = p.zo[sg];
+      const int lo = p.lo[sg], hi = p.hi[sg];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int64_t m = m0 + wm0 + i * 32 + lcol;
+        if (m >= p.M) continue;
+        if (p.out_acc) {
+          v4i t = {acc[j][i][4 * g], acc[j][i][4 * g + 1], acc[j][i][4 * g + 2], acc[j][i][4 * g + 3]};
+          *reinterpret_cast<v4i*>(p.out_acc + m * p.ldacc + n) = t;
+        }
+        float y[4];
+        y[0] = fmaf((float)acc[j][i][4 * g + 0], sc.x, bi.x);
+        y[1] = fmaf((float)acc[j][i][4 * g + 1], sc.y, bi.y);
+        y[2] = fmaf((float)acc[j][i][4 * g + 2], sc.z, bi.z);
+        y[3] = fmaf((float)acc[j][i][4 * g + 3], sc.w, bi.w);
+        if (p.act == RQ_ACT_GELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = gelu_f(y[e]);
+        } else if (gated) {
+          constexpr int J1 = TN > 1 ? 1 : 0;
+          const int ju = (j + J1) < TN ? (j + J1) : j;
+          const float u0 = fmaf((float)acc[ju][i][4 * g + 0], sc2.x, bi2.x);
+          const float u1 = fmaf((float)acc[ju][i][4 * g + 1], sc2.y, bi2.y);
+          const float u2 = fmaf((float)acc[ju][i][4 * g + 2], sc2.z, bi2.z);
+          const float u3 = fmaf((float)acc[ju][i][4 * g + 3], sc2.w, bi2.w);
+          y[0] = silu_f(y[0]) * u0; y[1] = silu_f(y[1]) * u1; y[2] = silu_f(y[2]) * u2; y[3] = silu_f(y[3]) * u3;
+        }
+        if (p.residual) {
+          const float4 r = *reinterpret_cast<const float4*>(p.residual + m * p.ldr + no);
+          y[0] += r.x; y[1] += r.y; y[2] += r.z; y[3] += r.w;
+        }
+        if (p.out_f32) *reinterpret_cast<float4*>(p.out_f32 + m * p.ldf + no) = make_float4(y[0], y[1], y[2], y[3]);
+        if (p.out_q) {
+          int c[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            int k = (int)(__builtin_rintf(y[e] * is) + zz);
+            c[e] = k < lo ? lo : (k > hi ? hi : k);
+          }
+          *reinterpret_cast<int*>(p.out_q + m * p.ldq + no) = rq_pack4(c[0], c[1], c[2], c[3]);
+        }
+      }
+    }
+  }
+}
+
+// 4-bit unpack of 16 packed bytes (32 codes, interleaved so that `& 0x0F0F0F0F` and `>> 4 & 0x0F0F0F0F` give 4 consecutive
+// codes each) into two 16-byte int8 chunks with the zero-point subtracted: ((x | 0x80) - z) ^ 0x80 is x - z per byte.
+__device__ __forceinline__ void unpack_u4(const v4i& pk, int z4, v4i& c0, v4i& c1) {
+  int lo, hi;
+  lo = pk[0] & 0x0F0F0F0F; hi = (pk[0] >> 4) & 0x0F0F0F0F;
+  c0[0] = ((lo | 0x80808080) - z4) ^ 0x80808080; c0[1] = ((hi | 0x80808080) - z4) ^ 0x80808080;
+  lo = pk[1] & 0x0F0F0F0F; hi = (pk[1] >> 4) & 0x0F0F0F0F;
+  c0[2] = ((lo | 0x80808080) - z4) ^ 0x80808080; c0[3] = ((hi | 0x80808080) - z4) ^ 0x80808080;
+  lo = pk[2] & 0x0F0F0F0F; hi = (pk[2] >> 4) & 0x0F0F0F0F;
+  c1[0] = ((lo | 0x80808080) - z4) ^ 0x80808080; c1[1] = ((hi | 0x80808080) - z4) ^ 0x80808080;
+  lo = pk[3] & 0x0F0F0F0F; hi = (pk[3] >> 4) & 0x0F0F0F0F;
+  c1[2] = ((lo | 0x80808080) - z4) ^ 0x80808080; c1[3] = ((hi | 0x80808080) - z4) ^ 0x80808080;
+}
+
+
+}  // namespace rqg

@@ -1,0 +1,425 @@
+// Pipelined weight-mode GEMM kernel (256 x 128 tiles, asynchronous global->LDS ring) and its epilogue.
+// Included by the per-format instantiation units.
+#pragma once
+
+#include "qgemm_common.h"
+
+namespace rqg {
+
+// Per-column epilogue constants.  They are fetched at kernel start (one column per thread), parked in registers
+// over the main loop and handed over through the start of the then-idle LDS ring, so that no global or scalar
+// memory latency sits in front of the first output of a tile.
+struct EpiLds {
+  float scale[128];      // s_a * s_w[n]
+  float bias[128];
+  int cs[128];           // (a_off - z_a) * colsum_w[n]
+  int dw[128];           // 128 - z_w[n] for centered weights, else 0
+  float is[128];         // 1 / s_o of the output column's re-quantization segment
+  float zz[128];         // z_o of that segment
+  int off4[128];         // storage offset of that segment replicated in 4 bytes
+};
+
+enum { OUT_ACC = 1, OUT_F32 = 2, OUT_RES = 4, OUT_Q = 8, OUT_ANY = 15 };
+
+// Epilogue: for MFMA tile (j, i) and e-group g the lane holds output channels n..n+3 of token m.
+//  * OUT selects the outputs at compile time (OUT_ANY: decided by the pointers at run time), CHECK the row bound;
+//  * v_cvt_pk_u8_f32 rounds to nearest-even, saturates to 0..255 and packs in one instruction; two
+//    v_permlane32_swap exchange dwords between lane l and lane l+32 (which hold interleaved groups of 4 channels of
+//    the same token) so that each lane owns 16 consecutive channels and issues one 16-byte store.
+template <int TM, int TN, int ACT, int OUT, bool CHECK>
+__device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[TN][TM], const EpiLds* el, const int (&rs)[TM],
+                                              int m0, int n0, int wm0, int wn0, int lane) {
+  const int lcol = lane & 31, half = lane >> 5, lrow4 = half * 4;
+  constexpr bool gated = ACT == RQ_ACT_SILU_GATED;
+  // everything the stores need, read from the kernel arguments once
+  int32_t* const out_acc = (OUT & OUT_ACC) ? p.out_acc : nullptr;
+  float* const out_f32 = (OUT & OUT_F32) ? p.out_f32 : nullptr;
+  const float* const residual = (OUT & OUT_RES) ? p.residual : nullptr;
+  int8_t* const out_q = (OUT & OUT_Q) ? p.out_q : nullptr;
+  const bool has_acc = (OUT & OUT_ACC) && (OUT != OUT_ANY || out_acc);
+  const bool has_f32 = (OUT & OUT_F32) && (OUT != OUT_ANY || out_f32);
+  const bool has_res = (OUT & OUT_RES) && (OUT != OUT_ANY || residual);
+  const bool has_q = (OUT & OUT_Q) && (OUT != OUT_ANY || out_q);
+  const int64_t ldacc = p.ldacc, ldf = p.ldf, ldr = p.ldr, ldq = p.ldq;
+  const int Mi = (int)p.M;
+  const float qm = p.qmaxf;
+  const bool wide_q = has_q && (ldq & 15) == 0 && (reinterpret_cast<uintptr_t>(out_q) & 15) == 0;
+  const bool corr = p.da != 0 || p.centered;
+  // row bases of this lane's TM tokens
+  int32_t* racc[TM]; float* rf32[TM]; const float* rres[TM]; int8_t* rq[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int64_t m = m0 + wm0 + i * 32 + lcol;
+    racc[i] = has_acc ? out_acc + m * ldacc : nullptr;
+    rf32[i] = has_f32 ? out_f32 + m * ldf : nullptr;
+    rres[i] = has_res ? residual + m * ldr : nullptr;
+    rq[i] = has_q ? out_q + m * ldq : nullptr;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    if (gated && (j & 1)) continue;
+    const int nb = n0 + wn0 + j * 32;              // first weight row of this MFMA tile
+    if (nb >= p.N) continue;                       // N is a multiple of 32 here (checked by the launcher)
+    const int nob = gated ? nb / 2 : nb;           // first output column
+    unsigned pk[TM][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int nl = wn0 + j * 32 + 8 * g + lrow4;   // weight row within the tile
+      const int nlo = gated ? (wn0 + j * 32) / 2 + 8 * g + lrow4 : nl;   // output column within the tile's outputs
+      const int n = n0 + nl;
+      const int no = nob + 8 * g + lrow4;
+      const float4 sc = *reinterpret_cast<const float4*>(&el->scale[nl]);
+      const float4 bi = *reinterpret_cast<const float4*>(&el->bias[nl]);
+      float4 sc2 = sc, bi2 = bi;
+      v4i cs = {0, 0, 0, 0}, dw = {0, 0, 0, 0}, cs2 = {0, 0, 0, 0}, dw2 = {0, 0, 0, 0};
+      if (corr) { cs = *reinterpret_cast<const v4i*>(&el->cs[nl]); dw = *reinterpret_cast<const v4i*>(&el->dw[nl]); }
+      if (gated) {
+        sc2 = *reinterpret_cast<const float4*>(&el->scale[nl + 32]);
+        bi2 = *reinterpret_cast<const float4*>(&el->bias[nl + 32]);
+        if (corr) { cs2 = *reinterpret_cast<const v4i*>(&el->cs[nl + 32]); dw2 = *reinterpret_cast<const v4i*>(&el->dw[nl + 32]); }
+      }
+      float is = 0.f, zz = 0.f;
+      unsigned o4 = 0;
+      if (has_q) { is = el->is[nlo]; zz = el->zz[nlo]; o4 = (unsigned)el->off4[nlo]; }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm0 + i * 32 + lcol;
+        const bool live = !CHECK || m < Mi;
+        int t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = acc[j][i][4 * g + e];
+        if (corr) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t[e] += cs[e] + dw[e] * rs[i];
+        }
+        if (has_acc && live) {
+          v4i tv = {t[0], t[1], t[2], t[3]};
+          *reinterpret_cast<v4i*>(racc[i] + n) = tv;
+        }
+        float y[4];
+        y[0] = fmaf((float)t[0], sc.x, bi.x);
+        y[1] = fmaf((float)t[1], sc.y, bi.y);
+        y[2] = fmaf((float)t[2], sc.z, bi.z);
+        y[3] = fmaf((float)t[3], sc.w, bi.w);
+        if (ACT == RQ_ACT_GELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = gelu_f(y[e]);
+        } else if (gated) {
+          constexpr int J1 = TN > 1 ? 1 : 0;
+          const int ju = (j + J1) < TN ? (j + J1) : j;
+          int u[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) u[e] = acc[ju][i][4 * g + e] + (corr ? cs2[e] + dw2[e] * rs[i] : 0);
+          y[0] = silu_f(y[0]) * fmaf((float)u[0], sc2.x, bi2.x);
+          y[1] = silu_f(y[1]) * fmaf((float)u[1], sc2.y, bi2.y);
+          y[2] = silu_f(y[2]) * fmaf((float)u[2], sc2.z, bi2.z);
+          y[3] = silu_f(y[3]) * fmaf((float)u[3], sc2.w, bi2.w);
+        }
+        if (has_res && live) {
+          const float4 r = *reinterpret_cast<const float4*>(rres[i] + no);
+          y[0] += r.x; y[1] += r.y; y[2] += r.z; y[3] += r.w;
+        }
+        if (has_f32 && live) *reinterpret_cast<float4*>(rf32[i] + no) = make_float4(y[0], y[1], y[2], y[3]);
+        if (has_q) {
+          unsigned w = 0;
+          w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[0], is, zz), qm), 0, w);
+          w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[1], is, zz), qm), 1, w);
+          w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[2], is, zz), qm), 2, w);
+          w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[3], is, zz), qm), 3, w);
+          // stored = code - off per byte, no borrow across bytes, any offset: ((w | H) - (o & ~H)) ^ ((w ^ ~o) & H)
+          w = ((w | 0x80808080u) - (o4 & 0x7F7F7F7Fu)) ^ ((w ^ ~o4) & 0x80808080u);
+          pk[i][g] = w;
+          if (!wide_q && live) *reinterpret_cast<unsigned*>(rq[i] + no) = w;
+        }
+      }
+    }
+    if (wide_q) {
+      // lanes l (half 0) and l+32 (half 1) hold channel groups {0,8,16,24}+{0..3} and {4,12,20,28}+{0..3}:
+      // after the two swaps lane l owns channels 0..15 and lane l+32 channels 16..31 of the same token
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm0 + i * 32 + lcol;
+        auto s02 = __builtin_amdgcn_permlane32_swap(pk[i][0], pk[i][2], false, false);
+        auto s13 = __builtin_amdgcn_permlane32_swap(pk[i][1], pk[i][3], false, false);
+        if (!CHECK || m < Mi) {
+          v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+          *reinterpret_cast<v4i*>(rq[i] + nob + half * 16) = tv;
+        }
+      }
+    }
+  }
+}
+
+// ---- pipelined kernel ------------------------------------------------------------------------------------------------
+// One workgroup (4 wavefronts) owns one 256 x 128 output tile (wavefront tile 128 x 64) and walks K in steps of 64
+// through an S-stage LDS ring.
+//  * Every load is asynchronous and goes global -> LDS directly (global_load_lds_dwordx4: each lane deposits 16
+//    bytes at ring_base + lane*16); no in-flight load is held in a register.  The bank swizzle of the int8 tiles is
+//    applied on the GLOBAL side: lane l fetches the chunk that belongs at LDS slot l.  Row r (64 B) keeps its four
+//    16-byte chunks rotated by (r >> 2), which makes the 32-row MFMA operand reads conflict-free.
+//  * 4-bit weights stay PACKED in LDS (32 bytes per row and k-step); each lane reads the 16-byte packet that holds
+//    its 32 codes of the k-step once and unpacks the nibbles in registers, zero-point subtracted, right before they
+//    enter the MFMA (the k assignment gives lane half h the chunks 2h and 2h+1, so the packet is contiguous).
+//  * Each activation fragment is refilled for the NEXT sub-step right after its own MFMAs are issued, so the LDS
+//    latency hides behind the remaining MFMAs; the barrier + refill of the ring sit inside the second sub-step.
+//  * One bare s_barrier per k-step (no fence: __syncthreads() would drain the asynchronous loads in flight).
+// Two workgroups share a CU, so one runs its epilogue / prologue while the other feeds the matrix cores.  Tiles are
+// dealt to the 8 XCDs in contiguous ranges (workgroup b runs on XCD b % 8) so that the tiles in flight on one XCD
+// share activation rows and weight columns in that XCD's L2.
+template <int N> __device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);   // vmcnt <= N, other counters unconstrained
+}
+
+template <bool W4, int S, int ACT, int OUT>
+__global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) {
+  constexpr int BM = 256, BN = 128, TM = 4, TN = 2;
+  constexpr int A_BYTES = BM * 64;
+  constexpr int B_BYTES = W4 ? BN * 32 : BN * 64;
+  constexpr int STAGE = A_BYTES + B_BYTES;
+  constexpr int LPS = W4 ? 5 : 6;                     // loads per thread and stage
+  static_assert(S >= 2 && S <= 4, "ring depth");
+  extern __shared__ __align__(16) int8_t ring[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 64;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // tile of this workgroup: XCD b % 8 gets the contiguous range [xcd * per_xcd, ...) of the tile list (n fastest)
+  const unsigned tiles_n = (unsigned)p.tiles_n;
+  const unsigned ntiles = (unsigned)p.tiles_m * tiles_n;
+  const unsigned per_xcd = (ntiles + 7u) / 8u;
+  const unsigned t = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || t >= ntiles) return;
+  const int tm = (int)(t / tiles_n), tn = (int)(t - (unsigned)tm * tiles_n);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int nk = p.K / 64;
+
+  // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
+  // lane l lands at 16-byte slot l of a 1 KB block = 16 tile rows of 64 B; the chunk that belongs at position
+  // (lane & 3) of row (lane >> 2) is chunk ((lane & 3) - (row >> 2)) & 3
+  unsigned aofs[4], bofs[2];
+  {
+    const int dl_row = lane >> 2;
+    const int dl_c = ((lane & 3) - (dl_row >> 2)) & 3;
+    const int Mi = (int)p.M;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int m = m0 + wave * 64 + i * 16 + dl_row;
+      m = m < Mi ? m : Mi - 1;
+      aofs[i] = (unsigned)m * (unsigned)p.lda + (unsigned)(dl_c * 16);
+    }
+    if (W4) {
+      const int row = tid >> 1;
+      int n = n0 + row;
+      n = n < p.N ? n : p.N - 1;
+      bofs[0] = (unsigned)n * (unsigned)p.ldb + (unsigned)(((tid & 1) ^ ((row >> 3) & 1)) * 16);
+      bofs[1] = bofs[0];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int n = n0 + wave * 32 + i * 16 + dl_row;
+        n = n < p.N ? n : p.N - 1;
+        bofs[i] = (unsigned)n * (unsigned)p.ldb + (unsigned)(dl_c * 16);
+      }
+    }
+  }
+  const int8_t* const gA = p.A;
+  const uint8_t* const gB = p.B;
+  auto issue = [&](int slot, int kt) {
+    int8_t* la = ring + slot * STAGE;
+    int8_t* lb = la + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gA + (aofs[i] + (unsigned)kt * 64u)),
+                                       (__attribute__((address_space(3))) void*)(la + (wave * 4 + i) * 1024), 16, 0, 0);
+    if (W4) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[0] + (unsigned)kt * 32u)),
+                                       (__attribute__((address_space(3))) void*)(lb + wave * 1024), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[i] + (unsigned)kt * 64u)),
+                                         (__attribute__((address_space(3))) void*)(lb + (wave * 2 + i) * 1024), 16, 0, 0);
+    }
+  };
+  // ---- prologue: S stages in flight ----
+#pragma unroll
+  for (int s = 0; s < S; ++s)
+    if (s < nk) issue(s, s);
+
+  // ---- MFMA operand fragments ----
+  int a_off[2];                                                    // MFMA tile i adds i * 2048
+#pragma unroll
+  for (int s = 0; s < 2; ++s) a_off[s] = (wm0 + l32) * 64 + (((2 * half + s + (l32 >> 2)) & 3) * 16);
+  int b_off[TN][W4 ? 1 : 2];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = wn0 + j * 32 + l32;
+#pragma unroll
+    for (int s = 0; s < (W4 ? 1 : 2); ++s)
+      b_off[j][s] = A_BYTES + (W4 ? n * 32 + ((half ^ ((n >> 3) & 1)) * 16) : n * 64 + (((2 * half + s + (n >> 2)) & 3) * 16));
+  }
+  int zb4[TN] = {0, 0};
+  if (W4) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      int n = n0 + wn0 + j * 32 + l32;
+      n = n < p.N ? n : p.N - 1;
+      zb4[j] = p.z_b[n] * 0x01010101;
+    }
+  }
+  v4i fa[TM];      // activation fragments of the sub-step being multiplied
+  v4i fb[TN];      // weight fragments of the sub-step being multiplied
+  v4i bnext[TN];   // W4: packed weights of the current k-step; int8: weight fragments of the next sub-step
+  auto load_a = [&](int slot, int s, int i) { fa[i] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + a_off[s] + i * 2048); };
+  auto load_b = [&](int slot, int s) {   // W4: only at s == 0 (one packet covers both sub-steps)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bnext[j] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[j][W4 ? 0 : s]);
+  };
+  auto take_b = [&](int s) {             // fb <- weights of sub-step s (unpack nibbles, subtract the zero-point)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if (W4) {
+        const int d0 = bnext[j][2 * s], d1 = bnext[j][2 * s + 1], z4 = zb4[j];
+        fb[j][0] = (((d0 & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
+        fb[j][1] = ((((d0 >> 4) & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
+        fb[j][2] = (((d1 & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
+        fb[j][3] = ((((d1 >> 4) & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
+      } else {
+        fb[j] = bnext[j];
+      }
+    }
+  };
+  v16i acc[TN][TM];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0;
+  // per-column epilogue constants: one column per thread pair, fetched now, parked in two registers over the main loop
+  float ep_f, ep_is = 0.f, ep_zz = 0.f; int ep_i, ep_off = 0;
+  {
+    int n = n0 + (tid & 127);
+    n = n < p.N ? n : p.N - 1;
+    if (tid < 128) {
+      ep_f = p.s_a * p.s_b[n];
+      ep_i = (p.da != 0 && p.colsum_b) ? p.da * p.colsum_b[n] : 0;
+      if ((OUT & OUT_Q) && p.out_q) {   // re-quantization constants of output column tid of this tile
+        const int no = (ACT == RQ_ACT_SILU_GATED ? n0 / 2 : n0) + tid;
+        int sg = p.n_seg > 1 ? no / p.seg_len : 0;
+        sg = sg < p.n_seg ? sg : p.n_seg - 1;
+        ep_is = p.inv_so[sg]; ep_zz = p.zcode[sg]; ep_off = p.off4[sg];
+      }
+    } else {
+      ep_f = p.bias ? p.bias[n] : 0.f;
+      ep_i = p.centered ? 128 - p.z_b[n] : 0;
+    }
+  }
+  int rs[TM] = {0, 0, 0, 0};
+  if (p.centered) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int m = m0 + wm0 + i * 32 + l32;
+      m = m < (int)p.M ? m : (int)p.M - 1;
+      rs[i] = p.rowsum_a[m];
+    }
+  }
+
+  // stage 0 has landed when at most the loads of stages 1 .. S-1 are outstanding
+  {
+    const int later = nk - 1 < S - 1 ? nk - 1 : S - 1;
+    if (later >= 3) wait_vm<3 * LPS>(); else if (later == 2) wait_vm<2 * LPS>(); else if (later == 1) wait_vm<LPS>(); else wait_vm<0>();
+  }
+  asm volatile("s_barrier" ::: "memory");
+  load_b(0, 0);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) load_a(0, 0, i);
+  int slot = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    // ---- sub-step 0 ----
+    take_b(0);
+    if (!W4) load_b(slot, 1);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
+      load_a(slot, 1, i);
+    }
+    take_b(1);
+    const int nslot = slot + 1 == S ? 0 : slot + 1;
+    const bool more = kt + 1 < nk;
+    if (more) {
+      // stage kt+1 has landed when at most the loads of stages kt+2 .. kt+S-1 are outstanding
+      const int rem = nk - 2 - kt;
+      const int later = rem < S - 2 ? rem : S - 2;
+      if (later >= 2) wait_vm<2 * LPS>(); else if (later == 1) wait_vm<LPS>(); else wait_vm<0>();
+    }
+    // ---- sub-step 1; its activation fragments are replaced by those of the next k-step as they are consumed ----
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
+      if (more) {
+        if (i == 0) {
+          // every read of stage kt by this wavefront has been issued; once they have returned (lgkmcnt) and all
+          // wavefronts are here, the slot may be refilled and stage kt+1 (already landed everywhere) may be read
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          if (kt + S < nk) issue(slot, kt + S);
+          load_b(nslot, 0);
+        }
+        load_a(nslot, 0, i);
+      }
+    }
+    slot = nslot;
+  }
+  // the ring is idle now: hand the per-column constants over through its first bytes
+  EpiLds* el = reinterpret_cast<EpiLds*>(ring);
+  __syncthreads();
+  if (tid < 128) { el->scale[tid] = ep_f; el->cs[tid] = ep_i; el->is[tid] = ep_is; el->zz[tid] = ep_zz; el->off4[tid] = ep_off; }
+  else { el->bias[tid - 128] = ep_f; el->dw[tid - 128] = ep_i; }
+  __syncthreads();
+  if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  else epilogue_wide<TM, TN, ACT, OUT, true>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+}
+
+
+// host side: one instantiation set per weight format lives in its own translation unit
+template <bool W4, int S, int ACT, int OUT>
+rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
+  p.tiles_m = (int)((p.M + 255) / 256);
+  p.tiles_n = (p.N + 127) / 128;
+  const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
+  constexpr int lds_bytes = S * (256 * 64 + (W4 ? 128 * 32 : 128 * 64));
+  static_assert(lds_bytes >= (int)sizeof(EpiLds), "the ring must hold the epilogue constants");
+  static bool attr_set = false;
+  if (!attr_set) {
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  const int64_t blocks = (ntiles + 7) / 8 * 8;
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
+  return RQ_OK;
+}
+
+template <bool W4, int S, int ACT>
+rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
+  const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
+  if (q && !f && !r && !a) return launch_pipe_one<W4, S, ACT, OUT_Q>(ctx, p);
+  if (ACT == RQ_ACT_NONE && f && r && !q && !a) return launch_pipe_one<W4, S, ACT, OUT_F32 | OUT_RES>(ctx, p);
+  return launch_pipe_one<W4, S, ACT, OUT_ANY>(ctx, p);
+}
+
+template <bool W4, int S>
+rq_status launch_pipe(rq_ctx* ctx, GemmParams& p) {
+  switch (p.act) {
+    case RQ_ACT_GELU: return launch_pipe_out<W4, S, RQ_ACT_GELU>(ctx, p);
+    case RQ_ACT_SILU_GATED: return launch_pipe_out<W4, S, RQ_ACT_SILU_GATED>(ctx, p);
+    default: return launch_pipe_out<W4, S, RQ_ACT_NONE>(ctx, p);
+  }
+}
+
+}  // namespace rqg

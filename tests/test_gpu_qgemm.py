@@ -25,7 +25,7 @@ def _act_codes(g, M, K, bits):
 @pytest.mark.parametrize("M,N,K", [(333, 192, 128), (128, 128, 64), (1000, 768, 768), (2049, 1536, 384), (77, 2304, 768),
                                    (513, 260, 3072)])
 @pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4), (6, 6)])
-@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("tile", [1, 2, 3])
 def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
     b, ctx = rq
     print("case", M, N, K, bits_a, bits_w, tile, flush=True)
