@@ -1,45 +1,74 @@
 // rq_ln_quant: LayerNorm / RMSNorm with the folded affine, fused with the layer-wise uniform quantizer
 // (Section "Scale reparameterization for LayerNorm activations"; quantizer of Section "Efficient quantizers").
 //
-// HBM-bound: 4 B read + 1 B written per element.  One row is held in the registers of LPR lanes
-// (LPR = 16, 32 or 64 lanes of a 64-wide wavefront); the row statistics are wavefront shuffles; the
-// codes leave as one dword (4 codes) per lane, contiguous across lanes.  All arithmetic is float64:
-// fp64 runs at the fp32 rate on this chip and the kernel has ALU headroom, so the codes agree with a
-// float64 reference except at exact ties.  The next row is fetched while the current one is quantized.
+// HBM-bound: 4 B read + 1 B written per element.  A row is held in the registers of LPR lanes (16, 32 or 64 lanes of
+// a 64-wide wavefront, so that narrow rows still fill the wavefront); the row statistics are reduced with DPP lane
+// exchanges inside 16-lane rows and one or two shuffles across them; the codes leave as one dword (4 codes) per
+// lane, contiguous across lanes.  The per-channel constants g = gamma~/s~ and h = beta~/s~ + z~ are computed once
+// per workgroup in float64 and staged in LDS.  All arithmetic is float64 (full rate on this chip), so the codes
+// agree with a float64 reference except at exact ties; rounding, saturation to 0..255 and byte packing are one
+// v_cvt_pk_u8_f32 per code.  Workgroups are persistent and fetch their next rows while the current ones are quantized.
 #include <vector>
 
 #include "rq_internal.h"
 
 namespace {
 
-template <int LPR, int NV, bool REG_AFFINE>
-__global__ __launch_bounds__(256) void ln_quant_kernel(
-    const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind, double eps,
-    const float* __restrict__ gamma_t, const float* __restrict__ beta_t, double inv_s, double zshift,
-    int lo, int hi, int8_t* __restrict__ q, int64_t ldq, int32_t* __restrict__ rowsum) {
-  constexpr int RPW = 64 / LPR;                 // rows per wavefront
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+
+// sum over the LPR lanes of a row group (LPR = 16, 32 or 64); every lane receives the total
+template <int LPR>
+__device__ __forceinline__ double group_sum(double v) {
+  v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+  v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+  v += dpp_f64<0x141>(v);   // row_half_mirror: pairs the two quads of 8 lanes
+  v += dpp_f64<0x140>(v);   // row_mirror: pairs the two halves of 16 lanes
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  if (LPR >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+template <int LPR>
+__device__ __forceinline__ int group_sum_i(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  if (LPR >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+// 1/sqrt(a) in float64: float32 estimate refined by two Newton steps (relative error ~1e-16)
+__device__ __forceinline__ double rsqrt_f64(double a) {
+  double r = (double)__builtin_amdgcn_rsqf((float)a);
+  r = r * fma(-0.5 * a, r * r, 1.5);
+  r = r * fma(-0.5 * a, r * r, 1.5);
+  return r;
+}
+
+template <int LPR, int NV>
+__global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
+                                                       double eps, const float* __restrict__ gamma_t,
+                                                       const float* __restrict__ beta_t, double inv_s, double zcode, float qmaxf,
+                                                       unsigned off4, int8_t* __restrict__ q, int64_t ldq,
+                                                       int32_t* __restrict__ rowsum) {
+  extern __shared__ __align__(16) double2 gh[];   // [D]: {gamma~ / s~, beta~ / s~ + z~}
+  constexpr int RPW = 64 / LPR;                   // rows per wavefront
   const int lane = threadIdx.x & 63;
-  const int sub = lane % LPR;                   // lane within the row
-  const int rsel = lane / LPR;                  // which of the wavefront's rows
-  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const int64_t nwave = (int64_t)gridDim.x * (blockDim.x >> 6);
+  const int sub = lane % LPR;                     // lane within the row
+  const int rsel = lane / LPR;                    // which of the wavefront's rows
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwave = (int64_t)gridDim.x * 4;
   const int chunks = D >> 2;
 
-  // g = gamma~/s~, h = beta~/s~ + z~ - store_off for this lane's channels
-  double g[REG_AFFINE ? NV * 4 : 1], h[REG_AFFINE ? NV * 4 : 1];
-  if (REG_AFFINE) {
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = sub + i * LPR;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int ch = c * 4 + e;
-        const bool ok = c < chunks;
-        g[i * 4 + e] = ok ? (double)gamma_t[ch] * inv_s : 0.0;
-        h[i * 4 + e] = ok ? (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zshift : 0.0;
-      }
-    }
-  }
+  for (int ch = threadIdx.x; ch < D; ch += 256)
+    gh[ch] = make_double2((double)gamma_t[ch] * inv_s, (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode);
 
   float4 cur[NV], nxt[NV];
   int64_t row = wave * RPW + rsel;
@@ -49,6 +78,7 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(
     const int c = sub + i * LPR;
     cur[i] = (row < T && c < chunks) ? *reinterpret_cast<const float4*>(x + row * ldx + c * 4) : make_float4(0, 0, 0, 0);
   }
+  __syncthreads();
   const double invD = 1.0 / (double)D;
   for (; (row - rsel) < T; row += stride) {       // wavefront-uniform trip count
     const int64_t nrow = row + stride;
@@ -64,21 +94,15 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(
       s1 += (a + b) + (c + d);
       s2 = fma(a, a, s2); s2 = fma(b, b, s2); s2 = fma(c, c, s2); s2 = fma(d, d, s2);
     }
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) {
-      s1 += __shfl_xor(s1, m, 64);
-      s2 += __shfl_xor(s2, m, 64);
-    }
-    double mean, var;
+    s2 = group_sum<LPR>(s2);
+    double mean = 0.0, var = s2 * invD;
     if (norm_kind == RQ_NORM_LAYERNORM) {
+      s1 = group_sum<LPR>(s1);
       mean = s1 * invD;
-      var = fma(-mean, mean, s2 * invD);
+      var = fma(-mean, mean, var);
       var = var < 0.0 ? 0.0 : var;
-    } else {
-      mean = 0.0;
-      var = s2 * invD;
     }
-    const double rstd = 1.0 / sqrt(var + eps);
+    const double rstd = rsqrt_f64(var + eps);
     const double nmr = -mean * rstd;
     int rs = 0;
     if (row < T) {
@@ -87,32 +111,27 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(
         const int c = sub + i * LPR;
         if (c < chunks) {
           const float xv[4] = {cur[i].x, cur[i].y, cur[i].z, cur[i].w};
-          int code[4];
+          unsigned w = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            double gg, hh;
-            if (REG_AFFINE) {
-              gg = g[i * 4 + e];
-              hh = h[i * 4 + e];
-            } else {
-              const int ch = c * 4 + e;
-              gg = (double)gamma_t[ch] * inv_s;
-              hh = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zshift;
-            }
+            const double2 g = gh[c * 4 + e];
             const double xh = fma((double)xv[e], rstd, nmr);
-            const double v = fma(xh, gg, hh);
-            int k = (int)rint(v);
-            k = k < lo ? lo : (k > hi ? hi : k);
-            code[e] = k;
-            rs += k;
+            const double v = rint(fma(xh, g.x, g.y));                 // exact integer in float64 ...
+            const float vf = fminf((float)v, qmaxf);                   // ... so the float32 conversion is exact too
+            if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);  // saturates below at 0 and packs the byte
+            if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
+            if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
+            if (e == 3) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 3, w);
           }
-          *reinterpret_cast<int*>(q + row * ldq + c * 4) = rq_pack4(code[0], code[1], code[2], code[3]);
+          // stored = code - off per byte, no borrow across bytes: ((w | H) - (o & ~H)) ^ ((w ^ ~o) & H)
+          w = ((w | 0x80808080u) - (off4 & 0x7F7F7F7Fu)) ^ ((w ^ ~off4) & 0x80808080u);
+          if (rowsum) rs = __builtin_amdgcn_sdot4((int)w, 0x01010101, rs, false);
+          *reinterpret_cast<unsigned*>(q + row * ldq + c * 4) = w;
         }
       }
     }
     if (rowsum) {
-#pragma unroll
-      for (int m = 1; m < LPR; m <<= 1) rs += __shfl_xor(rs, m, 64);
+      rs = group_sum_i<LPR>(rs);
       if (sub == 0 && row < T) rowsum[row] = rs;
     }
 #pragma unroll
@@ -121,15 +140,24 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(
 }
 
 template <int LPR, int NV>
-void launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zshift, int lo, int hi) {
+rq_status launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcode, float qmaxf, unsigned off4) {
   constexpr int RPW = 64 / LPR;
-  constexpr bool REG = NV <= 4;
   const int64_t rows_per_block = 4 * RPW;
   int64_t blocks = (d->T + rows_per_block - 1) / rows_per_block;
-  const int64_t cap = (int64_t)ctx->num_cu * 8;
+  const int lds = d->D * 16;
+  const int per_cu = lds > 40960 ? (lds > 81920 ? 1 : 2) : 4;
+  const int64_t cap = (int64_t)ctx->num_cu * per_cu;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV, REG>), dim3((unsigned)blocks), dim3(256), 0, ctx->stream, d->x, d->ldx, d->T,
-                     d->D, d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zshift, lo, hi, d->q, d->ldq, d->rowsum);
+  static bool attr_set = false;
+  if (!attr_set) {
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               8192 * 16));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T, d->D,
+                     d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
 }
 
 }  // namespace
@@ -137,22 +165,19 @@ void launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zshift, int l
 rq_status rq_launch_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
   const int chunks = d->D / 4;
   const double inv_s = 1.0 / (double)d->s_tilde;
-  const double zshift = (double)d->z_tilde - (double)d->store_off;
-  const int lo = -d->store_off, hi = (1 << d->bits) - 1 - d->store_off;
-  int lpr;
-  if (chunks % 64 == 0 || chunks > 128) lpr = 64;
-  else if (chunks % 32 == 0 || chunks > 64) lpr = 32;
-  else lpr = 16;
+  const double zcode = (double)d->z_tilde;
+  const float qmaxf = (float)((1 << d->bits) - 1);
+  const unsigned off4 = (unsigned)(d->store_off & 0xFF) * 0x01010101u;
+  // lanes per row: the smallest group that keeps a row within 8 float4 per lane
+  int lpr = 64;
+  for (int cand : {32, 16})
+    if ((chunks + cand - 1) / cand <= 8) lpr = cand;
   const int nv = (chunks + lpr - 1) / lpr;
-#define RQ_LN_CASE(L, N)                                  \
-  if (lpr == L && nv <= N) {                              \
-    launch<L, N>(ctx, d, inv_s, zshift, lo, hi);          \
-    RQ_HIP(hipGetLastError());                            \
-    return RQ_OK;                                         \
-  }
-  RQ_LN_CASE(16, 1) RQ_LN_CASE(16, 2) RQ_LN_CASE(16, 4)
-  RQ_LN_CASE(32, 1) RQ_LN_CASE(32, 2) RQ_LN_CASE(32, 3) RQ_LN_CASE(32, 4)
-  RQ_LN_CASE(64, 2) RQ_LN_CASE(64, 3) RQ_LN_CASE(64, 4) RQ_LN_CASE(64, 8) RQ_LN_CASE(64, 16) RQ_LN_CASE(64, 32)
+#define RQ_LN_CASE(L, N) \
+  if (lpr == L && nv <= N) return launch<L, N>(ctx, d, inv_s, zcode, qmaxf, off4);
+  RQ_LN_CASE(16, 1) RQ_LN_CASE(16, 2) RQ_LN_CASE(16, 3) RQ_LN_CASE(16, 4) RQ_LN_CASE(16, 6) RQ_LN_CASE(16, 8)
+  RQ_LN_CASE(32, 5) RQ_LN_CASE(32, 6) RQ_LN_CASE(32, 7) RQ_LN_CASE(32, 8)
+  RQ_LN_CASE(64, 5) RQ_LN_CASE(64, 6) RQ_LN_CASE(64, 8) RQ_LN_CASE(64, 12) RQ_LN_CASE(64, 16) RQ_LN_CASE(64, 32)
 #undef RQ_LN_CASE
   return rq_fail(ctx, RQ_ERR_SHAPE, "rq_ln_quant: D = %d exceeds the supported 8192", d->D);
 }

@@ -26,7 +26,35 @@ struct SmParams {
   int qmax;
 };
 
-template <int LPR, int MAXNV, bool HAS_BIAS>
+// reductions over the LPR lanes of a row group: DPP exchanges inside 16-lane rows, shuffles across them
+template <int LPR> __device__ __forceinline__ int group_max_i(int v) {
+  v = max(v, __builtin_amdgcn_update_dpp(INT32_MIN, v, 0xB1, 0xF, 0xF, false));   // lane ^ 1
+  v = max(v, __builtin_amdgcn_update_dpp(INT32_MIN, v, 0x4E, 0xF, 0xF, false));   // lane ^ 2
+  v = max(v, __builtin_amdgcn_update_dpp(INT32_MIN, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = max(v, __builtin_amdgcn_update_dpp(INT32_MIN, v, 0x140, 0xF, 0xF, false));  // row_mirror
+  if (LPR >= 32) v = max(v, __shfl_xor(v, 16, 64));
+  if (LPR >= 64) v = max(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+template <int LPR> __device__ __forceinline__ float group_sum_f(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  if (LPR >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+template <int LPR> __device__ __forceinline__ double group_max_d(double v) {
+#pragma unroll
+  for (int m = 1; m < LPR; m <<= 1) v = fmax(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+// F64CODE: the code's pre-round value 2 (log2 sum - (t_j - t_max) + log2 s) is formed in float64 (used for more than
+// 6 bits, where a float32 product could move ~3e-5 of the codes across a rounding boundary); otherwise one float32
+// fma.  Rounding to nearest-even, saturation at 0 and byte packing are one v_cvt_pk_u8_f32 per code either way.
+template <int LPR, int MAXNV, bool HAS_BIAS, bool F64CODE>
 __global__ __launch_bounds__(256) void softmax_kernel(const SmParams p) {
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
@@ -50,6 +78,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SmParams p) {
   }
 
   const float c1f = (float)p.c1;
+  const float qmaxf = (float)p.qmax;
   float ssum = 0.f;
   double tmax = -1e300;
   int amax = INT32_MIN;
@@ -66,8 +95,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SmParams p) {
         tmax = fmax(tmax, tv);
       }
     }
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) tmax = fmax(tmax, __shfl_xor(tmax, m, 64));
+    tmax = group_max_d<LPR>(tmax);
 #pragma unroll
     for (int v = 0; v < MAXNV; ++v)
 #pragma unroll
@@ -79,31 +107,26 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SmParams p) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const bool ok = c < chunks && (c * 4 + e) < limit;
-        amax = ok ? (a[v][e] > amax ? a[v][e] : amax) : amax;
+        a[v][e] = ok ? a[v][e] : INT32_MIN;          // masked and padding keys
+        amax = max(amax, a[v][e]);
       }
     }
+    amax = group_max_i<LPR>(amax);
 #pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) {
-      const int o = __shfl_xor(amax, m, 64);
-      amax = o > amax ? o : amax;
-    }
-#pragma unroll
-    for (int v = 0; v < MAXNV; ++v) {
-      const int c = sub + v * LPR;
+    for (int v = 0; v < MAXNV; ++v)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const bool ok = c < chunks && (c * 4 + e) < limit;
-        // acc - amax <= 0 and may wrap below INT32_MIN only if |acc| > 2^30, which the int32 contract excludes
-        const float ex = __builtin_amdgcn_exp2f((float)(a[v][e] - amax) * c1f);
-        ssum += ok ? ex : 0.f;
+        // acc - amax <= 0; INT32_MIN - amax wraps only if amax > 0, to a large positive value, so clamp the masked ones
+        const int d = a[v][e] == INT32_MIN ? -0x40000000 : a[v][e] - amax;
+        a[v][e] = d;
+        ssum += __builtin_amdgcn_exp2f((float)d * c1f);   // exp2(-huge) = 0
       }
-    }
   }
-#pragma unroll
-  for (int m = 1; m < LPR; m <<= 1) ssum += __shfl_xor(ssum, m, 64);
+  ssum = group_sum_f<LPR>(ssum);
   // code = rint(2 * (log2(sum) - (t_j - t_max) + log2 s))
   const double C0 = 2.0 * ((double)__builtin_amdgcn_logf(ssum) + p.log2s);
   const double m2c = -2.0 * p.c1;
+  const float C0f = (float)C0, m2cf = (float)m2c;
 
   if (!live) return;
   uint8_t* crow = p.codes + row * p.ld;
@@ -111,18 +134,25 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SmParams p) {
   for (int v = 0; v < MAXNV; ++v) {
     const int c = sub + v * LPR;
     if (c < chunks) {
-      int code[4];
+      unsigned w = 0;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int j = c * 4 + e;
-        double val;
-        if (HAS_BIAS) val = fma(t[v * 4 + e] - tmax, -2.0, C0);
-        else val = fma((double)(a[v][e] - amax), m2c, C0);
-        int k = (int)rint(val);
-        k = k < 0 ? 0 : (k > p.qmax ? p.qmax : k);
-        code[e] = j < limit ? k : p.qmax;
+        float vf;
+        if (HAS_BIAS) {
+          const int j = c * 4 + e;
+          vf = j < limit ? (float)rint(fma(t[v * 4 + e] - tmax, -2.0, C0)) : qmaxf;
+        } else if (F64CODE) {
+          vf = (float)rint(fma((double)a[v][e], m2c, C0));       // masked keys: huge positive -> saturates at qmax below
+        } else {
+          vf = fmaf((float)a[v][e], m2cf, C0f);
+        }
+        vf = fminf(vf, qmaxf);
+        if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);
+        if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
+        if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
+        if (e == 3) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 3, w);
       }
-      *reinterpret_cast<int*>(crow + c * 4) = rq_pack4(code[0], code[1], code[2], code[3]);
+      *reinterpret_cast<unsigned*>(crow + c * 4) = w;
     }
   }
 }
@@ -131,8 +161,9 @@ template <int LPR, int MAXNV>
 void launch(rq_ctx* ctx, const SmParams& p, bool has_bias) {
   const int64_t rows_per_block = 4 * (64 / LPR);
   const unsigned blocks = (unsigned)((p.rows + rows_per_block - 1) / rows_per_block);
-  if (has_bias) hipLaunchKernelGGL((softmax_kernel<LPR, MAXNV, true>), dim3(blocks), dim3(256), 0, ctx->stream, p);
-  else hipLaunchKernelGGL((softmax_kernel<LPR, MAXNV, false>), dim3(blocks), dim3(256), 0, ctx->stream, p);
+  if (has_bias) hipLaunchKernelGGL((softmax_kernel<LPR, MAXNV, true, true>), dim3(blocks), dim3(256), 0, ctx->stream, p);
+  else if (p.qmax > 63) hipLaunchKernelGGL((softmax_kernel<LPR, MAXNV, false, true>), dim3(blocks), dim3(256), 0, ctx->stream, p);
+  else hipLaunchKernelGGL((softmax_kernel<LPR, MAXNV, false, false>), dim3(blocks), dim3(256), 0, ctx->stream, p);
 }
 
 }  // namespace
