@@ -240,6 +240,31 @@ typedef struct {
 } rq_softmax_desc;
 rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d);
 
+/* ---- rq_qk_softmax_log2_quant -----------------------------------------------------------------------
+ * rq_qgemm in activation mode (exact int32 Q.K^T of the stored Q and K codes, attention Eq. of Section
+ * "Transformer blocks") and rq_softmax_log2_quant (Eq. (3.3-1), second line) in ONE kernel for rows of at
+ * most 288 keys: the accumulators of a 32-query tile against all keys stay in registers, so the logits are
+ * never written.  Same integers and same code arithmetic as the two separate calls.
+ * Q, K: token-major device int8 (row b*N + i, column h*d_head + c, row pitch ld_tok bytes), stored as
+ * code - off.  codes: [batch*H, N, ld] device, ld % 16 == 0, 16-byte aligned; positions N..ld-1 and masked
+ * keys receive the largest code.  d_head in {32, 64, 128}; RQ_ERR_SHAPE if N > 288.
+ */
+typedef struct {
+  int64_t batch;
+  int32_t H, N, d_head;
+  const int8_t *Q, *K;
+  int64_t ld_tok;
+  int32_t q_off, z_q, k_off, z_k;
+  double logit_scale;     /* s_q * s_k / sqrt(d_head) */
+  const float* bias;      /* [H, N, N] dense, or NULL */
+  int32_t mask;
+  float s_log;
+  int32_t bits;           /* 2..8 */
+  uint8_t* codes;
+  int64_t ld;
+} rq_qk_softmax_desc;
+rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d);
+
 /* ---- rq_attn_pv -----------------------------------------------------------------------------------------
  * P.V with shift de-quantized probabilities (case analysis before Eq. (3.3-2) and Eq. (3.3-2)):
  *    A^[i, j] = s~(code) * 2^floor(-code / 2),   s~ = s_log (even code) or s_log * sqrt2 (odd code),
@@ -311,6 +336,11 @@ typedef struct {
  * last-level cache between Q.K^T, Softmax and P.V.  Sets the chunk budget in bytes (process-wide, default
  * 64 MiB); call before rq_block_workspace_bytes. */
 rq_status rq_set_attn_chunk_bytes(int64_t bytes);
+/* For rows of up to 288 keys rq_block_forward computes Q.K^T and the Softmax-log2 codes in ONE kernel that keeps
+ * the exact int32 accumulators of a query tile in registers (same integers, same code arithmetic as rq_qgemm in
+ * activation mode followed by rq_softmax_log2_quant; the logits never reach memory).  on = 0 forces the two-kernel
+ * path for every length (process-wide; default 1); call before rq_block_workspace_bytes. */
+rq_status rq_set_attn_fused(int on);
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);

@@ -66,6 +66,12 @@ class SoftmaxDesc(C.Structure):
                 ("logit_scale", f64), ("bias", vp), ("mask", i32), ("s_log", f32), ("bits", i32), ("codes", vp)]
 
 
+class QkSoftmaxDesc(C.Structure):
+    _fields_ = [("batch", i64), ("H", i32), ("N", i32), ("d_head", i32), ("Q", vp), ("K", vp), ("ld_tok", i64),
+                ("q_off", i32), ("z_q", i32), ("k_off", i32), ("z_k", i32), ("logit_scale", f64), ("bias", vp),
+                ("mask", i32), ("s_log", f32), ("bits", i32), ("codes", vp), ("ld", i64)]
+
+
 class PvDesc(C.Structure):
     _fields_ = [("batch", i64), ("H", i32), ("Nq", i32), ("Nk", i32), ("d_head", i32), ("ld", i64), ("codes", vp),
                 ("V", vp), ("ldv", i64), ("s_log", f32), ("s_v", f32), ("z_v", i32), ("v_off", i32),
@@ -179,9 +185,11 @@ _rq_weight_quant_pack = _sig("rq_weight_quant_pack", i32, [vp, C.POINTER(WqDesc)
 _rq_qgemm = _sig("rq_qgemm", i32, [vp, C.POINTER(GemmDesc)])
 _rq_softmax = _sig("rq_softmax_log2_quant", i32, [vp, C.POINTER(SoftmaxDesc)])
 _rq_attn_pv = _sig("rq_attn_pv", i32, [vp, C.POINTER(PvDesc)])
+_rq_qk_softmax = _sig("rq_qk_softmax_log2_quant", i32, [vp, C.POINTER(QkSoftmaxDesc)])
 _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
+_rq_set_fused = _sig("rq_set_attn_fused", i32, [i32])
 _rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
 _rq_profile_reset = _sig("rq_profile_reset", i32, [vp])
 _rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i64)])
@@ -272,6 +280,16 @@ def rq_softmax_log2_quant(ctx, acc, G, H, Nq, Nk, ld, logit_scale, codes, bits, 
     ctx.check(_rq_softmax(ctx.handle, C.byref(d)))
 
 
+def rq_qk_softmax_log2_quant(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_off, z_q, k_off, z_k, logit_scale, codes, ld,
+                             bits, s_log=1.0, bias=None, mask=MASK_NONE):
+    """Fused Q.K^T + Softmax-log2 codes from a token-major int8 tensor (rows of at most 288 keys)."""
+    base = qkv.data_ptr()
+    d = QkSoftmaxDesc(batch=batch, H=H, N=seq, d_head=d_head, Q=base + q_col, K=base + k_col, ld_tok=qkv.stride(0),
+                      q_off=q_off, z_q=z_q, k_off=k_off, z_k=z_k, logit_scale=logit_scale, bias=_p(bias), mask=mask,
+                      s_log=s_log, bits=bits, codes=_p(codes), ld=ld)
+    ctx.check(_rq_qk_softmax(ctx.handle, C.byref(d)))
+
+
 def rq_attn_pv(ctx, codes, ld, V_ptr, ldv, batch, H, Nq, Nk, d_head, s_log, s_v, z_v, v_off, bits_p, *, mask=MASK_NONE,
                out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
     d = PvDesc(batch=batch, H=H, Nq=Nq, Nk=Nk, d_head=d_head, ld=ld, codes=_p(codes), V=V_ptr, ldv=ldv, s_log=s_log,
@@ -303,6 +321,12 @@ def rq_minmax_f32(ctx, v):
 
 def set_attn_chunk_bytes(nbytes: int):
     rc = _rq_set_chunk(nbytes)
+    if rc != RQ_OK:
+        raise RqError(rc, _rq_last_error(None).decode())
+
+
+def set_attn_fused(on: bool):
+    rc = _rq_set_fused(1 if on else 0)
     if rc != RQ_OK:
         raise RqError(rc, _rq_last_error(None).decode())
 

@@ -18,12 +18,18 @@ struct Plan {
 };
 
 int64_t g_attn_chunk_bytes = 64ll << 20;
+int g_attn_fused = 1;
+
+bool use_fused(const rq_block_params* p, int64_t seq) {
+  return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H);
+}
 
 Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   Plan pl;
   pl.batch = batch; pl.seq = seq; pl.T = batch * seq;
   pl.ld = (seq + 15) / 16 * 16;
-  const int64_t per_item = (int64_t)p->H * seq * pl.ld * 5;
+  const bool fused = use_fused(p, seq);       // no int32 logits in memory: only the codes count
+  const int64_t per_item = (int64_t)p->H * seq * pl.ld * (fused ? 1 : 5);
   pl.bchunk = g_attn_chunk_bytes / (per_item > 0 ? per_item : 1);
   if (pl.bchunk < 1) pl.bchunk = 1;
   if (pl.bchunk > batch) pl.bchunk = batch;
@@ -32,7 +38,7 @@ Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   pl.o_a = o; o += up((size_t)pl.T * p->D);
   pl.o_rowsum = o; o += up((size_t)pl.T * 4);
   pl.o_qkv = o; o += up((size_t)pl.T * 3 * p->D);
-  pl.o_acc = o; o += up((size_t)gch * seq * pl.ld * 4);
+  pl.o_acc = o; o += fused ? 0 : up((size_t)gch * seq * pl.ld * 4);
   pl.o_codes = o; o += up((size_t)gch * seq * pl.ld);
   pl.o_o = o; o += up((size_t)pl.T * p->D);
   pl.o_xbar = o; o += up((size_t)pl.T * p->D * 4);
@@ -62,6 +68,11 @@ rq_status check_linear(rq_ctx* ctx, const char* name, const rq_qlinear& l, int N
 }  // namespace
 
 extern "C" {
+
+rq_status rq_set_attn_fused(int on) {
+  g_attn_fused = on != 0;
+  return RQ_OK;
+}
 
 rq_status rq_set_attn_chunk_bytes(int64_t bytes) {
   if (bytes < (1 << 20)) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_attn_chunk_bytes: at least 1 MiB");
@@ -145,34 +156,44 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   }
   // ---- attention, chunked over batch items -----------------------------------------------------------------
   const int offo = rq_store_offset(ba, p->z_o);
+  const bool fused = use_fused(p, seq);
   for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
     const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
     const int8_t* qkv_c = qkv + b0 * seq * 3 * D;
-    {
-      rq_gemm_desc g;
-      std::memset(&g, 0, sizeof g);
-      g.M = seq; g.N = (int)seq; g.K = dh;
-      g.A = qkv_c; g.lda = 3 * D; g.a_off = offq; g.z_a = p->z_q; g.s_a = p->s_q;
-      g.B = qkv_c + D; g.ldb = 3 * D; g.b_format = RQ_B_ACT_I8; g.b_off = offk; g.z_b_scalar = p->z_k;
-      g.out_acc = acc; g.ldacc = pl.ld; g.acc_stride_group = seq * pl.ld;
-      g.batch_outer = nb; g.batch_inner = H;
-      g.a_stride_outer = seq * 3 * D; g.a_stride_inner = dh; g.b_stride_outer = seq * 3 * D; g.b_stride_inner = dh;
-      g.causal = p->mask == RQ_MASK_CAUSAL;
+    if (fused) {
       rq_prof_begin(ctx, RQ_STEP_QK);
-      st = rq_qgemm(ctx, &g);
+      st = rq_launch_qk_softmax(ctx, qkv_c, qkv_c + D, 3 * D, nb, H, (int)seq, dh, offq, p->z_q, offk, p->z_k,
+                                (double)p->s_q * (double)p->s_k / std::sqrt((double)dh), p->rel_bias, p->mask, p->s_log,
+                                p->bits_p, codes, pl.ld);
       rq_prof_end(ctx);
       if (st != RQ_OK) return st;
-    }
-    {
-      rq_softmax_desc d;
-      std::memset(&d, 0, sizeof d);
-      d.G = nb * H; d.H = H; d.Nq = (int)seq; d.Nk = (int)seq; d.ld = pl.ld; d.acc = acc;
-      d.logit_scale = (double)p->s_q * (double)p->s_k / std::sqrt((double)dh);
-      d.bias = p->rel_bias; d.mask = p->mask; d.s_log = p->s_log; d.bits = p->bits_p; d.codes = codes;
-      rq_prof_begin(ctx, RQ_STEP_SOFTMAX);
-      st = rq_softmax_log2_quant(ctx, &d);
-      rq_prof_end(ctx);
-      if (st != RQ_OK) return st;
+    } else {
+      {
+        rq_gemm_desc g;
+        std::memset(&g, 0, sizeof g);
+        g.M = seq; g.N = (int)seq; g.K = dh;
+        g.A = qkv_c; g.lda = 3 * D; g.a_off = offq; g.z_a = p->z_q; g.s_a = p->s_q;
+        g.B = qkv_c + D; g.ldb = 3 * D; g.b_format = RQ_B_ACT_I8; g.b_off = offk; g.z_b_scalar = p->z_k;
+        g.out_acc = acc; g.ldacc = pl.ld; g.acc_stride_group = seq * pl.ld;
+        g.batch_outer = nb; g.batch_inner = H;
+        g.a_stride_outer = seq * 3 * D; g.a_stride_inner = dh; g.b_stride_outer = seq * 3 * D; g.b_stride_inner = dh;
+        g.causal = p->mask == RQ_MASK_CAUSAL;
+        rq_prof_begin(ctx, RQ_STEP_QK);
+        st = rq_qgemm(ctx, &g);
+        rq_prof_end(ctx);
+        if (st != RQ_OK) return st;
+      }
+      {
+        rq_softmax_desc d;
+        std::memset(&d, 0, sizeof d);
+        d.G = nb * H; d.H = H; d.Nq = (int)seq; d.Nk = (int)seq; d.ld = pl.ld; d.acc = acc;
+        d.logit_scale = (double)p->s_q * (double)p->s_k / std::sqrt((double)dh);
+        d.bias = p->rel_bias; d.mask = p->mask; d.s_log = p->s_log; d.bits = p->bits_p; d.codes = codes;
+        rq_prof_begin(ctx, RQ_STEP_SOFTMAX);
+        st = rq_softmax_log2_quant(ctx, &d);
+        rq_prof_end(ctx);
+        if (st != RQ_OK) return st;
+      }
     }
     {
       rq_pv_desc d;

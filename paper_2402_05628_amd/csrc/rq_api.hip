@@ -297,6 +297,35 @@ rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d) {
   return rq_launch_softmax(ctx, d);
 }
 
+rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d) {
+  RQ_CHECK_CTX("rq_qk_softmax_log2_quant");
+  RQ_REQUIRE(d->Q && d->K && d->codes, RQ_ERR_INVALID_ARG, "rq_qk_softmax_log2_quant: Q, K and codes must be non-NULL");
+  RQ_REQUIRE(d->batch >= 0 && d->H > 0 && d->N > 0, RQ_ERR_SHAPE, "rq_qk_softmax_log2_quant: batch = %lld, H = %d, N = %d",
+             (long long)d->batch, d->H, d->N);
+  RQ_REQUIRE(d->d_head == 32 || d->d_head == 64 || d->d_head == 128, RQ_ERR_SHAPE,
+             "rq_qk_softmax_log2_quant: d_head = %d must be 32, 64 or 128", d->d_head);
+  RQ_REQUIRE(rq_qk_softmax_supported(d->N, d->d_head), RQ_ERR_SHAPE,
+             "rq_qk_softmax_log2_quant: N = %d exceeds 288; use rq_qgemm + rq_softmax_log2_quant", d->N);
+  RQ_REQUIRE(d->ld_tok >= (int64_t)d->H * d->d_head && d->ld_tok % 16 == 0, RQ_ERR_SHAPE,
+             "rq_qk_softmax_log2_quant: ld_tok = %lld must be >= H*d_head and a multiple of 16", (long long)d->ld_tok);
+  RQ_REQUIRE(rq_aligned(d->Q, 16) && rq_aligned(d->K, 16) && rq_aligned(d->codes, 16), RQ_ERR_INVALID_ARG,
+             "rq_qk_softmax_log2_quant: Q, K and codes need 16-byte alignment");
+  RQ_REQUIRE(d->ld >= d->N && d->ld % 16 == 0, RQ_ERR_SHAPE, "rq_qk_softmax_log2_quant: ld = %lld must be >= N and a multiple of 16",
+             (long long)d->ld);
+  RQ_REQUIRE(d->q_off >= 0 && d->q_off <= 128 && d->k_off >= 0 && d->k_off <= 128 && d->z_q >= 0 && d->z_q <= 255 && d->z_k >= 0 &&
+                 d->z_k <= 255,
+             RQ_ERR_INVALID_ARG, "rq_qk_softmax_log2_quant: offsets must be in 0..128 and zero-points in 0..255");
+  RQ_REQUIRE(d->bits >= 2 && d->bits <= 8, RQ_ERR_INVALID_ARG, "rq_qk_softmax_log2_quant: bits = %d not in 2..8", d->bits);
+  RQ_REQUIRE(d->s_log > 0.f && std::isfinite(d->s_log), RQ_ERR_INVALID_ARG, "rq_qk_softmax_log2_quant: s_log must be > 0");
+  RQ_REQUIRE(d->logit_scale > 0.0 && std::isfinite(d->logit_scale), RQ_ERR_INVALID_ARG,
+             "rq_qk_softmax_log2_quant: logit_scale must be > 0");
+  RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_qk_softmax_log2_quant: mask %d", d->mask);
+  RQ_NEED_DEVICE();
+  if (d->batch == 0) return RQ_OK;
+  return rq_launch_qk_softmax(ctx, d->Q, d->K, d->ld_tok, d->batch, d->H, d->N, d->d_head, d->q_off, d->z_q, d->k_off, d->z_k,
+                              d->logit_scale, d->bias, d->mask, d->s_log, d->bits, d->codes, d->ld);
+}
+
 rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   RQ_CHECK_CTX("rq_attn_pv");
   RQ_REQUIRE(d->codes && d->V, RQ_ERR_INVALID_ARG, "rq_attn_pv: codes and V must be non-NULL");

@@ -123,3 +123,49 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
                  bits_o=bits_v)
     assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-5)
     assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits_v), "attn_pv codes")
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p,bias,causal", [(2, 3, 197, 64, 4, 4, False, False), (3, 2, 49, 32, 6, 6, True, False),
+                                                                    (2, 2, 257, 64, 4, 4, False, False), (1, 2, 288, 128, 8, 8, False, True),
+                                                                    (2, 2, 64, 64, 8, 8, False, False), (1, 1, 1, 32, 8, 4, False, False),
+                                                                    (1, 2, 33, 64, 8, 6, True, True), (2, 1, 130, 128, 6, 4, False, False)])
+def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causal):
+    """The single-kernel Q.K^T + Softmax-log2 path against the oracle's integer logits and log-sqrt2 codes."""
+    b, ctx = rq
+    print("case", batch, H, seq, dh, bits, bits_p, bias, causal, flush=True)
+    g = np.random.default_rng(seq * 7 + dh + bits)
+    D = H * dh
+    qmax = 2 ** bits - 1
+    # q, k codes of ~N(0,1) values quantized on [-4, 4]
+    s_qk = 8.0 / qmax
+    z_q, z_k = int(g.integers(qmax // 3, 2 * qmax // 3 + 1)), int(g.integers(qmax // 3, 2 * qmax // 3 + 1))
+    codes = np.empty((batch * seq, 3 * D), np.int64)
+    codes[:, :D] = np.clip(np.rint(g.normal(size=(batch * seq, D)) / s_qk) + z_q, 0, qmax)
+    codes[:, D:2 * D] = np.clip(np.rint(g.normal(size=(batch * seq, D)) / s_qk) + z_k, 0, qmax)
+    codes[:, 2 * D:] = 0
+    offq, offk = b.store_offset(bits, z_q), b.store_offset(bits, z_k)
+    st = codes.copy()
+    st[:, :D] -= offq
+    st[:, D:2 * D] -= offk
+    qkv = dev(st.astype(np.int8))
+    ld = _ld(seq)
+    scale = s_qk * s_qk / math.sqrt(dh)
+    bias_a = g.normal(0, 0.5, size=(H, seq, seq)).astype(np.float32) if bias else None
+    s_log = np.float32(0.8)
+    want = np.empty((batch * H, seq, seq), np.int64)
+    for bi in range(batch):
+        r = slice(bi * seq, (bi + 1) * seq)
+        for h in range(H):
+            acc = orc.int_matmul_nt(codes[r, h * dh:(h + 1) * dh] - z_q, codes[r, D + h * dh:D + (h + 1) * dh] - z_k)
+            L = acc.astype(np.float64) * scale
+            if bias:
+                L = L + bias_a[h].astype(np.float64)
+            if causal:
+                L = np.where(np.arange(seq)[None, :] > np.arange(seq)[:, None], -np.inf, L)
+            want[bi * H + h] = orc.softmax_log_quant(L, s_log, bits_p)
+    out = torch.full((batch * H, seq, ld), 99, dtype=torch.uint8, device="cuda")
+    b.rq_qk_softmax_log2_quant(ctx, qkv, batch, seq, H, dh, 0, D, offq, z_q, offk, z_k, scale, out, ld, bits_p, s_log=float(s_log),
+                               bias=None if bias_a is None else dev(bias_a), mask=b.MASK_CAUSAL if causal else b.MASK_NONE)
+    got = out.cpu().numpy()
+    assert_codes_close(got[:, :, :seq], want, "fused codes N=%d b=%d" % (seq, bits_p))
+    assert np.all(got[:, :, seq:] == 2 ** bits_p - 1)

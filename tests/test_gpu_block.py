@@ -28,15 +28,16 @@ SMALL = {
 
 
 @pytest.mark.parametrize("name", list(SMALL))
-@pytest.mark.parametrize("chunk_mb", [64, 1])
-def test_block_forward_matches_oracle(rq, name, chunk_mb):
+@pytest.mark.parametrize("chunk_mb,fused", [(64, True), (1, True), (64, False), (1, False)])
+def test_block_forward_matches_oracle(rq, name, chunk_mb, fused):
     b, ctx = rq
     cfg = SMALL[name]
-    print("case", name, chunk_mb, flush=True)
+    print("case", name, chunk_mb, fused, flush=True)
     raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
     P = orc.calibrate_block(raw, cfg_dict(cfg))
     want, t = orc.block_forward(P, raw["x"], keep=True)
     b.set_attn_chunk_bytes(chunk_mb << 20)
+    b.set_attn_fused(fused)
     try:
         blk = b.Block(ctx, cfg, block_to_device(P))
         x = dev(raw["x"])
@@ -45,6 +46,7 @@ def test_block_forward_matches_oracle(rq, name, chunk_mb):
         torch.cuda.synchronize()
     finally:
         b.set_attn_chunk_bytes(64 << 20)
+        b.set_attn_fused(True)
     got = y.cpu().numpy().astype(np.float64)
     ref = np.abs(want).max()
     err = np.abs(got - want).max()
