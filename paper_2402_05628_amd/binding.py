@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librepquant.so")
+LIB_PATH = os.environ.get("REPQUANT_LIB") or os.path.join(_HERE, "librepquant.so")   # override: an experimental build
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

@@ -14,6 +14,10 @@
 #include "qgemm_common.h"
 
 rq_status rq_launch_qgemm_pipe_w4(rq_ctx* ctx, rqg::GemmParams& p);
+#ifdef RQ_GEMM_TS
+static long long* g_debug_ts = nullptr;
+extern "C" void rq_debug_gemm_ts(void* ptr) { g_debug_ts = static_cast<long long*>(ptr); }
+#endif
 rq_status rq_launch_qgemm_pipe_i8(rq_ctx* ctx, rqg::GemmParams& p);
 
 namespace {
@@ -152,6 +156,9 @@ extern "C" rq_status rq_set_gemm_tile(int32_t tile) {
 
 rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   GemmParams p;
+#ifdef RQ_GEMM_TS
+  p.ts = g_debug_ts;
+#endif
   p.M = d->M; p.N = d->N; p.K = d->K;
   p.A = d->A; p.lda = d->lda;
   p.B = static_cast<const uint8_t*>(d->B); p.ldb = d->ldb;

@@ -40,6 +40,9 @@ struct GemmParams {
   int off4[4];   // off_o replicated in the four bytes
   int lo[4], hi[4];
   int tiles_m, tiles_n;
+#ifdef RQ_GEMM_TS
+  long long* ts;
+#endif
 };
 
 __device__ __forceinline__ int swz(int row, int c) {

@@ -244,6 +244,19 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
                                          (__attribute__((address_space(3))) void*)(lb + (wave * 2 + i) * 1024), 16, 0, 0);
     }
   };
+#ifdef RQ_GEMM_TS   // development builds only: per-workgroup cycle stamps of the kernel's phases
+#define RQ_TS(k) do { if (p.ts && tid == 0) p.ts[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+  if (p.ts && tid == 0) {
+    unsigned xcc, hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    p.ts[(size_t)blockIdx.x * 8 + 6] = xcc;
+    p.ts[(size_t)blockIdx.x * 8 + 7] = hw;
+  }
+#else
+#define RQ_TS(k) do { } while (0)
+#endif
+  RQ_TS(0);
   // ---- prologue: S stages in flight ----
 #pragma unroll
   for (int s = 0; s < S; ++s)
@@ -334,6 +347,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
     if (later >= 3) wait_vm<3 * LPS>(); else if (later == 2) wait_vm<2 * LPS>(); else if (later == 1) wait_vm<LPS>(); else wait_vm<0>();
   }
   asm volatile("s_barrier" ::: "memory");
+  RQ_TS(1);
   load_b(0, 0);
 #pragma unroll
   for (int i = 0; i < TM; ++i) load_a(0, 0, i);
@@ -377,12 +391,14 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
   }
   // the ring is idle now: hand the per-column constants over through its first bytes
   EpiLds* el = reinterpret_cast<EpiLds*>(ring);
+  RQ_TS(2);
   __syncthreads();
   if (tid < 128) { el->scale[tid] = ep_f; el->cs[tid] = ep_i; el->is[tid] = ep_is; el->zz[tid] = ep_zz; el->off4[tid] = ep_off; }
   else { el->bias[tid - 128] = ep_f; el->dw[tid - 128] = ep_i; }
   __syncthreads();
   if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
   else epilogue_wide<TM, TN, ACT, OUT, true>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  RQ_TS(3);
 }
 
 

@@ -1,0 +1,254 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared entry point, the
+Python structures have the C layout, and every call validates its arguments before touching a device."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "repquant.h")
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2402_05628_amd import binding
+    return binding
+
+
+@pytest.fixture()
+def host_ctx(b):
+    ctx = b.Context(None)        # host-only context: validation runs, valid calls return RQ_ERR_UNSUPPORTED
+    yield ctx
+    ctx.close()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^(?:rq_status|size_t|int32_t|void|const char\*)\s+(rq_\w+)\s*\(", text, flags=re.M)
+    assert len(names) >= 20
+    return names
+
+
+def test_every_declared_symbol_is_exported(b):
+    missing = [n for n in _declared_functions() if not hasattr(b.lib, n)]
+    assert not missing, missing
+
+
+def test_named_hot_path_calls_are_declared():
+    names = set(_declared_functions())
+    for n in ("rq_reparam_fold", "rq_ln_quant", "rq_qgemm", "rq_softmax_log2_quant", "rq_attn_pv", "rq_block_forward"):
+        assert n in names
+
+
+def test_structures_have_the_c_layout(b, tmp_path):
+    """sizeof and the offset of the last field of every descriptor, as gcc lays the header out."""
+    pairs = [("rq_fold_desc", b.FoldDesc), ("rq_wq_desc", b.WqDesc), ("rq_ln_desc", b.LnDesc), ("rq_gemm_desc", b.GemmDesc),
+             ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_pv_desc", b.PvDesc),
+             ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw)]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
+    for cname, cls in pairs:
+        last = cls._fields_[-1][0]
+        lines.append('  printf("%s %%zu %%zu\\n", sizeof(%s), offsetof(%s, %s));' % (cname, cname, cname, last))
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    got = {l.split()[0]: (int(l.split()[1]), int(l.split()[2])) for l in out if l.strip()}
+    for cname, cls in pairs:
+        last = cls._fields_[-1][0]
+        assert got[cname] == (C.sizeof(cls), getattr(cls, last).offset), cname
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    src = tmp_path / "plain.c"
+    src.write_text('#include "repquant.h"\nint main(void) { return (int)RQ_OK; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                    str(tmp_path / "plain")], check=True)
+
+
+def test_store_offset_rule(b):
+    # off = z when code - z fits int8 for every code, otherwise 128
+    for bits in range(2, 9):
+        for z in range(0, 2 ** bits):
+            off = b.store_offset(bits, z)
+            lo, hi = -off, 2 ** bits - 1 - off
+            assert -128 <= lo and hi <= 127
+            if -z >= -128 and 2 ** bits - 1 - z <= 127:
+                assert off == z
+            else:
+                assert off == 128
+
+
+FAKE = 0x10000     # non-NULL, 64 KiB aligned: never dereferenced, validation fails or the host-only context refuses first
+
+
+def _ln_desc(b, **kw):
+    d = b.LnDesc(T=4, D=64, norm_kind=b.NORM_LAYERNORM, eps=1e-6, x=FAKE, ldx=64, gamma_t=FAKE, beta_t=FAKE, s_tilde=0.1,
+                 z_tilde=3, bits=4, store_off=3, q=FAKE, ldq=64, rowsum=None)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def _status(b, ctx, fn, desc):
+    return fn(ctx.handle, C.byref(desc))
+
+
+def test_ln_quant_validation(b, host_ctx):
+    fn = b.lib.rq_ln_quant
+    assert _status(b, host_ctx, fn, _ln_desc(b)) == 3                   # valid: refused only for lack of a device
+    assert "host-only" in b.lib.rq_last_error(host_ctx.handle).decode() or b.lib.rq_last_error(host_ctx.handle)
+    assert _status(b, host_ctx, fn, _ln_desc(b, x=None)) == 1
+    assert _status(b, host_ctx, fn, _ln_desc(b, bits=9)) == 1
+    assert _status(b, host_ctx, fn, _ln_desc(b, bits=1)) == 1
+    assert _status(b, host_ctx, fn, _ln_desc(b, s_tilde=0.0)) == 1
+    assert _status(b, host_ctx, fn, _ln_desc(b, s_tilde=float("nan"))) == 1
+    assert _status(b, host_ctx, fn, _ln_desc(b, D=66)) == 2             # D % 4
+    assert _status(b, host_ctx, fn, _ln_desc(b, ldx=32)) == 2           # pitch below D
+    assert _status(b, host_ctx, fn, _ln_desc(b, T=-1)) == 2
+    assert _status(b, host_ctx, fn, _ln_desc(b, x=FAKE + 4)) == 1       # misaligned
+    assert _status(b, host_ctx, fn, _ln_desc(b, store_off=200)) == 1    # code - off would not fit int8
+    msg = b.lib.rq_last_error(host_ctx.handle).decode()
+    assert "rq_ln_quant" in msg
+
+
+def test_null_context_and_null_descriptor(b, host_ctx):
+    assert b.lib.rq_ln_quant(None, C.byref(_ln_desc(b))) == 1
+    assert b.lib.rq_ln_quant(host_ctx.handle, None) == 1
+    assert b.lib.rq_qgemm(host_ctx.handle, None) == 1
+    assert b.lib.rq_softmax_log2_quant(host_ctx.handle, None) == 1
+    assert b.lib.rq_attn_pv(host_ctx.handle, None) == 1
+    assert b.lib.rq_reparam_fold(host_ctx.handle, None) == 1
+    assert len(b.lib.rq_last_error(None)) > 0
+
+
+def _gemm_desc(b, **kw):
+    d = b.GemmDesc()
+    d.M, d.N, d.K = 64, 64, 64
+    d.A, d.lda, d.a_off, d.z_a, d.s_a = FAKE, 64, 8, 8, 0.1
+    d.B, d.ldb, d.b_format = FAKE, 64, b.W_I8_BAKED
+    d.s_b, d.z_b, d.colsum_b = FAKE, FAKE, FAKE
+    d.batch_outer, d.batch_inner, d.n_seg = 1, 1, 1
+    d.out_f32, d.ldf = FAKE, 64
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_qgemm_validation(b, host_ctx):
+    fn = b.lib.rq_qgemm
+    assert _status(b, host_ctx, fn, _gemm_desc(b)) == 3
+    assert _status(b, host_ctx, fn, _gemm_desc(b, A=None)) == 1
+    assert _status(b, host_ctx, fn, _gemm_desc(b, out_f32=None)) == 1        # no output requested
+    assert _status(b, host_ctx, fn, _gemm_desc(b, K=60)) == 2                # K % 64
+    assert _status(b, host_ctx, fn, _gemm_desc(b, lda=32)) == 2
+    assert _status(b, host_ctx, fn, _gemm_desc(b, b_format=7)) == 1
+    assert _status(b, host_ctx, fn, _gemm_desc(b, s_a=-1.0)) == 1
+    assert _status(b, host_ctx, fn, _gemm_desc(b, b_format=b.W_U4, ldb=16)) == 2    # packed rows hold K/2 bytes
+    assert _status(b, host_ctx, fn, _gemm_desc(b, b_format=b.W_I8_CENTERED)) == 1   # centered weights need rowsum_a
+    assert _status(b, host_ctx, fn, _gemm_desc(b, act=5)) == 1
+
+
+def test_softmax_and_pv_validation(b, host_ctx):
+    sd = dict(G=2, H=2, Nq=8, Nk=8, ld=16, acc=FAKE, logit_scale=0.1, bias=None, mask=0, s_log=1.0, bits=4, codes=FAKE)
+    ok = b.SoftmaxDesc(**sd)
+    assert b.lib.rq_softmax_log2_quant(host_ctx.handle, C.byref(ok)) == 3
+    for k, v, want in (("bits", 9, 1), ("ld", 6, 2), ("ld", 8200, 2), ("s_log", 0.0, 1), ("logit_scale", -1.0, 1), ("mask", 3, 1),
+                       ("acc", None, 1), ("Nk", 0, 2)):
+        bad = b.SoftmaxDesc(**{**sd, k: v})
+        assert b.lib.rq_softmax_log2_quant(host_ctx.handle, C.byref(bad)) == want, (k, v)
+    causal = b.SoftmaxDesc(**{**sd, "mask": 1, "Nq": 4})
+    assert b.lib.rq_softmax_log2_quant(host_ctx.handle, C.byref(causal)) == 2
+
+    pd = dict(batch=1, H=2, Nq=8, Nk=8, d_head=32, ld=16, codes=FAKE, V=FAKE, ldv=192, s_log=1.0, s_v=0.1, z_v=3, v_off=3, bits_p=4,
+              mask=0, out_f32=FAKE, ldf=64)
+    assert b.lib.rq_attn_pv(host_ctx.handle, C.byref(b.PvDesc(**pd))) == 3
+    for k, v, want in (("d_head", 48, 2), ("ld", 8, 2), ("bits_p", 1, 1), ("s_v", 0.0, 1), ("V", None, 1), ("out_f32", None, 1),
+                       ("ldv", 32, 2)):
+        bad = b.PvDesc(**{**pd, k: v})
+        assert b.lib.rq_attn_pv(host_ctx.handle, C.byref(bad)) == want, (k, v)
+
+    qd = dict(batch=1, H=2, N=8, d_head=32, Q=FAKE, K=FAKE, ld_tok=192, q_off=3, z_q=3, k_off=3, z_k=3, logit_scale=0.1, bias=None,
+              mask=0, s_log=1.0, bits=4, codes=FAKE, ld=16)
+    assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(b.QkSoftmaxDesc(**qd))) == 3
+    for k, v, want in (("N", 300, 2), ("d_head", 48, 2), ("ld", 8, 2), ("bits", 0, 1), ("Q", None, 1), ("ld_tok", 40, 2)):
+        bad = b.QkSoftmaxDesc(**{**qd, k: v})
+        assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(bad)) == want, (k, v)
+
+
+def test_fold_and_weight_pack_validation(b, host_ctx):
+    fd = dict(D=64, D_out=32, s_ch=FAKE, z_ch=FAKE, gamma=FAKE, beta=FAKE, W=FAKE, b=FAKE, s_log=1.0, s_tilde=FAKE, z_tilde=FAKE,
+              gamma_t=FAKE, beta_t=FAKE, W_t=FAKE, b_t=FAKE, s_log_pair=None)
+    assert b.lib.rq_reparam_fold(host_ctx.handle, C.byref(b.FoldDesc(**fd))) == 3
+    for k, v, want in (("D", 0, 2), ("s_ch", None, 1), ("gamma_t", None, 1)):
+        assert b.lib.rq_reparam_fold(host_ctx.handle, C.byref(b.FoldDesc(**{**fd, k: v}))) == want, (k, v)
+    wq = b.WqDesc()
+    assert b.lib.rq_weight_quant_pack(host_ctx.handle, C.byref(wq)) in (1, 2)      # all-zero descriptor
+
+
+def test_block_forward_validation(b, host_ctx):
+    p = b.BlockParams()
+    assert b.lib.rq_block_workspace_bytes(C.byref(p), 1, 8) == 0          # D = 0
+    rc = b.lib.rq_block_forward(host_ctx.handle, C.byref(p), C.c_void_p(FAKE), C.c_void_p(FAKE), 1, 8, C.c_void_p(FAKE), 1 << 20)
+    assert rc in (1, 2)
+    assert "rq_block_forward" in b.lib.rq_last_error(host_ctx.handle).decode()
+    assert b.lib.rq_block_forward(None, C.byref(p), None, None, 1, 8, None, 0) == 1
+    assert b.lib.rq_set_attn_chunk_bytes(10) == 1
+    assert b.lib.rq_set_gemm_tile(99) == 1
+
+
+def test_workspace_bytes_grow_with_the_problem(b):
+    def params(D, H, Dm):
+        p = b.BlockParams()
+        p.D, p.H, p.Dm = D, H, Dm
+        return p
+    small = b.lib.rq_block_workspace_bytes(C.byref(params(384, 6, 1536)), 1, 197)
+    big = b.lib.rq_block_workspace_bytes(C.byref(params(768, 12, 3072)), 64, 197)
+    assert 0 < small < big
+    # ViT-B at batch 64: int8 activations, the float residual stream and the attention scratch stay far below HBM size
+    assert big < (1 << 30)
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    from paper_2402_05628_amd import synth
+    cfg = synth.CONFIGS[0]
+    a, c = synth.make_block(cfg, 0, 0), synth.make_block(cfg, 0, 0)
+    d = synth.make_block(cfg, 0, 1)
+    for k, v in a.items():
+        if v is None:
+            assert c[k] is None
+            continue
+        assert np.array_equal(v, c[k]), k
+    assert not np.array_equal(a["x"], d["x"])
+    assert a["x"].shape == (cfg.tokens, cfg.D) and a["x"].dtype == np.float32
+    assert a["w_qkv"].shape == (3 * cfg.D, cfg.D) and a["w_fc2"].shape == (cfg.D, cfg.Dm)
+    # the LN input carries a few channels tens of times larger than the median channel
+    ch = np.abs(a["x"]).mean(axis=0)
+    assert ch.max() / np.median(ch) > 20
+    shapes = [(c_.batch, c_.seq, c_.D, c_.H, c_.Dm) for c_ in synth.CONFIGS]
+    assert shapes[1] == (64, 197, 768, 12, 3072)
+    assert shapes[3][1:] == (2048, 4096, 32, 11008)
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2402_05628_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|#include\s+\"[^\"]*oracle", text, flags=re.M), os.path.join(dirpath, f)
+    for f in ("paper_2402_05628_amd/binding.py", "paper_2402_05628_amd/__init__.py", "paper_2402_05628_amd/_build.py"):
+        assert "oracle" not in open(os.path.join(ROOT, f)).read().lower(), f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr or "one GPU" in r.stderr
