@@ -20,7 +20,7 @@ Two tiers:
   quantization with a parity-selected scale.  The HIP path is compared to this
   tier; the definition tier pins it (the paper states the two are equal).
 
-Conventions the paper leaves open (each is listed again in the design doc):
+Conventions the paper leaves open:
   * rounding is round-half-to-even (numpy rint);
   * variance is the population variance; eps is a parameter;
   * z~ = rint(mean(z)) so that r2 = z - z~ is an integer vector;
