@@ -40,6 +40,7 @@ struct GemmParams {
   int off4[4];   // off_o replicated in the four bytes
   int lo[4], hi[4];
   int tiles_m, tiles_n;
+  int force_tall;   // host only: take the 320-row tile wherever it exists (testing)
 #ifdef RQ_GEMM_TS
   long long* ts;
 #endif
@@ -49,20 +50,18 @@ __device__ __forceinline__ int swz(int row, int c) {
   return (row >> 1) * 128 + (((((row & 1) << 2) | c) ^ ((row >> 1) & 7)) << 4);
 }
 
-// erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7), enough for
-// 8-bit re-quantization of GELU outputs; GELU(y) = y * Phi(y), Phi(y) = 1 - r/2 (y >= 0) or r/2 (y < 0).
+// GELU(y) = y Phi(y) = max(y, 0) - |y| q(|y|),  q(a) = erfc(a / sqrt 2) / 2, with erfc by the rational-times-Gaussian formula
+// 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7 on erf): t = 1 / (1 + p a / sqrt 2), q = (a1 t + ... + a5 t^5) e^(-a^2 / 2) / 2.
+// The constants below carry the 1/sqrt 2 and the 1/2; rcp and exp2 are the raw hardware approximations (1 ulp).
 __device__ __forceinline__ float gelu_f(float y) {
-  const float ax = fabsf(y) * 0.70710678118654752f;
-  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  p *= t;
-  const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
-  const float hr = 0.5f * p * e;
-  const float phi = y >= 0.f ? 1.0f - hr : hr;
-  return y * phi;
+  const float ay = fabsf(y);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.23164189f, ay, 1.0f));
+  float p = fmaf(0.5307027145f, t, -0.7265760135f);
+  p = fmaf(p, t, 0.7107068705f);
+  p = fmaf(p, t, -0.142248368f);
+  p = fmaf(p, t, 0.127414796f);
+  const float e = __builtin_amdgcn_exp2f(y * y * -0.72134752044f);
+  return fmaf(-ay, (p * t) * e, fmaxf(y, 0.f));
 }
 
 __device__ __forceinline__ float silu_f(float y) {

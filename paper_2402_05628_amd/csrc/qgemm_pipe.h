@@ -2,6 +2,8 @@
 // Included by the per-format instantiation units.
 #pragma once
 
+#include <type_traits>
+
 #include "qgemm_common.h"
 
 namespace rqg {
@@ -150,6 +152,67 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
   }
 }
 
+// Epilogue for float outputs with a residual (proj, FC2): y = s_a s_w[n] (acc + corrections) + b[n] + residual.
+// In the accumulator layout a lane owns 4 consecutive channels of one token, so direct stores would touch 32-byte
+// pieces of 32 different rows per instruction.  Each wavefront instead passes 32 x 64 outputs at a time through its
+// own 8.5 KB of the idle ring (row pitch 68 floats: conflict-free both ways) and then reads, adds and writes whole
+// 256-byte row segments, 16 lanes per row; the residual segments are requested before the LDS round trip.
+template <int TM, int TN, bool CHECK>
+__device__ __forceinline__ void epilogue_rows_f32(const GemmParams& p, v16i (&acc)[TN][TM], const EpiLds* el, const int (&rs)[TM],
+                                                  float* stage, int m0, int n0, int wm0, int wn0, int lane) {
+  static_assert(TN == 2, "64 output columns per wavefront");
+  constexpr int PITCH = 68;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int rrow = lane >> 4, rcol = (lane & 15) * 4;        // read-back: 4 rows x 16 float4 per pass
+  const bool corr = p.da != 0 || p.centered;
+  const int Mi = (int)p.M;
+  const int ncol = n0 + wn0 + rcol;
+  const bool col_ok = ncol < p.N;
+  const float* const residual = p.residual;
+  float* const out = p.out_f32;
+  const int64_t ldr = p.ldr, ldf = p.ldf;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int mb = m0 + wm0 + i * 32;
+    float4 res[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int m = mb + r * 4 + rrow;
+      res[r] = (col_ok && (!CHECK || m < Mi)) ? *reinterpret_cast<const float4*>(residual + (int64_t)m * ldr + ncol)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int nl = wn0 + j * 32 + 8 * g + half * 4;
+        const float4 sc = *reinterpret_cast<const float4*>(&el->scale[nl]);
+        const float4 bi = *reinterpret_cast<const float4*>(&el->bias[nl]);
+        int t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = acc[j][i][4 * g + e];
+        if (corr) {
+          const v4i cs = *reinterpret_cast<const v4i*>(&el->cs[nl]);
+          const v4i dw = *reinterpret_cast<const v4i*>(&el->dw[nl]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t[e] += cs[e] + dw[e] * rs[i];
+        }
+        const float4 y = make_float4(fmaf((float)t[0], sc.x, bi.x), fmaf((float)t[1], sc.y, bi.y), fmaf((float)t[2], sc.z, bi.z),
+                                     fmaf((float)t[3], sc.w, bi.w));
+        *reinterpret_cast<float4*>(stage + l32 * PITCH + j * 32 + 8 * g + half * 4) = y;
+      }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // this wavefront's own writes; no other wavefront touches `stage`
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int m = mb + r * 4 + rrow;
+      const float4 y = *reinterpret_cast<const float4*>(stage + (r * 4 + rrow) * PITCH + rcol);
+      if (col_ok && (!CHECK || m < Mi))
+        *reinterpret_cast<float4*>(out + (int64_t)m * ldf + ncol) = make_float4(y.x + res[r].x, y.y + res[r].y, y.z + res[r].z, y.w + res[r].w);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // reads done before the next pass overwrites the region
+  }
+}
+
 // ---- pipelined kernel ------------------------------------------------------------------------------------------------
 // One workgroup (4 wavefronts) owns one 256 x 128 output tile (wavefront tile 128 x 64) and walks K in steps of 64
 // through an S-stage LDS ring.
@@ -166,24 +229,31 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
 // Two workgroups share a CU, so one runs its epilogue / prologue while the other feeds the matrix cores.  Tiles are
 // dealt to the 8 XCDs in contiguous ranges (workgroup b runs on XCD b % 8) so that the tiles in flight on one XCD
 // share activation rows and weight columns in that XCD's L2.
+template <int R, class F> __device__ __forceinline__ void static_for_down(F&& f) {   // f(R), f(R-1), ..., f(0), each a constant
+  if constexpr (R >= 0) {
+    f(std::integral_constant<int, R>{});
+    static_for_down<R - 1>(f);
+  }
+}
+
 template <int N> __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);   // vmcnt <= N, other counters unconstrained
 }
 
-template <bool W4, int S, int ACT, int OUT>
-__global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) {
-  constexpr int BM = 256, BN = 128, TM = 4, TN = 2;
+template <bool W4, int S, int ACT, int OUT, int TM>
+__global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const GemmParams p) {
+  constexpr int BM = 64 * TM, BN = 128, TN = 2;       // TM = 4: 256 x 128 tiles, two workgroups per CU; TM = 5: 320 x 128, one
   constexpr int A_BYTES = BM * 64;
   constexpr int B_BYTES = W4 ? BN * 32 : BN * 64;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int LPS = W4 ? 5 : 6;                     // loads per thread and stage
-  static_assert(S >= 2 && S <= 4, "ring depth");
+  constexpr int LPS = TM + (W4 ? 1 : 2);              // loads per thread and stage
+  static_assert(S >= 2 && (S - 1) * LPS <= 63, "ring depth (the load counter holds 63)");
   extern __shared__ __align__(16) int8_t ring[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 64;
+  const int wm0 = (wave >> 1) * (32 * TM), wn0 = (wave & 1) * 64;
   const int l32 = lane & 31, half = lane >> 5;
 
   // tile of this workgroup: XCD b % 8 gets the contiguous range [xcd * per_xcd, ...) of the tile list (n fastest)
@@ -199,14 +269,14 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
   // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
   // lane l lands at 16-byte slot l of a 1 KB block = 16 tile rows of 64 B; the chunk that belongs at position
   // (lane & 3) of row (lane >> 2) is chunk ((lane & 3) - (row >> 2)) & 3
-  unsigned aofs[4], bofs[2];
+  unsigned aofs[TM], bofs[2];
   {
     const int dl_row = lane >> 2;
     const int dl_c = ((lane & 3) - (dl_row >> 2)) & 3;
     const int Mi = (int)p.M;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int m = m0 + wave * 64 + i * 16 + dl_row;
+    for (int i = 0; i < TM; ++i) {
+      int m = m0 + (wave * TM + i) * 16 + dl_row;
       m = m < Mi ? m : Mi - 1;
       aofs[i] = (unsigned)m * (unsigned)p.lda + (unsigned)(dl_c * 16);
     }
@@ -231,9 +301,9 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
     int8_t* la = ring + slot * STAGE;
     int8_t* lb = la + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gA + (aofs[i] + (unsigned)kt * 64u)),
-                                       (__attribute__((address_space(3))) void*)(la + (wave * 4 + i) * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(la + (wave * TM + i) * 1024), 16, 0, 0);
     if (W4) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[0] + (unsigned)kt * 32u)),
                                        (__attribute__((address_space(3))) void*)(lb + wave * 1024), 16, 0, 0);
@@ -280,29 +350,36 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
     for (int j = 0; j < TN; ++j) {
       int n = n0 + wn0 + j * 32 + l32;
       n = n < p.N ? n : p.N - 1;
-      zb4[j] = p.z_b[n] * 0x01010101;
+      zb4[j] = (int)((unsigned)(p.z_b[n] * 0x01010101) - 0x80808080u);   // z - 0x80 per byte (mod 2^32)
     }
   }
   v4i fa[TM];      // activation fragments of the sub-step being multiplied
-  v4i fb[TN];      // weight fragments of the sub-step being multiplied
-  v4i bnext[TN];   // W4: packed weights of the current k-step; int8: weight fragments of the next sub-step
+  v4i fb[TN];      // weight fragments of sub-step 0 (of the current, later of the next k-step)
+  v4i fbn[TN];     // weight fragments of sub-step 1
+  v4i bpk[TN];     // W4: the 16-byte packet that holds this lane's 32 codes of the k-step
   auto load_a = [&](int slot, int s, int i) { fa[i] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + a_off[s] + i * 2048); };
-  auto load_b = [&](int slot, int s) {   // W4: only at s == 0 (one packet covers both sub-steps)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bnext[j] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[j][W4 ? 0 : s]);
-  };
-  auto take_b = [&](int s) {             // fb <- weights of sub-step s (unpack nibbles, subtract the zero-point)
+  // weights of sub-step s of the stage in `slot` -> dst; W4: s == 0 also fetches the packet, s == 1 reuses it
+  auto unpack = [&](v4i (&dst)[TN], int s) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      if (W4) {
-        const int d0 = bnext[j][2 * s], d1 = bnext[j][2 * s + 1], z4 = zb4[j];
-        fb[j][0] = (((d0 & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
-        fb[j][1] = ((((d0 >> 4) & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
-        fb[j][2] = (((d1 & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
-        fb[j][3] = ((((d1 >> 4) & 0x0F0F0F0F) | 0x80808080) - z4) ^ 0x80808080;
-      } else {
-        fb[j] = bnext[j];
-      }
+      const int d0 = bpk[j][2 * s], d1 = bpk[j][2 * s + 1], z4 = zb4[j];
+      dst[j][0] = (int)((unsigned)(d0 & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
+      dst[j][1] = (int)((unsigned)((d0 >> 4) & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
+      dst[j][2] = (int)((unsigned)(d1 & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
+      dst[j][3] = (int)((unsigned)((d1 >> 4) & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
+    }
+  };
+  auto unpack_dword = [&](v4i (&dst)[TN], int s, int idx) {   // one of the 8 operand dwords: idx = j * 4 + c
+    const int j = idx >> 2, c = idx & 3;
+    const int d = bpk[j][2 * s + (c >> 1)];
+    // per byte: code - z without borrow across bytes = ((code | 0x80) - z) ^ 0x80, with 0x80 - z folded into zb4
+    dst[j][c] = (int)((unsigned)(((c & 1) ? (d >> 4) : d) & 0x0F0F0F0F) - (unsigned)zb4[j]) ^ 0x80808080;
+  };
+  auto fetch_b = [&](int slot, int s, v4i (&dst)[TN]) {   // int8 weights: fragments straight from LDS; W4: the packet (s == 0 only)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if (W4) bpk[j] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[j][0]);
+      else dst[j] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[j][W4 ? 0 : s]);
     }
   };
   v16i acc[TN][TM];
@@ -331,7 +408,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
       ep_i = p.centered ? 128 - p.z_b[n] : 0;
     }
   }
-  int rs[TM] = {0, 0, 0, 0};
+  int rs[TM] = {};
   if (p.centered) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -344,51 +421,78 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
   // stage 0 has landed when at most the loads of stages 1 .. S-1 are outstanding
   {
     const int later = nk - 1 < S - 1 ? nk - 1 : S - 1;
-    if (later >= 3) wait_vm<3 * LPS>(); else if (later == 2) wait_vm<2 * LPS>(); else if (later == 1) wait_vm<LPS>(); else wait_vm<0>();
+    static_for_down<S - 1>([&](auto RC) {
+      constexpr int r = decltype(RC)::value;
+      if (later == r) wait_vm<r * LPS>();
+    });
   }
   asm volatile("s_barrier" ::: "memory");
   RQ_TS(1);
-  load_b(0, 0);
+  fetch_b(0, 0, fb);
 #pragma unroll
   for (int i = 0; i < TM; ++i) load_a(0, 0, i);
+  if (W4) unpack(fb, 0);
   int slot = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    // ---- sub-step 0 ----
-    take_b(0);
-    if (!W4) load_b(slot, 1);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
-      load_a(slot, 1, i);
-    }
-    take_b(1);
+  // One k-step.  WAIT = stages that may still be in flight behind stage kt+1, ISSUE = refill the slot with stage kt+S,
+  // MORE = a next k-step exists.  While the MFMAs of sub-step 0 run, the weights of sub-step 1 are unpacked into fbn and the
+  // activation fragments are replaced one by one; while those of sub-step 1 run, the ring is refilled and the fragments
+  // (and unpacked weights) of the next k-step's sub-step 0 are fetched.
+  auto step = [&](auto WAITC, auto ISSUEC, auto MOREC, int kt) {
+    constexpr int WAIT = decltype(WAITC)::value;
+    constexpr bool ISSUE = decltype(ISSUEC)::value, MORE = decltype(MOREC)::value;
     const int nslot = slot + 1 == S ? 0 : slot + 1;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      // stage kt+1 has landed when at most the loads of stages kt+2 .. kt+S-1 are outstanding
-      const int rem = nk - 2 - kt;
-      const int later = rem < S - 2 ? rem : S - 2;
-      if (later >= 2) wait_vm<2 * LPS>(); else if (later == 1) wait_vm<LPS>(); else wait_vm<0>();
+    // The issue order below is pinned with scheduling fences: each MFMA is followed by the small piece of VALU / LDS work
+    // that hides behind it, so the matrix pipe never waits for the unpacking.
+    // ---- sub-step 0: multiply with fb; meanwhile build fbn (sub-step 1 weights) and replace the activation fragments ----
+#pragma unroll
+    for (int q = 0; q < TM * TN; ++q) {
+      const int i = q / TN, j = q % TN;
+      acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
+      if (W4) { if (q < 8) unpack_dword(fbn, 1, q); }
+      else if (q < TN) fbn[q] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[q][W4 ? 0 : 1]);
+      if (j == TN - 1) load_a(slot, 1, i);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // ---- sub-step 1; its activation fragments are replaced by those of the next k-step as they are consumed ----
+    if (MORE) {
+      wait_vm<WAIT * LPS>();     // stage kt+1 has landed (this wavefront's share)
+      // every read of stage kt by this wavefront has been issued; once they have returned (lgkmcnt) and all wavefronts
+      // are here, the slot may be refilled and stage kt+1 (landed everywhere) may be read
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      fetch_b(nslot, 0, fb);
+      if (ISSUE) issue(slot, kt + S);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- sub-step 1: multiply with fbn; meanwhile fetch the next k-step's sub-step 0 operands ----
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
-      if (more) {
-        if (i == 0) {
-          // every read of stage kt by this wavefront has been issued; once they have returned (lgkmcnt) and all
-          // wavefronts are here, the slot may be refilled and stage kt+1 (already landed everywhere) may be read
-          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-          if (kt + S < nk) issue(slot, kt + S);
-          load_b(nslot, 0);
+    for (int q = 0; q < TM * TN; ++q) {
+      const int i = q / TN, j = q % TN;
+      acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fbn[j], fa[i], acc[j][i], 0, 0, 0);
+      if (MORE) {
+        if (W4) {     // the packet was requested before MFMA 0; unpack it behind the later MFMAs
+          if (TM * TN >= 10) {
+            if (q >= 2 && q < 10) unpack_dword(fb, 0, q - 2);
+          } else {
+            if (q >= 2 && q < 6) unpack_dword(fb, 0, q - 2);
+            if (q >= 6) { unpack_dword(fb, 0, 4 + 2 * (q - 6)); unpack_dword(fb, 0, 5 + 2 * (q - 6)); }
+          }
         }
-        load_a(nslot, 0, i);
+        if (j == TN - 1) load_a(nslot, 0, i);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     slot = nslot;
-  }
+  };
+  using std::integral_constant;
+  int kt = 0;
+  for (; kt + S < nk; ++kt) step(integral_constant<int, S - 2>{}, integral_constant<bool, true>{}, integral_constant<bool, true>{}, kt);
+  // the last min(S, nk) k-steps: nothing left to issue, fewer and fewer stages in flight (r = k-steps after this one)
+  static_for_down<S - 1>([&](auto RC) {
+    constexpr int r = decltype(RC)::value;
+    if (r < nk) {     // uniform
+      step(integral_constant<int, (r > 0 ? r - 1 : 0)>{}, integral_constant<bool, false>{}, integral_constant<bool, (r > 0)>{}, kt);
+      ++kt;
+    }
+  });
   // the ring is idle now: hand the per-column constants over through its first bytes
   EpiLds* el = reinterpret_cast<EpiLds*>(ring);
   RQ_TS(2);
@@ -396,37 +500,58 @@ __global__ __launch_bounds__(256, 2) void qgemm_pipe_kernel(const GemmParams p) 
   if (tid < 128) { el->scale[tid] = ep_f; el->cs[tid] = ep_i; el->is[tid] = ep_is; el->zz[tid] = ep_zz; el->off4[tid] = ep_off; }
   else { el->bias[tid - 128] = ep_f; el->dw[tid - 128] = ep_i; }
   __syncthreads();
-  if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  if (OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE) {
+    float* stage = reinterpret_cast<float*>(ring + 4096 + wave * (32 * 68 * 4));
+    if (m0 + BM <= (int)p.M) epilogue_rows_f32<TM, TN, false>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
+    else epilogue_rows_f32<TM, TN, true>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
+  } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
   else epilogue_wide<TM, TN, ACT, OUT, true>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
   RQ_TS(3);
 }
 
 
 // host side: one instantiation set per weight format lives in its own translation unit
-template <bool W4, int S, int ACT, int OUT>
+template <bool W4, int S, int ACT, int OUT, int TM>
 rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
-  p.tiles_m = (int)((p.M + 255) / 256);
+  p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
   p.tiles_n = (p.N + 127) / 128;
   const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
-  constexpr int lds_bytes = S * (256 * 64 + (W4 ? 128 * 32 : 128 * 64));
-  static_assert(lds_bytes >= (int)sizeof(EpiLds), "the ring must hold the epilogue constants");
+  constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? 128 * 32 : 128 * 64));
+  static_assert(sizeof(EpiLds) <= 4096 && lds_bytes >= 4096 + 4 * 32 * 68 * 4 && lds_bytes <= 160 * 1024,
+                "the idle ring holds the epilogue constants and the row staging");
   static bool attr_set = false;
   if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT>),
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const int64_t blocks = (ntiles + 7) / 8 * 8;
-  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
   return RQ_OK;
+}
+
+// Tile height.  In units of the time one 256-row tile takes alone on a CU, two co-resident 256-row tiles take about 1.5
+// and a 320-row tile (which owns its CU) 1.25; pick what finishes the busiest CU first.
+inline bool prefer_tall(const rq_ctx* ctx, const GemmParams& p) {
+  if (p.force_tall) return true;
+  const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+  const int64_t tn = (p.N + 127) / 128;
+  const int64_t t256 = ((p.M + 255) / 256) * tn, t320 = ((p.M + 319) / 320) * tn;
+  const double c256 = t256 <= cu ? 1.0 : 1.5 * (double)((t256 + 2 * cu - 1) / (2 * cu));
+  const double c320 = 1.25 * (double)((t320 + cu - 1) / cu);
+  return c320 < c256;
 }
 
 template <bool W4, int S, int ACT>
 rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
-  if (q && !f && !r && !a) return launch_pipe_one<W4, S, ACT, OUT_Q>(ctx, p);
-  if (ACT == RQ_ACT_NONE && f && r && !q && !a) return launch_pipe_one<W4, S, ACT, OUT_F32 | OUT_RES>(ctx, p);
-  return launch_pipe_one<W4, S, ACT, OUT_ANY>(ctx, p);
+  if (q && !f && !r && !a) return launch_pipe_one<W4, S, ACT, OUT_Q, 4>(ctx, p);
+  if (ACT == RQ_ACT_NONE && f && r && !q && !a) {
+    constexpr int S_TALL = W4 ? 6 : 5;       // one workgroup per CU: the ring may take most of the LDS
+    if (prefer_tall(ctx, p)) return launch_pipe_one<W4, S_TALL, RQ_ACT_NONE, OUT_F32 | OUT_RES, 5>(ctx, p);
+    return launch_pipe_one<W4, S, ACT, OUT_F32 | OUT_RES, 4>(ctx, p);
+  }
+  return launch_pipe_one<W4, S, ACT, OUT_ANY, 4>(ctx, p);
 }
 
 template <bool W4, int S>

@@ -67,10 +67,13 @@ def test_accumulator_extremes(rq):
 
 
 @pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4)])
-def test_float_output_bias_residual(rq, bits_a, bits_w):
+@pytest.mark.parametrize("M,tile", [(515, 0), (515, 4), (963, 4), (320, 4)])
+def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
+    """tile 4 takes the 320-row tiles (one workgroup per CU) that large single-wave launches use."""
     b, ctx = rq
-    M, N, K = 515, 384, 256
-    g = np.random.default_rng(11 + bits_a)
+    N, K = 384, 256
+    print("case", bits_a, bits_w, M, tile, flush=True)
+    g = np.random.default_rng(11 + bits_a + M)
     qa, z_a = _act_codes(g, M, K, bits_a)
     lin = random_linear(g, N, K, bits_w)
     res = g.normal(size=(M, N)).astype(np.float32) * 3
@@ -81,14 +84,21 @@ def test_float_output_bias_residual(rq, bits_a, bits_w):
     rs = torch.empty(M, dtype=torch.int32, device="cuda")
     b.rq_rowsum_i8(ctx, A, rs)
     out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
-    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), residual=dev(res), out_f32=out, rowsum_a=rs)
+    b.set_gemm_tile(tile)
+    try:
+        b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), residual=dev(res), out_f32=out, rowsum_a=rs)
+        torch.cuda.synchronize()
+    finally:
+        b.set_gemm_tile(0)
     assert_float_close(out.cpu().numpy(), want, "qgemm f32")
 
 
 @pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
-@pytest.mark.parametrize("act", ["none3", "gelu", "gated"])
+@pytest.mark.parametrize("act", ["none3", "gelu", "gated", "gelu_q_only", "gated_q_only"])
 def test_requantized_output(rq, bits_a, bits_w, bits_o, act):
     b, ctx = rq
+    q_only = act.endswith("_q_only")      # the block's launches: re-quantized codes are the only output
+    act = act.replace("_q_only", "")
     M, K = 301, 256
     N = 384 if act != "gated" else 512
     g = np.random.default_rng(5 + bits_a + len(act))
@@ -124,10 +134,11 @@ def test_requantized_output(rq, bits_a, bits_w, bits_o, act):
         want = orc.uniform_quant(hid, s, z, bits_o)
         off = b.store_offset(bits_o, z)
         out = torch.zeros(want.shape, dtype=torch.int8, device="cuda")
-        outf = torch.zeros(want.shape, dtype=torch.float32, device="cuda")
+        outf = None if q_only else torch.zeros(want.shape, dtype=torch.float32, device="cuda")
         b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w, Dm if act == "gated" else 0),
                    act=b.ACT_GELU if act == "gelu" else b.ACT_SILU_GATED, out_q=out, out_f32=outf, bits_o=bits_o, s_o=[float(s)],
                    z_o=[z], off_o=[off], seg_len=want.shape[1], rowsum_a=rs)
-        assert_float_close(outf.cpu().numpy(), hid, "activation " + act)
+        if not q_only:
+            assert_float_close(outf.cpu().numpy(), hid, "activation " + act)
         got = out.cpu().numpy().astype(np.int64) + off
     assert_codes_close(got, want, "requant %s b%d" % (act, bits_o))
