@@ -1,220 +1,11 @@
-// Fused Q.K^T + Softmax-log2 quantizer for short rows (up to 288 keys): the exact int32 accumulators of one query
-// tile against ALL keys stay in registers, so the [G, N, N] logits never travel through memory
-// (attention Eq. of Section "Transformer blocks"; Eq. (3.3-1), second line).  Same arithmetic as rq_qgemm in
-// activation mode followed by rq_softmax_log2_quant:
-//   acc[i, j] = sum_c (q[i, c] - z_q)(k[j, c] - z_k)                         exact, int32, on the int8 matrix cores
-//   code[i, j] = clip(round(2 (log2 sum_k 2^(t_k - t_max) - (t_j - t_max) + log2 s)), 0, 2^b - 1),  t = scale * acc * log2 e (+ bias)
-// One workgroup of 8 wavefronts serves one (batch item, head): the keys are staged once in LDS (chunk-rotated rows, so
-// the 32-row MFMA operand reads are conflict-free), each wavefront owns 32 query rows.  Keys are the ROW operand and
-// queries the COLUMN operand, so a lane holds 4 consecutive keys of one query row per MFMA tile; the two lanes l and
-// l+32 together hold a whole row: the row maximum / sum need one lane exchange, and after two v_permlane32_swap each
-// lane owns 16 consecutive codes and issues one 16-byte store.
-#include "rq_internal.h"
+// Fused Q.K^T + Softmax-log2 quantizer: entry point; the kernels are instantiated per head width in their own files.
+#include "qk_softmax.h"
 
-namespace {
+using rqks::QksParams;
+rq_status rq_launch_qk_softmax_d32(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
+rq_status rq_launch_qk_softmax_d64(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
+rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-struct QksParams {
-  const int8_t* Q;
-  const int8_t* K;
-  int64_t ldq, ldk;            // row pitch (bytes) of the token-major tensors
-  int64_t so, si;              // strides between batch items / heads
-  int H, N;                    // heads, tokens per group (Nq == Nk)
-  int dq, dk;                  // storage offset minus zero-point of Q and of K
-  const float* bias;           // [H, N, N] or NULL
-  int causal;
-  double c1, log2s;            // logit_scale * log2(e), log2(s_log)
-  int qmax;
-  uint8_t* codes;
-  int64_t ld;                  // row pitch of the codes
-  int tiles;                   // ceil(N / 32)
-};
-
-template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE>
-__global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
-  constexpr int DH = KSTEPS * 32;
-  constexpr int CPR = DH / 16;          // 16-byte chunks per key row
-  constexpr int RPL = 16 / CPR;         // key rows per 256 bytes
-  extern __shared__ __align__(16) int8_t ks[];   // [NT * 32][DH], chunk c of row r stored at position (c + r / RPL) % CPR
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int64_t g = blockIdx.x;
-  const int64_t b = g / p.H;
-  const int h = (int)(g - b * p.H);
-  const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
-  const int8_t* Kg = p.K + b * p.so + (int64_t)h * p.si;
-  const int nt = p.tiles;
-
-  // ---- stage the keys of this group in LDS ----
-  for (int id = tid; id < nt * 32 * CPR; id += 512) {
-    const int r = id / CPR, c = id - r * CPR;
-    const int rr = r < p.N ? r : p.N - 1;
-    const v4i v = *reinterpret_cast<const v4i*>(Kg + (int64_t)rr * p.ldk + c * 16);
-    *reinterpret_cast<v4i*>(ks + r * DH + (((c + r / RPL) % CPR) * 16)) = v;
-  }
-  __syncthreads();
-
-  const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
-  const bool corr = p.dq != 0 || p.dk != 0;
-  for (int it = wave; it < nt; it += 8) {       // wavefront-uniform
-    const int qi = it * 32 + l32;
-    const int qi_ld = qi < p.N ? qi : p.N - 1;
-    v4i fq[KSTEPS];
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) fq[s] = *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
-    int base = 0;
-    if (corr) {
-      v16i rq;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) rq[e] = 0;
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) rq = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, fq[s], rq, 0, 0, 0);
-      base = p.dk * rq[0] + DH * p.dq * p.dk;   // every element of rq holds rowsum(q'[i, :]) of this lane's query row
-    }
-    v16i acc[NT];
-#pragma unroll
-    for (int jt = 0; jt < NT; ++jt) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[jt][e] = base;
-      if (jt < nt) {
-        v4i fk[KSTEPS];
-        const int r = jt * 32 + l32;
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
-          fk[s] = *reinterpret_cast<const v4i*>(ks + r * DH + ((((s * 2 + half) + r / RPL) % CPR) * 16));
-        if (p.dq != 0) {
-          v16i ck;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) ck[e] = 0;
-#pragma unroll
-          for (int s = 0; s < KSTEPS; ++s) ck = __builtin_amdgcn_mfma_i32_32x32x32_i8(fk[s], ones, ck, 0, 0, 0);
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[jt][e] += p.dq * ck[e];
-        }
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) acc[jt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fk[s], fq[s], acc[jt], 0, 0, 0);
-      }
-    }
-    // ---- softmax statistics of row qi: this lane holds keys jt*32 + 8*(e/4) + 4*half + e%4 ----
-    const int limit = p.causal ? (qi_ld + 1 < p.N ? qi_ld + 1 : p.N) : p.N;     // valid keys: j < limit
-    const float c1f = (float)p.c1;
-    const float qmaxf = (float)p.qmax;
-    float ssum = 0.f;
-    double C0;
-    double tmax = -1e300;
-    int amax = INT32_MIN;
-    const float* brow = HAS_BIAS ? p.bias + ((int64_t)h * p.N + qi_ld) * p.N : nullptr;
-    if (HAS_BIAS) {
-      // t = acc * c1 + bias * log2(e), kept as the float64 bit pattern is too costly in registers: recomputed below
-#pragma unroll
-      for (int jt = 0; jt < NT; ++jt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (jt < nt && j < limit) tmax = fmax(tmax, fma((double)acc[jt][e], p.c1, (double)brow[j] * 1.4426950408889634));
-        }
-      tmax = fmax(tmax, __shfl_xor(tmax, 32, 64));
-#pragma unroll
-      for (int jt = 0; jt < NT; ++jt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (jt < nt && j < limit)
-            ssum += __builtin_amdgcn_exp2f((float)(fma((double)acc[jt][e], p.c1, (double)brow[j] * 1.4426950408889634) - tmax));
-        }
-    } else {
-#pragma unroll
-      for (int jt = 0; jt < NT; ++jt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-          const bool ok = jt < nt && j < limit;
-          acc[jt][e] = ok ? acc[jt][e] : INT32_MIN;      // masked and padding keys
-          amax = max(amax, acc[jt][e]);
-        }
-      amax = max(amax, __shfl_xor(amax, 32, 64));
-#pragma unroll
-      for (int jt = 0; jt < NT; ++jt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int d = acc[jt][e] == INT32_MIN ? -0x40000000 : acc[jt][e] - amax;
-          acc[jt][e] = d;
-          ssum += __builtin_amdgcn_exp2f((float)d * c1f);     // exp2(-huge) = 0
-        }
-    }
-    ssum += __shfl_xor(ssum, 32, 64);
-    C0 = 2.0 * ((double)__builtin_amdgcn_logf(ssum) + p.log2s);
-    const double m2c = -2.0 * p.c1;
-    const float C0f = (float)C0, m2cf = (float)m2c;
-    // ---- codes ----
-    uint8_t* crow = p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld;
-#pragma unroll
-    for (int jt = 0; jt < NT; ++jt) {
-      if (jt < nt) {
-        unsigned pk[4];
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          unsigned w = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j = jt * 32 + 8 * gq + 4 * half + e;
-            float vf;
-            if (HAS_BIAS) {
-              const double t = j < limit ? fma((double)acc[jt][4 * gq + e], p.c1, (double)brow[j < p.N ? j : 0] * 1.4426950408889634) : -1e300;
-              vf = j < limit ? (float)rint(fma(t - tmax, -2.0, C0)) : qmaxf;
-            } else if (F64CODE) {
-              vf = (float)rint(fma((double)acc[jt][4 * gq + e], m2c, C0));    // masked keys: huge -> saturates at qmax
-            } else {
-              vf = fmaf((float)acc[jt][4 * gq + e], m2cf, C0f);
-            }
-            vf = fminf(vf, qmaxf);
-            if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);
-            if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
-            if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
-            if (e == 3) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 3, w);
-          }
-          pk[gq] = w;
-        }
-        // lane l holds key groups {0,8,16,24}+{0..3}, lane l+32 {4,12,20,28}+{0..3}: after the swaps lane l owns keys
-        // 0..15 and lane l+32 keys 16..31 of this tile
-        auto s02 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
-        auto s13 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
-        const int j0 = jt * 32 + half * 16;
-        if (qi < p.N && j0 < p.ld) {
-          v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
-          *reinterpret_cast<v4i*>(crow + j0) = tv;
-        }
-      }
-    }
-  }
-}
-
-template <int KSTEPS, int NT>
-rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
-  const int lds = NT * 32 * KSTEPS * 32;
-  const dim3 grid((unsigned)groups);
-  const bool f64 = p.qmax > 63;
-#define RQ_QKS_LAUNCH(B, F)                                                                                           \
-  do {                                                                                                                \
-    static bool attr_set = false;                                                                                     \
-    if (!attr_set) {                                                                                                  \
-      RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F>),                 \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));                                   \
-      attr_set = true;                                                                                                \
-    }                                                                                                                 \
-    hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F>), grid, dim3(512), lds, ctx->stream, p);                  \
-  } while (0)
-  if (p.bias) RQ_QKS_LAUNCH(true, true);
-  else if (f64) RQ_QKS_LAUNCH(false, true);
-  else RQ_QKS_LAUNCH(false, false);
-#undef RQ_QKS_LAUNCH
-  RQ_HIP(hipGetLastError());
-  return RQ_OK;
-}
-
-}  // namespace
 
 bool rq_qk_softmax_supported(int N, int d_head) { return N <= 288 && (d_head == 32 || d_head == 64 || d_head == 128); }
 
@@ -228,12 +19,10 @@ rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, in
   p.c1 = logit_scale * 1.4426950408889634; p.log2s = log2((double)s_log); p.qmax = (1 << bits) - 1;
   p.codes = codes; p.ld = ld; p.tiles = (N + 31) / 32;
   const int64_t groups = batch * H;
+  p.G = groups;
   const int ks = d_head / 32;
-#define RQ_QKS_CASE(KS, NTV) \
-  if (ks == KS && p.tiles <= NTV) return launch<KS, NTV>(ctx, p, groups);
-  RQ_QKS_CASE(1, 2) RQ_QKS_CASE(1, 4) RQ_QKS_CASE(1, 7) RQ_QKS_CASE(1, 9)
-  RQ_QKS_CASE(2, 2) RQ_QKS_CASE(2, 4) RQ_QKS_CASE(2, 7) RQ_QKS_CASE(2, 9)
-  RQ_QKS_CASE(4, 2) RQ_QKS_CASE(4, 4) RQ_QKS_CASE(4, 7) RQ_QKS_CASE(4, 9)
-#undef RQ_QKS_CASE
+  if (ks == 1) return rq_launch_qk_softmax_d32(ctx, p, groups);
+  if (ks == 2) return rq_launch_qk_softmax_d64(ctx, p, groups);
+  if (ks == 4) return rq_launch_qk_softmax_d128(ctx, p, groups);
   return rq_fail(ctx, RQ_ERR_SHAPE, "fused Q.K^T + softmax: N = %d, d_head = %d not supported", N, d_head);
 }
