@@ -266,6 +266,34 @@ typedef struct {
 } rq_qk_softmax_desc;
 rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d);
 
+/* ---- rq_attn_fused ------------------------------------------------------------------------------------
+ * rq_qk_softmax_log2_quant followed by rq_attn_pv in ONE kernel: the codes of a key tile are used as the
+ * operand of the shift de-quantized P.V product (case analysis before Eq. (3.3-2)) as soon as they are formed,
+ * so neither the logits nor the codes travel through memory.  Same integers, same code arithmetic, same
+ * output arithmetic as the separate calls.  Restrictions: no bias, no mask, codes of at most 4 bits (one shift
+ * window), and N * 16 / 32 + d_head <= 176 accumulator registers (e.g. N <= 224 at d_head 64); otherwise
+ * RQ_ERR_SHAPE and the caller takes the separate calls.  Q, K, V: token-major device int8 slices of one tensor
+ * with row pitch ld_tok (stored code - off).  codes (optional, may be NULL): [batch*H, N, ld] as in
+ * rq_qk_softmax_log2_quant.  Outputs as in rq_attn_pv: out_f32 and/or out_q, token-major [batch*N, H*d_head].
+ */
+typedef struct {
+  int64_t batch;
+  int32_t H, N, d_head;
+  const int8_t *Q, *K, *V;
+  int64_t ld_tok;
+  int32_t q_off, z_q, k_off, z_k, v_off, z_v;
+  double logit_scale;
+  float s_log, s_v;
+  int32_t bits_p;
+  uint8_t* codes; int64_t ld;
+  float* out_f32; int64_t ldf;
+  int8_t* out_q; int64_t ldq;
+  float s_o; int32_t z_o, off_o, bits_o;
+} rq_attn_fused_desc;
+rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);
+/* 1 if rq_attn_fused supports the shape (host, no context needed). */
+int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p);
+
 /* ---- rq_attn_pv -----------------------------------------------------------------------------------------
  * P.V with shift de-quantized probabilities (case analysis before Eq. (3.3-2) and Eq. (3.3-2)):
  *    A^[i, j] = s~(code) * 2^floor(-code / 2),   s~ = s_log (even code) or s_log * sqrt2 (odd code),
@@ -337,10 +365,11 @@ typedef struct {
  * last-level cache between Q.K^T, Softmax and P.V.  Sets the chunk budget in bytes (process-wide, default
  * 64 MiB); call before rq_block_workspace_bytes. */
 rq_status rq_set_attn_chunk_bytes(int64_t bytes);
-/* For rows of up to 288 keys rq_block_forward computes Q.K^T and the Softmax-log2 codes in ONE kernel that keeps
- * the exact int32 accumulators of a query tile in registers (same integers, same code arithmetic as rq_qgemm in
- * activation mode followed by rq_softmax_log2_quant; the logits never reach memory).  on = 0 forces the two-kernel
- * path for every length (process-wide; default 1); call before rq_block_workspace_bytes. */
+/* How rq_block_forward runs attention (process-wide; call before rq_block_workspace_bytes):
+ *   1 (default): rq_attn_fused where it applies (no bias, no mask, codes of at most 4 bits, short rows), else as 2;
+ *   2: rq_qk_softmax_log2_quant + rq_attn_pv for rows of up to 288 keys, else as 0;
+ *   0: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length.
+ * All three compute the same integers and the same codes. */
 rq_status rq_set_attn_fused(int on);
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,

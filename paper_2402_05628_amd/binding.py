@@ -72,6 +72,14 @@ class QkSoftmaxDesc(C.Structure):
                 ("mask", i32), ("s_log", f32), ("bits", i32), ("codes", vp), ("ld", i64)]
 
 
+class AttnFusedDesc(C.Structure):
+    _fields_ = [("batch", i64), ("H", i32), ("N", i32), ("d_head", i32), ("Q", vp), ("K", vp), ("V", vp), ("ld_tok", i64),
+                ("q_off", i32), ("z_q", i32), ("k_off", i32), ("z_k", i32), ("v_off", i32), ("z_v", i32),
+                ("logit_scale", f64), ("s_log", f32), ("s_v", f32), ("bits_p", i32), ("codes", vp), ("ld", i64),
+                ("out_f32", vp), ("ldf", i64), ("out_q", vp), ("ldq", i64), ("s_o", f32), ("z_o", i32), ("off_o", i32),
+                ("bits_o", i32)]
+
+
 class PvDesc(C.Structure):
     _fields_ = [("batch", i64), ("H", i32), ("Nq", i32), ("Nk", i32), ("d_head", i32), ("ld", i64), ("codes", vp),
                 ("V", vp), ("ldv", i64), ("s_log", f32), ("s_v", f32), ("z_v", i32), ("v_off", i32),
@@ -186,6 +194,8 @@ _rq_qgemm = _sig("rq_qgemm", i32, [vp, C.POINTER(GemmDesc)])
 _rq_softmax = _sig("rq_softmax_log2_quant", i32, [vp, C.POINTER(SoftmaxDesc)])
 _rq_attn_pv = _sig("rq_attn_pv", i32, [vp, C.POINTER(PvDesc)])
 _rq_qk_softmax = _sig("rq_qk_softmax_log2_quant", i32, [vp, C.POINTER(QkSoftmaxDesc)])
+_rq_attn_fused = _sig("rq_attn_fused", i32, [vp, C.POINTER(AttnFusedDesc)])
+_rq_attn_fused_supported = _sig("rq_attn_fused_supported", i32, [i32, i32, i32])
 _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
@@ -290,6 +300,24 @@ def rq_qk_softmax_log2_quant(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_of
     ctx.check(_rq_qk_softmax(ctx.handle, C.byref(d)))
 
 
+def attn_fused_supported(N: int, d_head: int, bits_p: int) -> bool:
+    return bool(_rq_attn_fused_supported(N, d_head, bits_p))
+
+
+def rq_attn_fused(ctx, qkv, batch, seq, H, d_head, q_off, z_q, k_off, z_k, v_off, z_v, logit_scale, s_log, s_v, bits_p, *,
+                  codes=None, ld=0, out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
+    """Whole attention of a [T, 3D] int8 tensor (Q | K | V column blocks) in one kernel."""
+    base, D = qkv.data_ptr(), H * d_head
+    d = AttnFusedDesc(batch=batch, H=H, N=seq, d_head=d_head, Q=base, K=base + D, V=base + 2 * D, ld_tok=qkv.stride(0),
+                      q_off=q_off, z_q=z_q, k_off=k_off, z_k=z_k, v_off=v_off, z_v=z_v, logit_scale=logit_scale, s_log=s_log,
+                      s_v=s_v, bits_p=bits_p, codes=_p(codes), ld=ld)
+    if out_f32 is not None:
+        d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
+    if out_q is not None:
+        d.out_q, d.ldq, d.s_o, d.z_o, d.off_o, d.bits_o = _p(out_q), out_q.stride(0), s_o, z_o, off_o, bits_o
+    ctx.check(_rq_attn_fused(ctx.handle, C.byref(d)))
+
+
 def rq_attn_pv(ctx, codes, ld, V_ptr, ldv, batch, H, Nq, Nk, d_head, s_log, s_v, z_v, v_off, bits_p, *, mask=MASK_NONE,
                out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
     d = PvDesc(batch=batch, H=H, Nq=Nq, Nk=Nk, d_head=d_head, ld=ld, codes=_p(codes), V=V_ptr, ldv=ldv, s_log=s_log,
@@ -325,8 +353,9 @@ def set_attn_chunk_bytes(nbytes: int):
         raise RqError(rc, _rq_last_error(None).decode())
 
 
-def set_attn_fused(on: bool):
-    rc = _rq_set_fused(1 if on else 0)
+def set_attn_fused(on):
+    """0: three kernels, 2: fused Q.K^T + softmax then P.V, 1 / True: whole attention in one kernel where it applies."""
+    rc = _rq_set_fused(int(on))
     if rc != RQ_OK:
         raise RqError(rc, _rq_last_error(None).decode())
 

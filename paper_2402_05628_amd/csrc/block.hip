@@ -70,7 +70,8 @@ rq_status check_linear(rq_ctx* ctx, const char* name, const rq_qlinear& l, int N
 extern "C" {
 
 rq_status rq_set_attn_fused(int on) {
-  g_attn_fused = on != 0;
+  if (on < 0 || on > 2) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_attn_fused: %d not in 0..2", on);
+  g_attn_fused = on;
   return RQ_OK;
 }
 
@@ -157,9 +158,25 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   // ---- attention, chunked over batch items -----------------------------------------------------------------
   const int offo = rq_store_offset(ba, p->z_o);
   const bool fused = use_fused(p, seq);
+  const bool whole = g_attn_fused == 1 && !p->rel_bias && p->mask == RQ_MASK_NONE && rq_attn_fused_supported((int)seq, dh, p->bits_p);
   for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
     const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
     const int8_t* qkv_c = qkv + b0 * seq * 3 * D;
+    if (whole) {
+      // Q.K^T, Softmax-log2 codes and P.V in one kernel: neither logits nor codes reach memory
+      rq_attn_fused_desc d;
+      std::memset(&d, 0, sizeof d);
+      d.batch = nb; d.H = H; d.N = (int)seq; d.d_head = dh; d.Q = qkv_c; d.K = qkv_c + D; d.V = qkv_c + 2 * D; d.ld_tok = 3 * D;
+      d.q_off = offq; d.z_q = p->z_q; d.k_off = offk; d.z_k = p->z_k; d.v_off = offv; d.z_v = p->z_v;
+      d.logit_scale = (double)p->s_q * (double)p->s_k / std::sqrt((double)dh);
+      d.s_log = p->s_log; d.s_v = p->s_v; d.bits_p = p->bits_p;
+      d.out_q = o + b0 * seq * D; d.ldq = D; d.s_o = p->s_o; d.z_o = p->z_o; d.off_o = offo; d.bits_o = ba;
+      rq_prof_begin(ctx, RQ_STEP_QK);
+      st = rq_launch_attn_fused(ctx, &d);
+      rq_prof_end(ctx);
+      if (st != RQ_OK) return st;
+      continue;
+    }
     if (fused) {
       rq_prof_begin(ctx, RQ_STEP_QK);
       st = rq_launch_qk_softmax(ctx, qkv_c, qkv_c + D, 3 * D, nb, H, (int)seq, dh, offq, p->z_q, offk, p->z_k,

@@ -32,13 +32,32 @@ struct QksParams {
   int64_t ld;                  // row pitch of the codes
   int tiles;                   // ceil(N / 32)
   int64_t G;                   // batch * H groups
+  // fused P.V (PV variants only): shift de-quantized probabilities times the stored values, re-quantized output
+  const int8_t* V;
+  int dv;                      // storage offset minus zero-point of V
+  double a_even, a_odd;        // s_log * s_v * (-1/128), the same divided by sqrt 2
+  float* out_f32;
+  int64_t ldf;
+  int8_t* out_q;
+  int64_t ldo;
+  double inv_so;
+  int zo, lo, hi;              // z_o - off_o and the clamp bounds of the stored code
 };
+
+// table of -(128 >> k), k = 0..7, as the two dwords of a byte permute: 2^-k = -(entry) / 128
+constexpr unsigned QKS_TAB_LO = 0xF0E0C080u, QKS_TAB_HI = 0xFFFEFCF8u;
 
 // NT = ceil(N / 32) exactly: tiles 0 .. NT-2 hold valid keys only, so only the last tile (or, with MASKALL = causal mask,
 // every tile) pays for per-element masking.
-template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL>
+// PV: the codes of a key tile go straight on as the column operand of the P.V product (after the two lane swaps a lane
+// owns 16 consecutive keys of its query row, which is that operand's layout); V^T is staged in LDS next to the keys;
+// even and odd codes accumulate separately and exactly in int32, as in rq_attn_pv (codes of at most 4 bits: one window).
+template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, bool PV>
 __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   constexpr int DH = KSTEPS * 32;
+  constexpr int TC = DH / 32;
+  constexpr int VTP = NT * 32 + 16;     // bytes per V^T row (skewed)
+  constexpr int VCH = PV ? ((NT * 8) * (DH / 4) + 511) / 512 : 1;   // (4 keys x 4 channels) pieces per thread
   constexpr int CPR = DH / 16;          // 16-byte chunks per key row
   constexpr int RPL = 16 / CPR;         // key rows per 256 bytes
   extern __shared__ __align__(16) int8_t ks[];   // [NT * 32][DH], chunk c of row r stored at position (c + r / RPL) % CPR
@@ -52,11 +71,26 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   // Workgroups are persistent over the (batch item, head) groups.  The keys and this wavefront's first query fragments of
   // the NEXT group are requested into registers before the current group's arithmetic, so their latency hides behind it.
   v4i kreg[KCH], qreg[KSTEPS];
+  unsigned vreg[VCH][4];
+  int8_t* const vt = ks + NT * 32 * DH;       // [DH][VTP]: V^T of this group
   auto request = [&](int64_t g) {
     const int64_t b = g / p.H;
     const int h = (int)(g - b * p.H);
     const int8_t* Kg = p.K + b * p.so + (int64_t)h * p.si;
     const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
+    if (PV) {
+      const int8_t* Vg = p.V + b * p.so + (int64_t)h * p.si;
+#pragma unroll
+      for (int u = 0; u < VCH; ++u) {
+        const int id = tid + u * 512;
+        const int c4 = id % (DH / 4), j4 = id / (DH / 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = j4 * 4 + e;
+          vreg[u][e] = (j4 < NT * 8 && j < p.N) ? *reinterpret_cast<const unsigned*>(Vg + (int64_t)j * p.ldk + c4 * 4) : 0u;
+        }
+      }
+    }
 #pragma unroll
     for (int u = 0; u < KCH; ++u) {
       const int id = tid + u * 512;
@@ -81,6 +115,29 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const int id = tid + u * 512;
     const int r = id / CPR, c = id - r * CPR;
     if (id < nchunks) *reinterpret_cast<v4i*>(ks + r * DH + (((c + r / RPL) % CPR) * 16)) = kreg[u];
+  }
+  if (PV) {      // 4 keys x 4 channels per piece, bytes transposed in registers: V^T[channel][key]
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) {
+      const int id = tid + u * 512;
+      const int c4 = id % (DH / 4), j4 = id / (DH / 4);
+      if (j4 < NT * 8) {
+        const unsigned r0 = vreg[u][0], r1 = vreg[u][1], r2 = vreg[u][2], r3 = vreg[u][3];
+        const unsigned lo01 = __builtin_amdgcn_perm(r1, r0, 0x05010400u);   // r0.b0 r1.b0 r0.b1 r1.b1
+        const unsigned hi01 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);   // r0.b2 r1.b2 r0.b3 r1.b3
+        const unsigned lo23 = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+        const unsigned hi23 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+        const unsigned o0 = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);  // channel 0 of keys 0..3
+        const unsigned o1 = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        const unsigned o2 = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        const unsigned o3 = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+        int8_t* dst = vt + (c4 * 4) * VTP + j4 * 4;
+        *reinterpret_cast<unsigned*>(dst) = o0;
+        *reinterpret_cast<unsigned*>(dst + VTP) = o1;
+        *reinterpret_cast<unsigned*>(dst + 2 * VTP) = o2;
+        *reinterpret_cast<unsigned*>(dst + 3 * VTP) = o3;
+      }
+    }
   }
   v4i fq0[KSTEPS];
 #pragma unroll
@@ -195,8 +252,16 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     C0 = 2.0 * ((double)__builtin_amdgcn_logf(ssum) + p.log2s);
     const double m2c = -2.0 * p.c1;
     const float C0f = (float)C0, m2cf = (float)m2c;
-    // ---- codes ----
-    uint8_t* crow = p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld;
+    // ---- codes (and, fused, their product with V) ----
+    uint8_t* crow = p.codes ? p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld : nullptr;
+    v16i E[PV ? TC : 1], O[PV ? TC : 1];
+    int se = 0, so = 0;
+    if (PV) {
+#pragma unroll
+      for (int c = 0; c < TC; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
+    }
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt) {
       if (jt < nt) {
@@ -229,10 +294,68 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         auto s02 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
         auto s13 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
         const int j0 = jt * 32 + half * 16;
-        if (qi < p.N && j0 < p.ld) {
-          v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
-          *reinterpret_cast<v4i*>(crow + j0) = tv;
+        const v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+        if (crow && qi < p.N && j0 < p.ld) *reinterpret_cast<v4i*>(crow + j0) = tv;
+        if (PV) {
+          v4i pe, po;
+#pragma unroll
+          for (int d4 = 0; d4 < 4; ++d4) {
+            const unsigned c = (unsigned)tv[d4];
+            unsigned pall = __builtin_amdgcn_perm(QKS_TAB_HI, QKS_TAB_LO, (c >> 1) & 0x07070707u);
+            if (MASKALL || jt == NT - 1) {      // masked and padding keys contribute nothing, whatever their code
+              int nv = limit - (j0 + d4 * 4);
+              nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+              pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
+            }
+            const unsigned odd = (c & 0x01010101u) * 0xFFu;
+            po[d4] = (int)(pall & odd);
+            pe[d4] = (int)(pall & ~odd);
+          }
+          if (p.dv != 0) {
+#pragma unroll
+            for (int d4 = 0; d4 < 4; ++d4) {
+              se = __builtin_amdgcn_sdot4(pe[d4], 0x01010101, se, false);
+              so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
+            }
+          }
+#pragma unroll
+          for (int c = 0; c < TC; ++c) {
+            const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
+            E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
+            O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
+          }
         }
+      }
+    }
+    if (PV) {
+      double psE = (double)se, psO = (double)so;
+      if (p.dv != 0) {   // the two halves of the wavefront saw different keys of the same row
+        psE += __shfl_xor(psE, 32, 64);
+        psO += __shfl_xor(psO, 32, 64);
+      }
+      if (qi < p.N) {
+        const int64_t tok = b * p.N + qi;
+        const double corr2 = (double)p.dv * (p.a_even * psE + p.a_odd * psO);
+#pragma unroll
+        for (int c = 0; c < TC; ++c)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const int col = h * DH + c * 32 + 8 * gq + half * 4;
+            double y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = p.a_even * (double)E[c][4 * gq + e] + p.a_odd * (double)O[c][4 * gq + e] + corr2;
+            if (p.out_f32)
+              *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4((float)y[0], (float)y[1], (float)y[2], (float)y[3]);
+            if (p.out_q) {
+              int k[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int q = (int)rint(y[e] * p.inv_so) + p.zo;
+                k[e] = q < p.lo ? p.lo : (q > p.hi ? p.hi : q);
+              }
+              *reinterpret_cast<int*>(p.out_q + tok * p.ldo + col) = rq_pack4(k[0], k[1], k[2], k[3]);
+            }
+          }
       }
     }
   }
@@ -240,28 +363,35 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   }
 }
 
+// accumulators of Q.K^T (16 per key tile) plus the even and odd accumulators of P.V (32 per 32 channels) per lane
+constexpr bool fused_pv_fits(int ksteps, int nt) { return nt * 16 + ksteps * 32 <= 176; }
+
 template <int KSTEPS, int NT>
 rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
-  const int lds = NT * 32 * KSTEPS * 32;
+  const bool pv = p.V != nullptr;
+  const int lds = NT * 32 * KSTEPS * 32 + (pv ? KSTEPS * 32 * (NT * 32 + 16) : 0);
   const int64_t cap = (int64_t)(ctx->num_cu > 0 ? ctx->num_cu : 256);      // one 8-wavefront workgroup per CU
   const dim3 grid((unsigned)(groups < cap ? groups : cap));
   const bool f64 = p.qmax > 63;
-#define RQ_QKS_LAUNCH(B, F, C)                                                                                        \
+#define RQ_QKS_LAUNCH(B, F, C, P)                                                                                        \
   do {                                                                                                                \
     static bool attr_set = false;                                                                                     \
     if (!attr_set) {                                                                                                  \
-      RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F, C>),              \
+      RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F, C, P>),           \
                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds));                                   \
       attr_set = true;                                                                                                \
     }                                                                                                                 \
-    hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F, C>), grid, dim3(512), lds, ctx->stream, p);               \
+    hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F, C, P>), grid, dim3(512), lds, ctx->stream, p);            \
   } while (0)
   // the float64 code path also serves every masked or biased case; the lean variant is the common one
-  if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true);
-  else if (p.bias) RQ_QKS_LAUNCH(true, true, false);
-  else if (p.causal) RQ_QKS_LAUNCH(false, true, true);
-  else if (f64) RQ_QKS_LAUNCH(false, true, false);
-  else RQ_QKS_LAUNCH(false, false, false);
+  if (pv) {
+    if constexpr (fused_pv_fits(KSTEPS, NT)) RQ_QKS_LAUNCH(false, false, false, true);
+    else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %d key tiles at d_head = %d do not fit the registers", NT, KSTEPS * 32);
+  } else if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true, false);
+  else if (p.bias) RQ_QKS_LAUNCH(true, true, false, false);
+  else if (p.causal) RQ_QKS_LAUNCH(false, true, true, false);
+  else if (f64) RQ_QKS_LAUNCH(false, true, false, false);
+  else RQ_QKS_LAUNCH(false, false, false, false);
 #undef RQ_QKS_LAUNCH
   RQ_HIP(hipGetLastError());
   return RQ_OK;

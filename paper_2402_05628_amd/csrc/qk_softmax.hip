@@ -7,6 +7,31 @@ rq_status rq_launch_qk_softmax_d64(rq_ctx* ctx, const rqks::QksParams& p, int64_
 rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 
 
+extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p) {
+  if (N <= 0 || N > 288 || bits_p < 2 || bits_p > 4 || !(d_head == 32 || d_head == 64 || d_head == 128)) return 0;
+  return rqks::fused_pv_fits(d_head / 32, (N + 31) / 32) ? 1 : 0;
+}
+
+rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
+  QksParams p;
+  p.Q = d->Q; p.K = d->K; p.V = d->V; p.ldq = d->ld_tok; p.ldk = d->ld_tok; p.so = (int64_t)d->N * d->ld_tok; p.si = d->d_head;
+  p.H = d->H; p.N = d->N; p.dq = d->q_off - d->z_q; p.dk = d->k_off - d->z_k; p.dv = d->v_off - d->z_v;
+  p.bias = nullptr; p.causal = 0;
+  p.c1 = d->logit_scale * 1.4426950408889634; p.log2s = log2((double)d->s_log); p.qmax = (1 << d->bits_p) - 1;
+  p.codes = d->codes; p.ld = d->ld; p.tiles = (d->N + 31) / 32;
+  const double ss = (double)d->s_log * (double)d->s_v;
+  p.a_even = -ss / 128.0;
+  p.a_odd = -ss / (128.0 * 1.4142135623730951);
+  p.out_f32 = d->out_f32; p.ldf = d->ldf; p.out_q = d->out_q; p.ldo = d->ldq;
+  p.inv_so = d->out_q ? 1.0 / (double)d->s_o : 0.0;
+  p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
+  p.G = d->batch * d->H;
+  const int ks = d->d_head / 32;
+  if (ks == 1) return rq_launch_qk_softmax_d32(ctx, p, p.G);
+  if (ks == 2) return rq_launch_qk_softmax_d64(ctx, p, p.G);
+  return rq_launch_qk_softmax_d128(ctx, p, p.G);
+}
+
 bool rq_qk_softmax_supported(int N, int d_head) { return N <= 288 && (d_head == 32 || d_head == 64 || d_head == 128); }
 
 // Q, K: token-major int8 (row b*N + i, column h*d_head + c), stored code - off.  codes: [batch*H, N, ld].
@@ -14,6 +39,7 @@ rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, in
                                int d_head, int q_off, int z_q, int k_off, int z_k, double logit_scale, const float* bias,
                                int mask, float s_log, int bits, uint8_t* codes, int64_t ld) {
   QksParams p;
+  p.V = nullptr; p.dv = 0; p.out_f32 = nullptr; p.out_q = nullptr;
   p.Q = Q; p.K = K; p.ldq = ld_tok; p.ldk = ld_tok; p.so = (int64_t)N * ld_tok; p.si = d_head;
   p.H = H; p.N = N; p.dq = q_off - z_q; p.dk = k_off - z_k; p.bias = bias; p.causal = mask == RQ_MASK_CAUSAL;
   p.c1 = logit_scale * 1.4426950408889634; p.log2s = log2((double)s_log); p.qmax = (1 << bits) - 1;

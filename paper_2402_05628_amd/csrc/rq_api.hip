@@ -326,6 +326,41 @@ rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d) {
                               d->logit_scale, d->bias, d->mask, d->s_log, d->bits, d->codes, d->ld);
 }
 
+rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
+  RQ_CHECK_CTX("rq_attn_fused");
+  RQ_REQUIRE(d->Q && d->K && d->V, RQ_ERR_INVALID_ARG, "rq_attn_fused: Q, K and V must be non-NULL");
+  RQ_REQUIRE(d->out_f32 || d->out_q, RQ_ERR_INVALID_ARG, "rq_attn_fused: no output requested");
+  RQ_REQUIRE(d->batch >= 0 && d->H > 0 && d->N > 0, RQ_ERR_SHAPE, "rq_attn_fused: batch = %lld, H = %d, N = %d", (long long)d->batch,
+             d->H, d->N);
+  RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_fused: bits_p = %d not in 2..8", d->bits_p);
+  RQ_REQUIRE(rq_attn_fused_supported(d->N, d->d_head, d->bits_p), RQ_ERR_SHAPE,
+             "rq_attn_fused: N = %d, d_head = %d, bits_p = %d outside the fused kernel's range; use the separate calls", d->N,
+             d->d_head, d->bits_p);
+  RQ_REQUIRE(d->ld_tok >= (int64_t)d->H * d->d_head && d->ld_tok % 16 == 0, RQ_ERR_SHAPE,
+             "rq_attn_fused: ld_tok = %lld must be >= H*d_head and a multiple of 16", (long long)d->ld_tok);
+  RQ_REQUIRE(rq_aligned(d->Q, 16) && rq_aligned(d->K, 16) && rq_aligned(d->V, 4), RQ_ERR_INVALID_ARG,
+             "rq_attn_fused: Q and K need 16-byte, V 4-byte alignment");
+  RQ_REQUIRE(!d->codes || (rq_aligned(d->codes, 16) && d->ld >= d->N && d->ld % 16 == 0), RQ_ERR_SHAPE,
+             "rq_attn_fused: codes need 16-byte alignment and ld >= N, a multiple of 16");
+  RQ_REQUIRE(d->q_off >= 0 && d->q_off <= 128 && d->k_off >= 0 && d->k_off <= 128 && d->v_off >= 0 && d->v_off <= 128 &&
+                 d->z_q >= 0 && d->z_q <= 255 && d->z_k >= 0 && d->z_k <= 255 && d->z_v >= 0 && d->z_v <= 255,
+             RQ_ERR_INVALID_ARG, "rq_attn_fused: offsets must be in 0..128 and zero-points in 0..255");
+  RQ_REQUIRE(d->s_log > 0.f && std::isfinite(d->s_log) && d->s_v > 0.f && std::isfinite(d->s_v), RQ_ERR_INVALID_ARG,
+             "rq_attn_fused: s_log and s_v must be > 0");
+  RQ_REQUIRE(d->logit_scale > 0.0 && std::isfinite(d->logit_scale), RQ_ERR_INVALID_ARG, "rq_attn_fused: logit_scale must be > 0");
+  const int64_t width = (int64_t)d->H * d->d_head;
+  RQ_REQUIRE(!d->out_f32 || (rq_aligned(d->out_f32, 16) && d->ldf >= width && d->ldf % 4 == 0), RQ_ERR_SHAPE,
+             "rq_attn_fused: out_f32 alignment / ldf");
+  if (d->out_q) {
+    RQ_REQUIRE(rq_aligned(d->out_q, 4) && d->ldq >= width && d->ldq % 4 == 0, RQ_ERR_SHAPE, "rq_attn_fused: out_q alignment / ldq");
+    RQ_REQUIRE(d->bits_o >= 2 && d->bits_o <= 8 && d->s_o > 0.f && fits_i8(d->bits_o, d->off_o), RQ_ERR_INVALID_ARG,
+               "rq_attn_fused: bad output quantizer (bits_o = %d, s_o = %g, off_o = %d)", d->bits_o, (double)d->s_o, d->off_o);
+  }
+  RQ_NEED_DEVICE();
+  if (d->batch == 0) return RQ_OK;
+  return rq_launch_attn_fused(ctx, d);
+}
+
 rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   RQ_CHECK_CTX("rq_attn_pv");
   RQ_REQUIRE(d->codes && d->V, RQ_ERR_INVALID_ARG, "rq_attn_pv: codes and V must be non-NULL");

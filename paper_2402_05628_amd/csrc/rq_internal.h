@@ -53,6 +53,7 @@ rq_status rq_launch_qgemm_act(rq_ctx* ctx, const rq_gemm_desc* d);
 rq_status rq_launch_softmax(rq_ctx* ctx, const rq_softmax_desc* d);
 rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d);
 bool rq_qk_softmax_supported(int N, int d_head);
+rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);
 rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, int64_t ld_tok, int64_t batch, int H, int N,
                                int d_head, int q_off, int z_q, int k_off, int z_k, double logit_scale, const float* bias,
                                int mask, float s_log, int bits, uint8_t* codes, int64_t ld);

@@ -48,7 +48,8 @@ def test_named_hot_path_calls_are_declared():
 def test_structures_have_the_c_layout(b, tmp_path):
     """sizeof and the offset of the last field of every descriptor, as gcc lays the header out."""
     pairs = [("rq_fold_desc", b.FoldDesc), ("rq_wq_desc", b.WqDesc), ("rq_ln_desc", b.LnDesc), ("rq_gemm_desc", b.GemmDesc),
-             ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_pv_desc", b.PvDesc),
+             ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_attn_fused_desc", b.AttnFusedDesc),
+             ("rq_pv_desc", b.PvDesc),
              ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
     for cname, cls in pairs:
@@ -181,6 +182,17 @@ def test_softmax_and_pv_validation(b, host_ctx):
     for k, v, want in (("N", 300, 2), ("d_head", 48, 2), ("ld", 8, 2), ("bits", 0, 1), ("Q", None, 1), ("ld_tok", 40, 2)):
         bad = b.QkSoftmaxDesc(**{**qd, k: v})
         assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(bad)) == want, (k, v)
+
+
+def test_attn_fused_validation(b, host_ctx):
+    fd = dict(batch=1, H=2, N=64, d_head=64, Q=FAKE, K=FAKE, V=FAKE, ld_tok=384, q_off=3, z_q=3, k_off=3, z_k=3, v_off=3, z_v=3,
+              logit_scale=0.1, s_log=1.0, s_v=0.1, bits_p=4, codes=None, ld=0, out_f32=FAKE, ldf=128)
+    assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**fd))) == 3
+    for k, v, want in (("N", 256, 2), ("bits_p", 6, 2), ("d_head", 48, 2), ("V", None, 1), ("out_f32", None, 1), ("s_v", 0.0, 1),
+                       ("ld_tok", 100, 2), ("ldf", 64, 2)):
+        assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**{**fd, k: v}))) == want, (k, v)
+    assert b.attn_fused_supported(197, 64, 4) and not b.attn_fused_supported(257, 64, 4) and not b.attn_fused_supported(197, 64, 6)
+    assert b.attn_fused_supported(288, 32, 4) and not b.attn_fused_supported(128, 128, 4) and b.attn_fused_supported(96, 128, 4)
 
 
 def test_fold_and_weight_pack_validation(b, host_ctx):

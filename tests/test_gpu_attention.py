@@ -169,3 +169,65 @@ def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causa
     got = out.cpu().numpy()
     assert_codes_close(got[:, :, :seq], want, "fused codes N=%d b=%d" % (seq, bits_p))
     assert np.all(got[:, :, seq:] == 2 ** bits_p - 1)
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p", [(2, 3, 197, 64, 4, 4), (3, 2, 49, 32, 6, 4), (1, 2, 224, 64, 4, 4),
+                                                        (2, 2, 64, 128, 8, 4), (1, 1, 1, 32, 8, 3), (2, 1, 288, 32, 4, 4),
+                                                        (5, 2, 100, 64, 8, 2)])
+def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
+    """rq_attn_fused (one kernel) against the oracle's logits -> log-sqrt2 codes -> shift de-quantized P.V -> uniform codes."""
+    b, ctx = rq
+    print("case", batch, H, seq, dh, bits, bits_p, flush=True)
+    assert b.attn_fused_supported(seq, dh, bits_p)
+    g = np.random.default_rng(seq * 3 + dh + bits)
+    D = H * dh
+    qmax = 2 ** bits - 1
+    s_qk = 8.0 / qmax
+    z = [int(g.integers(qmax // 3, 2 * qmax // 3 + 1)) for _ in range(3)]
+    codes = np.empty((batch * seq, 3 * D), np.int64)
+    for i in range(3):
+        codes[:, i * D:(i + 1) * D] = np.clip(np.rint(g.normal(size=(batch * seq, D)) / s_qk) + z[i], 0, qmax)
+    off = [b.store_offset(bits, zz) for zz in z]
+    st = codes.copy()
+    for i in range(3):
+        st[:, i * D:(i + 1) * D] -= off[i]
+    qkv = dev(st.astype(np.int8))
+    ld = _ld(seq)
+    scale = s_qk * s_qk / math.sqrt(dh)
+    s_log, s_v = np.float32(0.8), np.float32(s_qk)
+    want_codes = np.empty((batch * H, seq, seq), np.int64)
+    want = np.empty((batch * seq, D))
+    for bi in range(batch):
+        r = slice(bi * seq, (bi + 1) * seq)
+        for h in range(H):
+            c = slice(h * dh, (h + 1) * dh)
+            acc = orc.int_matmul_nt(codes[r, c] - z[0], codes[r, D + h * dh:D + (h + 1) * dh] - z[1])
+            pc = orc.softmax_log_quant(acc.astype(np.float64) * scale, s_log, bits_p)
+            want_codes[bi * H + h] = pc
+            want[r, c] = orc.attn_pv(pc, codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log, s_v, z[2], False)
+    s_o = np.float32((want.max() - want.min()) / qmax)
+    z_o = int(np.rint(-want.min() / np.float64(s_o)))
+    off_o = b.store_offset(bits, z_o)
+    outc = torch.full((batch * H, seq, ld), 99, dtype=torch.uint8, device="cuda")
+    outf = torch.zeros((batch * seq, D), dtype=torch.float32, device="cuda")
+    outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
+    b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
+                    codes=outc, ld=ld, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+    got_codes = outc.cpu().numpy()[:, :, :seq]
+    frac = assert_codes_close(got_codes, want_codes, "fused attention codes")
+    if frac == 0.0:      # identical codes -> the P.V sums are the same exact integers: only float rounding differs
+        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-5)
+        assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits), "fused attention out codes")
+    else:                # a tie flipped a code: compare P.V against the oracle's P.V of the codes the kernel produced
+        for bi in range(batch):
+            r = slice(bi * seq, (bi + 1) * seq)
+            for h in range(H):
+                c = slice(h * dh, (h + 1) * dh)
+                want[r, c] = orc.attn_pv(got_codes[bi * H + h].astype(np.int64), codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log,
+                                         s_v, z[2], False)
+        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-5)
+    # without the optional codes output the result is the same
+    outq2 = torch.zeros_like(outq)
+    b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
+                    out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+    assert torch.equal(outq, outq2)

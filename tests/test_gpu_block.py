@@ -28,7 +28,7 @@ SMALL = {
 
 
 @pytest.mark.parametrize("name", list(SMALL))
-@pytest.mark.parametrize("chunk_mb,fused", [(64, True), (1, True), (64, False), (1, False)])
+@pytest.mark.parametrize("chunk_mb,fused", [(64, 1), (1, 1), (64, 2), (1, 2), (64, 0), (1, 0)])
 def test_block_forward_matches_oracle(rq, name, chunk_mb, fused):
     b, ctx = rq
     cfg = SMALL[name]
@@ -46,7 +46,7 @@ def test_block_forward_matches_oracle(rq, name, chunk_mb, fused):
         torch.cuda.synchronize()
     finally:
         b.set_attn_chunk_bytes(64 << 20)
-        b.set_attn_fused(True)
+        b.set_attn_fused(1)
     got = y.cpu().numpy().astype(np.float64)
     ref = np.abs(want).max()
     err = np.abs(got - want).max()
