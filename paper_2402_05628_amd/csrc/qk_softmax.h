@@ -78,7 +78,11 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const int h = (int)(g - b * p.H);
     const int8_t* Kg = p.K + b * p.so + (int64_t)h * p.si;
     const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
+#ifdef RQ_ABL_PV_NOSTAGE
+    if (false) {
+#else
     if (PV) {
+#endif
       const int8_t* Vg = p.V + b * p.so + (int64_t)h * p.si;
 #pragma unroll
       for (int u = 0; u < VCH; ++u) {
@@ -116,7 +120,11 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const int r = id / CPR, c = id - r * CPR;
     if (id < nchunks) *reinterpret_cast<v4i*>(ks + r * DH + (((c + r / RPL) % CPR) * 16)) = kreg[u];
   }
-  if (PV) {      // 4 keys x 4 channels per piece, bytes transposed in registers: V^T[channel][key]
+#ifdef RQ_ABL_PV_NOSTAGE
+  if (false) {
+#else
+  if (PV) {      // 4 keys x 4 channels per piece
+#endif, bytes transposed in registers: V^T[channel][key]
 #pragma unroll
     for (int u = 0; u < VCH; ++u) {
       const int id = tid + u * 512;
@@ -307,7 +315,8 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
               nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
               pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
             }
-            const unsigned odd = (c & 0x01010101u) * 0xFFu;
+            const unsigned lsb = c & 0x01010101u;
+            const unsigned odd = (lsb << 8) - lsb;        // 0xFF in the bytes that hold odd codes
             po[d4] = (int)(pall & odd);
             pe[d4] = (int)(pall & ~odd);
           }
@@ -318,6 +327,10 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
               so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
             }
           }
+#ifdef RQ_ABL_PV_NOMFMA
+          E[0][0] += pe[0] ^ pe[1] ^ pe[2] ^ pe[3]; O[0][0] += po[0] ^ po[1] ^ po[2] ^ po[3];
+          if (false)
+#endif
 #pragma unroll
           for (int c = 0; c < TC; ++c) {
             const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
@@ -335,24 +348,27 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
       }
       if (qi < p.N) {
         const int64_t tok = b * p.N + qi;
-        const double corr2 = (double)p.dv * (p.a_even * psE + p.a_odd * psO);
+        // |E|, |O| <= 288 * 128 * 255 < 2^24: the integer sums convert to float32 exactly
+        const float ae = (float)p.a_even, ao = (float)p.a_odd, iso = (float)p.inv_so;
+        const float zof = (float)p.zo, lof = (float)p.lo, hif = (float)p.hi;
 #pragma unroll
         for (int c = 0; c < TC; ++c)
 #pragma unroll
           for (int gq = 0; gq < 4; ++gq) {
             const int col = h * DH + c * 32 + 8 * gq + half * 4;
-            double y[4];
+            float y[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = p.a_even * (double)E[c][4 * gq + e] + p.a_odd * (double)O[c][4 * gq + e] + corr2;
+            for (int e = 0; e < 4; ++e) {
+              if (p.dv == 0) y[e] = fmaf(ao, (float)O[c][4 * gq + e], ae * (float)E[c][4 * gq + e]);
+              else   // the zero-point term cancels most of the sum: form it in float64
+                y[e] = (float)(p.a_even * ((double)E[c][4 * gq + e] + (double)p.dv * psE) + p.a_odd * ((double)O[c][4 * gq + e] + (double)p.dv * psO));
+            }
             if (p.out_f32)
-              *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4((float)y[0], (float)y[1], (float)y[2], (float)y[3]);
+              *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4(y[0], y[1], y[2], y[3]);
             if (p.out_q) {
               int k[4];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int q = (int)rint(y[e] * p.inv_so) + p.zo;
-                k[e] = q < p.lo ? p.lo : (q > p.hi ? p.hi : q);
-              }
+              for (int e = 0; e < 4; ++e) k[e] = (int)fminf(fmaxf(rintf(fmaf(y[e], iso, zof)), lof), hif);
               *reinterpret_cast<int*>(p.out_q + tok * p.ldo + col) = rq_pack4(k[0], k[1], k[2], k[3]);
             }
           }
