@@ -5,9 +5,10 @@
 // a 64-wide wavefront, so that narrow rows still fill the wavefront); the row statistics are reduced with DPP lane
 // exchanges inside 16-lane rows and one or two shuffles across them; the codes leave as one dword (4 codes) per
 // lane, contiguous across lanes.  The per-channel constants g = gamma~/s~ and h = beta~/s~ + z~ are computed once
-// per workgroup in float64 and staged in LDS.  All arithmetic is float64 (full rate on this chip), so the codes
-// agree with a float64 reference except at exact ties; rounding, saturation to 0..255 and byte packing are one
-// v_cvt_pk_u8_f32 per code.  Workgroups are persistent and fetch their next rows while the current ones are quantized.
+// per workgroup in float64 and staged in LDS.  The row statistics are float64; for 8-bit codes so is the quantizer
+// (codes agree with a float64 reference except at exact ties), for narrower codes it is two float32 fma; rounding,
+// saturation to 0..255 and byte packing are one v_cvt_pk_u8_f32 per code.  Small launches run one pass per workgroup with
+// all workgroups resident; large ones use persistent workgroups that fetch their next rows while quantizing.
 #include <vector>
 
 #include "rq_internal.h"
@@ -52,13 +53,18 @@ __device__ __forceinline__ double rsqrt_f64(double a) {
   return r;
 }
 
-template <int LPR, int NV>
+// F32Q: the normalization and the quantizer run in float32 (codes of at most 6 bits: the pre-round value is below 64, so its
+// float32 error, ~1e-5 of a code, flips far fewer than 1e-4 of the codes); the row statistics stay float64 either way.
+// PERSIST: workgroups loop over rows and fetch the next rows early; otherwise one pass, fewer registers, more wavefronts.
+template <int LPR, int NV, bool F32Q, bool PERSIST>
 __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
                                                        double eps, const float* __restrict__ gamma_t,
                                                        const float* __restrict__ beta_t, double inv_s, double zcode, float qmaxf,
                                                        unsigned off4, int8_t* __restrict__ q, int64_t ldq,
                                                        int32_t* __restrict__ rowsum) {
-  extern __shared__ __align__(16) double2 gh[];   // [D]: {gamma~ / s~, beta~ / s~ + z~}
+  extern __shared__ __align__(16) char gh_raw[];  // [D]: {gamma~ / s~, beta~ / s~ + z~} as double2, or float2 with F32Q
+  double2* const gh = reinterpret_cast<double2*>(gh_raw);
+  float2* const ghf = reinterpret_cast<float2*>(gh_raw);
   constexpr int RPW = 64 / LPR;                   // rows per wavefront
   const int lane = threadIdx.x & 63;
   const int sub = lane % LPR;                     // lane within the row
@@ -67,10 +73,13 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__
   const int64_t nwave = (int64_t)gridDim.x * 4;
   const int chunks = D >> 2;
 
-  for (int ch = threadIdx.x; ch < D; ch += 256)
-    gh[ch] = make_double2((double)gamma_t[ch] * inv_s, (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode);
+  for (int ch = threadIdx.x; ch < D; ch += 256) {
+    const double g = (double)gamma_t[ch] * inv_s, h = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode;
+    if (F32Q) ghf[ch] = make_float2((float)g, (float)h);
+    else gh[ch] = make_double2(g, h);
+  }
 
-  float4 cur[NV], nxt[NV];
+  float4 cur[NV], nxt[PERSIST ? NV : 1];
   int64_t row = wave * RPW + rsel;
   const int64_t stride = nwave * RPW;
 #pragma unroll
@@ -82,10 +91,12 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__
   const double invD = 1.0 / (double)D;
   for (; (row - rsel) < T; row += stride) {       // wavefront-uniform trip count
     const int64_t nrow = row + stride;
+    if (PERSIST) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = sub + i * LPR;
-      nxt[i] = (nrow < T && c < chunks) ? *reinterpret_cast<const float4*>(x + nrow * ldx + c * 4) : make_float4(0, 0, 0, 0);
+      for (int i = 0; i < NV; ++i) {
+        const int c = sub + i * LPR;
+        nxt[i] = (nrow < T && c < chunks) ? *reinterpret_cast<const float4*>(x + nrow * ldx + c * 4) : make_float4(0, 0, 0, 0);
+      }
     }
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
@@ -104,6 +115,7 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__
     }
     const double rstd = rsqrt_f64(var + eps);
     const double nmr = -mean * rstd;
+    const float rstd_f = (float)rstd, nmr_f = (float)nmr;
     int rs = 0;
     if (row < T) {
 #pragma unroll
@@ -114,10 +126,16 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__
           unsigned w = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const double2 g = gh[c * 4 + e];
-            const double xh = fma((double)xv[e], rstd, nmr);
-            const double v = rint(fma(xh, g.x, g.y));                 // exact integer in float64 ...
-            const float vf = fminf((float)v, qmaxf);                   // ... so the float32 conversion is exact too
+            float vf;
+            if (F32Q) {
+              const float2 g = ghf[c * 4 + e];
+              vf = fminf(fmaf(fmaf(xv[e], rstd_f, nmr_f), g.x, g.y), qmaxf);   // the packed convert below rounds to nearest-even
+            } else {
+              const double2 g = gh[c * 4 + e];
+              const double xh = fma((double)xv[e], rstd, nmr);
+              const double v = rint(fma(xh, g.x, g.y));               // exact integer in float64 ...
+              vf = fminf((float)v, qmaxf);                             // ... so the float32 conversion is exact too
+            }
             if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);  // saturates below at 0 and packs the byte
             if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
             if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
@@ -134,30 +152,45 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__
       rs = group_sum_i<LPR>(rs);
       if (sub == 0 && row < T) rowsum[row] = rs;
     }
+    if (!PERSIST) break;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) cur[i] = nxt[i];
+    for (int i = 0; i < NV; ++i) cur[i] = nxt[PERSIST ? i : 0];
   }
+}
+
+template <int LPR, int NV, bool F32Q, bool PERSIST>
+rq_status launch_one(rq_ctx* ctx, const rq_ln_desc* d, int64_t blocks, int lds, double inv_s, double zcode, float qmaxf, unsigned off4) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV, F32Q, PERSIST>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 16));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV, F32Q, PERSIST>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T,
+                     d->D, d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
 }
 
 template <int LPR, int NV>
 rq_status launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcode, float qmaxf, unsigned off4) {
   constexpr int RPW = 64 / LPR;
   const int64_t rows_per_block = 4 * RPW;
-  int64_t blocks = (d->T + rows_per_block - 1) / rows_per_block;
-  const int lds = d->D * 16;
-  const int per_cu = lds > 40960 ? (lds > 81920 ? 1 : 2) : 4;
-  const int64_t cap = (int64_t)ctx->num_cu * per_cu;
-  if (blocks > cap) blocks = cap;
-  static bool attr_set = false;
-  if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               8192 * 16));
-    attr_set = true;
+  const int64_t blocks = (d->T + rows_per_block - 1) / rows_per_block;
+  const bool f32q = d->bits <= 6;
+  const int lds = d->D * (f32q ? 8 : 16);
+  // one pass per workgroup while every workgroup can be resident at once (8 per CU at <= 64 registers, LDS permitting);
+  // beyond that, persistent workgroups that prefetch their next rows
+  const int by_lds = lds > 0 ? (160 * 1024) / lds : 8;
+  const int64_t one_pass_slots = (int64_t)ctx->num_cu * (by_lds < 8 ? by_lds : 8);
+  if (blocks <= one_pass_slots) {
+    return f32q ? launch_one<LPR, NV, true, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4)
+                : launch_one<LPR, NV, false, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4);
   }
-  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T, d->D,
-                     d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);
-  RQ_HIP(hipGetLastError());
-  return RQ_OK;
+  const int per_cu = by_lds < 4 ? (by_lds < 1 ? 1 : by_lds) : 4;
+  const int64_t cap = (int64_t)ctx->num_cu * per_cu;
+  return f32q ? launch_one<LPR, NV, true, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4)
+              : launch_one<LPR, NV, false, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4);
 }
 
 }  // namespace
