@@ -327,10 +327,28 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
 #define RQ_TS(k) do { } while (0)
 #endif
   RQ_TS(0);
-  // ---- prologue: S stages in flight ----
+  // The weight zero-points are needed by the first unpack.  Loads return in order, so they are requested BEFORE the ring
+  // loads (and first used after them): their wait then does not include the ring's first stages.
+  int zraw[TN] = {0, 0};
+  if (W4) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      int n = n0 + wn0 + j * 32 + l32;
+      n = n < p.N ? n : p.N - 1;
+      zraw[j] = p.z_b[n];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- prologue ----
+  // A CU takes loads in at a bounded rate, so filling the whole ring first would keep the matrix cores waiting for bytes
+  // they do not need yet: with more than S k-steps only two stages are requested now and the rest of the ring during the
+  // first k-step (RAMP below); a shorter K requests everything at once.
+  const bool ramp = nk > S && S > 2;
 #pragma unroll
   for (int s = 0; s < S; ++s)
-    if (s < nk) issue(s, s);
+    if (s < nk && (s < 2 || !ramp)) issue(s, s);
+  __builtin_amdgcn_sched_barrier(0);
+  RQ_TS(4);
 
   // ---- MFMA operand fragments ----
   int a_off[2];                                                    // MFMA tile i adds i * 2048
@@ -344,15 +362,9 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
     for (int s = 0; s < (W4 ? 1 : 2); ++s)
       b_off[j][s] = A_BYTES + (W4 ? n * 32 + ((half ^ ((n >> 3) & 1)) * 16) : n * 64 + (((2 * half + s + (n >> 2)) & 3) * 16));
   }
-  int zb4[TN] = {0, 0};
-  if (W4) {
+  int zb4[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      int n = n0 + wn0 + j * 32 + l32;
-      n = n < p.N ? n : p.N - 1;
-      zb4[j] = (int)((unsigned)(p.z_b[n] * 0x01010101) - 0x80808080u);   // z - 0x80 per byte (mod 2^32)
-    }
-  }
+  for (int j = 0; j < TN; ++j) zb4[j] = (int)((unsigned)(zraw[j] * 0x01010101) - 0x80808080u);   // z - 0x80 per byte (mod 2^32)
   v4i fa[TM];      // activation fragments of the sub-step being multiplied
   v4i fb[TN];      // weight fragments of sub-step 0 (of the current, later of the next k-step)
   v4i fbn[TN];     // weight fragments of sub-step 1
@@ -418,9 +430,10 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
     }
   }
 
+  RQ_TS(5);
   // stage 0 has landed when at most the loads of stages 1 .. S-1 are outstanding
   {
-    const int later = nk - 1 < S - 1 ? nk - 1 : S - 1;
+    const int later = ramp ? 1 : (nk - 1 < S - 1 ? nk - 1 : S - 1);
     static_for_down<S - 1>([&](auto RC) {
       constexpr int r = decltype(RC)::value;
       if (later == r) wait_vm<r * LPS>();
@@ -437,9 +450,9 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
   // MORE = a next k-step exists.  While the MFMAs of sub-step 0 run, the weights of sub-step 1 are unpacked into fbn and the
   // activation fragments are replaced one by one; while those of sub-step 1 run, the ring is refilled and the fragments
   // (and unpacked weights) of the next k-step's sub-step 0 are fetched.
-  auto step = [&](auto WAITC, auto ISSUEC, auto MOREC, int kt) {
+  auto step = [&](auto WAITC, auto ISSUEC, auto MOREC, auto RAMPC, int kt) {
     constexpr int WAIT = decltype(WAITC)::value;
-    constexpr bool ISSUE = decltype(ISSUEC)::value, MORE = decltype(MOREC)::value;
+    constexpr bool ISSUE = decltype(ISSUEC)::value, MORE = decltype(MOREC)::value, RAMP = decltype(RAMPC)::value;
     const int nslot = slot + 1 == S ? 0 : slot + 1;
     // The issue order below is pinned with scheduling fences: each MFMA is followed by the small piece of VALU / LDS work
     // that hides behind it, so the matrix pipe never waits for the unpacking.
@@ -459,6 +472,10 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
       // are here, the slot may be refilled and stage kt+1 (landed everywhere) may be read
       asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
       fetch_b(nslot, 0, fb);
+      if (RAMP) {          // first k-step of a ramped start: the untouched slots 2 .. S-1 get their first stages now
+#pragma unroll
+        for (int s = 2; s < S; ++s) issue(s, s);
+      }
       if (ISSUE) issue(slot, kt + S);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -484,12 +501,18 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
   };
   using std::integral_constant;
   int kt = 0;
-  for (; kt + S < nk; ++kt) step(integral_constant<int, S - 2>{}, integral_constant<bool, true>{}, integral_constant<bool, true>{}, kt);
+  using T_ = integral_constant<bool, true>;
+  using F_ = integral_constant<bool, false>;
+  if (ramp) {     // k-step 0 with only stage 1 behind it
+    step(integral_constant<int, 0>{}, T_{}, T_{}, T_{}, 0);
+    kt = 1;
+  }
+  for (; kt + S < nk; ++kt) step(integral_constant<int, S - 2>{}, T_{}, T_{}, F_{}, kt);
   // the last min(S, nk) k-steps: nothing left to issue, fewer and fewer stages in flight (r = k-steps after this one)
   static_for_down<S - 1>([&](auto RC) {
     constexpr int r = decltype(RC)::value;
     if (r < nk) {     // uniform
-      step(integral_constant<int, (r > 0 ? r - 1 : 0)>{}, integral_constant<bool, false>{}, integral_constant<bool, (r > 0)>{}, kt);
+      step(integral_constant<int, (r > 0 ? r - 1 : 0)>{}, F_{}, integral_constant<bool, (r > 0)>{}, F_{}, kt);
       ++kt;
     }
   });

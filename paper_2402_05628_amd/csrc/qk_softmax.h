@@ -78,11 +78,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const int h = (int)(g - b * p.H);
     const int8_t* Kg = p.K + b * p.so + (int64_t)h * p.si;
     const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
-#ifdef RQ_ABL_PV_NOSTAGE
-    if (false) {
-#else
     if (PV) {
-#endif
       const int8_t* Vg = p.V + b * p.so + (int64_t)h * p.si;
 #pragma unroll
       for (int u = 0; u < VCH; ++u) {
@@ -120,11 +116,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const int r = id / CPR, c = id - r * CPR;
     if (id < nchunks) *reinterpret_cast<v4i*>(ks + r * DH + (((c + r / RPL) % CPR) * 16)) = kreg[u];
   }
-#ifdef RQ_ABL_PV_NOSTAGE
-  if (false) {
-#else
-  if (PV) {      // 4 keys x 4 channels per piece
-#endif, bytes transposed in registers: V^T[channel][key]
+  if (PV) {      // 4 keys x 4 channels per piece, bytes transposed in registers: V^T[channel][key]
 #pragma unroll
     for (int u = 0; u < VCH; ++u) {
       const int id = tid + u * 512;
@@ -327,10 +319,6 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
               so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
             }
           }
-#ifdef RQ_ABL_PV_NOMFMA
-          E[0][0] += pe[0] ^ pe[1] ^ pe[2] ^ pe[3]; O[0][0] += po[0] ^ po[1] ^ po[2] ^ po[3];
-          if (false)
-#endif
 #pragma unroll
           for (int c = 0; c < TC; ++c) {
             const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
