@@ -3,7 +3,7 @@
 //
 // HBM-bound: 4 B (int32 accumulator) read + 1 B (code) written per element.  One row lives in the registers
 // of LPR lanes (16, 32 or 64 of a 64-wide wavefront, so short rows of 49..257 keys still fill the wavefront);
-// max and sum are wavefront shuffles; codes leave as one dword (4 codes) per lane.  The probability is never
+// max and sum are DPP exchanges inside 16-lane rows plus shuffles across them; codes leave as one dword (4 codes) per lane.  The probability is never
 // formed:  -2 log2(softmax_j / s) = 2 (log2 sum_k 2^(t_k) - t_j + log2 s),  t = logit * log2(e).
 // Without a bias the row maximum is an integer maximum and t_j - t_max = c * (acc_j - acc_max) exactly;
 // the linear part runs in float64 (fp64 is full rate here), only the exponentials run in float32.
