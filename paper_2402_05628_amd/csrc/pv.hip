@@ -7,8 +7,10 @@
 // The power of two is an integer shift: inside a window of 8 shifts the probability is the int8 value
 // -(128 >> (k & 7)) = -2^(7 - k%8), looked up with one byte-permute per 4 codes.  Even and odd codes go to
 // separate exact int32 accumulators on the int8 matrix cores (v_mfma_i32_32x32x32_i8); the parity scale is
-// applied once per output.  Codes wider than 4 bits span several windows (k >= 8); those are visited one
-// window at a time, only if present, each contributing 2^(-8 w) times its exact integer sum.
+// applied once per output.  Codes wider than 4 bits span several windows (k >= 8): shifts are then taken relative to
+// the row's smallest shift (whose power of two multiplies the finished row), the windows of 8 relative shifts are
+// visited one at a time, only if present, each contributing 2^(-8 w) times its exact integer sum, and relative shifts
+// of 40 or more (below 2^-40 of the row's largest probability) are dropped.
 // V^T is staged per 256 keys in LDS (transposed on the way in) as the ROW operand; the codes go straight from
 // global memory into the COLUMN operand (each lane owns 16 consecutive keys of one query row), so a lane ends up
 // with 4 consecutive channels of one token.
@@ -77,9 +79,31 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
   wave_rows_end = wave_rows_end < p.Nq ? wave_rows_end : p.Nq;
   const int nk_wave = wave_live ? (p.causal ? (wave_rows_end < p.Nk ? wave_rows_end : p.Nk) : p.Nk) : 0;
 
-  // windows present in this wavefront's rows (WIDE only): bit w set if some valid code has code >> 4 == w
+  // WIDE (codes wider than 4 bits): shifts are taken relative to the row's smallest one, kmin = min over valid keys of
+  // code >> 1, and the power 2^-kmin is applied to the finished row.  Relative shifts of 40 or more (terms below 2^-40 of
+  // the row's largest probability; at most 4096 of them) are dropped: their sum is below 4e-9 of the result.  Windows of
+  // 8 relative shifts are visited one at a time, only if some row of the wavefront has a key in them.
+  constexpr int WINDOWS = 5;
+  int kmin = 0;
+  unsigned kmin4 = 0;
   unsigned present = 1u;
   if (WIDE && wave_live) {
+    int km = 127;
+    for (int j0 = half * 16; j0 < nk_wave; j0 += 32) {
+      const v4i cw = *reinterpret_cast<const v4i*>(crow + j0);
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = j0 + d4 * 4 + e;
+          const int k = (int)(((unsigned)cw[d4] >> (8 * e + 1)) & 0x7Fu);
+          km = (j < limit && k < km) ? k : km;
+        }
+      }
+    }
+    const int other = __shfl_xor(km, 32, 64);      // the other half of the wavefront holds the other keys of the same row
+    kmin = km < other ? km : other;
+    kmin4 = (unsigned)kmin * 0x01010101u;
     unsigned pm = 0;
     for (int j0 = half * 16; j0 < nk_wave; j0 += 32) {
       const v4i cw = *reinterpret_cast<const v4i*>(crow + j0);
@@ -88,8 +112,8 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = j0 + d4 * 4 + e;
-          const unsigned code = ((unsigned)cw[d4] >> (8 * e)) & 0xFFu;
-          pm |= (j < limit) ? (1u << (code >> 4)) : 0u;
+          const int kr = (int)(((unsigned)cw[d4] >> (8 * e + 1)) & 0x7Fu) - kmin;
+          pm |= (j < limit && kr < 8 * WINDOWS) ? (1u << (kr >> 3)) : 0u;
         }
       }
     }
@@ -101,7 +125,8 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
 
   // WIDE: per-window exact integer sums are folded into float64 running sums (each window has its own power of
   // two); otherwise one window, and the int32 accumulators simply run over all keys.
-  double outE[WIDE ? TC : 1][16], outO[WIDE ? TC : 1][16];
+  // (float32 is enough: each window's exact integer sum is rounded once, to 2^-24 of itself, far inside the 1e-4 code budget)
+  float outE[WIDE ? TC : 1][16], outO[WIDE ? TC : 1][16];
   double psE = 0.0, psO = 0.0;
   v16i E[TC], O[TC];
   int se = 0, so = 0;
@@ -110,7 +135,7 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       E[c][e] = 0; O[c][e] = 0;
-      if (WIDE) { outE[c][e] = 0.0; outO[c][e] = 0.0; }
+      if (WIDE) { outE[c][e] = 0.f; outO[c][e] = 0.f; }
     }
 
   for (int jb = 0; jb < nk_block; jb += JB) {
@@ -135,7 +160,7 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
     if (jb >= nk_wave) continue;
     int jend = nk_wave - jb;
     jend = jend < JB ? jend : JB;
-    for (int w = 0; w <= (WIDE ? p.wmax : 0); ++w) {
+    for (int w = 0; w < (WIDE ? WINDOWS : 1); ++w) {
       if (WIDE && !((present >> w) & 1u)) continue;
       if (WIDE) {
 #pragma unroll
@@ -151,14 +176,16 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
         v4i pe, po;
 #pragma unroll
         for (int d4 = 0; d4 < 4; ++d4) {
-          const unsigned c = (unsigned)cw[d4];
-          const unsigned sel = (c >> 1) & 0x07070707u;
-          unsigned pall = __builtin_amdgcn_perm(TAB_HI, TAB_LO, sel);
-          if (WIDE) pall &= byte_eq_mask((c >> 4) & 0x0F0F0F0Fu, wref);
           // validity of the 4 keys j0+4*d4 .. +3 (padding and causal mask)
           int nv = limit - (j0 + d4 * 4);
           nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
           const unsigned vm = nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
+          const unsigned c = (unsigned)cw[d4] | (WIDE ? ~vm : 0u);     // WIDE: invalid positions read as the largest code
+          // per byte: relative shift (code >> 1) - kmin; no borrow between bytes because every byte is >= kmin
+          const unsigned kr = WIDE ? ((c >> 1) & 0x7F7F7F7Fu) - kmin4 : (c >> 1);
+          const unsigned sel = kr & 0x07070707u;
+          unsigned pall = __builtin_amdgcn_perm(TAB_HI, TAB_LO, sel);
+          if (WIDE) pall &= byte_eq_mask((kr >> 3) & 0x1F1F1F1Fu, wref);
           pall &= vm;
           const unsigned odd = (c & 0x01010101u) * 0xFFu;
           po[d4] = (int)(pall & odd);
@@ -179,28 +206,34 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
         }
       }
       if (WIDE) {
-        const double wsc = __builtin_ldexp(1.0, -8 * w);
+        const float wsf = __builtin_ldexpf(1.0f, -8 * w);
+        // the zero-point term dv * sum(p) is added to the integer sums BEFORE the conversion, so that the large
+        // cancellation between the two happens exactly (all of it fits int32: |E| < 2^27, dv * sum(p) < 2^26)
+        int ce = 0, co = 0;
+        if (p.dv != 0) {     // uniform; the two halves of the wavefront saw different keys of the same row
+          ce = p.dv * (se + __shfl_xor(se, 32, 64));
+          co = p.dv * (so + __shfl_xor(so, 32, 64));
+        }
 #pragma unroll
         for (int c = 0; c < TC; ++c)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            outE[c][e] = fma((double)E[c][e], wsc, outE[c][e]);
-            outO[c][e] = fma((double)O[c][e], wsc, outO[c][e]);
+            outE[c][e] = fmaf((float)(E[c][e] + ce), wsf, outE[c][e]);
+            outO[c][e] = fmaf((float)(O[c][e] + co), wsf, outO[c][e]);
           }
-        psE = fma((double)se, wsc, psE);
-        psO = fma((double)so, wsc, psO);
       }
     }
   }
   if (!WIDE) { psE = (double)se; psO = (double)so; }
   if (!wave_live) return;
-  if (p.dv != 0) {   // the two halves of the wavefront saw different keys of the same row
+  if (!WIDE && p.dv != 0) {   // the two halves of the wavefront saw different keys of the same row
     psE += __shfl_xor(psE, 32, 64);
     psO += __shfl_xor(psO, 32, 64);
   }
   if (qi >= p.Nq) return;
   const int64_t tok = b * p.Nq + qi;
-  const double corr = (double)p.dv * (p.a_even * psE + p.a_odd * psO);
+  const double rowscale = WIDE ? __builtin_ldexp(1.0, -kmin) : 1.0;
+  const double corr = WIDE ? 0.0 : (double)p.dv * (p.a_even * psE + p.a_odd * psO);
 #pragma unroll
   for (int c = 0; c < TC; ++c) {
 #pragma unroll
@@ -209,9 +242,9 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
       double y[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const double ve = WIDE ? outE[WIDE ? c : 0][4 * gq + e] : (double)E[c][4 * gq + e];
-        const double vo = WIDE ? outO[WIDE ? c : 0][4 * gq + e] : (double)O[c][4 * gq + e];
-        y[e] = p.a_even * ve + p.a_odd * vo + corr;
+        const double ve = WIDE ? (double)outE[WIDE ? c : 0][4 * gq + e] : (double)E[c][4 * gq + e];
+        const double vo = WIDE ? (double)outO[WIDE ? c : 0][4 * gq + e] : (double)O[c][4 * gq + e];
+        y[e] = (p.a_even * ve + p.a_odd * vo + corr) * rowscale;
       }
       if (p.out_f32)
         *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4((float)y[0], (float)y[1], (float)y[2], (float)y[3]);
