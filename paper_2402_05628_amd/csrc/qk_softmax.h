@@ -57,71 +57,89 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   constexpr int DH = KSTEPS * 32;
   constexpr int TC = DH / 32;
   constexpr int VTP = NT * 32 + 16;     // bytes per V^T row (skewed)
-  constexpr int VCH = PV ? ((NT * 8) * (DH / 4) + 511) / 512 : 1;   // (4 keys x 4 channels) pieces per thread
   constexpr int CPR = DH / 16;          // 16-byte chunks per key row
   constexpr int RPL = 16 / CPR;         // key rows per 256 bytes
-  extern __shared__ __align__(16) int8_t ks[];   // [NT * 32][DH], chunk c of row r stored at position (c + r / RPL) % CPR
+  // Short rows leave most of the 8 wavefronts without a query tile, so a workgroup then serves GPB groups per pass:
+  // wavefront w works on group slot w / NT, query tile w % NT.
+  constexpr int GPB = NT <= 4 ? 8 / NT : 1;
+  constexpr int NCHUNK = NT * 32 * CPR;                     // 16-byte key chunks per group
+  constexpr int NPIECE = NT * 8 * (DH / 4);                 // (4 keys x 4 channels) pieces of V per group
+  constexpr int KS_BYTES = NT * 32 * DH, SLOT_BYTES = KS_BYTES + (PV ? DH * VTP : 0);
+  constexpr int KCH = (GPB * NCHUNK + 511) / 512;           // key chunks per thread and pass
+  constexpr int VCH = PV ? (GPB * NPIECE + 511) / 512 : 1;
+  extern __shared__ __align__(16) int8_t lds[];   // per slot: keys [NT * 32][DH] (chunk c of row r at position (c + r / RPL) % CPR), then V^T [DH][VTP]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   constexpr int nt = NT;
+  const int ws = GPB > 1 ? wave / NT : 0;                   // this wavefront's group slot
+  const int it0 = GPB > 1 ? wave % NT : wave;               // and its (first) query tile
+  const bool wave_active = GPB == 1 || wave < GPB * NT;
+  int8_t* const ks = lds + ws * SLOT_BYTES;
+  int8_t* const vt = ks + KS_BYTES;
+  const int Gi = (int)p.G;
   const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
   const bool corr = p.dq != 0 || p.dk != 0;
-  constexpr int KCH = (NT * 32 * CPR + 511) / 512;      // 16-byte key chunks per thread
-  const int nchunks = nt * 32 * CPR;
-  // Workgroups are persistent over the (batch item, head) groups.  The keys and this wavefront's first query fragments of
-  // the NEXT group are requested into registers before the current group's arithmetic, so their latency hides behind it.
+  // Workgroups are persistent over the (batch item, head) groups.  The keys (and values) and this wavefront's first query
+  // fragments of the NEXT pass are requested into registers before the current pass's arithmetic, so their latency hides.
   v4i kreg[KCH], qreg[KSTEPS];
   unsigned vreg[VCH][4];
-  int8_t* const vt = ks + NT * 32 * DH;       // [DH][VTP]: V^T of this group
-  auto request = [&](int64_t g) {
-    const int64_t b = g / p.H;
-    const int h = (int)(g - b * p.H);
-    const int8_t* Kg = p.K + b * p.so + (int64_t)h * p.si;
-    const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
+  auto group_base = [&](int g, const int8_t* base) {       // first byte of the group's slice of a token-major tensor
+    g = g < Gi ? g : Gi - 1;
+    const int b = g / p.H, h = g - b * p.H;
+    return base + (int64_t)b * p.so + (int64_t)h * p.si;
+  };
+  auto request = [&](int gq) {
     if (PV) {
-      const int8_t* Vg = p.V + b * p.so + (int64_t)h * p.si;
 #pragma unroll
       for (int u = 0; u < VCH; ++u) {
         const int id = tid + u * 512;
-        const int c4 = id % (DH / 4), j4 = id / (DH / 4);
+        const int slot = id / NPIECE, local = id - slot * NPIECE;
+        const int c4 = local % (DH / 4), j4 = local / (DH / 4);
+        const int8_t* Vg = group_base(gq + slot, p.V);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = j4 * 4 + e;
-          vreg[u][e] = (j4 < NT * 8 && j < p.N) ? *reinterpret_cast<const unsigned*>(Vg + (int64_t)j * p.ldk + c4 * 4) : 0u;
+          vreg[u][e] = (slot < GPB && j < p.N) ? *reinterpret_cast<const unsigned*>(Vg + (int64_t)j * p.ldk + c4 * 4) : 0u;
         }
       }
     }
 #pragma unroll
     for (int u = 0; u < KCH; ++u) {
       const int id = tid + u * 512;
-      const int r = id / CPR, c = id - r * CPR;
+      const int slot = id / NCHUNK, local = id - slot * NCHUNK;
+      const int r = local / CPR, c = local - r * CPR;
       const int rr = r < p.N ? r : p.N - 1;
-      if (id < nchunks) kreg[u] = *reinterpret_cast<const v4i*>(Kg + (int64_t)rr * p.ldk + c * 16);
+      if (slot < GPB) kreg[u] = *reinterpret_cast<const v4i*>(group_base(gq + slot, p.K) + (int64_t)rr * p.ldk + c * 16);
     }
-    const int qi = wave * 32 + l32;
+    const int qi = it0 * 32 + l32;
     const int qi_ld = qi < p.N ? qi : p.N - 1;
+    const int8_t* Qg = group_base(gq + ws, p.Q);
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qreg[s] = *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
   };
-  int64_t g = blockIdx.x;
-  if (g < p.G) request(g);
-  for (; g < p.G; g += gridDim.x) {
-  const int64_t b = g / p.H;
-  const int h = (int)(g - b * p.H);
+  int gq = (int)blockIdx.x * GPB;
+  if (gq < Gi) request(gq);
+  for (; gq < Gi; gq += (int)gridDim.x * GPB) {
+  const int64_t g = gq + ws;
+  const bool group_live = wave_active && g < p.G;
+  const int64_t b = (g < p.G ? g : p.G - 1) / p.H;
+  const int h = (int)((g < p.G ? g : p.G - 1) - b * p.H);
   const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
-  // ---- stage the keys of this group in LDS (every wavefront has finished with the previous group's keys) ----
+  // ---- stage the keys of this pass in LDS (every wavefront has finished with the previous pass) ----
 #pragma unroll
   for (int u = 0; u < KCH; ++u) {
     const int id = tid + u * 512;
-    const int r = id / CPR, c = id - r * CPR;
-    if (id < nchunks) *reinterpret_cast<v4i*>(ks + r * DH + (((c + r / RPL) % CPR) * 16)) = kreg[u];
+    const int slot = id / NCHUNK, local = id - slot * NCHUNK;
+    const int r = local / CPR, c = local - r * CPR;
+    if (slot < GPB) *reinterpret_cast<v4i*>(lds + slot * SLOT_BYTES + r * DH + (((c + r / RPL) % CPR) * 16)) = kreg[u];
   }
   if (PV) {      // 4 keys x 4 channels per piece, bytes transposed in registers: V^T[channel][key]
 #pragma unroll
     for (int u = 0; u < VCH; ++u) {
       const int id = tid + u * 512;
-      const int c4 = id % (DH / 4), j4 = id / (DH / 4);
-      if (j4 < NT * 8) {
+      const int slot = id / NPIECE, local = id - slot * NPIECE;
+      const int c4 = local % (DH / 4), j4 = local / (DH / 4);
+      if (slot < GPB) {
         const unsigned r0 = vreg[u][0], r1 = vreg[u][1], r2 = vreg[u][2], r3 = vreg[u][3];
         const unsigned lo01 = __builtin_amdgcn_perm(r1, r0, 0x05010400u);   // r0.b0 r1.b0 r0.b1 r1.b1
         const unsigned hi01 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);   // r0.b2 r1.b2 r0.b3 r1.b3
@@ -131,7 +149,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         const unsigned o1 = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
         const unsigned o2 = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
         const unsigned o3 = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
-        int8_t* dst = vt + (c4 * 4) * VTP + j4 * 4;
+        int8_t* dst = lds + slot * SLOT_BYTES + KS_BYTES + (c4 * 4) * VTP + j4 * 4;
         *reinterpret_cast<unsigned*>(dst) = o0;
         *reinterpret_cast<unsigned*>(dst + VTP) = o1;
         *reinterpret_cast<unsigned*>(dst + 2 * VTP) = o2;
@@ -143,15 +161,15 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
   for (int s = 0; s < KSTEPS; ++s) fq0[s] = qreg[s];
   __syncthreads();
-  if (g + gridDim.x < p.G) request(g + gridDim.x);
+  if (gq + (int)gridDim.x * GPB < Gi) request(gq + (int)gridDim.x * GPB);
 
-  for (int it = wave; it < nt; it += 8) {       // wavefront-uniform
+  for (int it = it0; group_live && it < nt; it += (GPB > 1 ? nt : 8)) {       // wavefront-uniform
     const int qi = it * 32 + l32;
     const int qi_ld = qi < p.N ? qi : p.N - 1;
     v4i fq[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s)
-      fq[s] = it == wave ? fq0[s] : *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
+      fq[s] = it == it0 ? fq0[s] : *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
     int base = 0;
     if (corr) {
       v16i rq;
@@ -372,10 +390,13 @@ constexpr bool fused_pv_fits(int ksteps, int nt) { return nt * 16 + ksteps * 32 
 
 template <int KSTEPS, int NT>
 rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
+  if (groups > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %lld groups exceed 2^30", (long long)groups);
   const bool pv = p.V != nullptr;
-  const int lds = NT * 32 * KSTEPS * 32 + (pv ? KSTEPS * 32 * (NT * 32 + 16) : 0);
+  constexpr int GPB = NT <= 4 ? 8 / NT : 1;      // groups per workgroup pass (as in the kernel)
+  const int lds = GPB * (NT * 32 * KSTEPS * 32 + (pv ? KSTEPS * 32 * (NT * 32 + 16) : 0));
   const int64_t cap = (int64_t)(ctx->num_cu > 0 ? ctx->num_cu : 256);      // one 8-wavefront workgroup per CU
-  const dim3 grid((unsigned)(groups < cap ? groups : cap));
+  const int64_t passes = (groups + GPB - 1) / GPB;
+  const dim3 grid((unsigned)(passes < cap ? passes : cap));
   const bool f64 = p.qmax > 63;
 #define RQ_QKS_LAUNCH(B, F, C, P)                                                                                        \
   do {                                                                                                                \
