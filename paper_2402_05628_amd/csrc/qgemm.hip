@@ -14,6 +14,8 @@
 #include "qgemm_common.h"
 
 rq_status rq_launch_qgemm_pipe_w4(rq_ctx* ctx, rqg::GemmParams& p);
+bool rq_qgemv_applies(const rqg::GemmParams& p, bool w4);
+rq_status rq_launch_qgemv_w4(rq_ctx* ctx, const rqg::GemmParams& p);
 #ifdef RQ_GEMM_TS
 static long long* g_debug_ts = nullptr;
 extern "C" void rq_debug_gemm_ts(void* ptr) { g_debug_ts = static_cast<long long*>(ptr); }
@@ -183,6 +185,7 @@ rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   const bool big = g_gemm_tile ? g_gemm_tile == 2 : big_tiles >= 2 * (int64_t)ctx->num_cu;
   const bool fits32 = (double)d->M * (double)d->lda < 4.0e9 && (double)d->N * (double)d->ldb < 4.0e9;
   p.force_tall = g_gemm_tile == 4;
+  if (g_gemm_tile == 0 && rq_qgemv_applies(p, w4)) return rq_launch_qgemv_w4(ctx, p);   // a few tokens: weight-bandwidth bound
   if ((g_gemm_tile == 3 || g_gemm_tile == 0 || g_gemm_tile == 4) && d->N % 32 == 0 && fits32) {
     const rq_status st = w4 ? rq_launch_qgemm_pipe_w4(ctx, p) : rq_launch_qgemm_pipe_i8(ctx, p);
     if (st != RQ_OK) return st;

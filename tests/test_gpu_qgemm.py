@@ -142,3 +142,60 @@ def test_requantized_output(rq, bits_a, bits_w, bits_o, act):
             assert_float_close(outf.cpu().numpy(), hid, "activation " + act)
         got = out.cpu().numpy().astype(np.int64) + off
     assert_codes_close(got, want, "requant %s b%d" % (act, bits_o))
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 768, 768), (3, 2304, 768), (16, 1024, 4096), (2, 512, 11008), (1, 96, 64), (5, 4096, 2112)])
+@pytest.mark.parametrize("bits_a", [8, 4])
+def test_few_token_path_w4(rq, M, N, K, bits_a):
+    """M <= 12 with packed 4-bit weights takes the matrix-vector kernel (16 takes the MFMA kernel): accumulators bit-exact, float output and
+    re-quantized codes against the oracle's linear."""
+    b, ctx = rq
+    print("case", M, N, K, bits_a, flush=True)
+    g = np.random.default_rng(M * 7 + N + K + bits_a)
+    qa, z_a = _act_codes(g, M, K, bits_a)
+    lin = random_linear(g, N, K, 4)
+    want_acc = orc.qlinear_acc(qa, z_a, lin["codes"], lin["z_w"])
+    s_a = np.float32(0.02)
+    y = orc.qlinear(qa, s_a, z_a, lin)
+    res = g.normal(size=(M, N)).astype(np.float32)
+    a_off = b.store_offset(bits_a, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    outf = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ld = lin_to_device(lin, 4)
+    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), ld, out_acc=acc, out_f32=outf, residual=dev(res), rowsum_a=rs)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), want_acc)
+    assert_float_close(outf.cpu().numpy(), y + res, "few-token f32")
+    s_o = np.float32((y.max() - y.min()) / 255)
+    z_o = int(np.rint(-y.min() / np.float64(s_o)))
+    off_o = b.store_offset(8, z_o)
+    outq = torch.zeros((M, N), dtype=torch.int8, device="cuda")
+    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), ld, out_q=outq, bits_o=8, s_o=[float(s_o)], z_o=[z_o], off_o=[off_o], seg_len=N, rowsum_a=rs)
+    # a handful of outputs: one float32-vs-float64 near-tie is allowed even when it exceeds 1e-4 of so few elements
+    assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(y, s_o, z_o, 8), "few-token codes",
+                       budget=max(1e-4, 1.5 / (M * N)))
+
+
+@pytest.mark.parametrize("act", ["gelu", "gated"])
+def test_few_token_path_activations(rq, act):
+    b, ctx = rq
+    M, K = 4, 512
+    N = 384 if act == "gelu" else 512
+    g = np.random.default_rng(77 + len(act))
+    qa, z_a = _act_codes(g, M, K, 8)
+    lin = random_linear(g, N, K, 4)
+    s_a = np.float32(1.5 / (np.sqrt(K) * (256 / 3.46) * (16 / 3.46) * 3e-3))
+    y = orc.qlinear(qa, s_a, z_a, lin)
+    Dm = N // 2
+    hid = orc.mlp_activation(y, orc.ACT_GELU if act == "gelu" else orc.ACT_SILU_GATED, Dm)
+    a_off = b.store_offset(8, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    outf = torch.zeros(hid.shape, dtype=torch.float32, device="cuda")
+    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, 4, Dm if act == "gated" else 0),
+               act=b.ACT_GELU if act == "gelu" else b.ACT_SILU_GATED, out_f32=outf, rowsum_a=rs)
+    assert_float_close(outf.cpu().numpy(), hid, "few-token " + act)
