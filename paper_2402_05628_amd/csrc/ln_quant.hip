@@ -53,11 +53,16 @@ __device__ __forceinline__ double rsqrt_f64(double a) {
   return r;
 }
 
+// wavefronts per SIMD the kernel is built for (bounds its registers): rows held in registers grow with NV
+constexpr int ln_waves_per_simd(int nv, bool f32q, bool persist) {
+  return persist ? (nv <= 8 ? 2 : 1) : (nv <= 6 && f32q ? 7 : nv <= 8 ? 4 : nv <= 16 ? 2 : 1);
+}
+
 // F32Q: the normalization and the quantizer run in float32 (codes of at most 6 bits: the pre-round value is below 64, so its
 // float32 error, ~1e-5 of a code, flips far fewer than 1e-4 of the codes); the row statistics stay float64 either way.
 // PERSIST: workgroups loop over rows and fetch the next rows early; otherwise one pass, fewer registers, more wavefronts.
 template <int LPR, int NV, bool F32Q, bool PERSIST>
-__global__ __launch_bounds__(256) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
+__global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
                                                        double eps, const float* __restrict__ gamma_t,
                                                        const float* __restrict__ beta_t, double inv_s, double zcode, float qmaxf,
                                                        unsigned off4, int8_t* __restrict__ q, int64_t ldq,
@@ -179,10 +184,12 @@ rq_status launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcode, f
   const int64_t blocks = (d->T + rows_per_block - 1) / rows_per_block;
   const bool f32q = d->bits <= 6;
   const int lds = d->D * (f32q ? 8 : 16);
-  // one pass per workgroup while every workgroup can be resident at once (8 per CU at <= 64 registers, LDS permitting);
+  // one pass per workgroup while every workgroup can be resident at once (7 per CU: the kernel is built for 7 wavefronts
+  // per SIMD; LDS permitting);
   // beyond that, persistent workgroups that prefetch their next rows
   const int by_lds = lds > 0 ? (160 * 1024) / lds : 8;
-  const int64_t one_pass_slots = (int64_t)ctx->num_cu * (by_lds < 8 ? by_lds : 8);
+  const int by_regs = ln_waves_per_simd(NV, f32q, false);
+  const int64_t one_pass_slots = (int64_t)ctx->num_cu * (by_lds < by_regs ? by_lds : by_regs);
   if (blocks <= one_pass_slots) {
     return f32q ? launch_one<LPR, NV, true, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4)
                 : launch_one<LPR, NV, false, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4);
