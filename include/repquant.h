@@ -218,6 +218,15 @@ rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
  * 1 = simple 128x128, 2 = simple 256x128, 3 = pipelined, 4 = pipelined with the 320-row tile wherever it exists. */
 rq_status rq_set_gemm_tile(int32_t tile);
 
+/* rq_qgemm (weight mode, float output + residual) and rq_ln_quant of that output in ONE kernel whose workgroups own whole
+ * output rows: xbar = GEMM + residual is written to d->out_f32 as usual and its normalized, quantized codes to ln->q
+ * without being read back (block equations for X-bar followed by the LayerNorm of the MLP branch).  ln->x is ignored
+ * (the input is the GEMM output); ln->T == d->M, ln->D == d->N.  Supported: RQ_W_U4 weights, N in {256, 512, 768}, no
+ * activation, out_f32 the only GEMM output, codes of at most 6 bits, ln->rowsum NULL; RQ_ERR_UNSUPPORTED otherwise (the
+ * caller then takes the two separate calls, which compute the same values up to the float32 order of summation of the
+ * row statistics). */
+rq_status rq_qgemm_ln_quant(rq_ctx* ctx, const rq_gemm_desc* d, const rq_ln_desc* ln);
+
 /* ---- rq_softmax_log2_quant --------------------------------------------------------------------------
  * Softmax fused with the log-sqrt2 quantizer in its base-2 form (Eq. (3.3-1), second line):
  *    l[j]  = logit_scale * acc[j] (+ bias[g % H, i, j]);  masked j (causal: j > i) are excluded;
@@ -371,6 +380,12 @@ rq_status rq_set_attn_chunk_bytes(int64_t bytes);
  *   0: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length.
  * All three compute the same integers and the same codes. */
 rq_status rq_set_attn_fused(int on);
+/* 1: rq_block_forward takes rq_qgemm_ln_quant for the output projection + second LayerNorm where it applies
+ * (process-wide); 0 (default): rq_qgemm followed by rq_ln_quant.  Both give the same float32 residual stream and the
+ * same codes up to the summation order of the row statistics; the fused kernel saves one read of the residual stream
+ * but runs one 64-row tile per compute unit with nothing to overlap its memory phase, and measures no faster on the
+ * ViT-B shape. */
+rq_status rq_set_proj_ln_fused(int on);
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);

@@ -200,6 +200,8 @@ _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockPara
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
 _rq_set_fused = _sig("rq_set_attn_fused", i32, [i32])
+_rq_set_proj_ln = _sig("rq_set_proj_ln_fused", i32, [i32])
+_rq_qgemm_ln = _sig("rq_qgemm_ln_quant", i32, [vp, C.POINTER(GemmDesc), C.POINTER(LnDesc)])
 _rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
 _rq_profile_reset = _sig("rq_profile_reset", i32, [vp])
 _rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i64)])
@@ -266,6 +268,24 @@ def rq_qgemm(ctx, A, a_off, z_a, s_a, lin, *, act=ACT_NONE, residual=None, out_a
             d.s_o[i], d.z_o[i], d.off_o[i] = s_o[i], z_o[i], off_o[i]
     d.batch_outer, d.batch_inner = 1, 1
     ctx.check(_rq_qgemm(ctx.handle, C.byref(d)))
+
+
+def rq_qgemm_ln_quant(ctx, A, a_off, z_a, s_a, lin, residual, out_f32, gamma_t, beta_t, s_tilde, z_tilde, bits, q,
+                      norm_kind=NORM_LAYERNORM, eps=1e-6, store_off=None):
+    """GEMM + residual written to out_f32 and its LayerNorm-quantized codes written to q, in one kernel; returns store_off."""
+    d = GemmDesc()
+    d.M, d.N, d.K = A.shape[0], lin["N"], lin["K"]
+    d.A, d.lda, d.a_off, d.z_a, d.s_a = _p(A), A.stride(0), a_off, z_a, s_a
+    d.B, d.ldb, d.b_format = _p(lin["w"]), lin["w"].stride(0), lin["format"]
+    d.s_b, d.z_b, d.colsum_b, d.bias = _p(lin["s_w"]), _p(lin["z_w"]), _p(lin["colsum_w"]), _p(lin.get("bias"))
+    d.residual, d.ldr = _p(residual), residual.stride(0)
+    d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
+    d.batch_outer, d.batch_inner = 1, 1
+    off = store_offset(bits, z_tilde) if store_off is None else store_off
+    ln = LnDesc(T=A.shape[0], D=lin["N"], norm_kind=norm_kind, eps=eps, x=None, ldx=lin["N"], gamma_t=_p(gamma_t), beta_t=_p(beta_t),
+                s_tilde=s_tilde, z_tilde=z_tilde, bits=bits, store_off=off, q=_p(q), ldq=q.stride(0), rowsum=None)
+    ctx.check(_rq_qgemm_ln(ctx.handle, C.byref(d), C.byref(ln)))
+    return off
 
 
 def rq_qk(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_off, z_q, k_off, z_k, acc, ld, causal=False):
@@ -349,6 +369,12 @@ def rq_minmax_f32(ctx, v):
 
 def set_attn_chunk_bytes(nbytes: int):
     rc = _rq_set_chunk(nbytes)
+    if rc != RQ_OK:
+        raise RqError(rc, _rq_last_error(None).decode())
+
+
+def set_proj_ln_fused(on: bool):
+    rc = _rq_set_proj_ln(1 if on else 0)
     if rc != RQ_OK:
         raise RqError(rc, _rq_last_error(None).decode())
 

@@ -19,6 +19,7 @@ struct Plan {
 
 int64_t g_attn_chunk_bytes = 64ll << 20;
 int g_attn_fused = 1;
+int g_proj_ln_fused = 0;
 
 bool use_fused(const rq_block_params* p, int64_t seq) {
   return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H);
@@ -72,6 +73,11 @@ extern "C" {
 rq_status rq_set_attn_fused(int on) {
   if (on < 0 || on > 2) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_attn_fused: %d not in 0..2", on);
   g_attn_fused = on;
+  return RQ_OK;
+}
+
+rq_status rq_set_proj_ln_fused(int on) {
+  g_proj_ln_fused = on != 0;
   return RQ_OK;
 }
 
@@ -232,27 +238,33 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
     rq_prof_end(ctx);
     if (st != RQ_OK) return st;
   }
+  // ---- output projection + residual, LN2 + layer-wise quant ------------------------------------------------------
+  // (one kernel whose workgroups own whole rows where it exists, else the projection followed by the row kernel)
+  const int off2 = rq_store_offset(ba, p->ln2_z);
   {
     rq_gemm_desc g;
     fill_linear(g, p->proj, o, T, D, p->s_o, p->z_o, offo, rowsum);
     g.residual = x; g.ldr = D; g.out_f32 = xbar; g.ldf = D;
-    rq_prof_begin(ctx, RQ_STEP_PROJ);
-    st = rq_qgemm(ctx, &g);
-    rq_prof_end(ctx);
-    if (st != RQ_OK) return st;
-  }
-  // ---- LN2 + layer-wise quant ----------------------------------------------------------------------------------
-  const int off2 = rq_store_offset(ba, p->ln2_z);
-  {
     rq_ln_desc d;
     std::memset(&d, 0, sizeof d);
     d.T = T; d.D = D; d.norm_kind = p->norm_kind; d.eps = p->eps; d.x = xbar; d.ldx = D;
     d.gamma_t = p->ln2_gamma_t; d.beta_t = p->ln2_beta_t; d.s_tilde = p->ln2_s; d.z_tilde = p->ln2_z; d.bits = ba;
     d.store_off = off2; d.q = a; d.ldq = D; d.rowsum = need_rowsum(p->fc1) ? rowsum : nullptr;
-    rq_prof_begin(ctx, RQ_STEP_LN2);
-    st = rq_ln_quant(ctx, &d);
-    rq_prof_end(ctx);
-    if (st != RQ_OK) return st;
+    if (g_proj_ln_fused && rq_qgemm_rowln_applies(&g, &d)) {
+      rq_prof_begin(ctx, RQ_STEP_PROJ);
+      st = rq_qgemm_ln_quant(ctx, &g, &d);
+      rq_prof_end(ctx);
+      if (st != RQ_OK) return st;
+    } else {
+      rq_prof_begin(ctx, RQ_STEP_PROJ);
+      st = rq_qgemm(ctx, &g);
+      rq_prof_end(ctx);
+      if (st != RQ_OK) return st;
+      rq_prof_begin(ctx, RQ_STEP_LN2);
+      st = rq_ln_quant(ctx, &d);
+      rq_prof_end(ctx);
+      if (st != RQ_OK) return st;
+    }
   }
   // ---- FC1 + activation, re-quantized ------------------------------------------------------------------------------
   const int offh = rq_store_offset(ba, p->z_h);

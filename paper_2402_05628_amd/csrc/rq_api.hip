@@ -142,11 +142,12 @@ int32_t rq_profile_read(rq_ctx* ctx, double* ms_total, int64_t* launches) {
     if (!d) return rq_fail(ctx, RQ_ERR_INVALID_ARG, name ": descriptor is NULL");            \
   } while (0)
 
+static rq_status check_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d);
+
 static bool fits_i8(int bits, int off) { return -off >= -128 && ((1 << bits) - 1 - off) <= 127; }
 
-rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
-  RQ_CHECK_CTX("rq_ln_quant");
-  RQ_REQUIRE(d->x && d->gamma_t && d->q, RQ_ERR_INVALID_ARG, "rq_ln_quant: x, gamma_t and q must be non-NULL");
+static rq_status check_ln(rq_ctx* ctx, const rq_ln_desc* d, bool need_x) {
+  RQ_REQUIRE((d->x || !need_x) && d->gamma_t && d->q, RQ_ERR_INVALID_ARG, "rq_ln_quant: x, gamma_t and q must be non-NULL");
   RQ_REQUIRE(d->norm_kind == RQ_NORM_LAYERNORM || d->norm_kind == RQ_NORM_RMSNORM, RQ_ERR_INVALID_ARG,
              "rq_ln_quant: norm_kind %d", d->norm_kind);
   RQ_REQUIRE(d->bits >= 2 && d->bits <= 8, RQ_ERR_INVALID_ARG, "rq_ln_quant: bits = %d not in 2..8", d->bits);
@@ -159,6 +160,13 @@ rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
   RQ_REQUIRE(d->ldx >= d->D && d->ldx % 4 == 0 && d->ldq >= d->D && d->ldq % 4 == 0, RQ_ERR_SHAPE,
              "rq_ln_quant: ldx/ldq must be >= D and multiples of 4");
   RQ_REQUIRE(rq_aligned(d->x, 16) && rq_aligned(d->q, 4), RQ_ERR_INVALID_ARG, "rq_ln_quant: x needs 16-byte, q 4-byte alignment");
+  return RQ_OK;
+}
+
+rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
+  RQ_CHECK_CTX("rq_ln_quant");
+  const rq_status st = check_ln(ctx, d, true);
+  if (st != RQ_OK) return st;
   RQ_NEED_DEVICE();
   if (d->T == 0) return RQ_OK;
   return rq_launch_ln_quant(ctx, d);
@@ -230,6 +238,14 @@ rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d) {
     if (d->M == 0) return RQ_OK;
     return rq_launch_qgemm_act(ctx, d);
   }
+  const rq_status st = check_qgemm_weight(ctx, d);
+  if (st != RQ_OK) return st;
+  RQ_NEED_DEVICE();
+  if (d->M == 0) return RQ_OK;
+  return rq_launch_qgemm_weight(ctx, d);
+}
+
+static rq_status check_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   RQ_REQUIRE(d->b_format == RQ_W_I8_BAKED || d->b_format == RQ_W_I8_CENTERED || d->b_format == RQ_W_U4, RQ_ERR_INVALID_ARG,
              "rq_qgemm: b_format %d", d->b_format);
   RQ_REQUIRE(d->K % 64 == 0, RQ_ERR_SHAPE, "rq_qgemm: K = %d must be a multiple of 64", d->K);
@@ -272,9 +288,28 @@ rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d) {
     }
   }
   RQ_REQUIRE(d->batch_outer <= 1 && d->batch_inner <= 1, RQ_ERR_UNSUPPORTED, "rq_qgemm: weight mode is not batched");
+  return RQ_OK;
+}
+
+rq_status rq_qgemm_ln_quant(rq_ctx* ctx, const rq_gemm_desc* d, const rq_ln_desc* ln) {
+  RQ_CHECK_CTX("rq_qgemm_ln_quant");
+  RQ_REQUIRE(ln, RQ_ERR_INVALID_ARG, "rq_qgemm_ln_quant: the LayerNorm descriptor is NULL");
+  RQ_REQUIRE(d->A && d->B, RQ_ERR_INVALID_ARG, "rq_qgemm: A and B must be non-NULL");
+  RQ_REQUIRE(d->M >= 0 && d->N > 0 && d->K > 0, RQ_ERR_SHAPE, "rq_qgemm: M = %lld, N = %d, K = %d", (long long)d->M, d->N, d->K);
+  RQ_REQUIRE(rq_aligned(d->A, 16) && rq_aligned(d->B, 16), RQ_ERR_INVALID_ARG, "rq_qgemm: A and B need 16-byte alignment");
+  RQ_REQUIRE(d->lda >= d->K && d->lda % 16 == 0, RQ_ERR_SHAPE, "rq_qgemm: lda = %lld must be >= K and a multiple of 16",
+             (long long)d->lda);
+  rq_status st = check_qgemm_weight(ctx, d);
+  if (st != RQ_OK) return st;
+  if ((st = check_ln(ctx, ln, false)) != RQ_OK) return st;
+  RQ_REQUIRE(ln->T == d->M && ln->D == d->N, RQ_ERR_SHAPE, "rq_qgemm_ln_quant: the normalization is %lld x %d, the GEMM output %lld x %d",
+             (long long)ln->T, ln->D, (long long)d->M, d->N);
+  RQ_REQUIRE(rq_qgemm_rowln_applies(d, ln), RQ_ERR_UNSUPPORTED,
+             "rq_qgemm_ln_quant: needs packed 4-bit weights, N in {256, 512, 768}, a residual, out_f32 as the only GEMM output, no "
+             "activation, codes of at most 6 bits and no rowsum; use rq_qgemm + rq_ln_quant otherwise");
   RQ_NEED_DEVICE();
   if (d->M == 0) return RQ_OK;
-  return rq_launch_qgemm_weight(ctx, d);
+  return rq_launch_qgemm_rowln(ctx, d, ln);
 }
 
 rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d) {

@@ -53,6 +53,8 @@ rq_status rq_launch_qgemm_act(rq_ctx* ctx, const rq_gemm_desc* d);
 rq_status rq_launch_softmax(rq_ctx* ctx, const rq_softmax_desc* d);
 rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d);
 bool rq_qk_softmax_supported(int N, int d_head);
+bool rq_qgemm_rowln_applies(const rq_gemm_desc* g, const rq_ln_desc* ln);
+rq_status rq_launch_qgemm_rowln(rq_ctx* ctx, const rq_gemm_desc* g, const rq_ln_desc* ln);
 rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);
 rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, int64_t ld_tok, int64_t batch, int H, int N,
                                int d_head, int q_off, int z_q, int k_off, int z_k, double logit_scale, const float* bias,

@@ -157,6 +157,24 @@ def test_qgemm_validation(b, host_ctx):
     assert _status(b, host_ctx, fn, _gemm_desc(b, act=5)) == 1
 
 
+def test_qgemm_ln_quant_validation(b, host_ctx):
+    fn = b.lib.rq_qgemm_ln_quant
+    def call(g=None, l=None):
+        gd = _gemm_desc(b, **{**dict(M=4, N=256, K=64, b_format=b.W_U4, ldb=32, residual=FAKE, ldr=256, ldf=256), **(g or {})})
+        ld = _ln_desc(b, **{**dict(T=4, D=256, x=None, ldx=256, ldq=256), **(l or {})})
+        return fn(host_ctx.handle, C.byref(gd), C.byref(ld))
+    assert call() == 3                                           # valid, refused only for lack of a device
+    assert "host-only" in b.lib.rq_last_error(host_ctx.handle).decode()
+    assert fn(host_ctx.handle, C.byref(_gemm_desc(b)), None) == 1
+    assert call(l={"T": 5}) == 2                                 # the two descriptors disagree on the shape
+    assert call(l={"bits": 9}) == 1
+    assert call(g={"residual": None}) == 3                       # the fused kernel covers only the residual form
+    assert "rq_qgemm + rq_ln_quant" in b.lib.rq_last_error(host_ctx.handle).decode()
+    assert call(g={"b_format": b.W_I8_BAKED, "ldb": 64}) == 3
+    assert call(l={"bits": 8, "store_off": 128}) == 3
+    assert call(g={"K": 60}) == 2
+
+
 def test_softmax_and_pv_validation(b, host_ctx):
     sd = dict(G=2, H=2, Nq=8, Nk=8, ld=16, acc=FAKE, logit_scale=0.1, bias=None, mask=0, s_log=1.0, bits=4, codes=FAKE)
     ok = b.SoftmaxDesc(**sd)

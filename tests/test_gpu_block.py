@@ -28,16 +28,17 @@ SMALL = {
 
 
 @pytest.mark.parametrize("name", list(SMALL))
-@pytest.mark.parametrize("chunk_mb,fused", [(64, 1), (1, 1), (64, 2), (1, 2), (64, 0), (1, 0)])
-def test_block_forward_matches_oracle(rq, name, chunk_mb, fused):
+@pytest.mark.parametrize("chunk_mb,fused,rowln", [(64, 1, 1), (1, 1, 0), (64, 2, 1), (1, 2, 0), (64, 0, 0), (1, 0, 1)])
+def test_block_forward_matches_oracle(rq, name, chunk_mb, fused, rowln):
     b, ctx = rq
     cfg = SMALL[name]
-    print("case", name, chunk_mb, fused, flush=True)
+    print("case", name, chunk_mb, fused, rowln, flush=True)
     raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
     P = orc.calibrate_block(raw, cfg_dict(cfg))
     want, t = orc.block_forward(P, raw["x"], keep=True)
     b.set_attn_chunk_bytes(chunk_mb << 20)
     b.set_attn_fused(fused)
+    b.set_proj_ln_fused(rowln)
     try:
         blk = b.Block(ctx, cfg, block_to_device(P))
         x = dev(raw["x"])
@@ -47,6 +48,7 @@ def test_block_forward_matches_oracle(rq, name, chunk_mb, fused):
     finally:
         b.set_attn_chunk_bytes(64 << 20)
         b.set_attn_fused(1)
+        b.set_proj_ln_fused(False)
     got = y.cpu().numpy().astype(np.float64)
     ref = np.abs(want).max()
     err = np.abs(got - want).max()

@@ -199,3 +199,33 @@ def test_few_token_path_activations(rq, act):
     b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, 4, Dm if act == "gated" else 0),
                act=b.ACT_GELU if act == "gelu" else b.ACT_SILU_GATED, out_f32=outf, rowsum_a=rs)
     assert_float_close(outf.cpu().numpy(), hid, "few-token " + act)
+
+
+@pytest.mark.parametrize("M,N,K,bits,kind", [(197, 768, 768, 4, 0), (64, 256, 128, 4, 0), (333, 512, 3072, 6, 1), (1, 768, 64, 4, 0),
+                                             (130, 768, 1536, 4, 1)])
+def test_gemm_with_layernorm_quant_epilogue(rq, M, N, K, bits, kind):
+    """rq_qgemm_ln_quant: xbar = linear + residual against the oracle's linear, and the codes against the oracle's
+    LayerNorm / RMSNorm quantizer applied to the oracle's xbar."""
+    from tests.helpers import folded_ln_case
+    b, ctx = rq
+    print("case", M, N, K, bits, kind, flush=True)
+    g = np.random.default_rng(M + N + K)
+    qa, z_a = _act_codes(g, M, K, 4)
+    lin = random_linear(g, N, K, 4)
+    s_a = np.float32(0.05)
+    res = (g.normal(size=(M, N)) * np.exp(1.5 * g.normal(size=N))[None, :]).astype(np.float32)
+    xbar = orc.qlinear(qa, s_a, z_a, lin) + res
+    # a folded affine and layer-wise quantizer calibrated on these rows (plus spare rows so that a single row calibrates too)
+    cal = np.concatenate([xbar, (g.normal(size=(40, N)) * np.abs(xbar).mean(axis=0)[None, :])], axis=0)
+    c = folded_ln_case(cal.astype(np.float32), 3, bits, kind)
+    want = orc.ln_quant(xbar, c["gamma_t"], c["beta_t"], c["s_t"], c["z_t"], bits, 1e-6, kind)
+    a_off = b.store_offset(4, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    outf = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    q = torch.zeros((M, N), dtype=torch.int8, device="cuda")
+    off = b.rq_qgemm_ln_quant(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, 4), dev(res), outf, dev(c["gamma_t"]),
+                              None if c["beta_t"] is None else dev(c["beta_t"]), float(c["s_t"]), int(c["z_t"]), bits, q,
+                              norm_kind=kind)
+    assert_float_close(outf.cpu().numpy(), xbar, "xbar")
+    got = q.cpu().numpy().astype(np.int64) + off
+    assert_codes_close(got, want, "codes after the fused normalization", budget=max(1e-4, 1.5 / (M * N)))
