@@ -138,6 +138,24 @@ def make_rows(T: int, D: int, seed: int, outliers: bool = True) -> np.ndarray:
     return x
 
 
+def make_rows_asymmetric(T: int, D: int, seed: int) -> np.ndarray:
+    """[T, D] float32 stand-in for a post-LayerNorm activation X' with the structure the per-channel dual clipping is
+    designed for: a per-channel scale and offset, and in every channel a few outliers at both extremes whose rate
+    and reach differ between the two sides and between channels (some channels left-biased, some right-biased)."""
+    g = np.random.Generator(np.random.Philox(key=0xD0A1C + seed))
+    f32 = np.float32
+    x = g.standard_normal((T, D), dtype=f32)
+    x *= np.exp(0.7 * g.standard_normal(D)).astype(f32)[None, :]
+    x += (0.5 * g.standard_normal(D)).astype(f32)[None, :]
+    for side in (1.0, -1.0):
+        rate = g.uniform(0.0, 0.01, size=D)                               # share of tokens that are outliers on this side
+        reach = np.exp(g.uniform(np.log(2.0), np.log(12.0), size=D))      # how far beyond the bulk they sit
+        hit = g.random((T, D)) < rate[None, :]
+        mag = (np.abs(g.standard_normal((T, D))) + 1.0) * reach[None, :]
+        x = np.where(hit, x + f32(side) * mag.astype(f32), x)
+    return x.astype(f32)
+
+
 def make_codes(shape, bits: int, seed: int) -> np.ndarray:
     """Uniform random b-bit codes (uint8)."""
     g = np.random.Generator(np.random.Philox(key=0xC0DE5 + seed))
