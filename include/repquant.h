@@ -350,6 +350,51 @@ typedef struct {
   const float* bias;      /* [N] or NULL */
 } rq_qlinear;
 
+/* ---- per-channel dual clipping, learnt (Section "Per-channel dual clipping": Eqs. for X'_up and X'_low, the arg-min
+ * Eq.; Section "Implementation details": Adam, 100 iterations, learning rate 0.01) ------------------------------
+ * For every channel d of X' = norm(x) * gamma + beta  [T, D]:
+ *   up = max_n X'[n,d] * Sigmoid(alpha1_d),  lo = min_n X'[n,d] * Sigmoid(alpha2_d),
+ *   s = (up - lo) / (2^bits - 1),  z = round(-lo / s),  X'^ = s (clip(round(X'/s) + z, 0, 2^bits - 1) - z),
+ * and (alpha1_d, alpha2_d) follow `iters` Adam steps (beta 0.9 / 0.999, eps 1e-8, bias-corrected) on
+ * sum_n (X' - X'^)^2 from alpha1 = alpha2 = alpha0, the two roundings differentiated straight-through (derivative 1)
+ * and the clip passing the gradient on [0, 2^bits - 1].  Float64 arithmetic throughout.  A channel whose maximum
+ * equals its minimum is left at alpha0 with loss 0.
+ *   x:          device float32 [T, ldx]; gamma == NULL means x already is X' (norm_kind, eps, beta ignored)
+ *   gamma/beta: device float32 [D]; beta may be NULL (= 0)
+ *   alpha1, alpha2: device float64 [D], out (required)
+ *   clip_up, clip_lo: device float32 [D] or NULL, out: Sigmoid(alpha), the factors rq_block_calibrate takes
+ *   up, lo, loss0, loss: device float64 [D] or NULL, out: the contracted bounds, the channel's sum of squares before
+ *               the first and after the last step
+ *   workspace:  device, at least rq_dual_clip_workspace_bytes(T) bytes, 16-byte aligned; unused when gamma == NULL
+ * Errors: RQ_ERR_INVALID_ARG (NULL / misaligned pointers, bits outside 2..16, iters < 0, lr or eps not finite and
+ * positive), RQ_ERR_SHAPE (T < 1, D < 1, ldx < D, D % 4 != 0 with gamma given), RQ_ERR_WORKSPACE. */
+typedef struct {
+  int64_t T;
+  int32_t D;
+  int64_t ldx;
+  const float* x;
+  int32_t norm_kind;
+  double eps;
+  const float* gamma;
+  const float* beta;
+  int32_t bits;
+  int32_t iters;
+  double lr;
+  double alpha0;
+  double* alpha1;
+  double* alpha2;
+  float* clip_up;
+  float* clip_lo;
+  double* up;
+  double* lo;
+  double* loss0;
+  double* loss;
+  void* workspace;
+  size_t workspace_bytes;
+} rq_dual_clip_desc;
+size_t rq_dual_clip_workspace_bytes(int64_t T);
+rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d);
+
 typedef struct {
   int32_t D, H, Dm;
   int32_t norm_kind, act, mask;

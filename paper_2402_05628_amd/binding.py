@@ -50,6 +50,13 @@ class LnDesc(C.Structure):
                 ("store_off", i32), ("q", vp), ("ldq", i64), ("rowsum", vp)]
 
 
+class DualClipDesc(C.Structure):
+    _fields_ = [("T", i64), ("D", i32), ("ldx", i64), ("x", vp), ("norm_kind", i32), ("eps", f64), ("gamma", vp),
+                ("beta", vp), ("bits", i32), ("iters", i32), ("lr", f64), ("alpha0", f64), ("alpha1", vp), ("alpha2", vp),
+                ("clip_up", vp), ("clip_lo", vp), ("up", vp), ("lo", vp), ("loss0", vp), ("loss", vp),
+                ("workspace", vp), ("workspace_bytes", C.c_size_t)]
+
+
 class GemmDesc(C.Structure):
     _fields_ = [("M", i64), ("N", i32), ("K", i32), ("A", vp), ("lda", i64), ("a_off", i32), ("z_a", i32),
                 ("s_a", f32), ("B", vp), ("ldb", i64), ("b_format", i32), ("s_b", vp), ("z_b", vp),
@@ -208,6 +215,8 @@ _rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i
 _rq_rowsum = _sig("rq_rowsum_i8", i32, [vp, vp, i64, i32, i64, vp])
 _rq_ln_cmm = _sig("rq_ln_channel_minmax", i32, [vp, vp, i64, i32, i64, i32, f64, vp, vp, vp, vp])
 _rq_minmax = _sig("rq_minmax_f32", i32, [vp, vp, i64, i64, i64, vp])
+_rq_dual_clip_ws = _sig("rq_dual_clip_workspace_bytes", C.c_size_t, [i64])
+_rq_dual_clip = _sig("rq_dual_clip_learn", i32, [vp, C.POINTER(DualClipDesc)])
 
 
 def rq_reparam_fold(ctx, s_ch, z_ch, gamma, beta, W, b, s_log=1.0):
@@ -359,6 +368,25 @@ def rq_ln_channel_minmax(ctx, x, gamma, beta, norm_kind=NORM_LAYERNORM, eps=1e-6
     cmax = torch.empty(D, dtype=torch.float64, device=x.device)
     ctx.check(_rq_ln_cmm(ctx.handle, _p(x), x.shape[0], D, x.stride(0), norm_kind, eps, _p(gamma), _p(beta), _p(cmin), _p(cmax)))
     return cmin, cmax
+
+
+def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYERNORM, eps=1e-6, iters=100, lr=0.01, alpha0=4.0):
+    """Learn the per-channel clipping factors of X' = norm(x) * gamma + beta (or of x itself when gamma is None).
+    Returns a dict of device tensors: alpha1, alpha2, up, lo, loss0, loss (float64 [D]), clip_up, clip_lo (float32 [D])."""
+    T, D = x.shape
+    f64t = dict(dtype=torch.float64, device=x.device)
+    out = {k: torch.empty(D, **f64t) for k in ("alpha1", "alpha2", "up", "lo", "loss0", "loss")}
+    out["clip_up"] = torch.empty(D, dtype=torch.float32, device=x.device)
+    out["clip_lo"] = torch.empty(D, dtype=torch.float32, device=x.device)
+    nbytes = _rq_dual_clip_ws(T) if gamma is not None else 0
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    d = DualClipDesc(T=T, D=D, ldx=x.stride(0), x=_p(x), norm_kind=norm_kind, eps=eps, gamma=_p(gamma), beta=_p(beta), bits=bits,
+                     iters=iters, lr=lr, alpha0=alpha0, alpha1=_p(out["alpha1"]), alpha2=_p(out["alpha2"]),
+                     clip_up=_p(out["clip_up"]), clip_lo=_p(out["clip_lo"]), up=_p(out["up"]), lo=_p(out["lo"]),
+                     loss0=_p(out["loss0"]), loss=_p(out["loss"]), workspace=_p(ws), workspace_bytes=nbytes)
+    ctx.check(_rq_dual_clip(ctx.handle, C.byref(d)))
+    out["_workspace"] = ws                      # keeps the scratch alive until the caller drops the result
+    return out
 
 
 def rq_minmax_f32(ctx, v):

@@ -454,4 +454,31 @@ rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols,
   return rq_launch_minmax_f32(ctx, v, rows, cols, ld, out2);
 }
 
+rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d) {
+  RQ_CHECK_CTX("rq_dual_clip_learn");
+  RQ_REQUIRE(d->x && d->alpha1 && d->alpha2, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: x, alpha1 and alpha2 must be non-NULL");
+  RQ_REQUIRE(d->T >= 1 && d->D >= 1 && d->ldx >= d->D, RQ_ERR_SHAPE, "rq_dual_clip_learn: T = %lld, D = %d, ldx = %lld",
+             (long long)d->T, d->D, (long long)d->ldx);
+  RQ_REQUIRE(rq_aligned(d->x, 4) && rq_aligned(d->alpha1, 8) && rq_aligned(d->alpha2, 8) && rq_aligned(d->up, 8) &&
+                 rq_aligned(d->lo, 8) && rq_aligned(d->loss0, 8) && rq_aligned(d->loss, 8) && rq_aligned(d->clip_up, 4) &&
+                 rq_aligned(d->clip_lo, 4),
+             RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: float32 arrays need 4-byte, float64 arrays 8-byte alignment");
+  RQ_REQUIRE(d->bits >= 2 && d->bits <= 16, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: bits = %d not in 2..16", d->bits);
+  RQ_REQUIRE(d->iters >= 0 && d->iters <= 100000, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: iters = %d", d->iters);
+  RQ_REQUIRE(d->lr > 0.0 && std::isfinite(d->lr) && std::isfinite(d->alpha0), RQ_ERR_INVALID_ARG,
+             "rq_dual_clip_learn: lr must be positive and finite, alpha0 finite");
+  if (d->gamma) {
+    RQ_REQUIRE(d->norm_kind == RQ_NORM_LAYERNORM || d->norm_kind == RQ_NORM_RMSNORM, RQ_ERR_INVALID_ARG,
+               "rq_dual_clip_learn: norm_kind %d", d->norm_kind);
+    RQ_REQUIRE(d->eps > 0.0 && std::isfinite(d->eps), RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: eps must be positive and finite");
+    RQ_REQUIRE(d->D % 4 == 0 && d->ldx % 4 == 0 && rq_aligned(d->x, 16), RQ_ERR_SHAPE,
+               "rq_dual_clip_learn: with a normalization D and ldx must be multiples of 4 and x 16-byte aligned");
+    RQ_REQUIRE(d->workspace && rq_aligned(d->workspace, 16) && d->workspace_bytes >= rq_dual_clip_workspace_bytes(d->T),
+               RQ_ERR_WORKSPACE, "rq_dual_clip_learn: workspace of %zu bytes, %zu needed (16-byte aligned)", d->workspace_bytes,
+               rq_dual_clip_workspace_bytes(d->T));
+  }
+  RQ_NEED_DEVICE();
+  return rq_launch_dual_clip(ctx, d);
+}
+
 }  // extern "C"

@@ -49,7 +49,7 @@ def test_structures_have_the_c_layout(b, tmp_path):
     """sizeof and the offset of the last field of every descriptor, as gcc lays the header out."""
     pairs = [("rq_fold_desc", b.FoldDesc), ("rq_wq_desc", b.WqDesc), ("rq_ln_desc", b.LnDesc), ("rq_gemm_desc", b.GemmDesc),
              ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_attn_fused_desc", b.AttnFusedDesc),
-             ("rq_pv_desc", b.PvDesc),
+             ("rq_pv_desc", b.PvDesc), ("rq_dual_clip_desc", b.DualClipDesc),
              ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
     for cname, cls in pairs:
@@ -173,6 +173,26 @@ def test_qgemm_ln_quant_validation(b, host_ctx):
     assert call(g={"b_format": b.W_I8_BAKED, "ldb": 64}) == 3
     assert call(l={"bits": 8, "store_off": 128}) == 3
     assert call(g={"K": 60}) == 2
+
+
+def test_dual_clip_validation(b, host_ctx):
+    fn = b.lib.rq_dual_clip_learn
+    def call(**kw):
+        f = dict(T=100, D=64, ldx=64, x=FAKE, norm_kind=b.NORM_LAYERNORM, eps=1e-6, gamma=FAKE, beta=None, bits=4, iters=100,
+                 lr=0.01, alpha0=4.0, alpha1=FAKE, alpha2=FAKE, workspace=FAKE, workspace_bytes=b.lib.rq_dual_clip_workspace_bytes(100))
+        f.update(kw)
+        return fn(host_ctx.handle, C.byref(b.DualClipDesc(**f)))
+    assert b.lib.rq_dual_clip_workspace_bytes(100) == 1600
+    assert call() == 3                                              # valid: refused only for lack of a device
+    assert call(gamma=None, workspace=None, workspace_bytes=0, D=7, ldx=7) == 3     # x given as X': no workspace, any D
+    assert fn(host_ctx.handle, None) == 1
+    assert call(x=None) == 1 and call(alpha1=None) == 1
+    assert call(bits=1) == 1 and call(bits=17) == 1
+    assert call(iters=-1) == 1 and call(lr=0.0) == 1 and call(lr=float("nan")) == 1
+    assert call(T=0) == 2 and call(ldx=32) == 2 and call(D=66, ldx=68) == 2
+    assert call(workspace_bytes=8) == 4 and call(workspace=None) == 4
+    assert "rq_dual_clip_learn" in b.lib.rq_last_error(host_ctx.handle).decode()
+    assert call(alpha1=FAKE + 4) == 1
 
 
 def test_softmax_and_pv_validation(b, host_ctx):
