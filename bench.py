@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, TOP/s
+PEAK_FP64_TFLOPS = 78.6       # MI355X vector float64
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
 
 
@@ -98,6 +99,54 @@ def standalone_row_kernels(rq, ctx, cfg, torch):
     return out
 
 
+DUAL_CLIP_FLOPS_PER_ELEMENT_PASS = 17      # mul, round, 7 add/sub, 2 compare, min, max, mul, 2 fma (4)
+
+
+def bench_dual_clip(args, cfg, rq, synth, np, torch):
+    """One step = learning the clipping factors of one LayerNorm activation [T, D] (100 Adam iterations)."""
+    iters, lr, alpha0 = 100, 0.01, 4.0
+    torch.cuda.set_device(0)
+    ctx = rq.Context(0)
+    raw = synth.make_block(cfg, args.config, 0)
+    x = torch.from_numpy(raw["x"]).cuda()
+    gamma, beta = torch.from_numpy(raw["ln1_gamma"]).cuda(), torch.from_numpy(raw["ln1_beta"]).cuda()
+    run = lambda: rq.rq_dual_clip_learn(ctx, x, cfg.bits_a, gamma=gamma, beta=beta, norm_kind=cfg.norm, eps=cfg.eps, iters=iters,
+                                        lr=lr, alpha0=alpha0)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    flops = DUAL_CLIP_FLOPS_PER_ELEMENT_PASS * cfg.tokens * cfg.D * (iters + 1)
+    achieved = flops / sec / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dual_clip_oracle as dco
+        from oracle import repquant_oracle as orc
+        Xp = orc.layernorm(raw["x"].astype(np.float64), raw["ln1_gamma"].astype(np.float64), raw["ln1_beta"].astype(np.float64),
+                           cfg.eps, cfg.norm)
+        nch = min(cfg.D, 384)
+        c0 = time.perf_counter()
+        dco.learn(Xp[:, :nch], cfg.bits_a, iters=iters, lr=lr, alpha0=alpha0)
+        c1 = time.perf_counter()
+        cpu = dict(value=(c1 - c0) * cfg.D / nch, unit="s per layer", cores=torch.get_num_threads(), kind="oracle",
+                   sample="%d of %d channels, all %d tokens, %d iterations: %.1f s, scaled by the channel count (channels are "
+                          "independent problems)" % (nch, cfg.D, cfg.tokens, iters, c1 - c0))
+    out = dict(metric="dual-clipping learner, seconds per layer on 1 MI355X", value=sec, unit="s per layer", n_gpus=1, steps=steps,
+               warmup=warmup, ms_per_step=sec * 1e3, higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64",
+               data="synthetic",
+               config=dict(workload=cfg.name + " LayerNorm-1 activation", tokens=cfg.tokens, hidden=cfg.D, bits_a=cfg.bits_a,
+                           iterations=iters, lr=lr, alpha0=alpha0),
+               roofline=dict(bound="alu", kernel="dual_clip_kernel", achieved=achieved, peak=PEAK_FP64_TFLOPS, unit="TFLOP/s",
+                             frac=achieved / PEAK_FP64_TFLOPS, traffic=None, flops_per_launch=flops),
+               cpu_baseline=cpu)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +158,9 @@ def main():
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true", help="append three 256 MiB elementwise copies (counter calibration)")
+    ap.add_argument("--workload", default="block", choices=["block", "dual_clip"],
+                    help="block: the quantized block forward (the headline metric); dual_clip: the calibration-side learner of "
+                         "the per-channel clipping factors on the same activations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box here has one); --gpus %d is not supported. "
@@ -123,6 +175,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.batch:
         cfg = cfg.with_batch(args.batch)
+    if args.workload == "dual_clip":
+        return bench_dual_clip(args, cfg, rq, synth, np, torch)
     if args.chunk_mb:
         rq.set_attn_chunk_bytes(args.chunk_mb << 20)
     if args.tile:

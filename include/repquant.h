@@ -394,6 +394,9 @@ typedef struct {
 } rq_dual_clip_desc;
 size_t rq_dual_clip_workspace_bytes(int64_t T);
 rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d);
+/* Tuning knob (process-wide): wavefronts per channel workgroup of rq_dual_clip_learn, 1..16; 0 (default) chooses by
+ * shape.  The result does not depend on it beyond the order of the sums. */
+rq_status rq_set_dual_clip_waves(int n);
 
 typedef struct {
   int32_t D, H, Dm;

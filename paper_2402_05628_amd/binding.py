@@ -217,6 +217,7 @@ _rq_ln_cmm = _sig("rq_ln_channel_minmax", i32, [vp, vp, i64, i32, i64, i32, f64,
 _rq_minmax = _sig("rq_minmax_f32", i32, [vp, vp, i64, i64, i64, vp])
 _rq_dual_clip_ws = _sig("rq_dual_clip_workspace_bytes", C.c_size_t, [i64])
 _rq_dual_clip = _sig("rq_dual_clip_learn", i32, [vp, C.POINTER(DualClipDesc)])
+_rq_dual_clip_waves = _sig("rq_set_dual_clip_waves", i32, [i32])
 
 
 def rq_reparam_fold(ctx, s_ch, z_ch, gamma, beta, W, b, s_log=1.0):
@@ -387,6 +388,11 @@ def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYER
     ctx.check(_rq_dual_clip(ctx.handle, C.byref(d)))
     out["_workspace"] = ws                      # keeps the scratch alive until the caller drops the result
     return out
+
+
+def set_dual_clip_waves(n: int):
+    if _rq_dual_clip_waves(int(n)) != 0:
+        raise ValueError("rq_set_dual_clip_waves(%r)" % (n,))
 
 
 def rq_minmax_f32(ctx, v):
