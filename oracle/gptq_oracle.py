@@ -37,9 +37,11 @@ F64 = np.float64
 
 
 def gram_matrix(A_int):
-    """H = A^T A for integer-valued activations (q - z_a), exact."""
-    A = np.asarray(A_int, dtype=np.int64)
-    return (A.T @ A).astype(F64)
+    """H = A^T A for integer-valued activations (q - z_a).  Taken in float64, where it is exact: every partial sum is an
+    integer below 2^53 (|a| <= 255, T < 10^11), whatever the order of the additions."""
+    A = np.asarray(A_int, dtype=F64)
+    assert np.array_equal(A, np.rint(A)) and np.abs(A).max(initial=0) <= 255
+    return A.T @ A
 
 
 def damped_hessian(H, W, percdamp=0.01):
