@@ -350,6 +350,41 @@ typedef struct {
   const float* bias;      /* [N] or NULL */
 } rq_qlinear;
 
+/* ---- GPTQ weight reconstruction on the folded weights (Algorithm 1, last step of every layer; Section "Sequential
+ * Quantization Pipeline"; the method is the published GPTQ of Frantar et al., 2022) ----------------------------
+ * Same outputs, formats and row permutation as rq_weight_quant_pack, and the same per-output-channel min/max grid,
+ * but the codes are chosen column by column with second-order error compensation against the layer's calibration
+ * inputs: H = A'^T A' + percdamp * mean(diag) * I with A' = stored + a_off - z_a (the integer part of the de-quantized
+ * activation codes; the scale cancels), input channels that are always zero get H_jj = 1 and weight 0; with U the upper
+ * Cholesky factor of H^-1, for j = 0 .. K-1: q_j = quantize(w_j), err = (w_j - dequant(q_j)) / U_jj,
+ * W[:, j+1:] -= err (x) U[j, j+1:].  Float64 arithmetic; the Gram matrix is exact.
+ *   W: device float32 [N, K];  A: device int8 [T, lda], the codes the preceding rq_ln_quant / rq_qgemm stored
+ *   workspace: device, 256-byte aligned, rq_gptq_workspace_bytes(N, K, T) bytes
+ * Errors: RQ_ERR_SHAPE (K not a multiple of 64 or above 8192, T outside 1..131071, lda < K, gate_up_rows),
+ * RQ_ERR_INVALID_ARG (NULL / misaligned pointers, bits / format combination as for rq_weight_quant_pack, percdamp),
+ * RQ_ERR_WORKSPACE. */
+typedef struct {
+  int32_t N, K;
+  int32_t bits;
+  int32_t format;        /* RQ_W_* */
+  int32_t gate_up_rows;  /* 0, or Dm for the gated-MLP interleave */
+  const float* W;        /* [N, K] */
+  const float* bias;     /* [N] or NULL; only permuted along with the rows into bias_out */
+  const int8_t* A;       /* [T, lda] stored activation codes */
+  int64_t T, lda;
+  int32_t a_off, z_a;
+  double percdamp;       /* 0.01 in the published method */
+  void* w_out;           /* int8 [N, K] or uint8 [N, K/2] */
+  float* s_w;            /* [N] out */
+  int32_t* z_w;          /* [N] out */
+  int32_t* colsum_w;     /* [N] out */
+  float* bias_out;       /* [N] out or NULL */
+  void* workspace;
+  size_t workspace_bytes;
+} rq_gptq_desc;
+size_t rq_gptq_workspace_bytes(int32_t N, int32_t K, int64_t T);
+rq_status rq_gptq_quant_pack(rq_ctx* ctx, const rq_gptq_desc* d);
+
 /* ---- per-channel dual clipping, learnt (Section "Per-channel dual clipping": Eqs. for X'_up and X'_low, the arg-min
  * Eq.; Section "Implementation details": Adam, 100 iterations, learning rate 0.01) ------------------------------
  * For every channel d of X' = norm(x) * gamma + beta  [T, D]:

@@ -44,6 +44,12 @@ class WqDesc(C.Structure):
                 ("bias", vp), ("w_out", vp), ("s_w", vp), ("z_w", vp), ("colsum_w", vp), ("bias_out", vp)]
 
 
+class GptqDesc(C.Structure):
+    _fields_ = [("N", i32), ("K", i32), ("bits", i32), ("format", i32), ("gate_up_rows", i32), ("W", vp), ("bias", vp),
+                ("A", vp), ("T", i64), ("lda", i64), ("a_off", i32), ("z_a", i32), ("percdamp", f64), ("w_out", vp), ("s_w", vp),
+                ("z_w", vp), ("colsum_w", vp), ("bias_out", vp), ("workspace", vp), ("workspace_bytes", C.c_size_t)]
+
+
 class LnDesc(C.Structure):
     _fields_ = [("T", i64), ("D", i32), ("norm_kind", i32), ("eps", f64), ("x", vp), ("ldx", i64),
                 ("gamma_t", vp), ("beta_t", vp), ("s_tilde", f32), ("z_tilde", i32), ("bits", i32),
@@ -215,6 +221,8 @@ _rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i
 _rq_rowsum = _sig("rq_rowsum_i8", i32, [vp, vp, i64, i32, i64, vp])
 _rq_ln_cmm = _sig("rq_ln_channel_minmax", i32, [vp, vp, i64, i32, i64, i32, f64, vp, vp, vp, vp])
 _rq_minmax = _sig("rq_minmax_f32", i32, [vp, vp, i64, i64, i64, vp])
+_rq_gptq_ws = _sig("rq_gptq_workspace_bytes", C.c_size_t, [i32, i32, i64])
+_rq_gptq = _sig("rq_gptq_quant_pack", i32, [vp, C.POINTER(GptqDesc)])
 _rq_dual_clip_ws = _sig("rq_dual_clip_workspace_bytes", C.c_size_t, [i64])
 _rq_dual_clip = _sig("rq_dual_clip_learn", i32, [vp, C.POINTER(DualClipDesc)])
 _rq_dual_clip_waves = _sig("rq_set_dual_clip_waves", i32, [i32])
@@ -253,6 +261,27 @@ def rq_weight_quant_pack(ctx, W, bias, bits, fmt=None, gate_up_rows=0):
     d = WqDesc(N=N, K=K, bits=bits, format=fmt, gate_up_rows=gate_up_rows, W=_p(W), bias=_p(bias), w_out=_p(w_out),
                s_w=_p(out["s_w"]), z_w=_p(out["z_w"]), colsum_w=_p(out["colsum_w"]), bias_out=_p(out["bias"]))
     ctx.check(_rq_weight_quant_pack(ctx.handle, C.byref(d)))
+    return out
+
+
+def rq_gptq_quant_pack(ctx, W, bias, bits, A, a_off, z_a, fmt=None, gate_up_rows=0, percdamp=0.01):
+    """GPTQ of a float weight matrix against the stored activation codes A [T, K]; same result layout as
+    rq_weight_quant_pack."""
+    N, K = W.shape
+    fmt = weight_format(bits) if fmt is None else fmt
+    dev = W.device
+    w_out = (torch.empty((N, K // 2), dtype=torch.uint8, device=dev) if fmt == W_U4
+             else torch.empty((N, K), dtype=torch.int8, device=dev))
+    out = dict(w=w_out, s_w=torch.empty(N, dtype=torch.float32, device=dev), z_w=torch.empty(N, dtype=torch.int32, device=dev),
+               colsum_w=torch.empty(N, dtype=torch.int32, device=dev), bias=torch.empty(N, dtype=torch.float32, device=dev),
+               N=N, K=K, bits=bits, format=fmt)
+    nbytes = _rq_gptq_ws(N, K, A.shape[0])
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    d = GptqDesc(N=N, K=K, bits=bits, format=fmt, gate_up_rows=gate_up_rows, W=_p(W), bias=_p(bias), A=_p(A), T=A.shape[0],
+                 lda=A.stride(0), a_off=a_off, z_a=z_a, percdamp=percdamp, w_out=_p(w_out), s_w=_p(out["s_w"]), z_w=_p(out["z_w"]),
+                 colsum_w=_p(out["colsum_w"]), bias_out=_p(out["bias"]), workspace=_p(ws), workspace_bytes=nbytes)
+    ctx.check(_rq_gptq(ctx.handle, C.byref(d)))
+    out["_workspace"] = ws                      # keeps the scratch alive until the caller drops the result
     return out
 
 

@@ -1,0 +1,434 @@
+// GPTQ weight reconstruction on the folded weights (Algorithm 1, "perform GPTQ to quantize the layer's weights";
+// Section "Sequential Quantization Pipeline").  The method is the published one of Frantar et al. (2022), computed here
+// in its Cholesky form:
+//   H = A^T A + lambda I                    exact integer Gram matrix of the layer's quantized inputs (int8 MFMA GEMM on a
+//                                            transposed copy), lambda = percdamp * mean(diag H), dead columns H_jj = 1
+//   U = upper Cholesky factor of H^-1        from ONE factorization: with J the index reversal, J H J = L L^T (blocked
+//                                            right-looking Cholesky, float64), X = L^-1 (blocked forward substitution),
+//                                            and U = J X J, because H = (J L J)(J L J)^T with J L J upper triangular
+//   for every column j (blocks of 64):       q_j = quantize(w_j) on the row's fixed min/max grid,
+//                                            err_j = (w_j - dequant(q_j)) / U_jj,  W[:, j+1:] -= err_j (x) U[j, j+1:]
+// inside a block each lane sweeps one output channel with its 64 columns in registers; the columns after the block are
+// updated once per block by a float64 GEMM (E [N x 64] times U[block, rest]).  Everything is float64 except the Gram
+// matrix (exact integers) so that the codes agree with a float64 reference except next to rounding ties.
+#include <cfloat>
+#include <cmath>
+
+#include "rq_internal.h"
+
+namespace {
+
+constexpr int NB = 64;       // block size of the factorization and of the sweep
+
+// ---- transposed int8 copy: At[k][t] = A[t][k], zero beyond T ------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_i8_kernel(const int8_t* __restrict__ A, int64_t T, int K, int64_t lda,
+                                                           int8_t* __restrict__ At, int64_t Tpad) {
+  __shared__ int8_t tile[64][65];
+  const int64_t t0 = (int64_t)blockIdx.x * 64;
+  const int k0 = blockIdx.y * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;                      // r: token, c: channel
+    tile[r][c] = t0 + r < T ? A[(t0 + r) * lda + k0 + c] : (int8_t)0;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, r = i & 63;
+    At[(int64_t)(k0 + c) * Tpad + t0 + r] = tile[r][c];
+  }
+}
+
+__global__ void fill_gram_consts_kernel(float* ones, int32_t* zeros, int K) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < K) { ones[i] = 1.f; zeros[i] = 0; }
+}
+
+// diag(H) before damping, dead flags, lambda.  With value = stored + delta:
+//   H_ij = G_ij + delta (S_i + S_j) + T delta^2,   G = stored^T stored,  S = column sums of stored
+__global__ __launch_bounds__(256) void diag_stats_kernel(const int32_t* __restrict__ G, const int32_t* __restrict__ S, int K,
+                                                         int64_t T, int delta, double percdamp, int32_t* __restrict__ dead,
+                                                         double* __restrict__ scal) {
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < K; i += 256) {
+    const double d = (double)G[(int64_t)i * K + i] + 2.0 * delta * (double)S[i] + (double)T * delta * delta;
+    const bool dd = d == 0.0;
+    dead[i] = dd ? 1 : 0;
+    acc += dd ? 1.0 : d;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) scal[0] = percdamp * (red[0] / (double)K);
+}
+
+// the damped Hessian with both indices reversed
+__global__ __launch_bounds__(256) void assemble_kernel(const int32_t* __restrict__ G, const int32_t* __restrict__ S, int K, int64_t T,
+                                                       int delta, const int32_t* __restrict__ dead, const double* __restrict__ scal,
+                                                       double* __restrict__ H) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)K * K) return;
+  const int i = (int)(idx / K), j = (int)(idx % K);
+  double v = (double)G[idx] + (double)delta * ((double)S[i] + (double)S[j]) + (double)T * delta * delta;
+  if (i == j) v = (dead[i] ? 1.0 : v) + scal[0];
+  H[(int64_t)(K - 1 - i) * K + (K - 1 - j)] = v;
+}
+
+// ---- generic strided float64 GEMM: C(m,n) = beta C(m,n) + alpha sum_k A(m,k) B(k,n), 64 x 64 tiles ----------------
+struct GemmF64 {
+  const double* A; int64_t sam, sak;
+  const double* B; int64_t sbk, sbn;
+  double* C; int64_t scm, scn;
+  int64_t M; int N, Kin;         // N and Kin are multiples of 64 / 16
+  double alpha, beta;
+};
+__global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64 g) {
+  __shared__ double As[16][68], Bs[16][68];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int64_t m0 = (int64_t)blockIdx.y * 64;
+  const int n0 = blockIdx.x * 64;
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  for (int k0 = 0; k0 < g.Kin; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * 256, kk = e >> 6, mm = e & 63;           // 16 x 64 elements of each operand
+      const int64_t m = m0 + mm;
+      As[kk][mm] = m < g.M ? g.A[m * g.sam + (int64_t)(k0 + kk) * g.sak] : 0.0;
+      Bs[kk][mm] = g.B[(int64_t)(k0 + kk) * g.sbk + (int64_t)(n0 + mm) * g.sbn];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t m = m0 + ty * 4 + i;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      double* c = g.C + m * g.scm + (int64_t)(n0 + tx * 4 + j) * g.scn;
+      *c = g.beta == 0.0 ? g.alpha * acc[i][j] : g.beta * *c + g.alpha * acc[i][j];
+    }
+  }
+}
+
+rq_status gemm_f64(rq_ctx* ctx, const GemmF64& g) {
+  if (g.M <= 0 || g.N <= 0) return RQ_OK;
+  hipLaunchKernelGGL(gemm_f64_kernel, dim3((unsigned)(g.N / 64), (unsigned)((g.M + 63) / 64)), dim3(256), 0, ctx->stream, g);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}
+
+// ---- diagonal block: L_kk = chol(H_kk) and its inverse (one workgroup) -----------------------------------------------
+__global__ __launch_bounds__(256) void potf2_inv_kernel(const double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
+                                                        int K, int kb) {
+  // the factor takes the lower triangle (column <= row); its inverse, also lower triangular, is kept transposed and
+  // shifted one column to the right in the unused strict upper part: inv(i, c) sits at a[c][i + 1]
+  __shared__ double a[NB][NB + 1];
+  const int tid = threadIdx.x;
+  const int64_t base = (int64_t)kb * NB * K + (int64_t)kb * NB;
+  for (int i = tid; i < NB * NB; i += 256) {
+    const int r = i >> 6, c = i & 63;
+    if (c <= r) a[r][c] = H[base + (int64_t)r * K + c];            // the lower triangle is the one the updates maintain
+  }
+  __syncthreads();
+  for (int j = 0; j < NB; ++j) {
+    const double d = sqrt(a[j][j]);
+    __syncthreads();
+    if (tid == 0) a[j][j] = d;
+    if (tid > j && tid < NB) a[tid][j] /= d;
+    __syncthreads();
+    // rank-1 update of the remaining lower triangle: row i = tid & 63, columns c = j + 1 + (tid >> 6), step 4
+    const int i = tid & 63;
+    if (i > j) {
+      const double lij = a[i][j];
+      for (int c = j + 1 + (tid >> 6); c <= i; c += 4) a[i][c] -= lij * a[c][j];
+    }
+    __syncthreads();
+  }
+  // inverse of the lower-triangular block by forward substitution, one column per lane of the first wavefront
+  if (tid < NB) {
+    const int c = tid;
+    for (int i = c; i < NB; ++i) {
+      double sum = 0.0;
+      for (int m = c; m < i; ++m) sum = fma(a[i][m], a[c][m + 1], sum);
+      a[c][i + 1] = ((i == c ? 1.0 : 0.0) - sum) / a[i][i];
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < NB * NB; i += 256) {
+    const int r = i >> 6, c = i & 63;
+    L[base + (int64_t)r * K + c] = c <= r ? a[r][c] : 0.0;
+    Dinv[(int64_t)kb * NB * NB + i] = c <= r ? a[c][r + 1] : 0.0;
+  }
+}
+
+// X = 0 with the inverted diagonal blocks in place
+__global__ __launch_bounds__(256) void init_inverse_kernel(double* __restrict__ X, const double* __restrict__ Dinv, int K) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)K * K) return;
+  const int i = (int)(idx / K), j = (int)(idx % K);
+  X[idx] = (i / NB == j / NB) ? Dinv[(int64_t)(i / NB) * NB * NB + (i % NB) * NB + (j % NB)] : 0.0;
+}
+
+// ---- per output channel: grid from the row's extremes (dead columns count as 0), float64 working copy ----------------
+__global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__ W, int K, int bits, const int32_t* __restrict__ dead,
+                                                       double* __restrict__ Wc, double* __restrict__ s64, double* __restrict__ z64) {
+  __shared__ float smin[256], smax[256];
+  const int tid = threadIdx.x, n = blockIdx.x;
+  const float* w = W + (int64_t)n * K;
+  float lo = FLT_MAX, hi = -FLT_MAX;
+  for (int k = tid; k < K; k += 256) {
+    const float v = dead[k] ? 0.f : w[k];
+    Wc[(int64_t)n * K + k] = (double)v;
+    lo = fminf(lo, v);
+    hi = fmaxf(hi, v);
+  }
+  smin[tid] = lo;
+  smax[tid] = hi;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      smin[tid] = fminf(smin[tid], smin[tid + s]);
+      smax[tid] = fmaxf(smax[tid], smax[tid + s]);
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double dlo = (double)smin[0], dhi = (double)smax[0];
+    const double s = (double)(float)((dhi - dlo) / (double)((1 << bits) - 1));      // the scale is stored as float32
+    s64[n] = s;
+    z64[n] = rint(-dlo / s);
+  }
+}
+
+// ---- the sweep inside one block of 64 columns: one lane per output channel -------------------------------------------
+__global__ __launch_bounds__(64) void sweep_block_kernel(double* __restrict__ Wc, const double* __restrict__ X, int N, int K, int j0,
+                                                         int bits, const double* __restrict__ s64, const double* __restrict__ z64,
+                                                         double* __restrict__ E, uint8_t* __restrict__ codes) {
+  __shared__ double Ub[NB][NB];                             // U[j0 + jj][j0 + cc] = X[K-1-j0-jj][K-1-j0-cc], upper triangular
+  for (int i = threadIdx.x; i < NB * NB; i += 64) {
+    const int jj = i >> 6, cc = i & 63;
+    Ub[jj][cc] = X[(int64_t)(K - 1 - j0 - jj) * K + (K - 1 - j0 - cc)];
+  }
+  __syncthreads();
+  const int n = blockIdx.x * 64 + threadIdx.x;
+  if (n >= N) return;
+  double w[NB];
+#pragma unroll
+  for (int c = 0; c < NB; ++c) w[c] = Wc[(int64_t)n * K + j0 + c];
+  const double s = s64[n], z = z64[n], qmax = (double)((1 << bits) - 1);
+#pragma unroll
+  for (int jj = 0; jj < NB; ++jj) {
+    const double q = fmin(fmax(rint(w[jj] / s) + z, 0.0), qmax);
+    const double err = (w[jj] - s * (q - z)) / Ub[jj][jj];
+    codes[(int64_t)n * K + j0 + jj] = (uint8_t)q;
+    E[(int64_t)n * NB + jj] = err;
+#pragma unroll
+    for (int cc = jj + 1; cc < NB; ++cc) w[cc] -= err * Ub[jj][cc];
+  }
+}
+
+// ---- codes -> storage format, column sums, row permutation of the gated MLP (same conventions as rq_weight_quant_pack) --
+__global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ codes, int K, int format, int gate_up_rows,
+                                                   const double* __restrict__ s64, const double* __restrict__ z64,
+                                                   const float* __restrict__ bias, void* __restrict__ w_out, float* __restrict__ s_w,
+                                                   int32_t* __restrict__ z_w, int32_t* __restrict__ colsum_w, float* __restrict__ bias_out) {
+  __shared__ int ssum[256];
+  const int tid = threadIdx.x, n = blockIdx.x;
+  const uint8_t* c = codes + (int64_t)n * K;
+  const int z = (int)z64[n];
+  int r = n;
+  if (gate_up_rows > 0) {
+    const int Dm = gate_up_rows, j = n < Dm ? n : n - Dm;
+    r = (j / 32) * 64 + (n < Dm ? 0 : 32) + (j % 32);
+  }
+  int csum = 0;
+  if (format == RQ_W_U4) {
+    uint8_t* out = static_cast<uint8_t*>(w_out) + (int64_t)r * (K / 2);
+    for (int g = tid; g < K / 8; g += 256) {
+      const uint8_t* q = c + g * 8;
+      const uint32_t pk = (uint32_t)(q[0] | (q[4] << 4)) | ((uint32_t)(q[1] | (q[5] << 4)) << 8) |
+                          ((uint32_t)(q[2] | (q[6] << 4)) << 16) | ((uint32_t)(q[3] | (q[7] << 4)) << 24);
+      *reinterpret_cast<uint32_t*>(out + g * 4) = pk;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) csum += (int)q[e] - z;
+    }
+  } else {
+    int8_t* out = static_cast<int8_t*>(w_out) + (int64_t)r * K;
+    const int off = format == RQ_W_I8_CENTERED ? 128 : z;
+    for (int k = tid; k < K; k += 256) {
+      out[k] = (int8_t)((int)c[k] - off);
+      csum += (int)c[k] - z;
+    }
+  }
+  ssum[tid] = csum;
+  __syncthreads();
+  for (int s2 = 128; s2 > 0; s2 >>= 1) {
+    if (tid < s2) ssum[tid] += ssum[tid + s2];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    s_w[r] = (float)s64[n];
+    z_w[r] = z;
+    colsum_w[r] = ssum[0];
+    if (bias_out) bias_out[r] = bias ? bias[n] : 0.f;
+  }
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t at, g, s, ones, zeros, dead, scal, h, l, x, dinv, tm, wc, e, codes, s64, z64, total;
+};
+Layout make_layout(int N, int K, int64_t T) {
+  const size_t Tpad = (size_t)((T + 63) / 64) * 64, KK = (size_t)K * K;
+  Layout o;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { const size_t at = p; p += align256(bytes); return at; };
+  o.at = take((size_t)K * Tpad);
+  o.g = take(KK * 4);
+  o.s = take((size_t)K * 4);
+  o.ones = take((size_t)K * 4);
+  o.zeros = take((size_t)K * 4);
+  o.dead = take((size_t)K * 4);
+  o.scal = take(64);
+  o.h = take(KK * 8);
+  o.l = take(KK * 8);
+  o.x = take(KK * 8);
+  o.dinv = take((size_t)(K / NB) * NB * NB * 8);
+  o.tm = take((size_t)NB * K * 8);
+  o.wc = take((size_t)N * K * 8);
+  o.e = take((size_t)N * NB * 8);
+  o.codes = take((size_t)N * K);
+  o.s64 = take((size_t)N * 8);
+  o.z64 = take((size_t)N * 8);
+  o.total = p;
+  return o;
+}
+
+}  // namespace
+
+size_t rq_gptq_workspace_bytes(int32_t N, int32_t K, int64_t T) {
+  if (N <= 0 || K <= 0 || T <= 0) return 0;
+  return make_layout(N, K, T).total;
+}
+
+rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
+  const int N = d->N, K = d->K, nb = K / NB;
+  const int64_t T = d->T, Tpad = (T + 63) / 64 * 64;
+  const Layout o = make_layout(N, K, T);
+  char* ws = static_cast<char*>(d->workspace);
+  int8_t* At = reinterpret_cast<int8_t*>(ws + o.at);
+  int32_t* G = reinterpret_cast<int32_t*>(ws + o.g);
+  int32_t* S = reinterpret_cast<int32_t*>(ws + o.s);
+  float* ones = reinterpret_cast<float*>(ws + o.ones);
+  int32_t* zeros = reinterpret_cast<int32_t*>(ws + o.zeros);
+  int32_t* dead = reinterpret_cast<int32_t*>(ws + o.dead);
+  double* scal = reinterpret_cast<double*>(ws + o.scal);
+  double* H = reinterpret_cast<double*>(ws + o.h);
+  double* L = reinterpret_cast<double*>(ws + o.l);
+  double* X = reinterpret_cast<double*>(ws + o.x);
+  double* Dinv = reinterpret_cast<double*>(ws + o.dinv);
+  double* Tm = reinterpret_cast<double*>(ws + o.tm);
+  double* Wc = reinterpret_cast<double*>(ws + o.wc);
+  double* E = reinterpret_cast<double*>(ws + o.e);
+  uint8_t* codes = reinterpret_cast<uint8_t*>(ws + o.codes);
+  double* s64 = reinterpret_cast<double*>(ws + o.s64);
+  double* z64 = reinterpret_cast<double*>(ws + o.z64);
+  hipStream_t st = ctx->stream;
+  const int delta = d->a_off - d->z_a;
+  const int64_t KK = (int64_t)K * K;
+
+  // ---- Gram matrix of the stored codes on the matrix cores, column sums, Hessian ----
+  hipLaunchKernelGGL(transpose_i8_kernel, dim3((unsigned)(Tpad / 64), (unsigned)(K / 64)), dim3(256), 0, st, d->A, T, K, d->lda, At, Tpad);
+  hipLaunchKernelGGL(fill_gram_consts_kernel, dim3((K + 255) / 256), dim3(256), 0, st, ones, zeros, K);
+  RQ_HIP(hipGetLastError());
+  rq_gemm_desc gd = {};
+  gd.M = K; gd.N = K; gd.K = (int32_t)Tpad;
+  gd.A = At; gd.lda = Tpad; gd.a_off = 0; gd.z_a = 0; gd.s_a = 1.f;
+  gd.B = At; gd.ldb = Tpad; gd.b_format = RQ_W_I8_BAKED; gd.s_b = ones; gd.z_b = zeros; gd.colsum_b = zeros;
+  gd.out_acc = G; gd.ldacc = K;
+  gd.batch_outer = 1; gd.batch_inner = 1; gd.n_seg = 1;
+  rq_status rc = rq_launch_qgemm_weight(ctx, &gd);
+  if (rc != RQ_OK) return rc;
+  rc = rq_launch_rowsum(ctx, At, K, (int32_t)Tpad, Tpad, S);
+  if (rc != RQ_OK) return rc;
+  hipLaunchKernelGGL(diag_stats_kernel, dim3(1), dim3(256), 0, st, G, S, K, T, delta, d->percdamp, dead, scal);
+  hipLaunchKernelGGL(assemble_kernel, dim3((unsigned)((KK + 255) / 256)), dim3(256), 0, st, G, S, K, T, delta, dead, scal, H);
+  RQ_HIP(hipGetLastError());
+
+  // ---- blocked right-looking Cholesky of the index-reversed Hessian: H = L L^T ----
+  for (int kb = 0; kb < nb; ++kb) {
+    hipLaunchKernelGGL(potf2_inv_kernel, dim3(1), dim3(256), 0, st, H, L, Dinv, K, kb);
+    RQ_HIP(hipGetLastError());
+    const int r0 = (kb + 1) * NB, rest = K - r0;
+    if (rest <= 0) break;
+    const int64_t c0 = (int64_t)kb * NB;
+    // panel: L[r0:, kb] = H[r0:, kb] Dinv_kk^T
+    GemmF64 g;
+    g.A = H + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
+    g.B = Dinv + (int64_t)kb * NB * NB; g.sbk = 1; g.sbn = NB;
+    g.C = L + (int64_t)r0 * K + c0; g.scm = K; g.scn = 1;
+    g.M = rest; g.N = NB; g.Kin = NB; g.alpha = 1.0; g.beta = 0.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+    // trailing update: H[r0:, r0:] -= L[r0:, kb] L[r0:, kb]^T
+    g.A = L + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
+    g.B = L + (int64_t)r0 * K + c0; g.sbk = 1; g.sbn = K;
+    g.C = H + (int64_t)r0 * K + r0; g.scm = K; g.scn = 1;
+    g.M = rest; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+  }
+  // ---- X = L^-1, block row by block row: X[i, :i] = -Dinv_ii (L[i, :i] X[:i, :i]) ----
+  hipLaunchKernelGGL(init_inverse_kernel, dim3((unsigned)((KK + 255) / 256)), dim3(256), 0, st, X, Dinv, K);
+  RQ_HIP(hipGetLastError());
+  for (int i = 1; i < nb; ++i) {
+    GemmF64 g;
+    g.A = L + (int64_t)i * NB * K; g.sam = K; g.sak = 1;
+    g.B = X; g.sbk = K; g.sbn = 1;
+    g.C = Tm; g.scm = K; g.scn = 1;
+    g.M = NB; g.N = i * NB; g.Kin = i * NB; g.alpha = 1.0; g.beta = 0.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+    g.A = Dinv + (int64_t)i * NB * NB; g.sam = NB; g.sak = 1;
+    g.B = Tm; g.sbk = K; g.sbn = 1;
+    g.C = X + (int64_t)i * NB * K; g.scm = K; g.scn = 1;
+    g.M = NB; g.N = i * NB; g.Kin = NB; g.alpha = -1.0; g.beta = 0.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+  }
+  // ---- the sweep ----
+  hipLaunchKernelGGL(row_init_kernel, dim3((unsigned)N), dim3(256), 0, st, d->W, K, d->bits, dead, Wc, s64, z64);
+  RQ_HIP(hipGetLastError());
+  for (int b = 0; b < nb; ++b) {
+    const int j0 = b * NB;
+    hipLaunchKernelGGL(sweep_block_kernel, dim3((unsigned)((N + 63) / 64)), dim3(64), 0, st, Wc, X, N, K, j0, d->bits, s64, z64, E, codes);
+    RQ_HIP(hipGetLastError());
+    const int rest = K - j0 - NB;
+    if (rest <= 0) break;
+    // W[:, j0+64:] -= E U[j0:j0+64, j0+64:],  U[a][b] = X[K-1-a][K-1-b]
+    GemmF64 g;
+    g.A = E; g.sam = NB; g.sak = 1;
+    g.B = X + (int64_t)(K - 1 - j0) * K + (K - 1 - j0 - NB); g.sbk = -(int64_t)K; g.sbn = -1;
+    g.C = Wc + j0 + NB; g.scm = K; g.scn = 1;
+    g.M = N; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+  }
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)N), dim3(256), 0, st, codes, K, d->format, d->gate_up_rows, s64, z64, d->bias, d->w_out,
+                     d->s_w, d->z_w, d->colsum_w, d->bias_out);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}

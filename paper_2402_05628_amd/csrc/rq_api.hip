@@ -481,4 +481,42 @@ rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d) {
   return rq_launch_dual_clip(ctx, d);
 }
 
+rq_status rq_gptq_quant_pack(rq_ctx* ctx, const rq_gptq_desc* d) {
+  RQ_CHECK_CTX("rq_gptq_quant_pack");
+  RQ_REQUIRE(d->W && d->A && d->w_out && d->s_w && d->z_w && d->colsum_w, RQ_ERR_INVALID_ARG,
+             "rq_gptq_quant_pack: W, A, w_out, s_w, z_w, colsum_w must be non-NULL");
+  RQ_REQUIRE(d->N > 0 && d->K > 0 && d->K % 64 == 0 && d->K <= 8192, RQ_ERR_SHAPE,
+             "rq_gptq_quant_pack: N = %d, K = %d (K must be a multiple of 64, at most 8192)", d->N, d->K);
+  RQ_REQUIRE(d->T >= 1 && d->T <= 131071 && d->lda >= d->K, RQ_ERR_SHAPE,
+             "rq_gptq_quant_pack: T = %lld must be in 1..131071 (int32 Gram sums) and lda = %lld >= K", (long long)d->T, (long long)d->lda);
+  RQ_REQUIRE(rq_aligned(d->W, 4) && rq_aligned(d->w_out, 4) && rq_aligned(d->s_w, 4) && rq_aligned(d->z_w, 4) &&
+                 rq_aligned(d->colsum_w, 4) && rq_aligned(d->bias, 4) && rq_aligned(d->bias_out, 4),
+             RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: arrays need 4-byte alignment");
+  switch (d->format) {
+    case RQ_W_U4:
+      RQ_REQUIRE(d->bits == 4, RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: RQ_W_U4 needs bits = 4, got %d", d->bits);
+      break;
+    case RQ_W_I8_CENTERED:
+      RQ_REQUIRE(d->bits >= 2 && d->bits <= 8, RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: bits = %d not in 2..8", d->bits);
+      break;
+    case RQ_W_I8_BAKED:
+      RQ_REQUIRE(d->bits >= 2 && d->bits <= 7, RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: RQ_W_I8_BAKED needs bits in 2..7, got %d",
+                 d->bits);
+      break;
+    default:
+      return rq_fail(ctx, RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: format %d", d->format);
+  }
+  if (d->gate_up_rows != 0)
+    RQ_REQUIRE(d->gate_up_rows > 0 && d->N == 2 * d->gate_up_rows && d->gate_up_rows % 32 == 0, RQ_ERR_SHAPE,
+               "rq_gptq_quant_pack: gate_up_rows = %d needs N = 2*gate_up_rows and a multiple of 32", d->gate_up_rows);
+  RQ_REQUIRE(d->a_off - d->z_a >= -255 && d->a_off - d->z_a <= 255, RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: a_off - z_a = %d",
+             d->a_off - d->z_a);
+  RQ_REQUIRE(d->percdamp > 0.0 && std::isfinite(d->percdamp), RQ_ERR_INVALID_ARG, "rq_gptq_quant_pack: percdamp must be > 0");
+  RQ_REQUIRE(d->workspace && rq_aligned(d->workspace, 256) && d->workspace_bytes >= rq_gptq_workspace_bytes(d->N, d->K, d->T),
+             RQ_ERR_WORKSPACE, "rq_gptq_quant_pack: workspace of %zu bytes, %zu needed (256-byte aligned)", d->workspace_bytes,
+             rq_gptq_workspace_bytes(d->N, d->K, d->T));
+  RQ_NEED_DEVICE();
+  return rq_launch_gptq(ctx, d);
+}
+
 }  // extern "C"

@@ -69,6 +69,7 @@ rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_
 rq_status rq_launch_channel_qparams(rq_ctx* ctx, const double* cmin, const double* cmax, const float* clip_up,
                                     const float* clip_lo, int D, int bits, float* s_ch, int32_t* z_ch);
 
+rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d);
 rq_status rq_launch_dual_clip(rq_ctx* ctx, const rq_dual_clip_desc* d);
 
 // profiling hooks used by rq_block_forward

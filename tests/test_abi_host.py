@@ -49,7 +49,7 @@ def test_structures_have_the_c_layout(b, tmp_path):
     """sizeof and the offset of the last field of every descriptor, as gcc lays the header out."""
     pairs = [("rq_fold_desc", b.FoldDesc), ("rq_wq_desc", b.WqDesc), ("rq_ln_desc", b.LnDesc), ("rq_gemm_desc", b.GemmDesc),
              ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_attn_fused_desc", b.AttnFusedDesc),
-             ("rq_pv_desc", b.PvDesc), ("rq_dual_clip_desc", b.DualClipDesc),
+             ("rq_pv_desc", b.PvDesc), ("rq_dual_clip_desc", b.DualClipDesc), ("rq_gptq_desc", b.GptqDesc),
              ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
     for cname, cls in pairs:
@@ -193,6 +193,29 @@ def test_dual_clip_validation(b, host_ctx):
     assert call(workspace_bytes=8) == 4 and call(workspace=None) == 4
     assert "rq_dual_clip_learn" in b.lib.rq_last_error(host_ctx.handle).decode()
     assert call(alpha1=FAKE + 4) == 1
+
+
+def test_gptq_validation(b, host_ctx):
+    fn = b.lib.rq_gptq_quant_pack
+    need = b.lib.rq_gptq_workspace_bytes(128, 64, 300)
+    assert need > 128 * 64 * 8 + 3 * 64 * 64 * 8
+    big = FAKE & ~0xFF
+    def call(**kw):
+        f = dict(N=128, K=64, bits=4, format=b.W_U4, gate_up_rows=0, W=FAKE, bias=None, A=FAKE, T=300, lda=64, a_off=8, z_a=8,
+                 percdamp=0.01, w_out=FAKE, s_w=FAKE, z_w=FAKE, colsum_w=FAKE, bias_out=None, workspace=big, workspace_bytes=need)
+        f.update(kw)
+        return fn(host_ctx.handle, C.byref(b.GptqDesc(**f)))
+    assert call() == 3
+    assert fn(host_ctx.handle, None) == 1
+    assert call(A=None) == 1 and call(W=None) == 1
+    assert call(K=96, lda=96) == 2 and call(K=16384, lda=16384) == 2       # K % 64, K <= 8192
+    assert call(T=0) == 2 and call(T=200000) == 2 and call(lda=32) == 2
+    assert call(bits=5) == 1                                               # packed 4-bit format needs bits = 4
+    assert call(format=b.W_I8_BAKED, bits=8) == 1 and call(format=9) == 1
+    assert call(gate_up_rows=48) == 2
+    assert call(percdamp=0.0) == 1
+    assert call(workspace_bytes=need - 1) == 4 and call(workspace=big + 8) == 4
+    assert "rq_gptq_quant_pack" in b.lib.rq_last_error(host_ctx.handle).decode()
 
 
 def test_softmax_and_pv_validation(b, host_ctx):
