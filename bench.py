@@ -147,6 +147,49 @@ def bench_dual_clip(args, cfg, rq, synth, np, torch):
     print(json.dumps(out))
 
 
+def bench_gptq(args, cfg, rq, synth, np, torch):
+    """One step = GPTQ of the QKV weight matrix [3D, D] against the block's LayerNorm-1 codes [T, D]."""
+    torch.cuda.set_device(0)
+    ctx = rq.Context(0)
+    g = synth.rng_for(args.config, 7)
+    N, K, T = 3 * cfg.D, cfg.D, cfg.tokens
+    W = (g.standard_normal((N, K)) * 0.02).astype(np.float32)
+    qmax = 2 ** cfg.bits_a - 1
+    z_a = qmax // 2 + 1
+    F = g.standard_normal((T, 8))
+    codes = np.clip(np.rint((F @ g.standard_normal((8, K)) * 0.5 + g.standard_normal((T, K))) * (qmax / 8.0)) + z_a, 0, qmax)
+    off = z_a if cfg.bits_a < 8 else 128
+    Wd, Ad = torch.from_numpy(W).cuda(), torch.from_numpy((codes - off).astype(np.int8)).cuda()
+    run = lambda: rq.rq_gptq_quant_pack(ctx, Wd, None, cfg.bits_w, Ad, off, z_a)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    # float64 work: Cholesky K^3/3, triangular inverse K^3/3, sweep N K^2 (in-block and lazy updates together)
+    flops = 2.0 * K ** 3 / 3.0 + float(N) * K * K
+    achieved = flops / sec / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gptq_oracle as gq
+        c0 = time.perf_counter()
+        gq.gptq(W, codes.astype(np.int64) - z_a, cfg.bits_w)
+        c1 = time.perf_counter()
+        cpu = dict(value=c1 - c0, unit="s per layer", cores=torch.get_num_threads(), kind="oracle",
+                   sample="the whole layer (%d x %d weights, %d tokens), elimination-form float64 numpy oracle" % (N, K, T))
+    out = dict(metric="GPTQ of one linear layer, seconds on 1 MI355X", value=sec, unit="s per layer", n_gpus=1, steps=steps,
+               warmup=warmup, ms_per_step=sec * 1e3, higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64",
+               data="synthetic", config=dict(workload=cfg.name + " QKV weights", N=N, K=K, tokens=T, bits_w=cfg.bits_w, bits_a=cfg.bits_a),
+               roofline=dict(bound="alu", kernel="rq_gptq_quant_pack (all kernels of the call)", achieved=achieved, peak=PEAK_FP64_TFLOPS,
+                             unit="TFLOP/s", frac=achieved / PEAK_FP64_TFLOPS, traffic=None, flops_per_launch=flops),
+               cpu_baseline=cpu)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,9 +201,9 @@ def main():
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true", help="append three 256 MiB elementwise copies (counter calibration)")
-    ap.add_argument("--workload", default="block", choices=["block", "dual_clip"],
+    ap.add_argument("--workload", default="block", choices=["block", "dual_clip", "gptq"],
                     help="block: the quantized block forward (the headline metric); dual_clip: the calibration-side learner of "
-                         "the per-channel clipping factors on the same activations")
+                         "the per-channel clipping factors on the same activations; gptq: GPTQ of the QKV weights against them")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box here has one); --gpus %d is not supported. "
@@ -177,6 +220,8 @@ def main():
         cfg = cfg.with_batch(args.batch)
     if args.workload == "dual_clip":
         return bench_dual_clip(args, cfg, rq, synth, np, torch)
+    if args.workload == "gptq":
+        return bench_gptq(args, cfg, rq, synth, np, torch)
     if args.chunk_mb:
         rq.set_attn_chunk_bytes(args.chunk_mb << 20)
     if args.tile:

@@ -4,11 +4,11 @@
 //   H = A^T A + lambda I                    exact integer Gram matrix of the layer's quantized inputs (int8 MFMA GEMM on a
 //                                            transposed copy), lambda = percdamp * mean(diag H), dead columns H_jj = 1
 //   U = upper Cholesky factor of H^-1        from ONE factorization: with J the index reversal, J H J = L L^T (blocked
-//                                            right-looking Cholesky, float64), X = L^-1 (blocked forward substitution),
+//                                            right-looking Cholesky, float64), X = L^-1 (diagonal blocks merged by doubling),
 //                                            and U = J X J, because H = (J L J)(J L J)^T with J L J upper triangular
 //   for every column j (blocks of 64):       q_j = quantize(w_j) on the row's fixed min/max grid,
 //                                            err_j = (w_j - dequant(q_j)) / U_jj,  W[:, j+1:] -= err_j (x) U[j, j+1:]
-// inside a block each lane sweeps one output channel with its 64 columns in registers; the columns after the block are
+// inside a block four lanes sweep one output channel with its 64 columns in their registers; the columns after the block are
 // updated once per block by a float64 GEMM (E [N x 64] times U[block, rest]).  Everything is float64 except the Gram
 // matrix (exact integers) so that the codes agree with a float64 reference except next to rounding ties.
 #include <cfloat>
@@ -76,12 +76,18 @@ __global__ __launch_bounds__(256) void assemble_kernel(const int32_t* __restrict
   H[(int64_t)(K - 1 - i) * K + (K - 1 - j)] = v;
 }
 
-// ---- generic strided float64 GEMM: C(m,n) = beta C(m,n) + alpha sum_k A(m,k) B(k,n), 64 x 64 tiles ----------------
+// ---- generic strided, batched float64 GEMM: C(m,n) = beta C(m,n) + alpha sum_k A(m,k) B(k,n), 64 x 64 tiles ---------
+// `tri` lets triangular operands skip the blocks that are zero (or not needed):
+//   TRI_B_LOWER: B(k, n) = 0 for k < n   -> the sum starts at the tile's first column
+//   TRI_A_LOWER: A(m, k) = 0 for k > m   -> the sum ends at the tile's last row
+//   TRI_C_LOWER: only tiles on or below the diagonal are computed (symmetric update, lower triangle in use)
+enum { TRI_NONE = 0, TRI_B_LOWER = 1, TRI_A_LOWER = 2, TRI_C_LOWER = 3 };
 struct GemmF64 {
-  const double* A; int64_t sam, sak;
-  const double* B; int64_t sbk, sbn;
-  double* C; int64_t scm, scn;
-  int64_t M; int N, Kin;         // N and Kin are multiples of 64 / 16
+  const double* A; int64_t sam, sak, bsa;
+  const double* B; int64_t sbk, sbn, bsb;
+  double* C; int64_t scm, scn, bsc;
+  int64_t M; int N, Kin;         // N and Kin are multiples of 64
+  int batch, tri;
   double alpha, beta;
 };
 __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64 g) {
@@ -89,18 +95,32 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64 g) {
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int64_t m0 = (int64_t)blockIdx.y * 64;
   const int n0 = blockIdx.x * 64;
+  if (g.tri == TRI_C_LOWER && n0 > m0) return;
+  const double* A = g.A + (int64_t)blockIdx.z * g.bsa;
+  const double* B = g.B + (int64_t)blockIdx.z * g.bsb;
+  double* C = g.C + (int64_t)blockIdx.z * g.bsc;
+  const int kbeg = g.tri == TRI_B_LOWER ? n0 : 0;
+  const int kend = g.tri == TRI_A_LOWER ? (int)(m0 + 64 < g.Kin ? m0 + 64 : g.Kin) : g.Kin;
+  // consecutive lanes walk whichever index of the operand is contiguous in memory
+  const bool a_kfast = g.sak == 1 || g.sak == -1, b_kfast = g.sbk == 1 || g.sbk == -1;
   double acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  for (int k0 = 0; k0 < g.Kin; k0 += 16) {
+  for (int k0 = kbeg; k0 < kend; k0 += 16) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int e = tid + i * 256, kk = e >> 6, mm = e & 63;           // 16 x 64 elements of each operand
-      const int64_t m = m0 + mm;
-      As[kk][mm] = m < g.M ? g.A[m * g.sam + (int64_t)(k0 + kk) * g.sak] : 0.0;
-      Bs[kk][mm] = g.B[(int64_t)(k0 + kk) * g.sbk + (int64_t)(n0 + mm) * g.sbn];
+      const int e = tid + i * 256;                                     // 16 x 64 elements of each operand
+      {
+        const int kk = a_kfast ? e & 15 : e >> 6, mm = a_kfast ? e >> 4 : e & 63;
+        const int64_t m = m0 + mm;
+        As[kk][mm] = m < g.M ? A[m * g.sam + (int64_t)(k0 + kk) * g.sak] : 0.0;
+      }
+      {
+        const int kk = b_kfast ? e & 15 : e >> 6, nn = b_kfast ? e >> 4 : e & 63;
+        Bs[kk][nn] = B[(int64_t)(k0 + kk) * g.sbk + (int64_t)(n0 + nn) * g.sbn];
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -121,60 +141,56 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64 g) {
     if (m >= g.M) continue;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      double* c = g.C + m * g.scm + (int64_t)(n0 + tx * 4 + j) * g.scn;
+      double* c = C + m * g.scm + (int64_t)(n0 + tx * 4 + j) * g.scn;
       *c = g.beta == 0.0 ? g.alpha * acc[i][j] : g.beta * *c + g.alpha * acc[i][j];
     }
   }
 }
 
 rq_status gemm_f64(rq_ctx* ctx, const GemmF64& g) {
-  if (g.M <= 0 || g.N <= 0) return RQ_OK;
-  hipLaunchKernelGGL(gemm_f64_kernel, dim3((unsigned)(g.N / 64), (unsigned)((g.M + 63) / 64)), dim3(256), 0, ctx->stream, g);
+  if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return RQ_OK;
+  hipLaunchKernelGGL(gemm_f64_kernel, dim3((unsigned)(g.N / 64), (unsigned)((g.M + 63) / 64), (unsigned)g.batch), dim3(256), 0,
+                     ctx->stream, g);
   RQ_HIP(hipGetLastError());
   return RQ_OK;
 }
 
-// ---- diagonal block: L_kk = chol(H_kk) and its inverse (one workgroup) -----------------------------------------------
-__global__ __launch_bounds__(256) void potf2_inv_kernel(const double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
-                                                        int K, int kb) {
-  // the factor takes the lower triangle (column <= row); its inverse, also lower triangular, is kept transposed and
-  // shifted one column to the right in the unused strict upper part: inv(i, c) sits at a[c][i + 1]
-  __shared__ double a[NB][NB + 1];
-  const int tid = threadIdx.x;
+// ---- diagonal block: L_kk = chol(H_kk) and its inverse (one wavefront, everything in registers) ------------------------
+// Lane i holds row i of the block; an entry of another row comes through v_readlane (the lane index is a compile-time
+// constant once the loops are unrolled), so neither LDS nor barriers are involved.
+__device__ __forceinline__ double lane_value(double v, int lane) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)b, lane), hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+__global__ __launch_bounds__(64) void potf2_inv_kernel(const double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
+                                                       int K, int kb) {
+  const int i = threadIdx.x;
   const int64_t base = (int64_t)kb * NB * K + (int64_t)kb * NB;
-  for (int i = tid; i < NB * NB; i += 256) {
-    const int r = i >> 6, c = i & 63;
-    if (c <= r) a[r][c] = H[base + (int64_t)r * K + c];            // the lower triangle is the one the updates maintain
-  }
-  __syncthreads();
+  double a[NB];
+#pragma unroll
+  for (int c = 0; c < NB; ++c) a[c] = H[base + (int64_t)i * K + c];          // only c <= i is used (the maintained triangle)
+  // left-looking: l_ij = (h_ij - sum_{k<j} l_ik l_jk) / l_jj
+#pragma unroll
   for (int j = 0; j < NB; ++j) {
-    const double d = sqrt(a[j][j]);
-    __syncthreads();
-    if (tid == 0) a[j][j] = d;
-    if (tid > j && tid < NB) a[tid][j] /= d;
-    __syncthreads();
-    // rank-1 update of the remaining lower triangle: row i = tid & 63, columns c = j + 1 + (tid >> 6), step 4
-    const int i = tid & 63;
-    if (i > j) {
-      const double lij = a[i][j];
-      for (int c = j + 1 + (tid >> 6); c <= i; c += 4) a[i][c] -= lij * a[c][j];
-    }
-    __syncthreads();
+    double sum = 0.0;
+#pragma unroll
+    for (int k = 0; k < j; ++k) sum = fma(a[k], lane_value(a[k], j), sum);
+    const double v = a[j] - sum;
+    const double d = sqrt(lane_value(v, j));
+    a[j] = i == j ? d : (i > j ? v / d : 0.0);
   }
-  // inverse of the lower-triangular block by forward substitution, one column per lane of the first wavefront
-  if (tid < NB) {
-    const int c = tid;
-    for (int i = c; i < NB; ++i) {
-      double sum = 0.0;
-      for (int m = c; m < i; ++m) sum = fma(a[i][m], a[c][m + 1], sum);
-      a[c][i + 1] = ((i == c ? 1.0 : 0.0) - sum) / a[i][i];
-    }
-  }
-  __syncthreads();
-  for (int i = tid; i < NB * NB; i += 256) {
-    const int r = i >> 6, c = i & 63;
-    L[base + (int64_t)r * K + c] = c <= r ? a[r][c] : 0.0;
-    Dinv[(int64_t)kb * NB * NB + i] = c <= r ? a[c][r + 1] : 0.0;
+#pragma unroll
+  for (int c = 0; c < NB; ++c) L[base + (int64_t)i * K + c] = a[c];
+  // inverse, lane c takes column c: x(r) = (delta_rc - sum_{m<r} l_rm x(m)) / l_rr, x(m) = 0 for m < c
+  double x[NB];
+#pragma unroll
+  for (int r = 0; r < NB; ++r) {
+    double sum = 0.0;
+#pragma unroll
+    for (int m = 0; m < r; ++m) sum = fma(lane_value(a[m], r), x[m], sum);
+    x[r] = r < i ? 0.0 : ((r == i ? 1.0 : 0.0) - sum) / lane_value(a[r], r);
+    Dinv[(int64_t)kb * NB * NB + r * NB + i] = x[r];
   }
 }
 
@@ -217,7 +233,39 @@ __global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__
   }
 }
 
-// ---- the sweep inside one block of 64 columns: one lane per output channel -------------------------------------------
+// ---- the sweep inside one block of 64 columns: four lanes per output channel -----------------------------------------
+// Lane q of a quad owns columns q, q + 4, ... of its channel's block.  Every step broadcasts the current column's
+// weight from its owner, all four lanes take the same code and error, and each updates the columns it owns.
+template <int SRC>
+__device__ __forceinline__ double quad_bcast(double v) {
+  const long long b = __double_as_longlong(v);
+  constexpr int ctrl = SRC * 0x55;                          // quad_perm: [SRC, SRC, SRC, SRC]
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)b, ctrl, 0xF, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), ctrl, 0xF, 0xF, true);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+
+template <int JJ>
+__device__ __forceinline__ void sweep_step(double (&w)[NB / 4], const double (*Ub)[NB], int q, double s, double z, double qmax,
+                                           uint8_t* code_row, double* e_row) {
+  const double x = quad_bcast<JJ & 3>(w[JJ >> 2]);
+  const double c = fmin(fmax(rint(x / s) + z, 0.0), qmax);
+  const double err = (x - s * (c - z)) / Ub[JJ][JJ];
+  if (q == (JJ & 3)) {
+    code_row[JJ] = (uint8_t)c;
+    e_row[JJ] = err;
+  }
+#pragma unroll
+  for (int t = 0; t < NB / 4; ++t) {
+    const int cc = 4 * t + q;                               // the column this lane's w[t] holds
+    if (4 * t + 3 > JJ) {                                   // some lane of the quad still has work in this slot
+      const double u = Ub[JJ][cc];
+      if (cc > JJ) w[t] -= err * u;
+    }
+  }
+  if constexpr (JJ + 1 < NB) sweep_step<JJ + 1>(w, Ub, q, s, z, qmax, code_row, e_row);
+}
+
 __global__ __launch_bounds__(64) void sweep_block_kernel(double* __restrict__ Wc, const double* __restrict__ X, int N, int K, int j0,
                                                          int bits, const double* __restrict__ s64, const double* __restrict__ z64,
                                                          double* __restrict__ E, uint8_t* __restrict__ codes) {
@@ -227,20 +275,24 @@ __global__ __launch_bounds__(64) void sweep_block_kernel(double* __restrict__ Wc
     Ub[jj][cc] = X[(int64_t)(K - 1 - j0 - jj) * K + (K - 1 - j0 - cc)];
   }
   __syncthreads();
-  const int n = blockIdx.x * 64 + threadIdx.x;
-  if (n >= N) return;
-  double w[NB];
+  const int q = threadIdx.x & 3;
+  int n = blockIdx.x * 16 + (threadIdx.x >> 2);
+  const bool live = n < N;
+  n = live ? n : N - 1;                                      // idle quads shadow the last channel and write nothing
+  double w[NB / 4];
 #pragma unroll
-  for (int c = 0; c < NB; ++c) w[c] = Wc[(int64_t)n * K + j0 + c];
+  for (int t = 0; t < NB / 4; ++t) w[t] = Wc[(int64_t)n * K + j0 + 4 * t + q];
   const double s = s64[n], z = z64[n], qmax = (double)((1 << bits) - 1);
+  __shared__ uint8_t code_s[16][NB];
+  __shared__ double e_s[16][NB];
+  sweep_step<0>(w, Ub, q, s, z, qmax, code_s[threadIdx.x >> 2], e_s[threadIdx.x >> 2]);
+  __syncthreads();
+  if (live) {
 #pragma unroll
-  for (int jj = 0; jj < NB; ++jj) {
-    const double q = fmin(fmax(rint(w[jj] / s) + z, 0.0), qmax);
-    const double err = (w[jj] - s * (q - z)) / Ub[jj][jj];
-    codes[(int64_t)n * K + j0 + jj] = (uint8_t)q;
-    E[(int64_t)n * NB + jj] = err;
-#pragma unroll
-    for (int cc = jj + 1; cc < NB; ++cc) w[cc] -= err * Ub[jj][cc];
+    for (int t = 0; t < NB / 4; ++t) {
+      codes[(int64_t)n * K + j0 + 4 * t + q] = code_s[threadIdx.x >> 2][4 * t + q];
+      E[(int64_t)n * NB + 4 * t + q] = e_s[threadIdx.x >> 2][4 * t + q];
+    }
   }
 }
 
@@ -294,7 +346,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t at, g, s, ones, zeros, dead, scal, h, l, x, dinv, tm, wc, e, codes, s64, z64, total;
+  size_t at, g, s, ones, zeros, dead, scal, h, l, x, dinv, wc, e, codes, s64, z64, total;
 };
 Layout make_layout(int N, int K, int64_t T) {
   const size_t Tpad = (size_t)((T + 63) / 64) * 64, KK = (size_t)K * K;
@@ -312,7 +364,6 @@ Layout make_layout(int N, int K, int64_t T) {
   o.l = take(KK * 8);
   o.x = take(KK * 8);
   o.dinv = take((size_t)(K / NB) * NB * NB * 8);
-  o.tm = take((size_t)NB * K * 8);
   o.wc = take((size_t)N * K * 8);
   o.e = take((size_t)N * NB * 8);
   o.codes = take((size_t)N * K);
@@ -345,7 +396,6 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
   double* L = reinterpret_cast<double*>(ws + o.l);
   double* X = reinterpret_cast<double*>(ws + o.x);
   double* Dinv = reinterpret_cast<double*>(ws + o.dinv);
-  double* Tm = reinterpret_cast<double*>(ws + o.tm);
   double* Wc = reinterpret_cast<double*>(ws + o.wc);
   double* E = reinterpret_cast<double*>(ws + o.e);
   uint8_t* codes = reinterpret_cast<uint8_t*>(ws + o.codes);
@@ -375,13 +425,14 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
 
   // ---- blocked right-looking Cholesky of the index-reversed Hessian: H = L L^T ----
   for (int kb = 0; kb < nb; ++kb) {
-    hipLaunchKernelGGL(potf2_inv_kernel, dim3(1), dim3(256), 0, st, H, L, Dinv, K, kb);
+    hipLaunchKernelGGL(potf2_inv_kernel, dim3(1), dim3(64), 0, st, H, L, Dinv, K, kb);
     RQ_HIP(hipGetLastError());
     const int r0 = (kb + 1) * NB, rest = K - r0;
     if (rest <= 0) break;
     const int64_t c0 = (int64_t)kb * NB;
     // panel: L[r0:, kb] = H[r0:, kb] Dinv_kk^T
-    GemmF64 g;
+    GemmF64 g = {};
+    g.batch = 1; g.tri = TRI_NONE;
     g.A = H + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
     g.B = Dinv + (int64_t)kb * NB * NB; g.sbk = 1; g.sbn = NB;
     g.C = L + (int64_t)r0 * K + c0; g.scm = K; g.scn = 1;
@@ -391,36 +442,50 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
     g.A = L + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
     g.B = L + (int64_t)r0 * K + c0; g.sbk = 1; g.sbn = K;
     g.C = H + (int64_t)r0 * K + r0; g.scm = K; g.scn = 1;
-    g.M = rest; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0;
+    g.M = rest; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0; g.tri = TRI_C_LOWER;
     if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
   }
-  // ---- X = L^-1, block row by block row: X[i, :i] = -Dinv_ii (L[i, :i] X[:i, :i]) ----
+  // ---- X = L^-1 by doubling: the 64-blocks on the diagonal are inverted already; two neighbouring inverted diagonal
+  //      blocks X11 (s x s) and X22 merge through X21 = -X22 (L21 X11).  All pairs of a level run as one batched GEMM
+  //      pair; H, no longer needed, holds L21 X11.  A shorter last pair (K / 64 not a power of two) runs on its own ----
   hipLaunchKernelGGL(init_inverse_kernel, dim3((unsigned)((KK + 255) / 256)), dim3(256), 0, st, X, Dinv, K);
   RQ_HIP(hipGetLastError());
-  for (int i = 1; i < nb; ++i) {
-    GemmF64 g;
-    g.A = L + (int64_t)i * NB * K; g.sam = K; g.sak = 1;
-    g.B = X; g.sbk = K; g.sbn = 1;
-    g.C = Tm; g.scm = K; g.scn = 1;
-    g.M = NB; g.N = i * NB; g.Kin = i * NB; g.alpha = 1.0; g.beta = 0.0;
-    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
-    g.A = Dinv + (int64_t)i * NB * NB; g.sam = NB; g.sak = 1;
-    g.B = Tm; g.sbk = K; g.sbn = 1;
-    g.C = X + (int64_t)i * NB * K; g.scm = K; g.scn = 1;
-    g.M = NB; g.N = i * NB; g.Kin = NB; g.alpha = -1.0; g.beta = 0.0;
-    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+  for (int64_t sz = NB; sz < K; sz *= 2) {
+    const int64_t full_pairs = K / (2 * sz);                 // pairs whose second half has the full size
+    const int64_t tail_start = full_pairs * 2 * sz;          // a last pair with a shorter second half, if any
+    const int64_t tail_second = K - tail_start > sz ? K - tail_start - sz : 0;
+    for (int part = 0; part < 2; ++part) {
+      const int64_t p0 = part == 0 ? 0 : tail_start, second = part == 0 ? sz : tail_second;
+      const int batch = part == 0 ? (int)full_pairs : (tail_second > 0 ? 1 : 0);
+      if (batch == 0) continue;
+      const int64_t pair_stride = 2 * sz * ((int64_t)K + 1);
+      const int64_t o21 = (p0 + sz) * K + p0, o11 = p0 * K + p0, o22 = (p0 + sz) * K + (p0 + sz);
+      GemmF64 g = {};
+      g.batch = batch;
+      g.A = L + o21; g.sam = K; g.sak = 1; g.bsa = pair_stride;
+      g.B = X + o11; g.sbk = K; g.sbn = 1; g.bsb = pair_stride;
+      g.C = H + o21; g.scm = K; g.scn = 1; g.bsc = pair_stride;
+      g.M = second; g.N = (int)sz; g.Kin = (int)sz; g.alpha = 1.0; g.beta = 0.0; g.tri = TRI_B_LOWER;
+      if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+      g.A = X + o22; g.sam = K; g.sak = 1; g.bsa = pair_stride;
+      g.B = H + o21; g.sbk = K; g.sbn = 1; g.bsb = pair_stride;
+      g.C = X + o21; g.scm = K; g.scn = 1; g.bsc = pair_stride;
+      g.M = second; g.N = (int)sz; g.Kin = (int)second; g.alpha = -1.0; g.beta = 0.0; g.tri = TRI_A_LOWER;
+      if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+    }
   }
   // ---- the sweep ----
   hipLaunchKernelGGL(row_init_kernel, dim3((unsigned)N), dim3(256), 0, st, d->W, K, d->bits, dead, Wc, s64, z64);
   RQ_HIP(hipGetLastError());
   for (int b = 0; b < nb; ++b) {
     const int j0 = b * NB;
-    hipLaunchKernelGGL(sweep_block_kernel, dim3((unsigned)((N + 63) / 64)), dim3(64), 0, st, Wc, X, N, K, j0, d->bits, s64, z64, E, codes);
+    hipLaunchKernelGGL(sweep_block_kernel, dim3((unsigned)((N + 15) / 16)), dim3(64), 0, st, Wc, X, N, K, j0, d->bits, s64, z64, E, codes);
     RQ_HIP(hipGetLastError());
     const int rest = K - j0 - NB;
     if (rest <= 0) break;
     // W[:, j0+64:] -= E U[j0:j0+64, j0+64:],  U[a][b] = X[K-1-a][K-1-b]
-    GemmF64 g;
+    GemmF64 g = {};
+    g.batch = 1; g.tri = TRI_NONE;
     g.A = E; g.sam = NB; g.sak = 1;
     g.B = X + (int64_t)(K - 1 - j0) * K + (K - 1 - j0 - NB); g.sbk = -(int64_t)K; g.sbn = -1;
     g.C = Wc + j0 + NB; g.scm = K; g.scn = 1;
