@@ -108,21 +108,29 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(const GemmF64 g) {
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  for (int k0 = kbeg; k0 < kend; k0 += 16) {
+  // the next 16-deep slice of both operands is requested into registers before the current one is multiplied
+  double ra[4], rb[4];
+  auto request = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int e = tid + i * 256;                                     // 16 x 64 elements of each operand
-      {
-        const int kk = a_kfast ? e & 15 : e >> 6, mm = a_kfast ? e >> 4 : e & 63;
-        const int64_t m = m0 + mm;
-        As[kk][mm] = m < g.M ? A[m * g.sam + (int64_t)(k0 + kk) * g.sak] : 0.0;
-      }
-      {
-        const int kk = b_kfast ? e & 15 : e >> 6, nn = b_kfast ? e >> 4 : e & 63;
-        Bs[kk][nn] = B[(int64_t)(k0 + kk) * g.sbk + (int64_t)(n0 + nn) * g.sbn];
-      }
+      const int ka = a_kfast ? e & 15 : e >> 6, ma = a_kfast ? e >> 4 : e & 63;
+      const int64_t m = m0 + ma;
+      ra[i] = m < g.M ? A[m * g.sam + (int64_t)(k0 + ka) * g.sak] : 0.0;
+      const int kb2 = b_kfast ? e & 15 : e >> 6, nb2 = b_kfast ? e >> 4 : e & 63;
+      rb[i] = B[(int64_t)(k0 + kb2) * g.sbk + (int64_t)(n0 + nb2) * g.sbn];
+    }
+  };
+  if (kbeg < kend) request(kbeg);
+  for (int k0 = kbeg; k0 < kend; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * 256;
+      As[a_kfast ? e & 15 : e >> 6][a_kfast ? e >> 4 : e & 63] = ra[i];
+      Bs[b_kfast ? e & 15 : e >> 6][b_kfast ? e >> 4 : e & 63] = rb[i];
     }
     __syncthreads();
+    if (k0 + 16 < kend) request(k0 + 16);
 #pragma unroll
     for (int kk = 0; kk < 16; ++kk) {
       double a[4], b[4];
