@@ -173,6 +173,17 @@ def channel_bounds(Xp, clip_up=None, clip_lo=None):
     return lo, up
 
 
+def channel_percentile_bounds(Xp, q_lo, q_hi):
+    """Per-channel percentile bounds of X' [T, D] (Section "Implementation details": "the default calibration strategy
+    is Percentile"; the paper gives no value, so the two fractions q_lo < q_hi in [0, 1] are parameters).  The q-th
+    fraction of n sorted values v_0 <= ... <= v_{n-1} sits at h = q (n - 1) and is interpolated linearly between
+    v_floor(h) and v_floor(h)+1 -- numpy's default definition, used here as the library routine it is."""
+    Xp = np.asarray(Xp, dtype=F64)
+    lo = np.percentile(Xp, 100.0 * q_lo, axis=0)
+    hi = np.percentile(Xp, 100.0 * q_hi, axis=0)
+    return lo, hi
+
+
 def ln_quant_channelwise(X, gamma, beta, s_ch, z_ch, bits, eps, kind=NORM_LAYERNORM):
     """Definition tier: LayerNorm, then channel-wise uniform quantization with s, z in R^D, Z^D."""
     Xp = layernorm(X, gamma, beta, eps, kind)

@@ -429,3 +429,26 @@ def test_gelu_silu_match_library_and_closed_form():
     assert orc.gelu(1.0) == pytest.approx(0.8413447460685429, rel=1e-14)      # Phi(1)
     h = np.stack([x, x[::-1]], axis=1)                                          # [n, 2*Dm] with Dm = 1
     assert np.allclose(orc.mlp_activation(h, orc.ACT_SILU_GATED, 1)[:, 0], orc.silu(x) * x[::-1])
+
+
+# ---------------------------------------------------------------- percentile calibration bounds
+def test_percentile_bounds_against_sorting_and_closed_forms():
+    """The interpolated order statistic written out by hand on sorted columns; q = 0 and 1 are min and max; an
+    arithmetic progression has percentiles on the same line."""
+    g = np.random.default_rng(11)
+    X = g.standard_normal((37, 5)) * np.array([1.0, 10.0, 0.1, 3.0, 1.0])
+    for q_lo, q_hi in [(0.01, 0.99), (0.25, 0.5), (0.0, 1.0), (0.001, 0.9999)]:
+        lo, hi = orc.channel_percentile_bounds(X, q_lo, q_hi)
+        S = np.sort(X, axis=0)
+        for q, got in ((q_lo, lo), (q_hi, hi)):
+            h = q * (X.shape[0] - 1)
+            k = int(math.floor(h))
+            k1 = min(k + 1, X.shape[0] - 1)
+            want = S[k] + (h - k) * (S[k1] - S[k])
+            np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    lo, hi = orc.channel_percentile_bounds(X, 0.0, 1.0)
+    assert np.array_equal(lo, X.min(axis=0)) and np.array_equal(hi, X.max(axis=0))
+    ramp = np.arange(101, dtype=np.float64)[:, None] * np.array([1.0, -2.0])
+    lo, hi = orc.channel_percentile_bounds(ramp, 0.1, 0.9)
+    np.testing.assert_allclose(lo, [10.0, -180.0], rtol=1e-14)
+    np.testing.assert_allclose(hi, [90.0, -20.0], rtol=1e-14)
