@@ -500,6 +500,15 @@ rq_status rq_rowsum_i8(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64
 rq_status rq_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
                                double eps, const float* gamma, const float* beta, double* cmin, double* cmax);
 rq_status rq_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_t cols, int64_t ld, double* out2);
+/* Percentile variant of rq_ln_channel_minmax (Section "Implementation details": the default calibration strategy is
+ * "Percentile"; no value is printed, so the fractions are arguments): for every channel of X' = norm(x) * gamma + beta
+ * the q_lo-th and q_hi-th fractions of its T values, 0 <= q_lo <= q_hi <= 1, each interpolated linearly between the
+ * order statistics floor(q (T - 1)) and the next one (exact selection, float64).  q_lo = 0, q_hi = 1 give min and max.
+ * gamma == NULL means x already is X' (norm_kind, eps, beta ignored; any D).  lo, hi: device double [D].
+ * workspace: device, 16 * T bytes, 16-byte aligned; unused when gamma == NULL. */
+rq_status rq_ln_channel_percentile(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
+                                   double eps, const float* gamma, const float* beta, double q_lo, double q_hi,
+                                   double* lo, double* hi, void* workspace, size_t workspace_bytes);
 
 typedef struct {
   int32_t D, H, Dm;

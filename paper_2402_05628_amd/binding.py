@@ -221,6 +221,7 @@ _rq_profile_read = _sig("rq_profile_read", i32, [vp, C.POINTER(f64), C.POINTER(i
 _rq_rowsum = _sig("rq_rowsum_i8", i32, [vp, vp, i64, i32, i64, vp])
 _rq_ln_cmm = _sig("rq_ln_channel_minmax", i32, [vp, vp, i64, i32, i64, i32, f64, vp, vp, vp, vp])
 _rq_minmax = _sig("rq_minmax_f32", i32, [vp, vp, i64, i64, i64, vp])
+_rq_ln_cpct = _sig("rq_ln_channel_percentile", i32, [vp, vp, i64, i32, i64, i32, f64, vp, vp, f64, f64, vp, vp, vp, C.c_size_t])
 _rq_gptq_ws = _sig("rq_gptq_workspace_bytes", C.c_size_t, [i32, i32, i64])
 _rq_gptq = _sig("rq_gptq_quant_pack", i32, [vp, C.POINTER(GptqDesc)])
 _rq_dual_clip_ws = _sig("rq_dual_clip_workspace_bytes", C.c_size_t, [i64])
@@ -417,6 +418,18 @@ def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYER
     ctx.check(_rq_dual_clip(ctx.handle, C.byref(d)))
     out["_workspace"] = ws                      # keeps the scratch alive until the caller drops the result
     return out
+
+
+def rq_ln_channel_percentile(ctx, x, q_lo, q_hi, gamma=None, beta=None, norm_kind=NORM_LAYERNORM, eps=1e-6):
+    """Per-channel percentile bounds of X' = norm(x) * gamma + beta (of x itself when gamma is None): float64 [D] each."""
+    T, D = x.shape
+    lo = torch.empty(D, dtype=torch.float64, device=x.device)
+    hi = torch.empty(D, dtype=torch.float64, device=x.device)
+    nbytes = 16 * T if gamma is not None else 0
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    ctx.check(_rq_ln_cpct(ctx.handle, _p(x), T, D, x.stride(0), norm_kind, eps, _p(gamma), _p(beta), q_lo, q_hi, _p(lo), _p(hi),
+                          _p(ws), nbytes))
+    return lo, hi, ws
 
 
 def set_dual_clip_waves(n: int):

@@ -481,6 +481,29 @@ rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d) {
   return rq_launch_dual_clip(ctx, d);
 }
 
+rq_status rq_ln_channel_percentile(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind, double eps,
+                                   const float* gamma, const float* beta, double q_lo, double q_hi, double* lo, double* hi,
+                                   void* workspace, size_t workspace_bytes) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_ln_channel_percentile: ctx is NULL");
+  RQ_REQUIRE(x && lo && hi, RQ_ERR_INVALID_ARG, "rq_ln_channel_percentile: x, lo, hi must be non-NULL");
+  RQ_REQUIRE(T > 0 && D > 0 && ldx >= D, RQ_ERR_SHAPE, "rq_ln_channel_percentile: T = %lld, D = %d, ldx = %lld", (long long)T, D,
+             (long long)ldx);
+  RQ_REQUIRE(q_lo >= 0.0 && q_lo <= q_hi && q_hi <= 1.0, RQ_ERR_INVALID_ARG,
+             "rq_ln_channel_percentile: fractions must satisfy 0 <= q_lo <= q_hi <= 1");
+  RQ_REQUIRE(rq_aligned(x, 4) && rq_aligned(lo, 8) && rq_aligned(hi, 8), RQ_ERR_INVALID_ARG, "rq_ln_channel_percentile: alignment");
+  if (gamma) {
+    RQ_REQUIRE(norm_kind == RQ_NORM_LAYERNORM || norm_kind == RQ_NORM_RMSNORM, RQ_ERR_INVALID_ARG,
+               "rq_ln_channel_percentile: norm_kind %d", norm_kind);
+    RQ_REQUIRE(eps > 0.0 && std::isfinite(eps), RQ_ERR_INVALID_ARG, "rq_ln_channel_percentile: eps must be positive and finite");
+    RQ_REQUIRE(D % 4 == 0 && ldx % 4 == 0 && rq_aligned(x, 16), RQ_ERR_SHAPE,
+               "rq_ln_channel_percentile: with a normalization D and ldx must be multiples of 4 and x 16-byte aligned");
+    RQ_REQUIRE(workspace && rq_aligned(workspace, 16) && workspace_bytes >= (size_t)T * 16, RQ_ERR_WORKSPACE,
+               "rq_ln_channel_percentile: workspace of %zu bytes, %zu needed (16-byte aligned)", workspace_bytes, (size_t)T * 16);
+  }
+  RQ_NEED_DEVICE();
+  return rq_launch_ln_channel_percentile(ctx, x, T, D, ldx, norm_kind, eps, gamma, beta, q_lo, q_hi, lo, hi, workspace);
+}
+
 rq_status rq_gptq_quant_pack(rq_ctx* ctx, const rq_gptq_desc* d) {
   RQ_CHECK_CTX("rq_gptq_quant_pack");
   RQ_REQUIRE(d->W && d->A && d->w_out && d->s_w && d->z_w && d->colsum_w, RQ_ERR_INVALID_ARG,

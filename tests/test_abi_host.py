@@ -218,6 +218,18 @@ def test_gptq_validation(b, host_ctx):
     assert "rq_gptq_quant_pack" in b.lib.rq_last_error(host_ctx.handle).decode()
 
 
+def test_percentile_validation(b, host_ctx):
+    fn = b.lib.rq_ln_channel_percentile
+    def call(x=FAKE, T=100, D=64, ldx=64, kind=0, eps=1e-6, gamma=FAKE, q=(0.01, 0.99), lo=FAKE, hi=FAKE, ws=FAKE, nbytes=1600):
+        return fn(host_ctx.handle, x, T, D, ldx, kind, eps, gamma, None, q[0], q[1], lo, hi, ws, nbytes)
+    assert call() == 3
+    assert call(gamma=None, ws=None, nbytes=0, D=7, ldx=7) == 3
+    assert call(x=None) == 1 and call(lo=None) == 1
+    assert call(q=(0.6, 0.4)) == 1 and call(q=(-0.1, 0.5)) == 1 and call(q=(0.5, 1.5)) == 1
+    assert call(T=0) == 2 and call(ldx=32) == 2 and call(D=66, ldx=68) == 2
+    assert call(nbytes=100) == 4 and call(kind=3) == 1 and call(eps=0.0) == 1
+
+
 def test_softmax_and_pv_validation(b, host_ctx):
     sd = dict(G=2, H=2, Nq=8, Nk=8, ld=16, acc=FAKE, logit_scale=0.1, bias=None, mask=0, s_log=1.0, bits=4, codes=FAKE)
     ok = b.SoftmaxDesc(**sd)

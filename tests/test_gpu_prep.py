@@ -104,3 +104,27 @@ def test_ln_channel_minmax(rq, T, D, kind):
     cmin, cmax = b.rq_ln_channel_minmax(ctx, dev(x), dev(gamma), dev(beta), norm_kind=kind)
     assert np.allclose(cmin.cpu().numpy(), Xp.min(0), rtol=1e-11, atol=1e-12)
     assert np.allclose(cmax.cpu().numpy(), Xp.max(0), rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("T,D,kind,q", [(333, 384, 0, (0.01, 0.99)), (1000, 128, 1, (0.001, 0.9999)), (50, 64, 0, (0.0, 1.0)),
+                                        (12608, 48, 0, (0.00001, 0.99999)), (7, 8, 0, (0.5, 0.5))])
+def test_ln_channel_percentile(rq, T, D, kind, q):
+    """Percentile calibration bounds (exact selection + linear interpolation) against numpy's definition."""
+    b, ctx = rq
+    print("case", T, D, kind, q, flush=True)
+    x = synth.make_rows(T, D, seed=D + 1)
+    x[: T // 3, 2] = x[0, 2]                                   # repeated values in one channel
+    g = np.random.default_rng(D)
+    gamma, beta = g.normal(1, 0.1, size=D).astype(np.float32), g.normal(0, 0.1, size=D).astype(np.float32)
+    Xp = orc.layernorm(x, gamma, beta, 1e-6, kind)
+    want_lo, want_hi = orc.channel_percentile_bounds(Xp, *q)
+    lo, hi, _ = b.rq_ln_channel_percentile(ctx, dev(x), q[0], q[1], dev(gamma), dev(beta), norm_kind=kind)
+    torch.cuda.synchronize()
+    scale = np.abs(Xp).max(axis=0)
+    assert np.all(np.abs(lo.cpu().numpy() - want_lo) <= 1e-11 * scale)
+    assert np.all(np.abs(hi.cpu().numpy() - want_hi) <= 1e-11 * scale)
+    # without a normalization the input is taken as X' itself
+    lo2, hi2, _ = b.rq_ln_channel_percentile(ctx, dev(x), q[0], q[1])
+    torch.cuda.synchronize()
+    w_lo, w_hi = orc.channel_percentile_bounds(x.astype(np.float64), *q)
+    assert np.allclose(lo2.cpu().numpy(), w_lo, rtol=1e-13, atol=0) and np.allclose(hi2.cpu().numpy(), w_hi, rtol=1e-13, atol=0)
