@@ -491,10 +491,11 @@ int32_t rq_profile_read(rq_ctx* ctx, double* ms_total /* [RQ_STEP_COUNT] */, int
  *                      (the channel extremes of the Eqs. for X'_up and X'_low), float64 math and output
  *                      (cmin, cmax: device double [D]).
  * rq_minmax_f32:       min and max of a [rows, cols] float32 region -> out2[0], out2[1] (device double).
- * rq_block_calibrate:  Algorithm 1 restricted to one block and to min/max bounds: walks the block on one
- *                      calibration batch, layer by layer, each layer seeing the quantized layers before it;
- *                      fills the caller-allocated arrays named in rq_block_params and writes the scalar
- *                      fields.  Weight quantization is round-to-nearest (GPTQ is not part of this library).
+ * rq_block_calibrate:  Algorithm 1 restricted to one block: walks the block on one calibration batch, layer by
+ *                      layer, each layer seeing the quantized layers before it; fills the caller-allocated
+ *                      arrays named in rq_block_params and writes the scalar fields.  By default bounds are
+ *                      min/max (times the given clip factors) and weights round-to-nearest; rq_block_raw can
+ *                      switch on the learnt clipping and GPTQ.
  */
 rq_status rq_rowsum_i8(rq_ctx* ctx, const int8_t* A, int64_t M, int32_t K, int64_t lda, int32_t* rowsum);
 rq_status rq_ln_channel_minmax(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
@@ -520,6 +521,16 @@ typedef struct {
   const float *ln1_clip_up, *ln1_clip_lo, *ln2_clip_up, *ln2_clip_lo;           /* [D] or NULL (= 1) */
   const float* rel_bias;
   float s_log;
+  /* Algorithm 1's two learning steps (both off when the fields are 0, the state after memset):
+   * learn_clip_iters > 0: the clip factors of both LayerNorms are learnt by rq_dual_clip_learn (that many Adam
+   *   iterations, learning rate learn_clip_lr, start learn_clip_alpha0) instead of being read from ln*_clip_up/lo;
+   * gptq != 0: every Linear is quantized by rq_gptq_quant_pack against the codes it is fed (gptq_percdamp, 0.01 in the
+   *   published method) instead of round-to-nearest; needs every K (D and Dm) a multiple of 64 and at most 8192. */
+  int32_t learn_clip_iters;
+  double learn_clip_lr;
+  double learn_clip_alpha0;
+  int32_t gptq;
+  double gptq_percdamp;
 } rq_block_raw;
 
 size_t rq_block_calibrate_workspace_bytes(const rq_block_raw* raw, int64_t batch, int64_t seq);

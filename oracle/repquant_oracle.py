@@ -414,8 +414,14 @@ def _f32(v):
     return np.asarray(v, dtype=F64).astype(np.float32)
 
 
-def _lin(W, b, bits):
-    codes, s_w, z_w = weight_quant(_f32(W), bits)
+def _lin(W, b, bits, A_int=None):
+    """Weight quantization of one Linear: round-to-nearest on the per-channel min/max grid, or -- when the layer's
+    integer-valued input codes A_int [T, K] are given -- GPTQ against them (Algorithm 1, last step of a layer)."""
+    if A_int is None:
+        codes, s_w, z_w = weight_quant(_f32(W), bits)
+    else:
+        from . import gptq_oracle
+        codes, s_w, z_w = gptq_oracle.gptq(_f32(W), A_int, bits)
     return dict(codes=codes, s_w=s_w, z_w=z_w, bias=_f32(b))
 
 
@@ -427,8 +433,13 @@ def _tensor_qparams(v, bits):
     return s, z
 
 
-def _fold_ln(Xin, gamma, beta, W, b, clip_up, clip_lo, c):
+def _fold_ln(Xin, gamma, beta, W, b, clip_up, clip_lo, c, learn_clip=None):
     Xp = layernorm(Xin, gamma, beta, c["eps"], c["norm"])
+    if learn_clip is not None:
+        # Algorithm 1, "Per-channel dual clipping": the factors are learnt on this layer's X'; they are kept as float32
+        from . import dual_clip_oracle
+        r = dual_clip_oracle.learn(Xp, c["bits_a"], **learn_clip)
+        clip_up, clip_lo = r["clip_up"].astype(np.float32), r["clip_lo"].astype(np.float32)
     lo, up = channel_bounds(Xp, clip_up, clip_lo)
     s_ch, _ = qparams_from_bounds(lo, up, c["bits_a"])
     s_ch = s_ch.astype(np.float32)                       # channel scales are stored float32
@@ -439,10 +450,12 @@ def _fold_ln(Xin, gamma, beta, W, b, clip_up, clip_lo, c):
     return ln, _f32(f["W_t"]), _f32(f["b_t"])
 
 
-def calibrate_block(raw, cfg):
+def calibrate_block(raw, cfg, learn_clip=None, gptq=False):
     """raw: dict of float32 arrays (x, ln1_gamma, ln1_beta, w_qkv, b_qkv, w_proj, b_proj, ln2_*, w_fc1,
     b_fc1, w_fc2, b_fc2, rel_bias, ln*_clip_up/lo); cfg: dict (batch, seq, D, H, Dm, bits_w, bits_a,
-    bits_p, norm, act, mask, eps).  Returns the parameter dict block_forward consumes."""
+    bits_p, norm, act, mask, eps).  Returns the parameter dict block_forward consumes.
+    learn_clip: None (use the given clip factors) or dict(iters, lr, alpha0) -- learn them per LayerNorm (Algorithm 1);
+    gptq: quantize every Linear with GPTQ against the codes it is fed, instead of round-to-nearest."""
     c = dict(cfg)
     D, H, seq, batch = c["D"], c["H"], c["seq"], c["batch"]
     dh = D // H
@@ -452,10 +465,10 @@ def calibrate_block(raw, cfg):
     P = dict(cfg=c, s_log=np.float32(1.0), rel_bias=raw.get("rel_bias"))
 
     ln1, Wt, bt = _fold_ln(X, raw["ln1_gamma"], raw["ln1_beta"], raw["w_qkv"], raw["b_qkv"],
-                           raw.get("ln1_clip_up"), raw.get("ln1_clip_lo"), c)
+                           raw.get("ln1_clip_up"), raw.get("ln1_clip_lo"), c, learn_clip)
     P["ln1"] = ln1
-    P["qkv"] = _lin(Wt, bt, bw)
     a1 = ln_quant(X, ln1["gamma_t"], ln1["beta_t"], ln1["s"], ln1["z"], ba, c["eps"], c["norm"])
+    P["qkv"] = _lin(Wt, bt, bw, a1 - ln1["z"] if gptq else None)
     qkv = qlinear(a1, ln1["s"], ln1["z"], P["qkv"])
     for i, nm in enumerate("qkv"):
         P["s_" + nm], P["z_" + nm] = _tensor_qparams(qkv[:, i * D:(i + 1) * D], ba)
@@ -473,17 +486,18 @@ def calibrate_block(raw, cfg):
             attn[r, cs] = attn_pv(codes, qv[r, cs], P["s_log"], P["s_v"], P["z_v"], causal)
     P["s_o"], P["z_o"] = _tensor_qparams(attn, ba)
     qo = uniform_quant(attn, P["s_o"], P["z_o"], ba)
-    P["proj"] = _lin(raw["w_proj"], raw["b_proj"], bw)
+    P["proj"] = _lin(raw["w_proj"], raw["b_proj"], bw, qo - P["z_o"] if gptq else None)
     xbar = qlinear(qo, P["s_o"], P["z_o"], P["proj"]) + X
 
     ln2, Wt, bt = _fold_ln(xbar, raw["ln2_gamma"], raw["ln2_beta"], raw["w_fc1"], raw["b_fc1"],
-                           raw.get("ln2_clip_up"), raw.get("ln2_clip_lo"), c)
+                           raw.get("ln2_clip_up"), raw.get("ln2_clip_lo"), c, learn_clip)
     P["ln2"] = ln2
-    P["fc1"] = _lin(Wt, bt, bw)
     a2 = ln_quant(xbar, ln2["gamma_t"], ln2["beta_t"], ln2["s"], ln2["z"], ba, c["eps"], c["norm"])
+    P["fc1"] = _lin(Wt, bt, bw, a2 - ln2["z"] if gptq else None)
     hid = mlp_activation(qlinear(a2, ln2["s"], ln2["z"], P["fc1"]), c["act"], c["Dm"])
     P["s_h"], P["z_h"] = _tensor_qparams(hid, ba)
-    P["fc2"] = _lin(raw["w_fc2"], raw["b_fc2"], bw)
+    qh = uniform_quant(hid, P["s_h"], P["z_h"], ba)
+    P["fc2"] = _lin(raw["w_fc2"], raw["b_fc2"], bw, qh - P["z_h"] if gptq else None)
     return P
 
 

@@ -124,7 +124,8 @@ class BlockRaw(C.Structure):
                 ("w_qkv", vp), ("b_qkv", vp), ("w_proj", vp), ("b_proj", vp), ("w_fc1", vp), ("b_fc1", vp),
                 ("w_fc2", vp), ("b_fc2", vp),
                 ("ln1_clip_up", vp), ("ln1_clip_lo", vp), ("ln2_clip_up", vp), ("ln2_clip_lo", vp),
-                ("rel_bias", vp), ("s_log", f32)]
+                ("rel_bias", vp), ("s_log", f32),
+                ("learn_clip_iters", i32), ("learn_clip_lr", f64), ("learn_clip_alpha0", f64), ("gptq", i32), ("gptq_percdamp", f64)]
 
 
 def _sig(name, restype, argtypes):
@@ -540,9 +541,10 @@ _rq_cal_ws = _sig("rq_block_calibrate_workspace_bytes", C.c_size_t, [C.POINTER(B
 _rq_calibrate = _sig("rq_block_calibrate", i32, [vp, C.POINTER(BlockRaw), vp, i64, i64, C.POINTER(BlockParams), vp, C.c_size_t])
 
 
-def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: int) -> "Block":
+def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: int, learn_clip=None, gptq=False) -> "Block":
     """Allocates the quantized-parameter arrays, runs rq_block_calibrate on the batch x and returns a Block.
-    raw: dict of device float32 tensors named as in synth.make_block (None allowed where the C struct allows NULL)."""
+    raw: dict of device float32 tensors named as in synth.make_block (None allowed where the C struct allows NULL).
+    learn_clip: None or dict(iters, lr, alpha0) -- learn the LayerNorm clip factors; gptq: GPTQ instead of round-to-nearest."""
     D, Dm = cfg.D, cfg.Dm
     gated = cfg.act != 0
     n1 = 2 * Dm if gated else Dm
@@ -551,6 +553,10 @@ def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: in
     br.D, br.H, br.Dm, br.norm_kind, br.mask = cfg.D, cfg.H, cfg.Dm, cfg.norm, cfg.mask
     br.act = ACT_SILU_GATED if gated else ACT_GELU
     br.bits_w, br.bits_a, br.bits_p, br.eps, br.s_log = cfg.bits_w, cfg.bits_a, cfg.bits_p, cfg.eps, 1.0
+    if learn_clip is not None:
+        br.learn_clip_iters, br.learn_clip_lr, br.learn_clip_alpha0 = learn_clip["iters"], learn_clip["lr"], learn_clip["alpha0"]
+    if gptq:
+        br.gptq, br.gptq_percdamp = 1, 0.01
     for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta", "w_qkv", "b_qkv", "w_proj", "b_proj", "w_fc1", "b_fc1",
               "w_fc2", "b_fc2", "ln1_clip_up", "ln1_clip_lo", "ln2_clip_up", "ln2_clip_lo", "rel_bias"):
         setattr(br, k, _p(raw.get(k)))

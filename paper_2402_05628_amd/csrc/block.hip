@@ -307,7 +307,7 @@ namespace {
 
 struct CalPlan {
   Plan fwd;
-  size_t o_cmin, o_cmax, o_sch, o_zch, o_wt, o_bt, o_f32, o_scal, total;
+  size_t o_cmin, o_cmax, o_sch, o_zch, o_wt, o_bt, o_f32, o_scal, o_clip, o_alpha, o_learn, o_gptq, gptq_bytes, total;
 };
 
 CalPlan make_cal_plan(const rq_block_raw* raw, int64_t batch, int64_t seq) {
@@ -328,6 +328,19 @@ CalPlan make_cal_plan(const rq_block_raw* raw, int64_t batch, int64_t seq) {
   c.o_bt = o; o += up((size_t)nmax * 4);
   c.o_f32 = o; o += up((size_t)c.fwd.T * nmax * 4);
   c.o_scal = o; o += up(256);
+  c.o_clip = c.o_alpha = c.o_learn = c.o_gptq = o;
+  c.gptq_bytes = 0;
+  if (raw->learn_clip_iters > 0) {
+    c.o_clip = o; o += up((size_t)2 * D * 4);
+    c.o_alpha = o; o += up((size_t)2 * D * 8);
+    c.o_learn = o; o += up(rq_dual_clip_workspace_bytes(c.fwd.T));
+  }
+  if (raw->gptq) {
+    const size_t need[4] = {rq_gptq_workspace_bytes(3 * D, D, c.fwd.T), rq_gptq_workspace_bytes(D, D, c.fwd.T),
+                            rq_gptq_workspace_bytes(n1, D, c.fwd.T), rq_gptq_workspace_bytes(D, Dm, c.fwd.T)};
+    for (size_t v : need) c.gptq_bytes = v > c.gptq_bytes ? v : c.gptq_bytes;
+    c.o_gptq = o; o += up(c.gptq_bytes);
+  }
   c.total = o;
   return c;
 }
@@ -356,6 +369,11 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
   RQ_REQUIRE(raw->ln1_gamma && raw->ln2_gamma && raw->w_qkv && raw->w_proj && raw->w_fc1 && raw->w_fc2, RQ_ERR_INVALID_ARG,
              "rq_block_calibrate: gammas and weights must be non-NULL");
   RQ_REQUIRE(raw->s_log > 0.f, RQ_ERR_INVALID_ARG, "rq_block_calibrate: s_log must be > 0");
+  RQ_REQUIRE(raw->learn_clip_iters >= 0 && raw->learn_clip_iters <= 100000, RQ_ERR_INVALID_ARG,
+             "rq_block_calibrate: learn_clip_iters = %d", raw->learn_clip_iters);
+  if (raw->gptq)
+    RQ_REQUIRE(raw->D % 64 == 0 && raw->Dm % 64 == 0 && raw->D <= 8192 && raw->Dm <= 8192 && batch * seq <= 131071,
+               RQ_ERR_UNSUPPORTED, "rq_block_calibrate: GPTQ needs D and Dm multiples of 64, at most 8192, and at most 131071 tokens");
   RQ_REQUIRE(out->ln1_gamma_t && out->ln1_beta_t && out->ln2_gamma_t && out->ln2_beta_t, RQ_ERR_INVALID_ARG,
              "rq_block_calibrate: out->ln*_gamma_t / beta_t must point to caller-allocated [D] arrays");
   const rq_qlinear* lins[4] = {&out->qkv, &out->proj, &out->fc1, &out->fc2};
@@ -406,21 +424,44 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
     *lo = h2[0]; *hi = h2[1];
     return RQ_OK;
   };
-  auto quant_linear = [&](rq_qlinear* l, const float* W, const float* b, int N, int K, int gate_rows) -> rq_status {
+  // weight quantization of one Linear; `A` = the codes it is fed (stored form) for GPTQ
+  auto quant_linear = [&](rq_qlinear* l, const float* W, const float* b, int N, int K, int gate_rows, const int8_t* A, int a_off,
+                          int z_a) -> rq_status {
+    l->N = N; l->K = K; l->bits = bw; l->format = wfmt;
+    if (raw->gptq) {
+      rq_gptq_desc d;
+      std::memset(&d, 0, sizeof d);
+      d.N = N; d.K = K; d.bits = bw; d.format = wfmt; d.gate_up_rows = gate_rows; d.W = W; d.bias = b;
+      d.A = A; d.T = T; d.lda = K; d.a_off = a_off; d.z_a = z_a; d.percdamp = raw->gptq_percdamp > 0.0 ? raw->gptq_percdamp : 0.01;
+      d.w_out = const_cast<void*>(l->w); d.s_w = const_cast<float*>(l->s_w); d.z_w = const_cast<int32_t*>(l->z_w);
+      d.colsum_w = const_cast<int32_t*>(l->colsum_w); d.bias_out = const_cast<float*>(l->bias);
+      d.workspace = ws + cp.o_gptq; d.workspace_bytes = cp.gptq_bytes;
+      return rq_gptq_quant_pack(ctx, &d);
+    }
     rq_wq_desc d;
     std::memset(&d, 0, sizeof d);
     d.N = N; d.K = K; d.bits = bw; d.format = wfmt; d.gate_up_rows = gate_rows; d.W = W; d.bias = b;
     d.w_out = const_cast<void*>(l->w); d.s_w = const_cast<float*>(l->s_w); d.z_w = const_cast<int32_t*>(l->z_w);
     d.colsum_w = const_cast<int32_t*>(l->colsum_w); d.bias_out = const_cast<float*>(l->bias);
-    l->N = N; l->K = K; l->bits = bw; l->format = wfmt;
     return rq_weight_quant_pack(ctx, &d);
   };
-  // LayerNorm activation: channel-wise (s, z) -> fold into the affine and the next Linear -> quantize that Linear
+  // LayerNorm activation: channel-wise (s, z) -> fold into the affine and the next Linear (left in wt / bt)
   auto fold_ln = [&](const float* xin, const float* gamma, const float* beta, const float* cu, const float* cl, const float* W,
-                     const float* b, int N, int gate_rows, float* gamma_t, float* beta_t, float* s_out, int32_t* z_out,
-                     rq_qlinear* lin) -> rq_status {
+                     const float* b, int N, float* gamma_t, float* beta_t, float* s_out, int32_t* z_out) -> rq_status {
     rq_status s2 = rq_ln_channel_minmax(ctx, xin, T, D, D, raw->norm_kind, raw->eps, gamma, beta, cmin, cmax);
     if (s2 != RQ_OK) return s2;
+    if (raw->learn_clip_iters > 0) {                       // Algorithm 1: learn the clip factors on this layer's X'
+      float* clip = reinterpret_cast<float*>(ws + cp.o_clip);
+      double* alpha = reinterpret_cast<double*>(ws + cp.o_alpha);
+      rq_dual_clip_desc dc;
+      std::memset(&dc, 0, sizeof dc);
+      dc.T = T; dc.D = D; dc.ldx = D; dc.x = xin; dc.norm_kind = raw->norm_kind; dc.eps = raw->eps; dc.gamma = gamma; dc.beta = beta;
+      dc.bits = ba; dc.iters = raw->learn_clip_iters; dc.lr = raw->learn_clip_lr; dc.alpha0 = raw->learn_clip_alpha0;
+      dc.alpha1 = alpha; dc.alpha2 = alpha + D; dc.clip_up = clip; dc.clip_lo = clip + D;
+      dc.workspace = ws + cp.o_learn; dc.workspace_bytes = rq_dual_clip_workspace_bytes(T);
+      if ((s2 = rq_dual_clip_learn(ctx, &dc)) != RQ_OK) return s2;
+      cu = clip; cl = clip + D;
+    }
     if ((s2 = rq_launch_channel_qparams(ctx, cmin, cmax, cu, cl, D, ba, s_ch, z_ch)) != RQ_OK) return s2;
     rq_fold_desc f;
     std::memset(&f, 0, sizeof f);
@@ -433,24 +474,24 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
     RQ_HIP(hipStreamSynchronize(ctx->stream));
     std::memcpy(s_out, h8, 4);
     std::memcpy(z_out, h8 + 4, 4);
-    return quant_linear(lin, wt, bt, N, D, gate_rows);
+    return RQ_OK;
   };
-  auto ln_q = [&](const float* xin, const float* gt, const float* btl, float s, int z, const rq_qlinear& next) -> rq_status {
+  auto ln_q = [&](const float* xin, const float* gt, const float* btl, float s, int z) -> rq_status {
     rq_ln_desc d;
     std::memset(&d, 0, sizeof d);
     d.T = T; d.D = D; d.norm_kind = raw->norm_kind; d.eps = raw->eps; d.x = xin; d.ldx = D; d.gamma_t = gt; d.beta_t = btl;
     d.s_tilde = s; d.z_tilde = z; d.bits = ba; d.store_off = rq_store_offset(ba, z); d.q = a; d.ldq = D;
-    d.rowsum = next.format == RQ_W_I8_CENTERED ? rowsum : nullptr;
+    d.rowsum = wfmt == RQ_W_I8_CENTERED ? rowsum : nullptr;
     return rq_ln_quant(ctx, &d);
   };
 
   // ---- LN1 -> QKV ----
-  if ((st = fold_ln(x, raw->ln1_gamma, raw->ln1_beta, raw->ln1_clip_up, raw->ln1_clip_lo, raw->w_qkv, raw->b_qkv, 3 * D, 0,
-                    const_cast<float*>(out->ln1_gamma_t), const_cast<float*>(out->ln1_beta_t), &out->ln1_s, &out->ln1_z,
-                    &out->qkv)) != RQ_OK)
+  if ((st = fold_ln(x, raw->ln1_gamma, raw->ln1_beta, raw->ln1_clip_up, raw->ln1_clip_lo, raw->w_qkv, raw->b_qkv, 3 * D,
+                    const_cast<float*>(out->ln1_gamma_t), const_cast<float*>(out->ln1_beta_t), &out->ln1_s, &out->ln1_z)) != RQ_OK)
     return st;
-  if ((st = ln_q(x, out->ln1_gamma_t, out->ln1_beta_t, out->ln1_s, out->ln1_z, out->qkv)) != RQ_OK) return st;
+  if ((st = ln_q(x, out->ln1_gamma_t, out->ln1_beta_t, out->ln1_s, out->ln1_z)) != RQ_OK) return st;
   const int off1 = rq_store_offset(ba, out->ln1_z);
+  if ((st = quant_linear(&out->qkv, wt, bt, 3 * D, D, 0, a, off1, out->ln1_z)) != RQ_OK) return st;
   rq_gemm_desc g;
   fill_linear(g, out->qkv, a, T, D, out->ln1_s, out->ln1_z, off1, rowsum);
   g.out_f32 = f32; g.ldf = 3 * D;
@@ -509,18 +550,19 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
     }
   }
   // ---- proj (plain channel-wise weight quantization), residual ----
-  if ((st = quant_linear(&out->proj, raw->w_proj, raw->b_proj, D, D, 0)) != RQ_OK) return st;
+  if ((st = quant_linear(&out->proj, raw->w_proj, raw->b_proj, D, D, 0, o, offo, out->z_o)) != RQ_OK) return st;
   if (out->proj.format == RQ_W_I8_CENTERED && (st = rq_rowsum_i8(ctx, o, T, D, D, rowsum)) != RQ_OK) return st;
   fill_linear(g, out->proj, o, T, D, out->s_o, out->z_o, offo, rowsum);
   g.residual = x; g.ldr = D; g.out_f32 = xbar; g.ldf = D;
   if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
   // ---- LN2 -> FC1 ----
   if ((st = fold_ln(xbar, raw->ln2_gamma, raw->ln2_beta, raw->ln2_clip_up, raw->ln2_clip_lo, raw->w_fc1, raw->b_fc1, n1,
-                    gated ? Dm : 0, const_cast<float*>(out->ln2_gamma_t), const_cast<float*>(out->ln2_beta_t), &out->ln2_s,
-                    &out->ln2_z, &out->fc1)) != RQ_OK)
+                    const_cast<float*>(out->ln2_gamma_t), const_cast<float*>(out->ln2_beta_t), &out->ln2_s, &out->ln2_z)) != RQ_OK)
     return st;
-  if ((st = ln_q(xbar, out->ln2_gamma_t, out->ln2_beta_t, out->ln2_s, out->ln2_z, out->fc1)) != RQ_OK) return st;
-  fill_linear(g, out->fc1, a, T, D, out->ln2_s, out->ln2_z, rq_store_offset(ba, out->ln2_z), rowsum);
+  if ((st = ln_q(xbar, out->ln2_gamma_t, out->ln2_beta_t, out->ln2_s, out->ln2_z)) != RQ_OK) return st;
+  const int off2 = rq_store_offset(ba, out->ln2_z);
+  if ((st = quant_linear(&out->fc1, wt, bt, n1, D, gated ? Dm : 0, a, off2, out->ln2_z)) != RQ_OK) return st;
+  fill_linear(g, out->fc1, a, T, D, out->ln2_s, out->ln2_z, off2, rowsum);
   g.act = raw->act; g.out_f32 = f32; g.ldf = Dm;
   if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
   {
@@ -528,8 +570,15 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
     if ((st = minmax_host(f32, T, Dm, Dm, &lo, &hi)) != RQ_OK) return st;
     qparams_from_minmax(lo, hi, ba, &out->s_h, &out->z_h);
   }
-  // ---- FC2 ----
-  return quant_linear(&out->fc2, raw->w_fc2, raw->b_fc2, D, Dm, 0);
+  // ---- FC2 (GPTQ wants the codes it is fed: FC1 once more, now quantized) ----
+  int8_t* hid = reinterpret_cast<int8_t*>(ws + pl.o_hid);
+  const int offh = rq_store_offset(ba, out->z_h);
+  if (raw->gptq) {
+    g.out_f32 = nullptr; g.out_q = hid; g.ldq = Dm; g.bits_o = ba; g.n_seg = 1; g.seg_len = Dm;
+    g.s_o[0] = out->s_h; g.z_o[0] = out->z_h; g.off_o[0] = offh;
+    if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
+  }
+  return quant_linear(&out->fc2, raw->w_fc2, raw->b_fc2, D, Dm, 0, hid, offh, out->z_h);
 }
 
 }  // extern "C"

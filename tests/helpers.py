@@ -120,3 +120,28 @@ def random_linear(g, N, K, bits):
     """Random weight codes with per-channel scale / zero-point, as an oracle linear dict."""
     return dict(codes=g.integers(0, 2 ** bits, size=(N, K)), s_w=g.uniform(1e-3, 5e-3, size=N).astype(np.float32),
                 z_w=g.integers(0, 2 ** bits, size=N), bias=g.normal(0, 0.5, size=N).astype(np.float32))
+
+
+def float_block(raw, cfg):
+    """The block without any quantization (float64): the reference that quantization error is measured against."""
+    from oracle import repquant_oracle as orc
+    X = raw["x"].astype(np.float64)
+    D, H, seq, batch = cfg.D, cfg.H, cfg.seq, cfg.batch
+    dh = D // H
+    f = lambda k: 0.0 if raw.get(k) is None else raw[k].astype(np.float64)
+    a = orc.layernorm(X, raw["ln1_gamma"].astype(np.float64), f("ln1_beta"), cfg.eps, cfg.norm)
+    qkv = a @ raw["w_qkv"].astype(np.float64).T + f("b_qkv")
+    out = np.empty_like(X)
+    for b in range(batch):
+        r = slice(b * seq, (b + 1) * seq)
+        for h in range(H):
+            L = qkv[r, h * dh:(h + 1) * dh] @ qkv[r, D + h * dh:D + (h + 1) * dh].T / np.sqrt(dh)
+            if raw.get("rel_bias") is not None:
+                L = L + raw["rel_bias"][h].astype(np.float64)
+            if cfg.mask == orc.MASK_CAUSAL:
+                L = np.where(np.tril(np.ones((seq, seq), dtype=bool)), L, -np.inf)
+            out[r, h * dh:(h + 1) * dh] = orc.softmax_rows(L) @ qkv[r, 2 * D + h * dh:2 * D + (h + 1) * dh]
+    xbar = out @ raw["w_proj"].astype(np.float64).T + f("b_proj") + X
+    a2 = orc.layernorm(xbar, raw["ln2_gamma"].astype(np.float64), f("ln2_beta"), cfg.eps, cfg.norm)
+    hid = orc.mlp_activation(a2 @ raw["w_fc1"].astype(np.float64).T + f("b_fc1"), cfg.act, cfg.Dm)
+    return hid @ raw["w_fc2"].astype(np.float64).T + f("b_fc2") + xbar

@@ -102,3 +102,51 @@ def test_block_calibrate_matches_oracle(rq, name):
     rel = np.abs(got - want_y).max() / np.abs(want_y).max()
     print("  calibrated-on-GPU block vs oracle block: max|d|/max|ref| = %.3g" % rel, flush=True)
     assert rel < 2e-2
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["swin_b_window_w6a6_b16", "llama_like_w4a8"])
+def test_block_calibrate_with_learnt_clipping_and_gptq(rq, name):
+    """Algorithm 1 with both learning steps on: the clip factors of the two LayerNorms learnt on the GPU and every
+    Linear quantized by GPTQ against the codes it is fed, against the oracle's calibration with the same options.
+    The first layer sees identical inputs on both sides, so its parameters must agree closely; later layers inherit
+    the occasional rounding-tie flip, so they are judged through the block they produce."""
+    b, ctx = rq
+    cfg = SMALL[name]
+    print("case", name, flush=True)
+    raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
+    learn = dict(iters=30, lr=0.01, alpha0=2.0)
+    P = orc.calibrate_block(raw, cfg_dict(cfg), learn_clip=learn, gptq=True)
+    x = dev(raw["x"])
+    blk = b.calibrate_block(ctx, cfg, _raw_to_device(raw), x, cfg.batch, cfg.seq, learn_clip=learn, gptq=True)
+    Q = blk.P
+    assert Q["ln1"]["z"] == P["ln1"]["z"]
+    assert abs(Q["ln1"]["s"] - float(P["ln1"]["s"])) <= 1e-6 * float(P["ln1"]["s"])
+    assert np.allclose(Q["ln1"]["gamma_t"].cpu().numpy(), P["ln1"]["gamma_t"], rtol=2e-6, atol=0)
+    from tests.helpers import lin_to_device
+    want = lin_to_device(P["qkv"], cfg.bits_w)
+    rows_off = (Q["qkv"]["w"].cpu().numpy() != want["w"].cpu().numpy()).any(axis=1).mean()
+    print("  QKV output channels with a differing code: %.4f" % rows_off, flush=True)
+    assert rows_off <= 0.01
+    assert np.allclose(Q["qkv"]["s_w"].cpu().numpy(), want["s_w"].cpu().numpy(), rtol=1e-6)
+    # the learning steps changed something: neither the clip factors nor the codes are the plain ones
+    P0 = orc.calibrate_block(raw, cfg_dict(cfg))
+    assert float(P0["ln1"]["s"]) != float(P["ln1"]["s"])
+    assert np.mean(P0["qkv"]["codes"] != P["qkv"]["codes"]) > 0.005
+    # Later layers: GPTQ is discontinuous in its inputs (one flipped activation code moves the Hessian, and with it
+    # codes all over the matrix), so the two calibrations are compared by what they achieve: the block's error against
+    # the unquantized block must be the same within a few per cent, and the two quantized blocks must stay close.
+    from tests.helpers import float_block
+    y_float = float_block(raw, cfg)
+    branch = np.linalg.norm(y_float - raw["x"].astype(np.float64))
+    want_y = orc.block_forward(P, raw["x"])
+    y = torch.zeros_like(x)
+    blk.forward(x, y, cfg.batch, cfg.seq)
+    got = y.cpu().numpy().astype(np.float64)
+    e_gpu, e_orc = np.linalg.norm(got - y_float) / branch, np.linalg.norm(want_y - y_float) / branch
+    e_rtn = np.linalg.norm(orc.block_forward(P0, raw["x"]) - y_float) / branch
+    between = np.linalg.norm(got - want_y) / branch
+    print("  error vs the float block: GPU-calibrated %.4f, oracle-calibrated %.4f, min/max + round-to-nearest %.4f; "
+          "GPU vs oracle block %.4f" % (e_gpu, e_orc, e_rtn, between), flush=True)
+    assert abs(e_gpu - e_orc) <= 0.1 * e_orc
+    assert between <= 0.5 * e_orc
