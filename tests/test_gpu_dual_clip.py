@@ -39,7 +39,7 @@ def _check(got, want, D):
 # T spans one wavefront, several workgroup shapes, rows held in registers and rows re-read every pass
 @pytest.mark.parametrize("T,D,bits,alpha0,iters", [
     (197, 24, 4, 4.0, 100), (1000, 40, 4, 0.0, 100), (3001, 16, 6, 1.0, 60), (50, 8, 8, 2.0, 30), (1, 8, 4, 4.0, 5),
-    (30000, 6, 4, 0.5, 25), (9000, 300, 4, 1.5, 20)])
+    (30000, 6, 4, 0.5, 25), (9000, 300, 4, 1.5, 20), (2, 3, 4, 1.0, 10), (64, 1, 16, 3.0, 10), (500, 5, 2, 0.0, 40)])
 def test_learner_matches_oracle_on_given_activations(rq, T, D, bits, alpha0, iters):
     b, ctx = rq
     print("case", T, D, bits, alpha0, iters, flush=True)

@@ -107,7 +107,8 @@ def test_ln_channel_minmax(rq, T, D, kind):
 
 
 @pytest.mark.parametrize("T,D,kind,q", [(333, 384, 0, (0.01, 0.99)), (1000, 128, 1, (0.001, 0.9999)), (50, 64, 0, (0.0, 1.0)),
-                                        (12608, 48, 0, (0.00001, 0.99999)), (7, 8, 0, (0.5, 0.5))])
+                                        (12608, 48, 0, (0.00001, 0.99999)), (7, 8, 0, (0.5, 0.5)), (1, 4, 0, (0.1, 0.9)),
+                                        (2, 4, 1, (0.3, 0.7))])
 def test_ln_channel_percentile(rq, T, D, kind, q):
     """Percentile calibration bounds (exact selection + linear interpolation) against numpy's definition."""
     b, ctx = rq
