@@ -461,7 +461,13 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
     for (int q = 0; q < TM * TN; ++q) {
       const int i = q / TN, j = q % TN;
       acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
-      if (W4) { if (q < 8) unpack_dword(fbn, 1, q); }
+      if (W4) {
+        if (TM * TN >= 8) { if (q < 8) unpack_dword(fbn, 1, q); }
+        else {     // fewer MFMAs than operand dwords: spread the 8 pieces over all of them
+#pragma unroll
+          for (int d = q * 8 / (TM * TN); d < (q + 1) * 8 / (TM * TN); ++d) unpack_dword(fbn, 1, d);
+        }
+      }
       else if (q < TN) fbn[q] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[q][W4 ? 0 : 1]);
       if (j == TN - 1) load_a(slot, 1, i);
       __builtin_amdgcn_sched_barrier(0);
@@ -488,6 +494,11 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
         if (W4) {     // the packet was requested before MFMA 0; unpack it behind the later MFMAs
           if (TM * TN >= 10) {
             if (q >= 2 && q < 10) unpack_dword(fb, 0, q - 2);
+          } else if (TM * TN < 8) {     // the 8 pieces behind the MFMAs after the second one
+            if (q >= 2) {
+#pragma unroll
+              for (int d = (q - 2) * 8 / (TM * TN - 2); d < (q - 1) * 8 / (TM * TN - 2); ++d) unpack_dword(fb, 0, d);
+            }
           } else {
             if (q >= 2 && q < 6) unpack_dword(fb, 0, q - 2);
             if (q >= 6) { unpack_dword(fb, 0, 4 + 2 * (q - 6)); unpack_dword(fb, 0, 5 + 2 * (q - 6)); }
@@ -553,16 +564,22 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   return RQ_OK;
 }
 
-// Tile height.  In units of the time one 256-row tile takes alone on a CU, two co-resident 256-row tiles take about 1.5
-// and a 320-row tile (which owns its CU) 1.25; pick what finishes the busiest CU first.
-inline bool prefer_tall(const rq_ctx* ctx, const GemmParams& p) {
-  if (p.force_tall) return true;
+// Tile height for the float + residual outputs.  In units of the time one 256-row tile takes alone on a CU, two co-resident
+// 256-row tiles take about 1.5, a 320-row tile (which owns its CU) 1.25 and two co-resident 192-row tiles 1.125; pick what
+// finishes the busiest CU first.  The 192-row tile only pays while the K loop is short (the epilogue's memory phase then
+// weighs as much as the loop and two smaller workgroups overlap it better); with a long loop it measures no faster.
+// Returns the number of 64-row groups per tile: 3, 4 or 5.
+inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
+  if (p.force_tall == 1) return 5;
+  if (p.force_tall == 2) return 3;
   const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   const int64_t tn = (p.N + 127) / 128;
-  const int64_t t256 = ((p.M + 255) / 256) * tn, t320 = ((p.M + 319) / 320) * tn;
+  const int64_t t192 = ((p.M + 191) / 192) * tn, t256 = ((p.M + 255) / 256) * tn, t320 = ((p.M + 319) / 320) * tn;
+  const double c192 = t192 <= cu ? 0.75 : 1.125 * (double)((t192 + 2 * cu - 1) / (2 * cu));
   const double c256 = t256 <= cu ? 1.0 : 1.5 * (double)((t256 + 2 * cu - 1) / (2 * cu));
   const double c320 = 1.25 * (double)((t320 + cu - 1) / cu);
-  return c320 < c256;
+  if (p.K <= 1024 && c192 < c256 && c192 < c320) return 3;
+  return c320 < c256 ? 5 : 4;
 }
 
 template <bool W4, int S, int ACT>
@@ -571,7 +588,9 @@ rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   if (q && !f && !r && !a) return launch_pipe_one<W4, S, ACT, OUT_Q, 4>(ctx, p);
   if (ACT == RQ_ACT_NONE && f && r && !q && !a) {
     constexpr int S_TALL = W4 ? 6 : 5;       // one workgroup per CU: the ring may take most of the LDS
-    if (prefer_tall(ctx, p)) return launch_pipe_one<W4, S_TALL, RQ_ACT_NONE, OUT_F32 | OUT_RES, 5>(ctx, p);
+    const int rows = pick_rows_f32(ctx, p);
+    if (rows == 3) return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 3>(ctx, p);
+    if (rows == 5) return launch_pipe_one<W4, S_TALL, RQ_ACT_NONE, OUT_F32 | OUT_RES, 5>(ctx, p);
     return launch_pipe_one<W4, S, ACT, OUT_F32 | OUT_RES, 4>(ctx, p);
   }
   return launch_pipe_one<W4, S, ACT, OUT_ANY, 4>(ctx, p);

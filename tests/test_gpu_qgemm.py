@@ -67,9 +67,10 @@ def test_accumulator_extremes(rq):
 
 
 @pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4)])
-@pytest.mark.parametrize("M,tile", [(515, 0), (515, 4), (963, 4), (320, 4)])
+@pytest.mark.parametrize("M,tile", [(515, 0), (515, 4), (963, 4), (320, 4), (515, 5), (192, 5), (770, 5)])
 def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
-    """tile 4 takes the 320-row tiles (one workgroup per CU) that large single-wave launches use."""
+    """tile 4 takes the 320-row tiles (one workgroup per CU) that large single-wave launches use, tile 5 the 192-row
+    tiles (two per CU) that launches with a short K loop use."""
     b, ctx = rq
     N, K = 384, 256
     print("case", bits_a, bits_w, M, tile, flush=True)
