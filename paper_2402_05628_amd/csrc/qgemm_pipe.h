@@ -240,8 +240,13 @@ template <int N> __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);   // vmcnt <= N, other counters unconstrained
 }
 
+// workgroups (= wavefronts per SIMD) a CU is meant to hold: bounds the registers the compiler may take
+constexpr int pipe_occupancy(int TM, int OUT) {
+  return TM <= 2 ? 4 : (TM == 3 ? (OUT == OUT_Q ? 3 : 2) : (TM == 4 ? 2 : 1));
+}
+
 template <bool W4, int S, int ACT, int OUT, int TM>
-__global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const GemmParams p) {
+__global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
   constexpr int BM = 64 * TM, BN = 128, TN = 2;       // TM = 4: 256 x 128 tiles, two workgroups per CU; TM = 5: 320 x 128, one
   constexpr int A_BYTES = BM * 64;
   constexpr int B_BYTES = W4 ? BN * 32 : BN * 64;
@@ -494,10 +499,11 @@ __global__ __launch_bounds__(256, TM <= 4 ? 2 : 1) void qgemm_pipe_kernel(const 
         if (W4) {     // the packet was requested before MFMA 0; unpack it behind the later MFMAs
           if (TM * TN >= 10) {
             if (q >= 2 && q < 10) unpack_dword(fb, 0, q - 2);
-          } else if (TM * TN < 8) {     // the 8 pieces behind the MFMAs after the second one
-            if (q >= 2) {
+          } else if (TM * TN < 8) {     // the 8 pieces behind the MFMAs after the second one (behind the last, if there are two)
+            constexpr int Q0 = TM * TN > 2 ? 2 : TM * TN - 1, NS = TM * TN - Q0;
+            if (q >= Q0) {
 #pragma unroll
-              for (int d = (q - 2) * 8 / (TM * TN - 2); d < (q - 1) * 8 / (TM * TN - 2); ++d) unpack_dword(fb, 0, d);
+              for (int d = (q - Q0) * 8 / NS; d < (q - Q0 + 1) * 8 / NS; ++d) unpack_dword(fb, 0, d);
             }
           } else {
             if (q >= 2 && q < 6) unpack_dword(fb, 0, q - 2);
@@ -551,8 +557,9 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   p.tiles_n = (p.N + 127) / 128;
   const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
   constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? 128 * 32 : 128 * 64));
-  static_assert(sizeof(EpiLds) <= 4096 && lds_bytes >= 4096 + 4 * 32 * 68 * 4 && lds_bytes <= 160 * 1024,
-                "the idle ring holds the epilogue constants and the row staging");
+  constexpr bool row_staging = OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE;
+  static_assert(sizeof(EpiLds) <= 4096 && lds_bytes >= 4096 + (row_staging ? 4 * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
+                "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static bool attr_set = false;
   if (!attr_set) {
     RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM>),
@@ -570,8 +577,7 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
 // weighs as much as the loop and two smaller workgroups overlap it better); with a long loop it measures no faster.
 // Returns the number of 64-row groups per tile: 3, 4 or 5.
 inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
-  if (p.force_tall == 1) return 5;
-  if (p.force_tall == 2) return 3;
+  if (p.force_rows >= 3 && p.force_rows <= 5) return p.force_rows;
   const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   const int64_t tn = (p.N + 127) / 128;
   const int64_t t192 = ((p.M + 191) / 192) * tn, t256 = ((p.M + 255) / 256) * tn, t320 = ((p.M + 319) / 320) * tn;
@@ -585,7 +591,15 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
 template <bool W4, int S, int ACT>
 rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
-  if (q && !f && !r && !a) return launch_pipe_one<W4, S, ACT, OUT_Q, 4>(ctx, p);
+  if (q && !f && !r && !a) {
+    // Re-quantized codes only (QKV, FC1).  With a short K loop the prologue and the epilogue weigh as much as the loop
+    // itself, and more, smaller workgroups per CU (three of 192 rows, four of 128 rows) overlap those phases better than
+    // two of 256 rows; with a long loop the large tile's operand reuse wins.  Measured on the four workloads' shapes.
+    const int rows = p.force_rows ? p.force_rows : (p.K <= 256 ? 2 : (p.K <= 1024 ? 3 : 4));
+    if (rows == 2) return launch_pipe_one<W4, 3, ACT, OUT_Q, 2>(ctx, p);
+    if (rows == 3) return launch_pipe_one<W4, 3, ACT, OUT_Q, 3>(ctx, p);
+    return launch_pipe_one<W4, S, ACT, OUT_Q, 4>(ctx, p);
+  }
   if (ACT == RQ_ACT_NONE && f && r && !q && !a) {
     constexpr int S_TALL = W4 ? 6 : 5;       // one workgroup per CU: the ring may take most of the LDS
     const int rows = pick_rows_f32(ctx, p);

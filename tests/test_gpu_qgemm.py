@@ -95,12 +95,23 @@ def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
 
 
 @pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
-@pytest.mark.parametrize("act", ["none3", "gelu", "gated", "gelu_q_only", "gated_q_only"])
-def test_requantized_output(rq, bits_a, bits_w, bits_o, act):
+@pytest.mark.parametrize("act,tile", [("none3", 0), ("gelu", 0), ("gated", 0), ("gelu_q_only", 0), ("gated_q_only", 0),
+                                      ("none3", 5), ("none3", 6), ("none3", 7), ("gelu_q_only", 5), ("gelu_q_only", 6),
+                                      ("gated_q_only", 5), ("gated_q_only", 6), ("gated_q_only", 7)])
+def test_requantized_output(rq, bits_a, bits_w, bits_o, act, tile):
+    """tile 5 / 6 / 7: the 192- / 128- / 256-row tiles of the kernel that writes re-quantized codes only."""
     b, ctx = rq
     q_only = act.endswith("_q_only")      # the block's launches: re-quantized codes are the only output
     act = act.replace("_q_only", "")
     M, K = 301, 256
+    b.set_gemm_tile(tile)
+    try:
+        _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act, q_only, M, K)
+    finally:
+        b.set_gemm_tile(0)
+
+
+def _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act, q_only, M, K):
     N = 384 if act != "gated" else 512
     g = np.random.default_rng(5 + bits_a + len(act))
     qa, z_a = _act_codes(g, M, K, bits_a)
