@@ -3,8 +3,8 @@
 //
 // The objective is a sum over channels and Adam updates every parameter on its own, so the D channels are D separate
 // two-parameter problems.  One workgroup owns one channel for the whole optimization: it reads its column of the
-// activation ONCE, keeps X' in registers as float64 (up to RPT rows per lane; rows beyond that are re-read and
-// re-normalized every pass), and runs all passes with two barriers each.  With u = x'/s, r = round(u), v = r + z,
+// activation ONCE, keeps X' as float64 (up to RPT rows per lane in registers, further rows in LDS; what still does not
+// fit is re-read and re-normalized every pass), and runs all passes with two barriers each.  With u = x'/s, r = round(u), v = r + z,
 // q = clip(v), d = q - z, e = s d - x' every pass takes three sums over the tokens,
 //   L = sum e^2,   G = sum_{v inside} e (r - u) + sum_{v clipped} e d,   Cout = sum_{v clipped} e,
 // which give the straight-through gradient (both roundings with derivative 1, the clip passing it on [0, qmax])
@@ -331,6 +331,13 @@ extern "C" rq_status rq_set_dual_clip_waves(int n) {
   return RQ_OK;
 }
 
+rq_status rq_launch_row_stats(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind, double eps,
+                              double* stats) {
+  hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, ctx->stream, x, T, D, ldx, norm_kind, eps, stats);
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}
+
 size_t rq_dual_clip_workspace_bytes(int64_t T) { return T > 0 ? (size_t)T * 2 * sizeof(double) : 0; }
 
 rq_status rq_launch_dual_clip(rq_ctx* ctx, const rq_dual_clip_desc* d) {
@@ -343,8 +350,8 @@ rq_status rq_launch_dual_clip(rq_ctx* ctx, const rq_dual_clip_desc* d) {
   p.loss0 = d->loss0; p.loss = d->loss; p.up = d->up; p.lo = d->lo;
   if (d->gamma) {
     double* stats = static_cast<double*>(d->workspace);
-    hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)((d->T + 3) / 4)), dim3(256), 0, ctx->stream, d->x, d->T, d->D, d->ldx,
-                       d->norm_kind, d->eps, stats);
+    const rq_status rc = rq_launch_row_stats(ctx, d->x, d->T, d->D, d->ldx, d->norm_kind, d->eps, stats);
+    if (rc != RQ_OK) return rc;
     p.stats = stats;
   }
   Shape sh = choose_shape(d->T, d->D, ctx->num_cu);

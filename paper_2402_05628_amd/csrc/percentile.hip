@@ -24,35 +24,6 @@ __device__ __forceinline__ double from_key(unsigned long long k) {
   return __longlong_as_double((long long)u);
 }
 
-__global__ __launch_bounds__(256) void row_stats2_kernel(const float* __restrict__ x, int64_t T, int D, int64_t ldx, int norm_kind,
-                                                         double eps, double* __restrict__ stats) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= T) return;
-  const float* xr = x + row * ldx;
-  double s1 = 0.0, s2 = 0.0;
-  for (int c = lane; c < D / 4; c += 64) {
-    const float4 v = *reinterpret_cast<const float4*>(xr + c * 4);
-    const double a = v.x, b = v.y, cc = v.z, dd = v.w;
-    s1 += (a + b) + (cc + dd);
-    s2 = fma(a, a, s2); s2 = fma(b, b, s2); s2 = fma(cc, cc, s2); s2 = fma(dd, dd, s2);
-  }
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) { s1 += __shfl_xor(s1, m, 64); s2 += __shfl_xor(s2, m, 64); }
-  double mean = 0.0, var;
-  if (norm_kind == RQ_NORM_LAYERNORM) {
-    mean = s1 / (double)D;
-    var = fma(-mean, mean, s2 / (double)D);
-    var = var < 0.0 ? 0.0 : var;
-  } else {
-    var = s2 / (double)D;
-  }
-  if (lane == 0) {
-    stats[2 * row] = mean;
-    stats[2 * row + 1] = 1.0 / sqrt(var + eps);
-  }
-}
-
 __global__ __launch_bounds__(512) void channel_percentile_kernel(const float* __restrict__ x, int64_t T, int D, int64_t ldx,
                                                                  const double* __restrict__ stats, const float* __restrict__ gamma,
                                                                  const float* __restrict__ beta, double q_lo, double q_hi,
@@ -125,7 +96,8 @@ rq_status rq_launch_ln_channel_percentile(rq_ctx* ctx, const float* x, int64_t T
   double* stats = nullptr;
   if (gamma) {
     stats = static_cast<double*>(workspace);
-    hipLaunchKernelGGL(row_stats2_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, ctx->stream, x, T, D, ldx, norm_kind, eps, stats);
+    const rq_status rc = rq_launch_row_stats(ctx, x, T, D, ldx, norm_kind, eps, stats);      // mean and 1 / sqrt(var + eps) per row
+    if (rc != RQ_OK) return rc;
   }
   hipLaunchKernelGGL(channel_percentile_kernel, dim3((unsigned)D), dim3(512), 0, ctx->stream, x, T, D, ldx, stats, gamma, beta, q_lo,
                      q_hi, lo, hi);

@@ -69,6 +69,9 @@ rq_status rq_launch_minmax_f32(rq_ctx* ctx, const float* v, int64_t rows, int64_
 rq_status rq_launch_channel_qparams(rq_ctx* ctx, const double* cmin, const double* cmax, const float* clip_up,
                                     const float* clip_lo, int D, int bits, float* s_ch, int32_t* z_ch);
 
+// mean and 1 / sqrt(var + eps) of every row, float64, interleaved: stats[2 * row], stats[2 * row + 1]
+rq_status rq_launch_row_stats(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind, double eps,
+                              double* stats);
 rq_status rq_launch_ln_channel_percentile(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind,
                                           double eps, const float* gamma, const float* beta, double q_lo, double q_hi,
                                           double* lo, double* hi, void* workspace);
