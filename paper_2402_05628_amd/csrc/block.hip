@@ -164,7 +164,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   // ---- attention, chunked over batch items -----------------------------------------------------------------
   const int offo = rq_store_offset(ba, p->z_o);
   const bool fused = use_fused(p, seq);
-  const bool whole = g_attn_fused == 1 && !p->rel_bias && p->mask == RQ_MASK_NONE && rq_attn_fused_supported((int)seq, dh, p->bits_p);
+  const bool whole = g_attn_fused == 1 && !p->rel_bias && p->mask == RQ_MASK_NONE && rq_attn_fused_preferred((int)seq, dh, p->bits_p);
   for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
     const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
     const int8_t* qkv_c = qkv + b0 * seq * 3 * D;

@@ -52,6 +52,12 @@ constexpr unsigned QKS_TAB_LO = 0xF0E0C080u, QKS_TAB_HI = 0xFFFEFCF8u;
 // PV: the codes of a key tile go straight on as the column operand of the P.V product (after the two lane swaps a lane
 // owns 16 consecutive keys of its query row, which is that operand's layout); V^T is staged in LDS next to the keys;
 // even and odd codes accumulate separately and exactly in int32, as in rq_attn_pv (codes of at most 4 bits: one window).
+// Registers per lane: the accumulators of Q.K^T (16 per key tile) and the even and odd accumulators of P.V (32 per 32
+// channels).  While both fit, every key tile's codes go straight into its P.V products; beyond that the codes of all tiles
+// are packed first (4 registers per tile, the Q.K^T accumulators die as they are converted) and P.V runs afterwards.
+constexpr bool fused_pv_fits(int ksteps, int nt) { return nt * 16 + ksteps * 32 <= 176; }
+constexpr bool fused_pv_supported(int ksteps, int nt) { return fused_pv_fits(ksteps, nt) || (nt * 16 <= 176 && nt * 4 + ksteps * 32 <= 176); }
+
 template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, bool PV>
 __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   constexpr int DH = KSTEPS * 32;
@@ -161,7 +167,13 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
   for (int s = 0; s < KSTEPS; ++s) fq0[s] = qreg[s];
   __syncthreads();
-  if (gq + (int)gridDim.x * GPB < Gi) request(gq + (int)gridDim.x * GPB);
+  // The next pass's operands are requested into registers ahead of time.  Where the Q.K^T accumulators and the P.V ones
+  // do not fit together (LATE), the request waits until this wavefront's last query tile has turned its accumulators into
+  // packed codes, so that its registers are not live while the accumulators are.
+  constexpr bool LATE = PV && !fused_pv_fits(KSTEPS, NT);
+  const bool more = gq + (int)gridDim.x * GPB < Gi;
+  bool requested = false;
+  if (!LATE && more) { request(gq + (int)gridDim.x * GPB); requested = true; }
 
   for (int it = it0; group_live && it < nt; it += (GPB > 1 ? nt : 8)) {       // wavefront-uniform
     const int qi = it * 32 + l32;
@@ -272,9 +284,43 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const float C0f = (float)C0, m2cf = (float)m2c;
     // ---- codes (and, fused, their product with V) ----
     uint8_t* crow = p.codes ? p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld : nullptr;
+    constexpr bool SPLIT = PV && !fused_pv_fits(KSTEPS, NT);      // P.V after all codes, from packed codes
     v16i E[PV ? TC : 1], O[PV ? TC : 1];
+    v4i tvs[SPLIT ? NT : 1];
     int se = 0, so = 0;
-    if (PV) {
+    // the P.V products of one key tile from its 16 codes per lane
+    auto pv_tile = [&](int jt, const v4i& tv) {
+      const int j0 = jt * 32 + half * 16;
+      v4i pe, po;
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4) {
+        const unsigned c = (unsigned)tv[d4];
+        unsigned pall = __builtin_amdgcn_perm(QKS_TAB_HI, QKS_TAB_LO, (c >> 1) & 0x07070707u);
+        if (MASKALL || jt == NT - 1) {      // masked and padding keys contribute nothing, whatever their code
+          int nv = limit - (j0 + d4 * 4);
+          nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+          pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
+        }
+        const unsigned lsb = c & 0x01010101u;
+        const unsigned odd = (lsb << 8) - lsb;        // 0xFF in the bytes that hold odd codes
+        po[d4] = (int)(pall & odd);
+        pe[d4] = (int)(pall & ~odd);
+      }
+      if (p.dv != 0) {
+#pragma unroll
+        for (int d4 = 0; d4 < 4; ++d4) {
+          se = __builtin_amdgcn_sdot4(pe[d4], 0x01010101, se, false);
+          so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < TC; ++c) {
+        const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
+        E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
+        O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
+      }
+    };
+    if (PV && !SPLIT) {
 #pragma unroll
       for (int c = 0; c < TC; ++c)
 #pragma unroll
@@ -314,37 +360,19 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         const int j0 = jt * 32 + half * 16;
         const v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
         if (crow && qi < p.N && j0 < p.ld) *reinterpret_cast<v4i*>(crow + j0) = tv;
-        if (PV) {
-          v4i pe, po;
-#pragma unroll
-          for (int d4 = 0; d4 < 4; ++d4) {
-            const unsigned c = (unsigned)tv[d4];
-            unsigned pall = __builtin_amdgcn_perm(QKS_TAB_HI, QKS_TAB_LO, (c >> 1) & 0x07070707u);
-            if (MASKALL || jt == NT - 1) {      // masked and padding keys contribute nothing, whatever their code
-              int nv = limit - (j0 + d4 * 4);
-              nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
-              pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
-            }
-            const unsigned lsb = c & 0x01010101u;
-            const unsigned odd = (lsb << 8) - lsb;        // 0xFF in the bytes that hold odd codes
-            po[d4] = (int)(pall & odd);
-            pe[d4] = (int)(pall & ~odd);
-          }
-          if (p.dv != 0) {
-#pragma unroll
-            for (int d4 = 0; d4 < 4; ++d4) {
-              se = __builtin_amdgcn_sdot4(pe[d4], 0x01010101, se, false);
-              so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
-            }
-          }
-#pragma unroll
-          for (int c = 0; c < TC; ++c) {
-            const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
-            E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
-            O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
-          }
-        }
+        if (SPLIT) tvs[jt] = tv;
+        else if (PV) pv_tile(jt, tv);
       }
+    }
+    if (SPLIT) {
+      if (more && !requested && it + (GPB > 1 ? nt : 8) >= nt) { request(gq + (int)gridDim.x * GPB); requested = true; }
+#pragma unroll
+      for (int c = 0; c < TC; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt)
+        if (jt < nt) pv_tile(jt, tvs[jt]);
     }
     if (PV) {
       double psE = (double)se, psO = (double)so;
@@ -381,12 +409,10 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
       }
     }
   }
+  if (more && !requested) request(gq + (int)gridDim.x * GPB);      // wavefronts without a query tile in this pass
   __syncthreads();      // every wavefront is done with this group's keys
   }
 }
-
-// accumulators of Q.K^T (16 per key tile) plus the even and odd accumulators of P.V (32 per 32 channels) per lane
-constexpr bool fused_pv_fits(int ksteps, int nt) { return nt * 16 + ksteps * 32 <= 176; }
 
 template <int KSTEPS, int NT>
 rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
@@ -410,7 +436,7 @@ rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
   } while (0)
   // the float64 code path also serves every masked or biased case; the lean variant is the common one
   if (pv) {
-    if constexpr (fused_pv_fits(KSTEPS, NT)) RQ_QKS_LAUNCH(false, false, false, true);
+    if constexpr (fused_pv_supported(KSTEPS, NT)) RQ_QKS_LAUNCH(false, false, false, true);
     else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %d key tiles at d_head = %d do not fit the registers", NT, KSTEPS * 32);
   } else if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true, false);
   else if (p.bias) RQ_QKS_LAUNCH(true, true, false, false);

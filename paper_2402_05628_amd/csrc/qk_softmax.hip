@@ -9,7 +9,16 @@ rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64
 
 extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p) {
   if (N <= 0 || N > 288 || bits_p < 2 || bits_p > 4 || !(d_head == 32 || d_head == 64 || d_head == 128)) return 0;
-  return rqks::fused_pv_fits(d_head / 32, (N + 31) / 32) ? 1 : 0;
+  return rqks::fused_pv_supported(d_head / 32, (N + 31) / 32) ? 1 : 0;
+}
+
+// Where the one-kernel attention is also the faster choice: the variants that hold everything in registers.  The
+// nine-tile ones (257 .. 288 keys) and most 128-wide heads compile with register spills and measure slower than
+// rq_qk_softmax_log2_quant + rq_attn_pv (257 keys, d_head 64: 0.49 ms against 0.34 ms at 2048 groups).
+bool rq_attn_fused_preferred(int N, int d_head, int bits_p) {
+  if (!rq_attn_fused_supported(N, d_head, bits_p)) return false;
+  const int ks = d_head / 32, nt = (N + 31) / 32;
+  return rqks::fused_pv_fits(ks, nt) || (ks <= 2 && nt <= 8);
 }
 
 rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {

@@ -173,7 +173,8 @@ def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causa
 
 @pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p", [(2, 3, 197, 64, 4, 4), (3, 2, 49, 32, 6, 4), (1, 2, 224, 64, 4, 4),
                                                         (2, 2, 64, 128, 8, 4), (1, 1, 1, 32, 8, 3), (2, 1, 288, 32, 4, 4),
-                                                        (5, 2, 100, 64, 8, 2)])
+                                                        (5, 2, 100, 64, 8, 2), (2, 2, 257, 64, 4, 4), (1, 3, 256, 64, 8, 4),
+                                                        (2, 1, 288, 64, 4, 4), (1, 2, 160, 128, 4, 4), (1, 2, 288, 128, 8, 4)])
 def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     """rq_attn_fused (one kernel) against the oracle's logits -> log-sqrt2 codes -> shift de-quantized P.V -> uniform codes."""
     b, ctx = rq
@@ -215,8 +216,10 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
                     codes=outc, ld=ld, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
     got_codes = outc.cpu().numpy()[:, :, :seq]
     frac = assert_codes_close(got_codes, want_codes, "fused attention codes")
+    # float32 epilogue on exact integer sums: the even- and odd-code terms can cancel, so an element far below the row's
+    # scale carries the rounding of the larger terms (6e-8 of them) -- hence 1e-4 element-wise, not 1e-5
     if frac == 0.0:      # identical codes -> the P.V sums are the same exact integers: only float rounding differs
-        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-5)
+        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-4)
         assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits), "fused attention out codes")
     else:                # a tie flipped a code: compare P.V against the oracle's P.V of the codes the kernel produced
         for bi in range(batch):
@@ -225,7 +228,7 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
                 c = slice(h * dh, (h + 1) * dh)
                 want[r, c] = orc.attn_pv(got_codes[bi * H + h].astype(np.int64), codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log,
                                          s_v, z[2], False)
-        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-5)
+        assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-4)
     # without the optional codes output the result is the same
     outq2 = torch.zeros_like(outq)
     b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
