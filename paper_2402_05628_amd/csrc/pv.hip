@@ -160,6 +160,15 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
     if (jb >= nk_wave) continue;
     int jend = nk_wave - jb;
     jend = jend < JB ? jend : JB;
+    // WIDE: this lane's codes of the whole block, requested together and once for all windows
+    v4i cws[WIDE ? JB / 32 : 1];
+    if (WIDE) {
+#pragma unroll
+      for (int t = 0; t < JB / 32; ++t) {
+        const int j0 = jb + t * 32 + half * 16;
+        cws[t] = (t * 32 < jend && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
+      }
+    }
     for (int w = 0; w < (WIDE ? WINDOWS : 1); ++w) {
       if (WIDE && !((present >> w) & 1u)) continue;
       if (WIDE) {
@@ -170,9 +179,9 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
         se = 0; so = 0;
       }
       const unsigned wref = (unsigned)w * 0x01010101u;
-      for (int js = 0; js < jend; js += 32) {
+      // one key tile: its 16 codes per lane -> even / odd operands of this window -> the P.V products
+      auto key_tile = [&](int js, const v4i& cw) {
         const int j0 = jb + js + half * 16;
-        const v4i cw = j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
         v4i pe, po;
 #pragma unroll
         for (int d4 = 0; d4 < 4; ++d4) {
@@ -203,6 +212,16 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
           const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VT_PITCH + js + half * 16);
           E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
           O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
+        }
+      };
+      if (WIDE) {
+#pragma unroll
+        for (int t = 0; t < JB / 32; ++t)
+          if (t * 32 < jend) key_tile(t * 32, cws[t]);
+      } else {
+        for (int js = 0; js < jend; js += 32) {
+          const int j0 = jb + js + half * 16;
+          key_tile(js, j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0});
         }
       }
       if (WIDE) {
