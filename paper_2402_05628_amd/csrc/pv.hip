@@ -37,6 +37,7 @@ struct PvParams {
   double inv_so;
   int zo, lo, hi;      // z_o - off_o, clamp bounds of the stored code
   int tiles_i;
+  int num_cu;          // causal: every second round of workgroups walks its group's query tiles backwards
 };
 
 constexpr int JB = 256;          // keys staged per LDS block
@@ -61,7 +62,11 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
   const int l32 = lane & 31, half = lane >> 5;
   const int blocks_per_group = (p.tiles_i + 3) / 4;
   const int64_t g = blockIdx.x / blocks_per_group;
-  const int it = (blockIdx.x % blocks_per_group) * 4 + wave;
+  // With a causal mask the work of a workgroup grows with its query tile.  Workgroups b and b + (number of CUs) tend to
+  // share a CU, so every second round takes the tiles of its groups in reverse: a long one then sits next to a short one.
+  int blk = blockIdx.x % blocks_per_group;
+  if (p.causal && ((blockIdx.x / (unsigned)p.num_cu) & 1u)) blk = blocks_per_group - 1 - blk;
+  const int it = blk * 4 + wave;
   const bool wave_live = it < p.tiles_i;
   const int64_t b = g / p.H;
   const int h = (int)(g % p.H);
@@ -72,7 +77,7 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
   const uint8_t* crow = Cg + (int64_t)qi_ld * p.ld;
   const int limit = p.causal ? (qi_ld + 1 < p.Nk ? qi_ld + 1 : p.Nk) : p.Nk;
   // keys this workgroup needs: up to the last row of its last tile when causal
-  int blk_rows_end = ((blockIdx.x % blocks_per_group) * 4 + 4) * 32;
+  int blk_rows_end = (blk * 4 + 4) * 32;
   blk_rows_end = blk_rows_end < p.Nq ? blk_rows_end : p.Nq;
   const int nk_block = p.causal ? (blk_rows_end < p.Nk ? blk_rows_end : p.Nk) : p.Nk;
   int wave_rows_end = (it + 1) * 32;
@@ -304,6 +309,7 @@ rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   p.inv_so = d->out_q ? 1.0 / (double)d->s_o : 0.0;
   p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
   p.tiles_i = (d->Nq + 31) / 32;
+  p.num_cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   const bool wide = d->bits_p > 4;
   const int64_t groups = d->batch * d->H;
   switch (d->d_head) {
