@@ -253,12 +253,15 @@ rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d);
 
 /* ---- rq_qk_softmax_log2_quant -----------------------------------------------------------------------
  * rq_qgemm in activation mode (exact int32 Q.K^T of the stored Q and K codes, attention Eq. of Section
- * "Transformer blocks") and rq_softmax_log2_quant (Eq. (3.3-1), second line) in ONE kernel for rows of at
- * most 288 keys: the accumulators of a 32-query tile against all keys stay in registers, so the logits are
- * never written.  Same integers and same code arithmetic as the two separate calls.
+ * "Transformer blocks") and rq_softmax_log2_quant (Eq. (3.3-1), second line) in ONE kernel: the logits are
+ * never written.  Same integers and same code arithmetic as the two separate calls.  Rows of at most 288
+ * keys keep the accumulators of a 32-query tile against all keys in registers.  Longer rows (up to 65536
+ * keys, bias == NULL only) form the accumulators twice: a first sweep over the keys keeps a running integer
+ * maximum and a running float32 sum per row, a second sweep emits the codes; only the order in which the
+ * sum is accumulated differs from the separate calls.
  * Q, K: token-major device int8 (row b*N + i, column h*d_head + c, row pitch ld_tok bytes), stored as
  * code - off.  codes: [batch*H, N, ld] device, ld % 16 == 0, 16-byte aligned; positions N..ld-1 and masked
- * keys receive the largest code.  d_head in {32, 64, 128}; RQ_ERR_SHAPE if N > 288.
+ * keys receive the largest code.  d_head in {32, 64, 128}; RQ_ERR_SHAPE if N > 288 with a bias, or N > 65536.
  */
 typedef struct {
   int64_t batch;
@@ -462,9 +465,10 @@ typedef struct {
 rq_status rq_set_attn_chunk_bytes(int64_t bytes);
 /* How rq_block_forward runs attention (process-wide; call before rq_block_workspace_bytes):
  *   1 (default): rq_attn_fused where it applies (no bias, no mask, codes of at most 4 bits, short rows), else as 2;
- *   2: rq_qk_softmax_log2_quant + rq_attn_pv for rows of up to 288 keys, else as 0;
+ *   2: rq_qk_softmax_log2_quant + rq_attn_pv wherever that call applies, else as 0;
  *   0: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length.
- * All three compute the same integers and the same codes. */
+ * All three compute the same integers and the same codes (rows beyond 288 keys in mode 2: up to the order in which the
+ * float32 row sum is accumulated). */
 rq_status rq_set_attn_fused(int on);
 /* 1: rq_block_forward takes rq_qgemm_ln_quant for the output projection + second LayerNorm where it applies
  * (process-wide); 0 (default): rq_qgemm followed by rq_ln_quant.  Both give the same float32 residual stream and the

@@ -353,7 +353,7 @@ def rq_softmax_log2_quant(ctx, acc, G, H, Nq, Nk, ld, logit_scale, codes, bits, 
 
 def rq_qk_softmax_log2_quant(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_off, z_q, k_off, z_k, logit_scale, codes, ld,
                              bits, s_log=1.0, bias=None, mask=MASK_NONE):
-    """Fused Q.K^T + Softmax-log2 codes from a token-major int8 tensor (rows of at most 288 keys)."""
+    """Fused Q.K^T + Softmax-log2 codes from a token-major int8 tensor (rows beyond 288 keys: without a bias only)."""
     base = qkv.data_ptr()
     d = QkSoftmaxDesc(batch=batch, H=H, N=seq, d_head=d_head, Q=base + q_col, K=base + k_col, ld_tok=qkv.stride(0),
                       q_off=q_off, z_q=z_q, k_off=k_off, z_k=z_k, logit_scale=logit_scale, bias=_p(bias), mask=mask,

@@ -22,7 +22,7 @@ int g_attn_fused = 1;
 int g_proj_ln_fused = 0;
 
 bool use_fused(const rq_block_params* p, int64_t seq) {
-  return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H);
+  return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H, p->rel_bias != nullptr);
 }
 
 Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {

@@ -5,6 +5,7 @@ using rqks::QksParams;
 rq_status rq_launch_qk_softmax_d32(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 rq_status rq_launch_qk_softmax_d64(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
+rq_status rq_launch_qk_softmax_long(rq_ctx* ctx, const rqks::QksParams& p, int d_head);
 
 
 extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p) {
@@ -41,7 +42,11 @@ rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   return rq_launch_qk_softmax_d128(ctx, p, p.G);
 }
 
-bool rq_qk_softmax_supported(int N, int d_head) { return N <= 288 && (d_head == 32 || d_head == 64 || d_head == 128); }
+// Rows of up to 288 keys keep their logits in registers; longer rows form them twice, which is implemented without an
+// additive bias only.
+bool rq_qk_softmax_supported(int N, int d_head, bool has_bias) {
+  return (N <= 288 || (!has_bias && N <= 65536)) && (d_head == 32 || d_head == 64 || d_head == 128);
+}
 
 // Q, K: token-major int8 (row b*N + i, column h*d_head + c), stored code - off.  codes: [batch*H, N, ld].
 rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, int64_t ld_tok, int64_t batch, int H, int N,
@@ -56,6 +61,10 @@ rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, in
   const int64_t groups = batch * H;
   p.G = groups;
   const int ks = d_head / 32;
+  if (N > 288) {
+    if (bias) return rq_fail(ctx, RQ_ERR_SHAPE, "fused Q.K^T + softmax: rows of %d keys with a bias are not supported", N);
+    return rq_launch_qk_softmax_long(ctx, p, d_head);
+  }
   if (ks == 1) return rq_launch_qk_softmax_d32(ctx, p, groups);
   if (ks == 2) return rq_launch_qk_softmax_d64(ctx, p, groups);
   if (ks == 4) return rq_launch_qk_softmax_d128(ctx, p, groups);

@@ -339,8 +339,9 @@ rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d) {
              (long long)d->batch, d->H, d->N);
   RQ_REQUIRE(d->d_head == 32 || d->d_head == 64 || d->d_head == 128, RQ_ERR_SHAPE,
              "rq_qk_softmax_log2_quant: d_head = %d must be 32, 64 or 128", d->d_head);
-  RQ_REQUIRE(rq_qk_softmax_supported(d->N, d->d_head), RQ_ERR_SHAPE,
-             "rq_qk_softmax_log2_quant: N = %d exceeds 288; use rq_qgemm + rq_softmax_log2_quant", d->N);
+  RQ_REQUIRE(rq_qk_softmax_supported(d->N, d->d_head, d->bias != nullptr), RQ_ERR_SHAPE,
+             "rq_qk_softmax_log2_quant: N = %d exceeds %s; use rq_qgemm + rq_softmax_log2_quant", d->N,
+             d->bias ? "288 (rows with a bias)" : "65536");
   RQ_REQUIRE(d->ld_tok >= (int64_t)d->H * d->d_head && d->ld_tok % 16 == 0, RQ_ERR_SHAPE,
              "rq_qk_softmax_log2_quant: ld_tok = %lld must be >= H*d_head and a multiple of 16", (long long)d->ld_tok);
   RQ_REQUIRE(rq_aligned(d->Q, 16) && rq_aligned(d->K, 16) && rq_aligned(d->codes, 16), RQ_ERR_INVALID_ARG,

@@ -252,20 +252,24 @@ def test_softmax_and_pv_validation(b, host_ctx):
     qd = dict(batch=1, H=2, N=8, d_head=32, Q=FAKE, K=FAKE, ld_tok=192, q_off=3, z_q=3, k_off=3, z_k=3, logit_scale=0.1, bias=None,
               mask=0, s_log=1.0, bits=4, codes=FAKE, ld=16)
     assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(b.QkSoftmaxDesc(**qd))) == 3
-    for k, v, want in (("N", 300, 2), ("d_head", 48, 2), ("ld", 8, 2), ("bits", 0, 1), ("Q", None, 1), ("ld_tok", 40, 2)):
+    for k, v, want in (("N", 70000, 2), ("d_head", 48, 2), ("ld", 8, 2), ("bits", 0, 1), ("Q", None, 1), ("ld_tok", 40, 2)):
         bad = b.QkSoftmaxDesc(**{**qd, k: v})
         assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(bad)) == want, (k, v)
+    # rows beyond 288 keys: accepted without a bias, refused with one
+    long_row = {**qd, "N": 300, "ld": 304}
+    assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(b.QkSoftmaxDesc(**long_row))) == 3
+    assert b.lib.rq_qk_softmax_log2_quant(host_ctx.handle, C.byref(b.QkSoftmaxDesc(**{**long_row, "bias": FAKE}))) == 2
 
 
 def test_attn_fused_validation(b, host_ctx):
     fd = dict(batch=1, H=2, N=64, d_head=64, Q=FAKE, K=FAKE, V=FAKE, ld_tok=384, q_off=3, z_q=3, k_off=3, z_k=3, v_off=3, z_v=3,
               logit_scale=0.1, s_log=1.0, s_v=0.1, bits_p=4, codes=None, ld=0, out_f32=FAKE, ldf=128)
     assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**fd))) == 3
-    for k, v, want in (("N", 256, 2), ("bits_p", 6, 2), ("d_head", 48, 2), ("V", None, 1), ("out_f32", None, 1), ("s_v", 0.0, 1),
+    for k, v, want in (("N", 320, 2), ("bits_p", 6, 2), ("d_head", 48, 2), ("V", None, 1), ("out_f32", None, 1), ("s_v", 0.0, 1),
                        ("ld_tok", 100, 2), ("ldf", 64, 2)):
         assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**{**fd, k: v}))) == want, (k, v)
-    assert b.attn_fused_supported(197, 64, 4) and not b.attn_fused_supported(257, 64, 4) and not b.attn_fused_supported(197, 64, 6)
-    assert b.attn_fused_supported(288, 32, 4) and not b.attn_fused_supported(128, 128, 4) and b.attn_fused_supported(96, 128, 4)
+    assert b.attn_fused_supported(197, 64, 4) and b.attn_fused_supported(257, 64, 4) and not b.attn_fused_supported(197, 64, 6)
+    assert b.attn_fused_supported(288, 128, 4) and not b.attn_fused_supported(289, 32, 4) and b.attn_fused_supported(96, 128, 4)
 
 
 def test_fold_and_weight_pack_validation(b, host_ctx):

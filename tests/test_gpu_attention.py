@@ -128,7 +128,11 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
 @pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p,bias,causal", [(2, 3, 197, 64, 4, 4, False, False), (3, 2, 49, 32, 6, 6, True, False),
                                                                     (2, 2, 257, 64, 4, 4, False, False), (1, 2, 288, 128, 8, 8, False, True),
                                                                     (2, 2, 64, 64, 8, 8, False, False), (1, 1, 1, 32, 8, 4, False, False),
-                                                                    (1, 2, 33, 64, 8, 6, True, True), (2, 1, 130, 128, 6, 4, False, False)])
+                                                                    (1, 2, 33, 64, 8, 6, True, True), (2, 1, 130, 128, 6, 4, False, False),
+                                                                    # rows beyond 288 keys: the two-sweep kernel
+                                                                    (1, 2, 289, 64, 4, 4, False, False), (2, 1, 320, 128, 8, 8, False, True),
+                                                                    (1, 3, 500, 32, 6, 6, False, True), (1, 1, 1000, 64, 8, 4, False, False),
+                                                                    (1, 2, 1025, 128, 8, 8, False, True), (2, 2, 384, 64, 4, 3, False, True)])
 def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causal):
     """The single-kernel Q.K^T + Softmax-log2 path against the oracle's integer logits and log-sqrt2 codes."""
     b, ctx = rq
