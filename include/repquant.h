@@ -316,8 +316,12 @@ int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p);
  * The power of two is applied as an integer shift: each probability becomes -(128 >> k) in int8
  * (k = code >> 1 within a window of 8 shifts), the two parities accumulate separately in exact int32
  * on the matrix cores, and the two sums are combined once per output with s_log and s_log/sqrt2.
+ * Codes wider than 4 bits span several windows: rows of up to 256 keys visit them one at a time (each window's exact
+ * integer sum rounded once to float32); longer rows hand the powers of two (exact in bfloat16 whatever the shift) and
+ * code - z_v (exact in bfloat16) to the bfloat16 matrix cores and accumulate in float32.
  * codes [batch*H, Nq, ld]; V is token-major int8 (row b*Nk + j, column h*d_head + c) stored code - v_off.
- * Outputs are token-major [batch*Nq, H*d_head].  d_head in {32, 64, 128}; ld % 16 == 0, codes 16-byte aligned.
+ * Outputs are token-major [batch*Nq, H*d_head].  d_head in {32, 64, 128}; ld % 16 == 0, ldv % 16 == 0, codes and V
+ * 16-byte aligned (whole 16-byte pieces of the key rows are read).
  */
 typedef struct {
   int64_t batch;

@@ -11,7 +11,8 @@
 // the row's smallest shift (whose power of two multiplies the finished row), the windows of 8 relative shifts are
 // visited one at a time, only if present, each contributing 2^(-8 w) times its exact integer sum, and relative shifts
 // of 40 or more (below 2^-40 of the row's largest probability) are dropped.
-// V^T is staged per 256 keys in LDS (transposed on the way in) as the ROW operand; the codes go straight from
+// (Rows of more than 256 keys with such codes take pv_long_kernel below instead: powers of two as bfloat16, one pass.)
+// V^T is staged per 256 keys in LDS (whole key rows read, bytes transposed in registers) as the ROW operand; the codes go straight from
 // global memory into the COLUMN operand (each lane owns 16 consecutive keys of one query row), so a lane ends up
 // with 4 consecutive channels of one token.
 #include "rq_internal.h"
@@ -54,10 +55,14 @@ __device__ __forceinline__ unsigned byte_eq_mask(unsigned x, unsigned ref4) {
   return (z >> 7) * 0xFFu;
 }
 
+// WIDE: codes wider than 4 bits (several windows); rows of more than 256 keys with such codes go to pv_long_kernel.
 template <int DH, bool WIDE>
 __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
   constexpr int TC = DH / 32;
-  __shared__ __align__(16) int8_t vt[DH * VT_PITCH];
+  constexpr int CP = DH / 16;          // 16-byte pieces per key row
+  // V^T: channel r at byte r * VT_PITCH + (r / 16) * 16 -- the extra 16 bytes per 16 channels spread the transposing
+  // writes of a wavefront (8 pieces of a key row side by side) over the banks
+  __shared__ __align__(16) int8_t vt[DH * VT_PITCH + CP * 16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int blocks_per_group = (p.tiles_i + 3) / 4;
@@ -145,35 +150,37 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
 
   for (int jb = 0; jb < nk_block; jb += JB) {
     __syncthreads();
-    // ---- stage V^T for keys jb .. jb+JB-1: thread -> (4 keys, 4 channels), byte transpose in registers ----
-    for (int id = tid; id < (JB / 4) * (DH / 4); id += 256) {
-      const int j4 = id % (JB / 4), c4 = id / (JB / 4);
-      unsigned r[4];
+    // ---- stage V^T for keys jb .. jb+JB-1: thread -> (4 keys, 16 channels); the lanes of a wavefront read whole key
+    // rows (16 bytes each), the bytes are transposed in registers, and every channel's 4 keys go out as one dword ----
+    // (keys past the last one this workgroup needs are not staged: their probabilities are masked to zero, so whatever
+    // the LDS holds there contributes nothing)
+    const int nj4 = ((nk_block - jb < JB ? nk_block - jb : JB) + 3) / 4;
+    for (int id = tid; id < nj4 * CP; id += 256) {
+      const int c16 = id % CP, j4 = id / CP;
+      v4i r[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int j = jb + j4 * 4 + e;
-        r[e] = j < p.Nk ? *reinterpret_cast<const unsigned*>(Vg + (int64_t)j * p.ldv + c4 * 4) : 0u;
+        r[e] = j < p.Nk ? *reinterpret_cast<const v4i*>(Vg + (int64_t)j * p.ldv + c16 * 16) : v4i{0, 0, 0, 0};
       }
+      int8_t* const dst = vt + (c16 * 16) * VT_PITCH + c16 * 16 + j4 * 4;     // row c16*16 of the skewed layout
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const unsigned o = ((r[0] >> (8 * e)) & 0xFFu) | (((r[1] >> (8 * e)) & 0xFFu) << 8) |
-                           (((r[2] >> (8 * e)) & 0xFFu) << 16) | (((r[3] >> (8 * e)) & 0xFFu) << 24);
-        *reinterpret_cast<unsigned*>(vt + (c4 * 4 + e) * VT_PITCH + j4 * 4) = o;
+      for (int d = 0; d < 4; ++d) {
+        const unsigned r0 = (unsigned)r[0][d], r1 = (unsigned)r[1][d], r2 = (unsigned)r[2][d], r3 = (unsigned)r[3][d];
+        const unsigned lo01 = __builtin_amdgcn_perm(r1, r0, 0x05010400u);   // r0.b0 r1.b0 r0.b1 r1.b1
+        const unsigned hi01 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);   // r0.b2 r1.b2 r0.b3 r1.b3
+        const unsigned lo23 = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+        const unsigned hi23 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+        *reinterpret_cast<unsigned*>(dst + (4 * d + 0) * VT_PITCH) = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);   // channel 4d of keys 0..3
+        *reinterpret_cast<unsigned*>(dst + (4 * d + 1) * VT_PITCH) = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        *reinterpret_cast<unsigned*>(dst + (4 * d + 2) * VT_PITCH) = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        *reinterpret_cast<unsigned*>(dst + (4 * d + 3) * VT_PITCH) = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
       }
     }
     __syncthreads();
     if (jb >= nk_wave) continue;
     int jend = nk_wave - jb;
     jend = jend < JB ? jend : JB;
-    // WIDE: this lane's codes of the whole block, requested together and once for all windows
-    v4i cws[WIDE ? JB / 32 : 1];
-    if (WIDE) {
-#pragma unroll
-      for (int t = 0; t < JB / 32; ++t) {
-        const int j0 = jb + t * 32 + half * 16;
-        cws[t] = (t * 32 < jend && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
-      }
-    }
     for (int w = 0; w < (WIDE ? WINDOWS : 1); ++w) {
       if (WIDE && !((present >> w) & 1u)) continue;
       if (WIDE) {
@@ -214,20 +221,14 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
         }
 #pragma unroll
         for (int c = 0; c < TC; ++c) {
-          const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VT_PITCH + js + half * 16);
+          const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VT_PITCH + ((c * 32 + l32) >> 4) * 16 + js + half * 16);
           E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
           O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
         }
       };
-      if (WIDE) {
-#pragma unroll
-        for (int t = 0; t < JB / 32; ++t)
-          if (t * 32 < jend) key_tile(t * 32, cws[t]);
-      } else {
-        for (int js = 0; js < jend; js += 32) {
-          const int j0 = jb + js + half * 16;
-          key_tile(js, j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0});
-        }
+      for (int js = 0; js < jend; js += 32) {
+        const int j0 = jb + js + half * 16;
+        key_tile(js, j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0});
       }
       if (WIDE) {
         const float wsf = __builtin_ldexpf(1.0f, -8 * w);
@@ -285,6 +286,203 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
   }
 }
 
+// ---- long rows of wide codes: one pass on the bf16 matrix cores ------------------------------------------------------
+// With codes wider than 4 bits the int8 scheme above visits every window of 8 shifts separately, after a pass over the
+// row's codes for its smallest shift.  A power of two 2^-k (k = 0..127) is exact in bfloat16 whatever k is, and so is
+// code - z_v (|.| <= 255: 8 significant bits), so for long rows the probabilities go to the matrix cores as bfloat16
+// instead: no windows, no reference shift, one MFMA pass with float32 accumulation (products exact; the sums round like
+// any float32 dot product, about 2^-24 per term, far inside the tolerance of the codes).  Even and odd codes still
+// accumulate separately; the parity scale is applied once per output.
+//  * V^T is staged per 128 keys as bfloat16 of (code - z_v), double-buffered, one barrier per block; the zero-point
+//    term therefore needs no separate sum.
+//  * A workgroup of 8 wavefronts serves 8 query tiles of one (batch item, head); wavefronts w and w + 4 take tiles from
+//    the two ends of the group, which evens out the work under a causal mask.
+//  * Contraction index of an MFMA k-step s (16 keys): lane half h, element e <-> key 16 h + 8 s + e of the 32-key tile,
+//    for both operands: a lane's 16 codes are one 16-byte load, its V^T piece one 16-byte LDS read.
+constexpr int JL = 128;                  // keys per LDS block
+constexpr int VL_PITCH = JL * 2 + 16;    // bytes per V^T row (bfloat16), skewed: 68 dwords
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int DH>
+constexpr int pv_long_lds() { return 2 * (DH * VL_PITCH + (DH / 16) * 16); }
+
+template <int DH>
+__global__ __launch_bounds__(512) void pv_long_kernel(const PvParams p, const int wgs_per_group) {
+  constexpr int TC = DH / 32;
+  constexpr int CP = DH / 16;            // 16-byte pieces per key row
+  constexpr int VBUF = DH * VL_PITCH + CP * 16;
+  constexpr int NIDS = (JL / 4) * CP;    // (4 keys, 16 channels) pieces per block: at most 256
+  extern __shared__ __align__(16) int8_t lds[];      // two V^T buffers: channel r at r * VL_PITCH + (r / 16) * 16
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const int T = p.tiles_i;
+  const int lowT = (T + 1) / 2;                      // tiles taken from the front; T - lowT from the back
+  const int64_t g = blockIdx.x / wgs_per_group;
+  const int wb = (int)(blockIdx.x - g * wgs_per_group);
+  const int kq = 4 * wb + (wave & 3);
+  const bool active = wave < 4 ? kq < lowT : kq < T - lowT;
+  const int it = !active ? 0 : (wave < 4 ? kq : T - 1 - kq);
+  const int it_max = 4 * wb < T - lowT ? T - 1 - 4 * wb : (4 * wb + 3 < lowT ? 4 * wb + 3 : lowT - 1);
+  auto keys_of = [&](int tile) {                     // keys the rows of query tile `tile` can see
+    int rows_end = (tile + 1) * 32;
+    rows_end = rows_end < p.Nq ? rows_end : p.Nq;
+    return p.causal ? (rows_end < p.Nk ? rows_end : p.Nk) : p.Nk;
+  };
+  const int nk_wg = keys_of(it_max);                 // workgroup-uniform
+  const int nk_wave = active ? keys_of(it) : 0;
+  const int nblk = (nk_wg + JL - 1) / JL;
+
+  const int64_t b = g / p.H;
+  const int h = (int)(g - b * p.H);
+  const int8_t* const Vg = p.V + b * p.Nk * p.ldv + h * DH;
+  const int qi = it * 32 + l32;
+  const int qi_ld = qi < p.Nq ? qi : p.Nq - 1;
+  const uint8_t* const crow = p.codes + (g * p.Nq + qi_ld) * p.ld;
+  const int limit = p.causal ? (qi_ld + 1 < p.Nk ? qi_ld + 1 : p.Nk) : p.Nk;        // valid keys of this row: j < limit
+  const int min_limit = p.causal ? (it * 32 + 1 < p.Nk ? it * 32 + 1 : p.Nk) : p.Nk;  // the smallest limit in this wavefront
+
+  // ---- V: 4 keys x 16 channels per thread, requested one block ahead ----
+  const int c16 = tid % CP, j4 = tid / CP;
+  v4i vreg[4];
+  auto request = [&](int blk) {
+    if (tid < NIDS) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = blk * JL + j4 * 4 + e;
+        vreg[e] = j < p.Nk ? *reinterpret_cast<const v4i*>(Vg + (int64_t)j * p.ldv + c16 * 16) : v4i{0, 0, 0, 0};
+      }
+    }
+  };
+  const float dvf = (float)(p.dv - 128);
+  auto deposit = [&](int blk) {
+    if (tid < NIDS) {
+      int8_t* const dst = lds + (blk & 1) * VBUF + (c16 * 16) * VL_PITCH + c16 * 16 + j4 * 8;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        unsigned u[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] = (unsigned)vreg[e][d] ^ 0x80808080u;      // stored code + 128, unsigned
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) {
+          unsigned f[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) f[e] = __float_as_uint((float)((u[e] >> (8 * bb)) & 0xFFu) + dvf);   // code - z_v, exact
+          uint2 w;          // the upper halves are the bfloat16 values (exact: at most 8 significant bits)
+          w.x = __builtin_amdgcn_perm(f[1], f[0], 0x07060302u);
+          w.y = __builtin_amdgcn_perm(f[3], f[2], 0x07060302u);
+          *reinterpret_cast<uint2*>(dst + (4 * d + bb) * VL_PITCH) = w;
+        }
+      }
+    }
+  };
+
+  v16f E[TC], O[TC];
+#pragma unroll
+  for (int c = 0; c < TC; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { E[c][e] = 0.f; O[c][e] = 0.f; }
+
+  request(0);
+  deposit(0);
+  if (nblk > 1) request(1);
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int jb = blk * JL;
+    // this lane's codes of the block (16 per key tile), requested before the barrier
+    v4i cw[JL / 32];
+#pragma unroll
+    for (int t = 0; t < JL / 32; ++t) {
+      const int j0 = jb + t * 32 + half * 16;
+      cw[t] = (jb + t * 32 < nk_wave && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
+    }
+    __syncthreads();        // block blk is in place; every wavefront has finished with the buffer block blk + 1 goes into
+    if (blk + 1 < nblk) {
+      deposit(blk + 1);
+      if (blk + 2 < nblk) request(blk + 2);
+    }
+    const int8_t* const buf = lds + (blk & 1) * VBUF;
+#pragma unroll
+    for (int t = 0; t < JL / 32; ++t) {
+      if (jb + t * 32 < nk_wave) {          // wavefront-uniform
+        const int j0 = jb + t * 32 + half * 16;
+        const bool partial = jb + t * 32 + 32 > min_limit;
+        v4i pe[2], po[2];
+#pragma unroll
+        for (int d4 = 0; d4 < 4; ++d4) {
+          unsigned c = (unsigned)cw[t][d4];
+          if (partial) {      // masked and padding keys read as code 255, whose power of two is stored as zero
+            int nv = limit - (j0 + d4 * 4);
+            nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+            c |= nv == 4 ? 0u : ~((1u << (8 * nv)) - 1u);
+          }
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr) {
+            // two codes as halfwords; bfloat16 bits of 2^-k are (127 - k) << 7 = 0x3F80 - ((code & 0xFE) << 6)
+            const unsigned cx = __builtin_amdgcn_perm(0u, c, pr ? 0x0C030C02u : 0x0C010C00u);
+            const unsigned bits = 0x3F803F80u - ((cx & 0x00FE00FEu) << 6);
+            const unsigned odd = (cx & 0x00010001u) * 0xFFFFu;       // 0xFFFF in the halfwords that hold odd codes
+            const unsigned vo = bits & odd;
+            po[d4 >> 1][(d4 & 1) * 2 + pr] = (int)vo;
+            pe[d4 >> 1][(d4 & 1) * 2 + pr] = (int)(bits ^ vo);
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < TC; ++c) {
+          const int r = c * 32 + l32;
+#pragma unroll
+          for (int s = 0; s < 2; ++s) {
+            const v4i fv = *reinterpret_cast<const v4i*>(buf + r * VL_PITCH + (r >> 4) * 16 + (t * 32 + half * 16 + s * 8) * 2);
+            E[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fv), __builtin_bit_cast(v8bf, pe[s]), E[c], 0, 0, 0);
+            O[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fv), __builtin_bit_cast(v8bf, po[s]), O[c], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (!active || qi >= p.Nq) return;
+  const int64_t tok = b * p.Nq + qi;
+  // the parity scales of the int8 scheme carry its -1/128; here the probabilities are the powers of two themselves
+  const double ae = -128.0 * p.a_even, ao = -128.0 * p.a_odd;
+#pragma unroll
+  for (int c = 0; c < TC; ++c) {
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      const int col = h * DH + c * 32 + 8 * gq + half * 4;
+      double y[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = ae * (double)E[c][4 * gq + e] + ao * (double)O[c][4 * gq + e];
+      if (p.out_f32)
+        *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4((float)y[0], (float)y[1], (float)y[2], (float)y[3]);
+      if (p.out_q) {
+        int k[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int q = (int)rint(y[e] * p.inv_so) + p.zo;
+          k[e] = q < p.lo ? p.lo : (q > p.hi ? p.hi : q);
+        }
+        *reinterpret_cast<int*>(p.out_q + tok * p.ldq + col) = rq_pack4(k[0], k[1], k[2], k[3]);
+      }
+    }
+  }
+}
+
+template <int DH>
+rq_status launch_long(rq_ctx* ctx, const PvParams& p, int64_t groups) {
+  const int wgs_per_group = ((p.tiles_i + 1) / 2 + 3) / 4;
+  const int64_t blocks = groups * wgs_per_group;
+  if (blocks > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "rq_attn_pv: %lld workgroups exceed 2^30", (long long)blocks);
+  constexpr int lds = pv_long_lds<DH>();
+  static bool attr_set = false;
+  if (!attr_set) {
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pv_long_kernel<DH>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((pv_long_kernel<DH>), dim3((unsigned)blocks), dim3(512), lds, ctx->stream, p, wgs_per_group);
+  return RQ_OK;
+}
+
 template <int DH>
 void launch(rq_ctx* ctx, const PvParams& p, int64_t groups, bool wide) {
   const int blocks_per_group = (p.tiles_i + 3) / 4;
@@ -312,6 +510,18 @@ rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   p.num_cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   const bool wide = d->bits_p > 4;
   const int64_t groups = d->batch * d->H;
+  if (wide && d->Nk > JB) {
+    rq_status st = RQ_ERR_SHAPE;
+    switch (d->d_head) {
+      case 32: st = launch_long<32>(ctx, p, groups); break;
+      case 64: st = launch_long<64>(ctx, p, groups); break;
+      case 128: st = launch_long<128>(ctx, p, groups); break;
+      default: return rq_fail(ctx, RQ_ERR_SHAPE, "rq_attn_pv: d_head = %d must be 32, 64 or 128", d->d_head);
+    }
+    if (st != RQ_OK) return st;
+    RQ_HIP(hipGetLastError());
+    return RQ_OK;
+  }
   switch (d->d_head) {
     case 32: launch<32>(ctx, p, groups, wide); break;
     case 64: launch<64>(ctx, p, groups, wide); break;

@@ -407,8 +407,8 @@ rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d) {
              d->d_head);
   RQ_REQUIRE(d->ld >= d->Nk && d->ld % 16 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ld = %lld must be >= Nk and a multiple of 16",
              (long long)d->ld);
-  RQ_REQUIRE(rq_aligned(d->codes, 16) && rq_aligned(d->V, 4), RQ_ERR_INVALID_ARG, "rq_attn_pv: codes need 16-byte, V 4-byte alignment");
-  RQ_REQUIRE(d->ldv >= (int64_t)d->H * d->d_head && d->ldv % 4 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ldv must be >= H*d_head and a multiple of 4");
+  RQ_REQUIRE(rq_aligned(d->codes, 16) && rq_aligned(d->V, 16), RQ_ERR_INVALID_ARG, "rq_attn_pv: codes and V need 16-byte alignment");
+  RQ_REQUIRE(d->ldv >= (int64_t)d->H * d->d_head && d->ldv % 16 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ldv must be >= H*d_head and a multiple of 16");
   RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_pv: bits_p = %d not in 2..8", d->bits_p);
   RQ_REQUIRE(d->s_log > 0.f && d->s_v > 0.f, RQ_ERR_INVALID_ARG, "rq_attn_pv: s_log and s_v must be > 0");
   RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_attn_pv: mask %d", d->mask);

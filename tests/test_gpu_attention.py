@@ -89,7 +89,10 @@ def test_softmax_log2_codes(rq, G, H, N, bits, bias, causal):
 @pytest.mark.parametrize("batch,H,seq,dh,bits_p,bits_v,causal", [(2, 3, 197, 64, 4, 4, False), (2, 2, 49, 32, 6, 6, False),
                                                                  (1, 2, 257, 64, 4, 4, False), (1, 2, 600, 128, 8, 8, True),
                                                                  (2, 2, 64, 64, 8, 8, False), (1, 1, 1, 32, 4, 8, False),
-                                                                 (1, 2, 300, 64, 4, 8, True)])
+                                                                 (1, 2, 300, 64, 4, 8, True),
+                                                                 # wide codes on rows beyond 256 keys: the bfloat16 kernel
+                                                                 (1, 2, 300, 64, 6, 8, False), (2, 1, 700, 32, 8, 6, True),
+                                                                 (1, 1, 1025, 128, 8, 8, False), (1, 2, 257, 128, 5, 4, True)])
 def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
     b, ctx = rq
     print("case", batch, H, seq, dh, bits_p, bits_v, causal, flush=True)
@@ -121,7 +124,9 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
     b.rq_attn_pv(ctx, dev(cp), ld, qd.data_ptr() + 2 * D, 3 * D, batch, H, seq, seq, dh, float(s_log), float(s_v), z_v, offv, bits_p,
                  mask=b.MASK_CAUSAL if causal else b.MASK_NONE, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o,
                  bits_o=bits_v)
-    assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-5)
+    # exact integer sums everywhere except for wide codes on long rows, which accumulate in float32 on the bfloat16
+    # matrix cores: n terms of magnitude <= |v| p_j each round to 2^-24 of the running sum
+    assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-4 if (bits_p > 4 and seq > 256) else 1e-5)
     assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits_v), "attn_pv codes")
 
 
