@@ -280,14 +280,13 @@ typedef struct {
 rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d);
 
 /* ---- rq_attn_fused ------------------------------------------------------------------------------------
- * rq_qk_softmax_log2_quant followed by rq_attn_pv in ONE kernel: the codes of a key tile are used as the
- * operand of the shift de-quantized P.V product (case analysis before Eq. (3.3-2)) as soon as they are formed,
- * so neither the logits nor the codes travel through memory.  Same integers, same code arithmetic, same
+ * rq_qk_softmax_log2_quant followed by rq_attn_pv in ONE kernel: the codes of a query tile's whole row stay
+ * packed in registers and become the operand of the shift de-quantized P.V product (case analysis before
+ * Eq. (3.3-2)), so neither the logits nor the codes travel through memory.  Same integers, same code arithmetic, same
  * output arithmetic as the separate calls.  Restrictions: no bias, no mask, codes of at most 4 bits (one shift
- * window), N <= 288, d_head in {32, 64, 128}; otherwise RQ_ERR_SHAPE and the caller takes the separate calls.  While
- * ceil(N / 32) * 16 + d_head <= 176 accumulator registers (e.g. N <= 224 at d_head 64) the codes feed P.V tile by tile;
- * longer rows first pack the codes of the whole row in registers (the 257 .. 288-key and most 128-wide-head variants
- * spill registers and are slower than the two separate calls, which rq_block_forward then prefers).  Q, K, V: token-major device int8 slices of one tensor
+ * window), N <= 288, d_head in {32, 64, 128}; otherwise RQ_ERR_SHAPE and the caller takes the separate calls.  (The
+ * 257 .. 288-key variants spill registers and are slower than the two separate calls, which rq_block_forward then
+ * prefers.)  Q, K, V: token-major device int8 slices of one tensor
  * with row pitch ld_tok (stored code - off).  codes (optional, may be NULL): [batch*H, N, ld] as in
  * rq_qk_softmax_log2_quant.  Outputs as in rq_attn_pv: out_f32 and/or out_q, token-major [batch*N, H*d_head].
  */

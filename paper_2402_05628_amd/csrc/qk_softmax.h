@@ -53,10 +53,10 @@ constexpr unsigned QKS_TAB_LO = 0xF0E0C080u, QKS_TAB_HI = 0xFFFEFCF8u;
 // owns 16 consecutive keys of its query row, which is that operand's layout); V^T is staged in LDS next to the keys;
 // even and odd codes accumulate separately and exactly in int32, as in rq_attn_pv (codes of at most 4 bits: one window).
 // Registers per lane: the accumulators of Q.K^T (16 per key tile) and the even and odd accumulators of P.V (32 per 32
-// channels).  While both fit, every key tile's codes go straight into its P.V products; beyond that the codes of all tiles
-// are packed first (4 registers per tile, the Q.K^T accumulators die as they are converted) and P.V runs afterwards.
-constexpr bool fused_pv_fits(int ksteps, int nt) { return nt * 16 + ksteps * 32 <= 176; }
-constexpr bool fused_pv_supported(int ksteps, int nt) { return fused_pv_fits(ksteps, nt) || (nt * 16 <= 176 && nt * 4 + ksteps * 32 <= 176); }
+// channels) are never live together: the codes of all key tiles are packed first (4 registers per tile, the Q.K^T
+// accumulators die as they are converted) and P.V runs afterwards from the packed codes.  (Feeding every tile's codes
+// straight into its P.V products, where both sets fit, measured slower at every shape: 42 against 36 us at ViT-B.)
+constexpr bool fused_pv_supported(int ksteps, int nt) { return nt * 16 <= 176 && nt * 4 + ksteps * 32 <= 176; }
 
 template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, bool PV>
 __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
@@ -167,10 +167,10 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
   for (int s = 0; s < KSTEPS; ++s) fq0[s] = qreg[s];
   __syncthreads();
-  // The next pass's operands are requested into registers ahead of time.  Where the Q.K^T accumulators and the P.V ones
-  // do not fit together (LATE), the request waits until this wavefront's last query tile has turned its accumulators into
-  // packed codes, so that its registers are not live while the accumulators are.
-  constexpr bool LATE = PV && !fused_pv_fits(KSTEPS, NT);
+  // The next pass's operands are requested into registers ahead of time.  With P.V fused (LATE) the request waits until
+  // this wavefront's last query tile has turned its accumulators into packed codes, so that its registers are not live
+  // while the accumulators are.
+  constexpr bool LATE = PV;
   const bool more = gq + (int)gridDim.x * GPB < Gi;
   bool requested = false;
   if (!LATE && more) { request(gq + (int)gridDim.x * GPB); requested = true; }
@@ -214,6 +214,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) acc[jt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fk[s], fq[s], acc[jt], 0, 0, 0);
       }
+      if (NT >= 7) __builtin_amdgcn_sched_barrier(0);     // keep the operand reads of later tiles from piling up in registers
     }
     // ---- softmax statistics of row qi: this lane holds keys jt*32 + 8*(e/4) + 4*half + e%4 ----
     const int limit = MASKALL ? (qi_ld + 1 < p.N ? qi_ld + 1 : p.N) : p.N;     // valid keys: j < limit
@@ -284,9 +285,8 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const float C0f = (float)C0, m2cf = (float)m2c;
     // ---- codes (and, fused, their product with V) ----
     uint8_t* crow = p.codes ? p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld : nullptr;
-    constexpr bool SPLIT = PV && !fused_pv_fits(KSTEPS, NT);      // P.V after all codes, from packed codes
     v16i E[PV ? TC : 1], O[PV ? TC : 1];
-    v4i tvs[SPLIT ? NT : 1];
+    v4i tvs[PV ? NT : 1];         // the packed codes of every key tile: P.V runs after all of them
     int se = 0, so = 0;
     // the P.V products of one key tile from its 16 codes per lane
     auto pv_tile = [&](int jt, const v4i& tv) {
@@ -320,12 +320,6 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
       }
     };
-    if (PV && !SPLIT) {
-#pragma unroll
-      for (int c = 0; c < TC; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
-    }
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt) {
       if (jt < nt) {
@@ -360,11 +354,10 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         const int j0 = jt * 32 + half * 16;
         const v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
         if (crow && qi < p.N && j0 < p.ld) *reinterpret_cast<v4i*>(crow + j0) = tv;
-        if (SPLIT) tvs[jt] = tv;
-        else if (PV) pv_tile(jt, tv);
+        if (PV) tvs[jt] = tv;
       }
     }
-    if (SPLIT) {
+    if (PV) {
       if (more && !requested && it + (GPB > 1 ? nt : 8) >= nt) { request(gq + (int)gridDim.x * GPB); requested = true; }
 #pragma unroll
       for (int c = 0; c < TC; ++c)

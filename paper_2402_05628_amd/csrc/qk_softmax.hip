@@ -13,13 +13,12 @@ extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bi
   return rqks::fused_pv_supported(d_head / 32, (N + 31) / 32) ? 1 : 0;
 }
 
-// Where the one-kernel attention is also the faster choice: the variants that hold everything in registers.  The
-// nine-tile ones (257 .. 288 keys) and most 128-wide heads compile with register spills and measure slower than
-// rq_qk_softmax_log2_quant + rq_attn_pv (257 keys, d_head 64: 0.49 ms against 0.34 ms at 2048 groups).
+// Where the one-kernel attention is also the faster choice: up to 8 key tiles.  The nine-tile variants (257 .. 288 keys)
+// compile with register spills and measure slower than rq_qk_softmax_log2_quant + rq_attn_pv (257 keys, d_head 64, 588
+// groups: 85 us against 36 + 34 us).
 bool rq_attn_fused_preferred(int N, int d_head, int bits_p) {
   if (!rq_attn_fused_supported(N, d_head, bits_p)) return false;
-  const int ks = d_head / 32, nt = (N + 31) / 32;
-  return rqks::fused_pv_fits(ks, nt) || (ks <= 2 && nt <= 8);
+  return (N + 31) / 32 <= 8;
 }
 
 rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
