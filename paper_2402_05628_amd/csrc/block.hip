@@ -25,22 +25,33 @@ bool use_fused(const rq_block_params* p, int64_t seq) {
   return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H, p->rel_bias != nullptr);
 }
 
+// the whole attention in one kernel: neither logits nor codes reach memory
+bool use_whole(const rq_block_params* p, int64_t seq) {
+  return g_attn_fused == 1 && p->H > 0 && p->D % p->H == 0 && !p->rel_bias && p->mask == RQ_MASK_NONE &&
+         rq_attn_fused_preferred((int)seq, p->D / p->H, p->bits_p);
+}
+
 Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   Plan pl;
   pl.batch = batch; pl.seq = seq; pl.T = batch * seq;
   pl.ld = (seq + 15) / 16 * 16;
   const bool fused = use_fused(p, seq);       // no int32 logits in memory: only the codes count
+  const bool whole = use_whole(p, seq);      // nothing to keep cache-resident between kernels: one chunk
   const int64_t per_item = (int64_t)p->H * seq * pl.ld * (fused ? 1 : 5);
-  pl.bchunk = g_attn_chunk_bytes / (per_item > 0 ? per_item : 1);
+  pl.bchunk = whole ? batch : g_attn_chunk_bytes / (per_item > 0 ? per_item : 1);
   if (pl.bchunk < 1) pl.bchunk = 1;
   if (pl.bchunk > batch) pl.bchunk = batch;
+  if (batch > 0) {      // equal chunks: a small last chunk would run its kernels on a nearly empty chip
+    const int64_t chunks = (batch + pl.bchunk - 1) / pl.bchunk;
+    pl.bchunk = (batch + chunks - 1) / chunks;
+  }
   const int64_t gch = pl.bchunk * p->H;
   size_t o = 0;
   pl.o_a = o; o += up((size_t)pl.T * p->D);
   pl.o_rowsum = o; o += up((size_t)pl.T * 4);
   pl.o_qkv = o; o += up((size_t)pl.T * 3 * p->D);
   pl.o_acc = o; o += fused ? 0 : up((size_t)gch * seq * pl.ld * 4);
-  pl.o_codes = o; o += up((size_t)gch * seq * pl.ld);
+  pl.o_codes = o; o += whole ? 0 : up((size_t)gch * seq * pl.ld);
   pl.o_o = o; o += up((size_t)pl.T * p->D);
   pl.o_xbar = o; o += up((size_t)pl.T * p->D * 4);
   pl.o_hid = o; o += up((size_t)pl.T * p->Dm);
@@ -164,7 +175,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   // ---- attention, chunked over batch items -----------------------------------------------------------------
   const int offo = rq_store_offset(ba, p->z_o);
   const bool fused = use_fused(p, seq);
-  const bool whole = g_attn_fused == 1 && !p->rel_bias && p->mask == RQ_MASK_NONE && rq_attn_fused_preferred((int)seq, dh, p->bits_p);
+  const bool whole = use_whole(p, seq);
   for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
     const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
     const int8_t* qkv_c = qkv + b0 * seq * 3 * D;

@@ -226,9 +226,20 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
           O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
         }
       };
-      for (int js = 0; js < jend; js += 32) {
+      // the codes of the next two key tiles are in flight while the current one is worked on
+      auto codes_of = [&](int js) {
         const int j0 = jb + js + half * 16;
-        key_tile(js, j0 < p.ld ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0});
+        return (js < jend && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
+      };
+      if (WIDE) {       // short rows, visited once per window: the extra registers would cost a wavefront per SIMD
+        for (int js = 0; js < jend; js += 32) key_tile(js, codes_of(js));
+      } else {
+        v4i c0 = codes_of(0), c1 = codes_of(32);
+        for (int js = 0; js < jend; js += 32) {
+          const v4i c2 = codes_of(js + 64);
+          key_tile(js, c0);
+          c0 = c1; c1 = c2;
+        }
       }
       if (WIDE) {
         const float wsf = __builtin_ldexpf(1.0f, -8 * w);

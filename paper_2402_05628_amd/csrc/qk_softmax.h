@@ -58,6 +58,17 @@ constexpr unsigned QKS_TAB_LO = 0xF0E0C080u, QKS_TAB_HI = 0xFFFEFCF8u;
 // straight into its P.V products, where both sets fit, measured slower at every shape: 42 against 36 us at ViT-B.)
 constexpr bool fused_pv_supported(int ksteps, int nt) { return nt * 16 <= 176 && nt * 4 + ksteps * 32 <= 176; }
 
+// LDS per group: keys [nt * 32][dh], then (fused P.V) V^T [dh][nt * 32 + 16]
+constexpr int slot_bytes(int ksteps, int nt, bool pv) { return nt * 32 * ksteps * 32 + (pv ? ksteps * 32 * (nt * 32 + 16) : 0); }
+// Groups per workgroup pass: short rows share a pass so that every wavefront has a tile (1 .. 4 tiles: 8, 4, 2, 2 groups).
+// (Longer rows whose tile count does not divide 8 -- 5, 6, 9 tiles -- measured no faster with 3 or 4 groups per pass: the
+// staging of a pass is not overlapped with its arithmetic, and it grows with the groups.)
+constexpr int groups_per_pass(int ksteps, int nt, bool pv) {
+  int want = nt <= 4 ? 8 / nt : 1;
+  while (want > 1 && want * slot_bytes(ksteps, nt, pv) > 160 * 1024) --want;
+  return want;
+}
+
 template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, bool PV>
 __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   constexpr int DH = KSTEPS * 32;
@@ -65,9 +76,10 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   constexpr int VTP = NT * 32 + 16;     // bytes per V^T row (skewed)
   constexpr int CPR = DH / 16;          // 16-byte chunks per key row
   constexpr int RPL = 16 / CPR;         // key rows per 256 bytes
-  // Short rows leave most of the 8 wavefronts without a query tile, so a workgroup then serves GPB groups per pass:
-  // wavefront w works on group slot w / NT, query tile w % NT.
-  constexpr int GPB = NT <= 4 ? 8 / NT : 1;
+  // A workgroup serves GPB groups per pass; their GPB * NT (group slot, query tile) tasks are dealt to the 8 wavefronts in
+  // turn (task t: slot t / NT, tile t % NT), so that rows whose tile count does not divide 8 leave few wavefronts idle.
+  constexpr int GPB = groups_per_pass(KSTEPS, NT, PV);
+  constexpr int NTASK = GPB * NT;
   constexpr int NCHUNK = NT * 32 * CPR;                     // 16-byte key chunks per group
   constexpr int NPIECE = NT * 8 * (DH / 4);                 // (4 keys x 4 channels) pieces of V per group
   constexpr int KS_BYTES = NT * 32 * DH, SLOT_BYTES = KS_BYTES + (PV ? DH * VTP : 0);
@@ -77,11 +89,8 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   constexpr int nt = NT;
-  const int ws = GPB > 1 ? wave / NT : 0;                   // this wavefront's group slot
-  const int it0 = GPB > 1 ? wave % NT : wave;               // and its (first) query tile
-  const bool wave_active = GPB == 1 || wave < GPB * NT;
-  int8_t* const ks = lds + ws * SLOT_BYTES;
-  int8_t* const vt = ks + KS_BYTES;
+  const int ws0 = wave / NT;                                // this wavefront's first task: group slot
+  const int it0 = wave - ws0 * NT;                          // and query tile
   const int Gi = (int)p.G;
   const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
   const bool corr = p.dq != 0 || p.dk != 0;
@@ -119,18 +128,13 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     }
     const int qi = it0 * 32 + l32;
     const int qi_ld = qi < p.N ? qi : p.N - 1;
-    const int8_t* Qg = group_base(gq + ws, p.Q);
+    const int8_t* Qg = group_base(gq + ws0, p.Q);
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qreg[s] = *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
   };
   int gq = (int)blockIdx.x * GPB;
   if (gq < Gi) request(gq);
   for (; gq < Gi; gq += (int)gridDim.x * GPB) {
-  const int64_t g = gq + ws;
-  const bool group_live = wave_active && g < p.G;
-  const int64_t b = (g < p.G ? g : p.G - 1) / p.H;
-  const int h = (int)((g < p.G ? g : p.G - 1) - b * p.H);
-  const int8_t* Qg = p.Q + b * p.so + (int64_t)h * p.si;
   // ---- stage the keys of this pass in LDS (every wavefront has finished with the previous pass) ----
 #pragma unroll
   for (int u = 0; u < KCH; ++u) {
@@ -175,13 +179,21 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   bool requested = false;
   if (!LATE && more) { request(gq + (int)gridDim.x * GPB); requested = true; }
 
-  for (int it = it0; group_live && it < nt; it += (GPB > 1 ? nt : 8)) {       // wavefront-uniform
+  for (int task = wave; task < NTASK; task += 8) {       // wavefront-uniform
+    const int ws = task / NT, it = task - ws * NT;
+    const int64_t g = gq + ws;
+    if (g >= p.G) break;
+    const int64_t b = g / p.H;
+    const int h = (int)(g - b * p.H);
+    const int8_t* const Qg = p.Q + b * p.so + (int64_t)h * p.si;
+    const int8_t* const ks = lds + ws * SLOT_BYTES;
+    const int8_t* const vt = ks + KS_BYTES;
     const int qi = it * 32 + l32;
     const int qi_ld = qi < p.N ? qi : p.N - 1;
     v4i fq[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s)
-      fq[s] = it == it0 ? fq0[s] : *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
+      fq[s] = task == wave ? fq0[s] : *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
     int base = 0;
     if (corr) {
       v16i rq;
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
       }
     }
     if (PV) {
-      if (more && !requested && it + (GPB > 1 ? nt : 8) >= nt) { request(gq + (int)gridDim.x * GPB); requested = true; }
+      if (more && !requested && task + 8 >= NTASK) { request(gq + (int)gridDim.x * GPB); requested = true; }
 #pragma unroll
       for (int c = 0; c < TC; ++c)
 #pragma unroll
@@ -411,8 +423,8 @@ template <int KSTEPS, int NT>
 rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
   if (groups > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %lld groups exceed 2^30", (long long)groups);
   const bool pv = p.V != nullptr;
-  constexpr int GPB = NT <= 4 ? 8 / NT : 1;      // groups per workgroup pass (as in the kernel)
-  const int lds = GPB * (NT * 32 * KSTEPS * 32 + (pv ? KSTEPS * 32 * (NT * 32 + 16) : 0));
+  const int GPB = groups_per_pass(KSTEPS, NT, pv);      // groups per workgroup pass (as in the kernel)
+  const int lds = GPB * slot_bytes(KSTEPS, NT, pv);
   const int64_t cap = (int64_t)(ctx->num_cu > 0 ? ctx->num_cu : 256);      // one 8-wavefront workgroup per CU
   const int64_t passes = (groups + GPB - 1) / GPB;
   const dim3 grid((unsigned)(passes < cap ? passes : cap));
