@@ -237,7 +237,32 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     double tmax = -1e300;
     int amax = INT32_MIN;
     const float* brow = HAS_BIAS ? p.bias + ((int64_t)h * p.N + qi_ld) * p.N : nullptr;
-    if (HAS_BIAS) {
+    if (HAS_BIAS && !F64CODE) {
+      // Codes of at most 6 bits: t = acc * c1 + bias * log2(e) in float32 (c1 split into two floats, so the product is
+      // as good as exact), every bias read once; the accumulator registers then hold t, later t - t_max.
+      const float c1lo = (float)(p.c1 - (double)c1f);
+      float tmf = -INFINITY;
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+          const bool ok = jt < nt && j < limit;
+          const float af = (float)acc[jt][e];
+          const float t = ok ? fmaf(af, c1f, fmaf(af, c1lo, brow[ok ? j : 0] * 1.4426950408889634f)) : -INFINITY;
+          acc[jt][e] = __float_as_int(t);
+          tmf = fmaxf(tmf, t);
+        }
+      tmf = fmaxf(tmf, __shfl_xor(tmf, 32, 64));
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float d = __int_as_float(acc[jt][e]) - tmf;      // masked and padding keys: -inf
+          acc[jt][e] = __float_as_int(d);
+          ssum += __builtin_amdgcn_exp2f(d);
+        }
+    } else if (HAS_BIAS) {
       // t = acc * c1 + bias * log2(e), kept as the float64 bit pattern is too costly in registers: recomputed below
 #pragma unroll
       for (int jt = 0; jt < NT; ++jt)
@@ -343,7 +368,9 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
           for (int e = 0; e < 4; ++e) {
             const int j = jt * 32 + 8 * gq + 4 * half + e;
             float vf;
-            if (HAS_BIAS) {
+            if (HAS_BIAS && !F64CODE) {
+              vf = fmaf(__int_as_float(acc[jt][4 * gq + e]), -2.f, C0f);     // masked keys: +inf -> saturates at qmax
+            } else if (HAS_BIAS) {
               const double t = j < limit ? fma((double)acc[jt][4 * gq + e], p.c1, (double)brow[j < p.N ? j : 0] * 1.4426950408889634) : -1e300;
               vf = j < limit ? (float)rint(fma(t - tmax, -2.0, C0)) : qmaxf;
             } else if (F64CODE) {
@@ -444,7 +471,8 @@ rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
     if constexpr (fused_pv_supported(KSTEPS, NT)) RQ_QKS_LAUNCH(false, false, false, true);
     else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %d key tiles at d_head = %d do not fit the registers", NT, KSTEPS * 32);
   } else if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true, false);
-  else if (p.bias) RQ_QKS_LAUNCH(true, true, false, false);
+  else if (p.bias && f64) RQ_QKS_LAUNCH(true, true, false, false);
+  else if (p.bias) RQ_QKS_LAUNCH(true, false, false, false);
   else if (p.causal) RQ_QKS_LAUNCH(false, true, true, false);
   else if (f64) RQ_QKS_LAUNCH(false, true, false, false);
   else RQ_QKS_LAUNCH(false, false, false, false);

@@ -134,6 +134,9 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
                                                                     (2, 2, 257, 64, 4, 4, False, False), (1, 2, 288, 128, 8, 8, False, True),
                                                                     (2, 2, 64, 64, 8, 8, False, False), (1, 1, 1, 32, 8, 4, False, False),
                                                                     (1, 2, 33, 64, 8, 6, True, True), (2, 1, 130, 128, 6, 4, False, False),
+                                                                    # bias with codes of at most 6 bits: float32 logits
+                                                                    (2, 4, 49, 32, 6, 4, True, False), (1, 3, 197, 64, 4, 4, True, False),
+                                                                    (1, 2, 100, 128, 6, 6, True, False),
                                                                     # rows beyond 288 keys: the two-sweep kernel
                                                                     (1, 2, 289, 64, 4, 4, False, False), (2, 1, 320, 128, 8, 8, False, True),
                                                                     (1, 3, 500, 32, 6, 6, False, True), (1, 1, 1000, 64, 8, 4, False, False),
