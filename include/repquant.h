@@ -283,8 +283,10 @@ rq_status rq_qk_softmax_log2_quant(rq_ctx* ctx, const rq_qk_softmax_desc* d);
  * rq_qk_softmax_log2_quant followed by rq_attn_pv in ONE kernel: the codes of a query tile's whole row stay
  * packed in registers and become the operand of the shift de-quantized P.V product (case analysis before
  * Eq. (3.3-2)), so neither the logits nor the codes travel through memory.  Same integers, same code arithmetic, same
- * output arithmetic as the separate calls.  Restrictions: no bias, no mask, codes of at most 4 bits (one shift
- * window), N <= 288, d_head in {32, 64, 128}; otherwise RQ_ERR_SHAPE and the caller takes the separate calls.  (The
+ * output arithmetic as the separate calls.  Restrictions: no mask, N <= 288, d_head in {32, 64, 128}; without a bias
+ * and with codes of at most 4 bits (one shift window: int8 matrix cores) every such N; with a bias and / or codes of 5
+ * or 6 bits, rows of up to 160 keys (attention windows; wide codes take the bfloat16 matrix cores as in rq_attn_pv);
+ * otherwise RQ_ERR_SHAPE and the caller takes the separate calls.  (The
  * 257 .. 288-key variants spill registers and are slower than the two separate calls, which rq_block_forward then
  * prefers.)  Q, K, V: token-major device int8 slices of one tensor
  * with row pitch ld_tok (stored code - off).  codes (optional, may be NULL): [batch*H, N, ld] as in
@@ -303,10 +305,11 @@ typedef struct {
   float* out_f32; int64_t ldf;
   int8_t* out_q; int64_t ldq;
   float s_o; int32_t z_o, off_o, bits_o;
+  const float* bias;      /* [H, N, N] dense, or NULL (last member: a zero-filled descriptor of the earlier layout reads as NULL) */
 } rq_attn_fused_desc;
 rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);
 /* 1 if rq_attn_fused supports the shape (host, no context needed). */
-int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p);
+int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p, int32_t has_bias);
 
 /* ---- rq_attn_pv -----------------------------------------------------------------------------------------
  * P.V with shift de-quantized probabilities (case analysis before Eq. (3.3-2) and Eq. (3.3-2)):
@@ -467,7 +470,7 @@ typedef struct {
  * 64 MiB); call before rq_block_workspace_bytes. */
 rq_status rq_set_attn_chunk_bytes(int64_t bytes);
 /* How rq_block_forward runs attention (process-wide; call before rq_block_workspace_bytes):
- *   1 (default): rq_attn_fused where it applies (no bias, no mask, codes of at most 4 bits, short rows), else as 2;
+ *   1 (default): rq_attn_fused where it applies (no mask, short rows; see there), else as 2;
  *   2: rq_qk_softmax_log2_quant + rq_attn_pv wherever that call applies, else as 0;
  *   0: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length.
  * All three compute the same integers and the same codes (rows beyond 288 keys in mode 2: up to the order in which the

@@ -90,7 +90,7 @@ class AttnFusedDesc(C.Structure):
                 ("q_off", i32), ("z_q", i32), ("k_off", i32), ("z_k", i32), ("v_off", i32), ("z_v", i32),
                 ("logit_scale", f64), ("s_log", f32), ("s_v", f32), ("bits_p", i32), ("codes", vp), ("ld", i64),
                 ("out_f32", vp), ("ldf", i64), ("out_q", vp), ("ldq", i64), ("s_o", f32), ("z_o", i32), ("off_o", i32),
-                ("bits_o", i32)]
+                ("bits_o", i32), ("bias", vp)]
 
 
 class PvDesc(C.Structure):
@@ -209,7 +209,7 @@ _rq_softmax = _sig("rq_softmax_log2_quant", i32, [vp, C.POINTER(SoftmaxDesc)])
 _rq_attn_pv = _sig("rq_attn_pv", i32, [vp, C.POINTER(PvDesc)])
 _rq_qk_softmax = _sig("rq_qk_softmax_log2_quant", i32, [vp, C.POINTER(QkSoftmaxDesc)])
 _rq_attn_fused = _sig("rq_attn_fused", i32, [vp, C.POINTER(AttnFusedDesc)])
-_rq_attn_fused_supported = _sig("rq_attn_fused_supported", i32, [i32, i32, i32])
+_rq_attn_fused_supported = _sig("rq_attn_fused_supported", i32, [i32, i32, i32, i32])
 _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
@@ -361,17 +361,17 @@ def rq_qk_softmax_log2_quant(ctx, qkv, batch, seq, H, d_head, q_col, k_col, q_of
     ctx.check(_rq_qk_softmax(ctx.handle, C.byref(d)))
 
 
-def attn_fused_supported(N: int, d_head: int, bits_p: int) -> bool:
-    return bool(_rq_attn_fused_supported(N, d_head, bits_p))
+def attn_fused_supported(N: int, d_head: int, bits_p: int, has_bias: bool = False) -> bool:
+    return bool(_rq_attn_fused_supported(N, d_head, bits_p, int(has_bias)))
 
 
 def rq_attn_fused(ctx, qkv, batch, seq, H, d_head, q_off, z_q, k_off, z_k, v_off, z_v, logit_scale, s_log, s_v, bits_p, *,
-                  codes=None, ld=0, out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
+                  codes=None, ld=0, out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8, bias=None):
     """Whole attention of a [T, 3D] int8 tensor (Q | K | V column blocks) in one kernel."""
     base, D = qkv.data_ptr(), H * d_head
     d = AttnFusedDesc(batch=batch, H=H, N=seq, d_head=d_head, Q=base, K=base + D, V=base + 2 * D, ld_tok=qkv.stride(0),
                       q_off=q_off, z_q=z_q, k_off=k_off, z_k=z_k, v_off=v_off, z_v=z_v, logit_scale=logit_scale, s_log=s_log,
-                      s_v=s_v, bits_p=bits_p, codes=_p(codes), ld=ld)
+                      s_v=s_v, bits_p=bits_p, codes=_p(codes), ld=ld, bias=_p(bias))
     if out_f32 is not None:
         d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
     if out_q is not None:

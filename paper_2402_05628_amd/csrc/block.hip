@@ -27,8 +27,8 @@ bool use_fused(const rq_block_params* p, int64_t seq) {
 
 // the whole attention in one kernel: neither logits nor codes reach memory
 bool use_whole(const rq_block_params* p, int64_t seq) {
-  return g_attn_fused == 1 && p->H > 0 && p->D % p->H == 0 && !p->rel_bias && p->mask == RQ_MASK_NONE &&
-         rq_attn_fused_preferred((int)seq, p->D / p->H, p->bits_p);
+  return g_attn_fused == 1 && p->H > 0 && p->D % p->H == 0 && p->mask == RQ_MASK_NONE &&
+         rq_attn_fused_preferred((int)seq, p->D / p->H, p->bits_p, p->rel_bias != nullptr);
 }
 
 Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
@@ -186,7 +186,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
       d.batch = nb; d.H = H; d.N = (int)seq; d.d_head = dh; d.Q = qkv_c; d.K = qkv_c + D; d.V = qkv_c + 2 * D; d.ld_tok = 3 * D;
       d.q_off = offq; d.z_q = p->z_q; d.k_off = offk; d.z_k = p->z_k; d.v_off = offv; d.z_v = p->z_v;
       d.logit_scale = (double)p->s_q * (double)p->s_k / std::sqrt((double)dh);
-      d.s_log = p->s_log; d.s_v = p->s_v; d.bits_p = p->bits_p;
+      d.s_log = p->s_log; d.s_v = p->s_v; d.bits_p = p->bits_p; d.bias = p->rel_bias;
       d.out_q = o + b0 * seq * D; d.ldq = D; d.s_o = p->s_o; d.z_o = p->z_o; d.off_o = offo; d.bits_o = ba;
       rq_prof_begin(ctx, RQ_STEP_QK);
       st = rq_launch_attn_fused(ctx, &d);

@@ -16,6 +16,8 @@ namespace rqks {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 struct QksParams {
   const int8_t* Q;
@@ -57,6 +59,8 @@ constexpr unsigned QKS_TAB_LO = 0xF0E0C080u, QKS_TAB_HI = 0xFFFEFCF8u;
 // accumulators die as they are converted) and P.V runs afterwards from the packed codes.  (Feeding every tile's codes
 // straight into its P.V products, where both sets fit, measured slower at every shape: 42 against 36 us at ViT-B.)
 constexpr bool fused_pv_supported(int ksteps, int nt) { return nt * 16 <= 176 && nt * 4 + ksteps * 32 <= 176; }
+// the one-kernel attention with a bias and / or codes of 5 or 6 bits exists for rows of up to this many key tiles
+constexpr int FUSED_EXT_TILES = 5;
 
 // LDS per group: keys [nt * 32][dh], then (fused P.V) V^T [dh][nt * 32 + 16]
 constexpr int slot_bytes(int ksteps, int nt, bool pv) { return nt * 32 * ksteps * 32 + (pv ? ksteps * 32 * (nt * 32 + 16) : 0); }
@@ -69,8 +73,12 @@ constexpr int groups_per_pass(int ksteps, int nt, bool pv) {
   return want;
 }
 
-template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, bool PV>
+// PVM: 0 = codes only; 1 = fused P.V on the int8 matrix cores (codes of at most 4 bits: one shift window); 2 = fused P.V
+// for wider codes on the bfloat16 matrix cores: a power of two 2^-k is exact in bfloat16 whatever k is, and so is
+// code - z_v, so there are no windows and no zero-point sum; the products are exact, the sums round in float32.
+template <int KSTEPS, int NT, bool HAS_BIAS, bool F64CODE, bool MASKALL, int PVM>
 __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
+  constexpr bool PV = PVM != 0, WIDE = PVM == 2;
   constexpr int DH = KSTEPS * 32;
   constexpr int TC = DH / 32;
   constexpr int VTP = NT * 32 + 16;     // bytes per V^T row (skewed)
@@ -322,7 +330,8 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     const float C0f = (float)C0, m2cf = (float)m2c;
     // ---- codes (and, fused, their product with V) ----
     uint8_t* crow = p.codes ? p.codes + (g * p.N + (qi < p.N ? qi : 0)) * p.ld : nullptr;
-    v16i E[PV ? TC : 1], O[PV ? TC : 1];
+    v16i E[PV && !WIDE ? TC : 1], O[PV && !WIDE ? TC : 1];
+    v16f Ef[WIDE ? TC : 1], Of[WIDE ? TC : 1];
     v4i tvs[PV ? NT : 1];         // the packed codes of every key tile: P.V runs after all of them
     int se = 0, so = 0;
     // the P.V products of one key tile from its 16 codes per lane
@@ -353,8 +362,55 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
       for (int c = 0; c < TC; ++c) {
         const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
-        E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
-        O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
+        constexpr int ci = 0;      // (dead code in the wide variants, whose int accumulator arrays have one element)
+        E[WIDE ? ci : c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[WIDE ? ci : c], 0, 0, 0);
+        O[WIDE ? ci : c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[WIDE ? ci : c], 0, 0, 0);
+      }
+    };
+    // the same for wide codes: probabilities and values as bfloat16 (contraction index of k-step s: key 8 s + e of the
+    // lane's 16 keys, for both operands)
+    auto pv_tile_wide = [&](int jt, const v4i& tv) {
+      const int j0 = jt * 32 + half * 16;
+      v4i pe[2], po[2];
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4) {
+        unsigned c = (unsigned)tv[d4];
+        if (MASKALL || jt == NT - 1) {      // masked and padding keys read as code 255, whose power of two is stored as zero
+          int nv = limit - (j0 + d4 * 4);
+          nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
+          c |= nv == 4 ? 0u : ~((1u << (8 * nv)) - 1u);
+        }
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          // two codes as halfwords; bfloat16 bits of 2^-k are (127 - k) << 7 = 0x3F80 - ((code & 0xFE) << 6)
+          const unsigned cx = __builtin_amdgcn_perm(0u, c, pr ? 0x0C030C02u : 0x0C010C00u);
+          const unsigned bits = 0x3F803F80u - ((cx & 0x00FE00FEu) << 6);
+          const unsigned odd = (cx & 0x00010001u) * 0xFFFFu;       // 0xFFFF in the halfwords that hold odd codes
+          const unsigned vo = bits & odd;
+          po[d4 >> 1][(d4 & 1) * 2 + pr] = (int)vo;
+          pe[d4 >> 1][(d4 & 1) * 2 + pr] = (int)(bits ^ vo);
+        }
+      }
+      const float dvf = (float)(p.dv - 128);
+#pragma unroll
+      for (int c = 0; c < TC; ++c) {
+        const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          v4i a;      // 8 values code - z_v of this channel as bfloat16 (exact: at most 8 significant bits)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const unsigned u = (unsigned)fv[2 * s + q] ^ 0x80808080u;      // stored code + 128, unsigned
+            const unsigned f0 = __float_as_uint((float)(u & 0xFFu) + dvf), f1 = __float_as_uint((float)((u >> 8) & 0xFFu) + dvf);
+            const unsigned f2 = __float_as_uint((float)((u >> 16) & 0xFFu) + dvf), f3 = __float_as_uint((float)(u >> 24) + dvf);
+            a[2 * q] = (int)__builtin_amdgcn_perm(f1, f0, 0x07060302u);
+            a[2 * q + 1] = (int)__builtin_amdgcn_perm(f3, f2, 0x07060302u);
+          }
+          v16f& ef = Ef[WIDE ? c : 0];
+          v16f& of = Of[WIDE ? c : 0];
+          ef = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, pe[s]), ef, 0, 0, 0);
+          of = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, po[s]), of, 0, 0, 0);
+        }
       }
     };
 #pragma unroll
@@ -398,13 +454,23 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     }
     if (PV) {
       if (more && !requested && task + 8 >= NTASK) { request(gq + (int)gridDim.x * GPB); requested = true; }
+      if (WIDE) {
 #pragma unroll
-      for (int c = 0; c < TC; ++c)
+        for (int c = 0; c < TC; ++c)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
+          for (int e = 0; e < 16; ++e) { Ef[WIDE ? c : 0][e] = 0.f; Of[WIDE ? c : 0][e] = 0.f; }
 #pragma unroll
-      for (int jt = 0; jt < NT; ++jt)
-        if (jt < nt) pv_tile(jt, tvs[jt]);
+        for (int jt = 0; jt < NT; ++jt)
+          if (jt < nt) pv_tile_wide(jt, tvs[jt]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < TC; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { E[WIDE ? 0 : c][e] = 0; O[WIDE ? 0 : c][e] = 0; }
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+          if (jt < nt) pv_tile(jt, tvs[jt]);
+      }
     }
     if (PV) {
       double psE = (double)se, psO = (double)so;
@@ -425,9 +491,12 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
             float y[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              if (p.dv == 0) y[e] = fmaf(ao, (float)O[c][4 * gq + e], ae * (float)E[c][4 * gq + e]);
+              // (wide codes: the probabilities were the powers of two themselves, not -128 times them, and V carried its zero-point)
+              if (WIDE) y[e] = -128.f * fmaf(ao, Of[WIDE ? c : 0][4 * gq + e], ae * Ef[WIDE ? c : 0][4 * gq + e]);
+              else if (p.dv == 0) y[e] = fmaf(ao, (float)O[WIDE ? 0 : c][4 * gq + e], ae * (float)E[WIDE ? 0 : c][4 * gq + e]);
               else   // the zero-point term cancels most of the sum: form it in float64
-                y[e] = (float)(p.a_even * ((double)E[c][4 * gq + e] + (double)p.dv * psE) + p.a_odd * ((double)O[c][4 * gq + e] + (double)p.dv * psO));
+                y[e] = (float)(p.a_even * ((double)E[WIDE ? 0 : c][4 * gq + e] + (double)p.dv * psE) +
+                               p.a_odd * ((double)O[WIDE ? 0 : c][4 * gq + e] + (double)p.dv * psO));
             }
             if (p.out_f32)
               *reinterpret_cast<float4*>(p.out_f32 + tok * p.ldf + col) = make_float4(y[0], y[1], y[2], y[3]);
@@ -468,14 +537,21 @@ rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
   } while (0)
   // the float64 code path also serves every masked or biased case; the lean variant is the common one
   if (pv) {
-    if constexpr (fused_pv_supported(KSTEPS, NT)) RQ_QKS_LAUNCH(false, false, false, true);
-    else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %d key tiles at d_head = %d do not fit the registers", NT, KSTEPS * 32);
-  } else if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true, false);
-  else if (p.bias && f64) RQ_QKS_LAUNCH(true, true, false, false);
-  else if (p.bias) RQ_QKS_LAUNCH(true, false, false, false);
-  else if (p.causal) RQ_QKS_LAUNCH(false, true, true, false);
-  else if (f64) RQ_QKS_LAUNCH(false, true, false, false);
-  else RQ_QKS_LAUNCH(false, false, false, false);
+    const bool wide = p.qmax > 15;      // more than one window of 8 shifts
+    if constexpr (fused_pv_supported(KSTEPS, NT)) {
+      if (!p.bias && !wide) RQ_QKS_LAUNCH(false, false, false, 1);
+      else if constexpr (NT <= FUSED_EXT_TILES) {      // with a bias and / or wide codes: windows of up to 160 keys
+        if (p.bias && wide) RQ_QKS_LAUNCH(true, false, false, 2);
+        else if (wide) RQ_QKS_LAUNCH(false, false, false, 2);
+        else RQ_QKS_LAUNCH(true, false, false, 1);
+      } else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention with a bias or wide codes: %d key tiles not supported", NT);
+    } else return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %d key tiles at d_head = %d do not fit the registers", NT, KSTEPS * 32);
+  } else if (p.bias && p.causal) RQ_QKS_LAUNCH(true, true, true, 0);
+  else if (p.bias && f64) RQ_QKS_LAUNCH(true, true, false, 0);
+  else if (p.bias) RQ_QKS_LAUNCH(true, false, false, 0);
+  else if (p.causal) RQ_QKS_LAUNCH(false, true, true, 0);
+  else if (f64) RQ_QKS_LAUNCH(false, true, false, 0);
+  else RQ_QKS_LAUNCH(false, false, false, 0);
 #undef RQ_QKS_LAUNCH
   RQ_HIP(hipGetLastError());
   return RQ_OK;

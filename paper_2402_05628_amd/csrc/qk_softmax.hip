@@ -8,16 +8,19 @@ rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64
 rq_status rq_launch_qk_softmax_long(rq_ctx* ctx, const rqks::QksParams& p, int d_head);
 
 
-extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p) {
-  if (N <= 0 || N > 288 || bits_p < 2 || bits_p > 4 || !(d_head == 32 || d_head == 64 || d_head == 128)) return 0;
-  return rqks::fused_pv_supported(d_head / 32, (N + 31) / 32) ? 1 : 0;
+extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p, int32_t has_bias) {
+  if (N <= 0 || N > 288 || bits_p < 2 || !(d_head == 32 || d_head == 64 || d_head == 128)) return 0;
+  const int nt = (N + 31) / 32;
+  if (!rqks::fused_pv_supported(d_head / 32, nt)) return 0;
+  if (bits_p <= 4 && !has_bias) return 1;
+  return bits_p <= 6 && nt <= rqks::FUSED_EXT_TILES ? 1 : 0;      // with a bias and / or codes of 5 or 6 bits
 }
 
 // Where the one-kernel attention is also the faster choice: up to 8 key tiles.  Nine tiles (257 .. 288 keys) on the 8
 // wavefronts of a workgroup take two rounds per group; rq_qk_softmax_log2_quant + rq_attn_pv are then as fast or faster
 // (257 keys, d_head 64, 1024 groups: 117 us against 53 + 51 us).
-bool rq_attn_fused_preferred(int N, int d_head, int bits_p) {
-  if (!rq_attn_fused_supported(N, d_head, bits_p)) return false;
+bool rq_attn_fused_preferred(int N, int d_head, int bits_p, bool has_bias) {
+  if (!rq_attn_fused_supported(N, d_head, bits_p, has_bias)) return false;
   return (N + 31) / 32 <= 8;
 }
 
@@ -25,7 +28,7 @@ rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   QksParams p;
   p.Q = d->Q; p.K = d->K; p.V = d->V; p.ldq = d->ld_tok; p.ldk = d->ld_tok; p.so = (int64_t)d->N * d->ld_tok; p.si = d->d_head;
   p.H = d->H; p.N = d->N; p.dq = d->q_off - d->z_q; p.dk = d->k_off - d->z_k; p.dv = d->v_off - d->z_v;
-  p.bias = nullptr; p.causal = 0;
+  p.bias = d->bias; p.causal = 0;
   p.c1 = d->logit_scale * 1.4426950408889634; p.log2s = log2((double)d->s_log); p.qmax = (1 << d->bits_p) - 1;
   p.codes = d->codes; p.ld = d->ld; p.tiles = (d->N + 31) / 32;
   const double ss = (double)d->s_log * (double)d->s_v;

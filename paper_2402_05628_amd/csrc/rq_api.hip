@@ -369,9 +369,10 @@ rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   RQ_REQUIRE(d->batch >= 0 && d->H > 0 && d->N > 0, RQ_ERR_SHAPE, "rq_attn_fused: batch = %lld, H = %d, N = %d", (long long)d->batch,
              d->H, d->N);
   RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_fused: bits_p = %d not in 2..8", d->bits_p);
-  RQ_REQUIRE(rq_attn_fused_supported(d->N, d->d_head, d->bits_p), RQ_ERR_SHAPE,
-             "rq_attn_fused: N = %d, d_head = %d, bits_p = %d outside the fused kernel's range; use the separate calls", d->N,
-             d->d_head, d->bits_p);
+  RQ_REQUIRE(rq_attn_fused_supported(d->N, d->d_head, d->bits_p, d->bias != nullptr), RQ_ERR_SHAPE,
+             "rq_attn_fused: N = %d, d_head = %d, bits_p = %d%s outside the fused kernel's range; use the separate calls", d->N,
+             d->d_head, d->bits_p, d->bias ? " with a bias" : "");
+  RQ_REQUIRE(rq_aligned(d->bias, 4), RQ_ERR_INVALID_ARG, "rq_attn_fused: bias needs 4-byte alignment");
   RQ_REQUIRE(d->ld_tok >= (int64_t)d->H * d->d_head && d->ld_tok % 16 == 0, RQ_ERR_SHAPE,
              "rq_attn_fused: ld_tok = %lld must be >= H*d_head and a multiple of 16", (long long)d->ld_tok);
   RQ_REQUIRE(rq_aligned(d->Q, 16) && rq_aligned(d->K, 16) && rq_aligned(d->V, 4), RQ_ERR_INVALID_ARG,

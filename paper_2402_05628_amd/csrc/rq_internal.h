@@ -53,7 +53,7 @@ rq_status rq_launch_qgemm_act(rq_ctx* ctx, const rq_gemm_desc* d);
 rq_status rq_launch_softmax(rq_ctx* ctx, const rq_softmax_desc* d);
 rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d);
 bool rq_qk_softmax_supported(int N, int d_head, bool has_bias);
-bool rq_attn_fused_preferred(int N, int d_head, int bits_p);
+bool rq_attn_fused_preferred(int N, int d_head, int bits_p, bool has_bias);
 bool rq_qgemm_rowln_applies(const rq_gemm_desc* g, const rq_ln_desc* ln);
 rq_status rq_launch_qgemm_rowln(rq_ctx* ctx, const rq_gemm_desc* g, const rq_ln_desc* ln);
 rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);

@@ -265,10 +265,13 @@ def test_attn_fused_validation(b, host_ctx):
     fd = dict(batch=1, H=2, N=64, d_head=64, Q=FAKE, K=FAKE, V=FAKE, ld_tok=384, q_off=3, z_q=3, k_off=3, z_k=3, v_off=3, z_v=3,
               logit_scale=0.1, s_log=1.0, s_v=0.1, bits_p=4, codes=None, ld=0, out_f32=FAKE, ldf=128)
     assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**fd))) == 3
-    for k, v, want in (("N", 320, 2), ("bits_p", 6, 2), ("d_head", 48, 2), ("V", None, 1), ("out_f32", None, 1), ("s_v", 0.0, 1),
+    for k, v, want in (("N", 320, 2), ("bits_p", 7, 2), ("d_head", 48, 2), ("V", None, 1), ("out_f32", None, 1), ("s_v", 0.0, 1),
                        ("ld_tok", 100, 2), ("ldf", 64, 2)):
         assert b.lib.rq_attn_fused(host_ctx.handle, C.byref(b.AttnFusedDesc(**{**fd, k: v}))) == want, (k, v)
     assert b.attn_fused_supported(197, 64, 4) and b.attn_fused_supported(257, 64, 4) and not b.attn_fused_supported(197, 64, 6)
+    # with a bias and / or codes of 5 or 6 bits: rows of up to 160 keys
+    assert b.attn_fused_supported(49, 32, 6, True) and b.attn_fused_supported(160, 64, 5) and not b.attn_fused_supported(161, 64, 4, True)
+    assert not b.attn_fused_supported(49, 32, 7) and not b.attn_fused_supported(49, 32, 8, True)
     assert b.attn_fused_supported(288, 128, 4) and not b.attn_fused_supported(289, 32, 4) and b.attn_fused_supported(96, 128, 4)
 
 

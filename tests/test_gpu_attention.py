@@ -189,9 +189,21 @@ def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causa
                                                         (2, 1, 288, 64, 4, 4), (1, 2, 160, 128, 4, 4), (1, 2, 288, 128, 8, 4)])
 def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     """rq_attn_fused (one kernel) against the oracle's logits -> log-sqrt2 codes -> shift de-quantized P.V -> uniform codes."""
+    _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, False)
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p,bias", [(4, 4, 49, 32, 6, 6, True), (3, 2, 49, 32, 4, 4, True), (2, 3, 64, 32, 6, 5, False),
+                                                             (2, 2, 144, 32, 6, 6, True), (1, 2, 160, 64, 8, 6, False), (2, 1, 100, 128, 6, 6, True),
+                                                             (1, 1, 1, 32, 6, 6, True), (2, 2, 33, 64, 4, 3, True)])
+def test_attn_fused_whole_windows(rq, batch, H, seq, dh, bits, bits_p, bias):
+    """The one-kernel attention with a relative-position bias and / or codes of 5 or 6 bits (bfloat16 P.V): window attention."""
+    _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias)
+
+
+def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias):
     b, ctx = rq
-    print("case", batch, H, seq, dh, bits, bits_p, flush=True)
-    assert b.attn_fused_supported(seq, dh, bits_p)
+    print("case", batch, H, seq, dh, bits, bits_p, bias, flush=True)
+    assert b.attn_fused_supported(seq, dh, bits_p, bias)
     g = np.random.default_rng(seq * 3 + dh + bits)
     D = H * dh
     qmax = 2 ** bits - 1
@@ -208,6 +220,7 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     ld = _ld(seq)
     scale = s_qk * s_qk / math.sqrt(dh)
     s_log, s_v = np.float32(0.8), np.float32(s_qk)
+    bias_a = g.normal(0, 0.5, size=(H, seq, seq)).astype(np.float32) if bias else None
     want_codes = np.empty((batch * H, seq, seq), np.int64)
     want = np.empty((batch * seq, D))
     for bi in range(batch):
@@ -215,7 +228,10 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
         for h in range(H):
             c = slice(h * dh, (h + 1) * dh)
             acc = orc.int_matmul_nt(codes[r, c] - z[0], codes[r, D + h * dh:D + (h + 1) * dh] - z[1])
-            pc = orc.softmax_log_quant(acc.astype(np.float64) * scale, s_log, bits_p)
+            L = acc.astype(np.float64) * scale
+            if bias:
+                L = L + bias_a[h].astype(np.float64)
+            pc = orc.softmax_log_quant(L, s_log, bits_p)
             want_codes[bi * H + h] = pc
             want[r, c] = orc.attn_pv(pc, codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log, s_v, z[2], False)
     s_o = np.float32((want.max() - want.min()) / qmax)
@@ -225,7 +241,8 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     outf = torch.zeros((batch * seq, D), dtype=torch.float32, device="cuda")
     outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
     b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
-                    codes=outc, ld=ld, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+                    codes=outc, ld=ld, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits,
+                    bias=None if bias_a is None else dev(bias_a))
     got_codes = outc.cpu().numpy()[:, :, :seq]
     frac = assert_codes_close(got_codes, want_codes, "fused attention codes")
     # float32 epilogue on exact integer sums: the even- and odd-code terms can cancel, so an element far below the row's
@@ -244,5 +261,5 @@ def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     # without the optional codes output the result is the same
     outq2 = torch.zeros_like(outq)
     b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
-                    out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+                    out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits, bias=None if bias_a is None else dev(bias_a))
     assert torch.equal(outq, outq2)
