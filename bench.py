@@ -206,8 +206,8 @@ def main():
                          "the per-channel clipping factors on the same activations; gptq: GPTQ of the QKV weights against them")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (every box here has one); --gpus %d is not supported. "
-              "DESIGN.md describes how the path would shard." % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (batch items never interact, so more GPUs "
+              "would each take a slice of the batch with the same folded weights)." % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
