@@ -41,8 +41,7 @@ struct PvParams {
   int num_cu;          // causal: every second round of workgroups walks its group's query tiles backwards
 };
 
-constexpr int JB = 256;          // keys staged per LDS block
-constexpr int VT_PITCH = JB + 16;  // bytes per V^T row (skewed: 68 dwords -> conflict-free 16-byte reads)
+constexpr int JB = 256;          // keys staged per LDS block (288 for rows of 257 .. 288 keys)
 
 // table of -(128 >> k), k = 0..7, as the 8 bytes {lo dword, hi dword} for v_perm_b32
 constexpr unsigned TAB_LO = 0xF0E0C080u, TAB_HI = 0xFFFEFCF8u;
@@ -56,8 +55,11 @@ __device__ __forceinline__ unsigned byte_eq_mask(unsigned x, unsigned ref4) {
 }
 
 // WIDE: codes wider than 4 bits (several windows); rows of more than 256 keys with such codes go to pv_long_kernel.
-template <int DH, bool WIDE>
+// JBK: keys staged per LDS block, 256, or 288 for rows of 257 .. 288 keys (one block instead of a second one for a few keys:
+// every block costs a load -> transpose -> barrier round trip that the few MFMAs of a short row do not hide).
+template <int DH, bool WIDE, int JBK>
 __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
+  constexpr int JB = JBK, VT_PITCH = JBK + 16;      // bytes per V^T row (skewed: 68 / 76 dwords -> conflict-free 16-byte reads)
   constexpr int TC = DH / 32;
   constexpr int CP = DH / 16;          // 16-byte pieces per key row
   // V^T: channel r at byte r * VT_PITCH + (r / 16) * 16 -- the extra 16 bytes per 16 channels spread the transposing
@@ -149,6 +151,16 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
     }
 
   for (int jb = 0; jb < nk_block; jb += JB) {
+    // this wavefront's keys of the block, and (narrow codes) the codes of its first two key tiles, requested before the
+    // values are staged so that the two latencies overlap
+    int jend = nk_wave - jb;
+    jend = jend < JB ? jend : JB;
+    auto codes_of = [&](int js) {
+      const int j0 = jb + js + half * 16;
+      return (js < jend && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
+    };
+    v4i c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
+    if (!WIDE) { c0 = codes_of(0); c1 = codes_of(32); }
     __syncthreads();
     // ---- stage V^T for keys jb .. jb+JB-1: thread -> (4 keys, 16 channels); the lanes of a wavefront read whole key
     // rows (16 bytes each), the bytes are transposed in registers, and every channel's 4 keys go out as one dword ----
@@ -179,8 +191,6 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
     }
     __syncthreads();
     if (jb >= nk_wave) continue;
-    int jend = nk_wave - jb;
-    jend = jend < JB ? jend : JB;
     for (int w = 0; w < (WIDE ? WINDOWS : 1); ++w) {
       if (WIDE && !((present >> w) & 1u)) continue;
       if (WIDE) {
@@ -226,15 +236,9 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
           O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
         }
       };
-      // the codes of the next two key tiles are in flight while the current one is worked on
-      auto codes_of = [&](int js) {
-        const int j0 = jb + js + half * 16;
-        return (js < jend && j0 < p.ld) ? *reinterpret_cast<const v4i*>(crow + j0) : v4i{0, 0, 0, 0};
-      };
       if (WIDE) {       // short rows, visited once per window: the extra registers would cost a wavefront per SIMD
         for (int js = 0; js < jend; js += 32) key_tile(js, codes_of(js));
       } else {
-        v4i c0 = codes_of(0), c1 = codes_of(32);
         for (int js = 0; js < jend; js += 32) {
           const v4i c2 = codes_of(js + 64);
           key_tile(js, c0);
@@ -498,8 +502,9 @@ template <int DH>
 void launch(rq_ctx* ctx, const PvParams& p, int64_t groups, bool wide) {
   const int blocks_per_group = (p.tiles_i + 3) / 4;
   const dim3 grid((unsigned)(groups * blocks_per_group));
-  if (wide) hipLaunchKernelGGL((pv_kernel<DH, true>), grid, dim3(256), 0, ctx->stream, p);
-  else hipLaunchKernelGGL((pv_kernel<DH, false>), grid, dim3(256), 0, ctx->stream, p);
+  if (wide) hipLaunchKernelGGL((pv_kernel<DH, true, 256>), grid, dim3(256), 0, ctx->stream, p);
+  else if (p.Nk > 256 && p.Nk <= 288) hipLaunchKernelGGL((pv_kernel<DH, false, 288>), grid, dim3(256), 0, ctx->stream, p);
+  else hipLaunchKernelGGL((pv_kernel<DH, false, 256>), grid, dim3(256), 0, ctx->stream, p);
 }
 
 }  // namespace
