@@ -148,10 +148,10 @@ void launch_tile(rq_ctx* ctx, GemmParams& p) {
 
 }  // namespace
 
-static int g_gemm_tile = 0;   // 0: choose by shape, 1: 128x128 simple, 2: 256x128 simple, 3: pipelined; 4 .. 7: pipelined with 320- / 192- / 128- / 256-row tiles where they exist
+static int g_gemm_tile = 0;   // 0: choose by shape, 1: 128x128 simple, 2: 256x128 simple, 3: pipelined; 4 .. 7: pipelined with 320- / 192- / 128- / 256-row tiles where they exist; 8: 256 x 256 tiles
 
 extern "C" rq_status rq_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 7) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: %d not in 0..7", tile);
+  if (tile < 0 || tile > 8) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: %d not in 0..8", tile);
   g_gemm_tile = tile;
   return RQ_OK;
 }
@@ -184,7 +184,7 @@ rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   const int64_t big_tiles = ((d->M + 255) / 256) * ((d->N + 127) / 128);
   const bool big = g_gemm_tile ? g_gemm_tile == 2 : big_tiles >= 2 * (int64_t)ctx->num_cu;
   const bool fits32 = (double)d->M * (double)d->lda < 4.0e9 && (double)d->N * (double)d->ldb < 4.0e9;
-  p.force_rows = g_gemm_tile == 4 ? 5 : (g_gemm_tile == 5 ? 3 : (g_gemm_tile == 6 ? 2 : (g_gemm_tile == 7 ? 4 : 0)));
+  p.force_rows = g_gemm_tile == 4 ? 5 : (g_gemm_tile == 5 ? 3 : (g_gemm_tile == 6 ? 2 : (g_gemm_tile == 7 ? 4 : (g_gemm_tile == 8 ? 6 : 0))));
   if (g_gemm_tile == 0 && rq_qgemv_applies(p, w4)) return rq_launch_qgemv_w4(ctx, p);   // a few tokens: weight-bandwidth bound
   if ((g_gemm_tile == 3 || g_gemm_tile == 0 || g_gemm_tile >= 4) && d->N % 32 == 0 && fits32) {
     const rq_status st = w4 ? rq_launch_qgemm_pipe_w4(ctx, p) : rq_launch_qgemm_pipe_i8(ctx, p);

@@ -11,15 +11,17 @@ namespace rqg {
 // Per-column epilogue constants.  They are fetched at kernel start (one column per thread), parked in registers
 // over the main loop and handed over through the start of the then-idle LDS ring, so that no global or scalar
 // memory latency sits in front of the first output of a tile.
-struct EpiLds {
-  float scale[128];      // s_a * s_w[n]
-  float bias[128];
-  int cs[128];           // (a_off - z_a) * colsum_w[n]
-  int dw[128];           // 128 - z_w[n] for centered weights, else 0
-  float is[128];         // 1 / s_o of the output column's re-quantization segment
-  float zz[128];         // z_o of that segment
-  int off4[128];         // storage offset of that segment replicated in 4 bytes
+template <int BN>
+struct EpiLdsT {
+  float scale[BN];      // s_a * s_w[n]
+  float bias[BN];
+  int cs[BN];           // (a_off - z_a) * colsum_w[n]
+  int dw[BN];           // 128 - z_w[n] for centered weights, else 0
+  float is[BN];         // 1 / s_o of the output column's re-quantization segment
+  float zz[BN];         // z_o of that segment
+  int off4[BN];         // storage offset of that segment replicated in 4 bytes
 };
+typedef EpiLdsT<128> EpiLds;
 
 enum { OUT_ACC = 1, OUT_F32 = 2, OUT_RES = 4, OUT_Q = 8, OUT_ANY = 15 };
 
@@ -28,8 +30,8 @@ enum { OUT_ACC = 1, OUT_F32 = 2, OUT_RES = 4, OUT_Q = 8, OUT_ANY = 15 };
 //  * v_cvt_pk_u8_f32 rounds to nearest-even, saturates to 0..255 and packs in one instruction; two
 //    v_permlane32_swap exchange dwords between lane l and lane l+32 (which hold interleaved groups of 4 channels of
 //    the same token) so that each lane owns 16 consecutive channels and issues one 16-byte store.
-template <int TM, int TN, int ACT, int OUT, bool CHECK>
-__device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[TN][TM], const EpiLds* el, const int (&rs)[TM],
+template <int TM, int TN, int ACT, int OUT, bool CHECK, typename EL = EpiLds>
+__device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[TN][TM], const EL* el, const int (&rs)[TM],
                                               int m0, int n0, int wm0, int wn0, int lane) {
   const int lcol = lane & 31, half = lane >> 5, lrow4 = half * 4;
   constexpr bool gated = ACT == RQ_ACT_SILU_GATED;
@@ -157,59 +159,64 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
 // pieces of 32 different rows per instruction.  Each wavefront instead passes 32 x 64 outputs at a time through its
 // own 8.5 KB of the idle ring (row pitch 68 floats: conflict-free both ways) and then reads, adds and writes whole
 // 256-byte row segments, 16 lanes per row; the residual segments are requested before the LDS round trip.
-template <int TM, int TN, bool CHECK>
-__device__ __forceinline__ void epilogue_rows_f32(const GemmParams& p, v16i (&acc)[TN][TM], const EpiLds* el, const int (&rs)[TM],
+template <int TM, int TN, bool CHECK, typename EL = EpiLds>
+__device__ __forceinline__ void epilogue_rows_f32(const GemmParams& p, v16i (&acc)[TN][TM], const EL* el, const int (&rs)[TM],
                                                   float* stage, int m0, int n0, int wm0, int wn0, int lane) {
-  static_assert(TN == 2, "64 output columns per wavefront");
+  static_assert(TN % 2 == 0, "64 output columns per wavefront and pass");
   constexpr int PITCH = 68;
   const int l32 = lane & 31, half = lane >> 5;
   const int rrow = lane >> 4, rcol = (lane & 15) * 4;        // read-back: 4 rows x 16 float4 per pass
   const bool corr = p.da != 0 || p.centered;
   const int Mi = (int)p.M;
-  const int ncol = n0 + wn0 + rcol;
-  const bool col_ok = ncol < p.N;
   const float* const residual = p.residual;
   float* const out = p.out_f32;
   const int64_t ldr = p.ldr, ldf = p.ldf;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int mb = m0 + wm0 + i * 32;
-    float4 res[8];
+  for (int jh = 0; jh < TN; jh += 2) {       // 64 columns at a time
+    const int ncol = n0 + wn0 + jh * 32 + rcol;
+    const bool col_ok = ncol < p.N;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int m = mb + r * 4 + rrow;
-      res[r] = (col_ok && (!CHECK || m < Mi)) ? *reinterpret_cast<const float4*>(residual + (int64_t)m * ldr + ncol)
-                                              : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int i = 0; i < TM; ++i) {
+      const int mb = m0 + wm0 + i * 32;
+      float4 res[8];
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int nl = wn0 + j * 32 + 8 * g + half * 4;
-        const float4 sc = *reinterpret_cast<const float4*>(&el->scale[nl]);
-        const float4 bi = *reinterpret_cast<const float4*>(&el->bias[nl]);
-        int t[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) t[e] = acc[j][i][4 * g + e];
-        if (corr) {
-          const v4i cs = *reinterpret_cast<const v4i*>(&el->cs[nl]);
-          const v4i dw = *reinterpret_cast<const v4i*>(&el->dw[nl]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) t[e] += cs[e] + dw[e] * rs[i];
-        }
-        const float4 y = make_float4(fmaf((float)t[0], sc.x, bi.x), fmaf((float)t[1], sc.y, bi.y), fmaf((float)t[2], sc.z, bi.z),
-                                     fmaf((float)t[3], sc.w, bi.w));
-        *reinterpret_cast<float4*>(stage + l32 * PITCH + j * 32 + 8 * g + half * 4) = y;
+      for (int r = 0; r < 8; ++r) {
+        const int m = mb + r * 4 + rrow;
+        res[r] = (col_ok && (!CHECK || m < Mi)) ? *reinterpret_cast<const float4*>(residual + (int64_t)m * ldr + ncol)
+                                                : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // this wavefront's own writes; no other wavefront touches `stage`
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int m = mb + r * 4 + rrow;
-      const float4 y = *reinterpret_cast<const float4*>(stage + (r * 4 + rrow) * PITCH + rcol);
-      if (col_ok && (!CHECK || m < Mi))
-        *reinterpret_cast<float4*>(out + (int64_t)m * ldf + ncol) = make_float4(y.x + res[r].x, y.y + res[r].y, y.z + res[r].z, y.w + res[r].w);
+      for (int jj = 0; jj < 2; ++jj) {
+        const int j = jh + jj;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int nl = wn0 + j * 32 + 8 * g + half * 4;
+          const float4 sc = *reinterpret_cast<const float4*>(&el->scale[nl]);
+          const float4 bi = *reinterpret_cast<const float4*>(&el->bias[nl]);
+          int t[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t[e] = acc[j][i][4 * g + e];
+          if (corr) {
+            const v4i cs = *reinterpret_cast<const v4i*>(&el->cs[nl]);
+            const v4i dw = *reinterpret_cast<const v4i*>(&el->dw[nl]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] += cs[e] + dw[e] * rs[i];
+          }
+          const float4 y = make_float4(fmaf((float)t[0], sc.x, bi.x), fmaf((float)t[1], sc.y, bi.y), fmaf((float)t[2], sc.z, bi.z),
+                                       fmaf((float)t[3], sc.w, bi.w));
+          *reinterpret_cast<float4*>(stage + l32 * PITCH + jj * 32 + 8 * g + half * 4) = y;
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // this wavefront's own writes; no other wavefront touches `stage`
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int m = mb + r * 4 + rrow;
+        const float4 y = *reinterpret_cast<const float4*>(stage + (r * 4 + rrow) * PITCH + rcol);
+        if (col_ok && (!CHECK || m < Mi))
+          *reinterpret_cast<float4*>(out + (int64_t)m * ldf + ncol) = make_float4(y.x + res[r].x, y.y + res[r].y, y.z + res[r].z, y.w + res[r].w);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // reads done before the next pass overwrites the region
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // reads done before the next pass overwrites the region
   }
 }
 
@@ -245,20 +252,26 @@ constexpr int pipe_occupancy(int TM, int OUT) {
   return TM <= 2 ? 4 : (TM == 3 ? (OUT == OUT_Q ? 3 : 2) : (TM == 4 ? 2 : 1));
 }
 
-template <bool W4, int S, int ACT, int OUT, int TM>
-__global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
-  constexpr int BM = 64 * TM, BN = 128, TN = 2;       // TM = 4: 256 x 128 tiles, two workgroups per CU; TM = 5: 320 x 128, one
+// TN = 2: tiles 128 columns wide (wavefront tile 32 TM x 64); TN = 4: 256 columns (wavefront tile 32 TM x 128, one workgroup
+// per CU): per MFMA half the bytes through the CU's load path and the LDS, for large products with a long K loop.
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2>
+__global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;           // TM = 4: 256-row tiles, two workgroups per CU; TM = 5: 320 rows, one
   constexpr int A_BYTES = BM * 64;
   constexpr int B_BYTES = W4 ? BN * 32 : BN * 64;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int LPS = TM + (W4 ? 1 : 2);              // loads per thread and stage
+  constexpr int BL = W4 ? TN / 2 : TN;                // weight loads per thread and stage
+  constexpr int LPS = TM + BL;                        // loads per thread and stage
+  typedef EpiLdsT<BN> EL;
+  constexpr int EPI_BYTES = TN == 2 ? 4096 : 8192;    // the epilogue constants at the start of the idle ring
+  static_assert(sizeof(EL) <= EPI_BYTES, "epilogue constants");
   static_assert(S >= 2 && (S - 1) * LPS <= 63, "ring depth (the load counter holds 63)");
   extern __shared__ __align__(16) int8_t ring[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 1) * (32 * TM), wn0 = (wave & 1) * 64;
+  const int wm0 = (wave >> 1) * (32 * TM), wn0 = (wave & 1) * (32 * TN);
   const int l32 = lane & 31, half = lane >> 5;
 
   // tile of this workgroup: XCD b % 8 gets the contiguous range [xcd * per_xcd, ...) of the tile list (n fastest)
@@ -274,7 +287,7 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
   // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
   // lane l lands at 16-byte slot l of a 1 KB block = 16 tile rows of 64 B; the chunk that belongs at position
   // (lane & 3) of row (lane >> 2) is chunk ((lane & 3) - (row >> 2)) & 3
-  unsigned aofs[TM], bofs[2];
+  unsigned aofs[TM], bofs[BL];
   {
     const int dl_row = lane >> 2;
     const int dl_c = ((lane & 3) - (dl_row >> 2)) & 3;
@@ -286,15 +299,17 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
       aofs[i] = (unsigned)m * (unsigned)p.lda + (unsigned)(dl_c * 16);
     }
     if (W4) {
-      const int row = tid >> 1;
-      int n = n0 + row;
-      n = n < p.N ? n : p.N - 1;
-      bofs[0] = (unsigned)n * (unsigned)p.ldb + (unsigned)(((tid & 1) ^ ((row >> 3) & 1)) * 16);
-      bofs[1] = bofs[0];
+#pragma unroll
+      for (int u = 0; u < BL; ++u) {       // 128 weight rows (32 bytes each) per load of the workgroup
+        const int row = u * 128 + (tid >> 1);
+        int n = n0 + row;
+        n = n < p.N ? n : p.N - 1;
+        bofs[u] = (unsigned)n * (unsigned)p.ldb + (unsigned)(((tid & 1) ^ ((row >> 3) & 1)) * 16);
+      }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        int n = n0 + wave * 32 + i * 16 + dl_row;
+      for (int i = 0; i < BL; ++i) {
+        int n = n0 + wave * (16 * BL) + i * 16 + dl_row;
         n = n < p.N ? n : p.N - 1;
         bofs[i] = (unsigned)n * (unsigned)p.ldb + (unsigned)(dl_c * 16);
       }
@@ -310,13 +325,15 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gA + (aofs[i] + (unsigned)kt * 64u)),
                                        (__attribute__((address_space(3))) void*)(la + (wave * TM + i) * 1024), 16, 0, 0);
     if (W4) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[0] + (unsigned)kt * 32u)),
-                                       (__attribute__((address_space(3))) void*)(lb + wave * 1024), 16, 0, 0);
+#pragma unroll
+      for (int u = 0; u < BL; ++u)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[u] + (unsigned)kt * 32u)),
+                                         (__attribute__((address_space(3))) void*)(lb + u * 4096 + wave * 1024), 16, 0, 0);
     } else {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < BL; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[i] + (unsigned)kt * 64u)),
-                                         (__attribute__((address_space(3))) void*)(lb + (wave * 2 + i) * 1024), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)(lb + (wave * BL + i) * 1024), 16, 0, 0);
     }
   };
 #ifdef RQ_GEMM_TS   // development builds only: per-workgroup cycle stamps of the kernel's phases
@@ -334,7 +351,7 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
   RQ_TS(0);
   // The weight zero-points are needed by the first unpack.  Loads return in order, so they are requested BEFORE the ring
   // loads (and first used after them): their wait then does not include the ring's first stages.
-  int zraw[TN] = {0, 0};
+  int zraw[TN] = {};
   if (W4) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -407,22 +424,27 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0;
   // per-column epilogue constants: one column per thread pair, fetched now, parked in two registers over the main loop
-  float ep_f, ep_is = 0.f, ep_zz = 0.f; int ep_i, ep_off = 0;
-  {
-    int n = n0 + (tid & 127);
+  // (wide tiles: CPT columns per thread, 128 apart)
+  constexpr int CPT = BN / 128;
+  float ep_f[CPT], ep_is[CPT], ep_zz[CPT]; int ep_i[CPT], ep_off[CPT];
+#pragma unroll
+  for (int u = 0; u < CPT; ++u) {
+    ep_is[u] = 0.f; ep_zz[u] = 0.f; ep_off[u] = 0;
+    const int col = (tid & 127) + 128 * u;
+    int n = n0 + col;
     n = n < p.N ? n : p.N - 1;
     if (tid < 128) {
-      ep_f = p.s_a * p.s_b[n];
-      ep_i = (p.da != 0 && p.colsum_b) ? p.da * p.colsum_b[n] : 0;
-      if ((OUT & OUT_Q) && p.out_q) {   // re-quantization constants of output column tid of this tile
-        const int no = (ACT == RQ_ACT_SILU_GATED ? n0 / 2 : n0) + tid;
+      ep_f[u] = p.s_a * p.s_b[n];
+      ep_i[u] = (p.da != 0 && p.colsum_b) ? p.da * p.colsum_b[n] : 0;
+      if ((OUT & OUT_Q) && p.out_q) {   // re-quantization constants of output column col of this tile
+        const int no = (ACT == RQ_ACT_SILU_GATED ? n0 / 2 : n0) + col;
         int sg = p.n_seg > 1 ? no / p.seg_len : 0;
         sg = sg < p.n_seg ? sg : p.n_seg - 1;
-        ep_is = p.inv_so[sg]; ep_zz = p.zcode[sg]; ep_off = p.off4[sg];
+        ep_is[u] = p.inv_so[sg]; ep_zz[u] = p.zcode[sg]; ep_off[u] = p.off4[sg];
       }
     } else {
-      ep_f = p.bias ? p.bias[n] : 0.f;
-      ep_i = p.centered ? 128 - p.z_b[n] : 0;
+      ep_f[u] = p.bias ? p.bias[n] : 0.f;
+      ep_i[u] = p.centered ? 128 - p.z_b[n] : 0;
     }
   }
   int rs[TM] = {};
@@ -467,10 +489,11 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
       const int i = q / TN, j = q % TN;
       acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[j][i], 0, 0, 0);
       if (W4) {
-        if (TM * TN >= 8) { if (q < 8) unpack_dword(fbn, 1, q); }
-        else {     // fewer MFMAs than operand dwords: spread the 8 pieces over all of them
+        constexpr int NDW = TN * 4;      // operand dwords of a sub-step
+        if (TM * TN >= NDW) { if (q < NDW) unpack_dword(fbn, 1, q); }
+        else {     // fewer MFMAs than operand dwords: spread the pieces over all of them
 #pragma unroll
-          for (int d = q * 8 / (TM * TN); d < (q + 1) * 8 / (TM * TN); ++d) unpack_dword(fbn, 1, d);
+          for (int d = q * NDW / (TM * TN); d < (q + 1) * NDW / (TM * TN); ++d) unpack_dword(fbn, 1, d);
         }
       }
       else if (q < TN) fbn[q] = *reinterpret_cast<const v4i*>(ring + slot * STAGE + b_off[q][W4 ? 0 : 1]);
@@ -497,7 +520,13 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
       acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fbn[j], fa[i], acc[j][i], 0, 0, 0);
       if (MORE) {
         if (W4) {     // the packet was requested before MFMA 0; unpack it behind the later MFMAs
-          if (TM * TN >= 10) {
+          if (TN == 4) {     // 16 pieces behind the MFMAs after the second one
+            constexpr int Q0 = 2, NS = TM * TN - Q0;
+            if (q >= Q0) {
+#pragma unroll
+              for (int d = (q - Q0) * 16 / NS; d < (q - Q0 + 1) * 16 / NS; ++d) unpack_dword(fb, 0, d);
+            }
+          } else if (TM * TN >= 10) {
             if (q >= 2 && q < 10) unpack_dword(fb, 0, q - 2);
           } else if (TM * TN < 8) {     // the 8 pieces behind the MFMAs after the second one (behind the last, if there are two)
             constexpr int Q0 = TM * TN > 2 ? 2 : TM * TN - 1, NS = TM * TN - Q0;
@@ -534,40 +563,46 @@ __global__ __launch_bounds__(256, pipe_occupancy(TM, OUT)) void qgemm_pipe_kerne
     }
   });
   // the ring is idle now: hand the per-column constants over through its first bytes
-  EpiLds* el = reinterpret_cast<EpiLds*>(ring);
+  EL* el = reinterpret_cast<EL*>(ring);
   RQ_TS(2);
   __syncthreads();
-  if (tid < 128) { el->scale[tid] = ep_f; el->cs[tid] = ep_i; el->is[tid] = ep_is; el->zz[tid] = ep_zz; el->off4[tid] = ep_off; }
-  else { el->bias[tid - 128] = ep_f; el->dw[tid - 128] = ep_i; }
+#pragma unroll
+  for (int u = 0; u < CPT; ++u) {
+    const int col = (tid & 127) + 128 * u;
+    if (tid < 128) { el->scale[col] = ep_f[u]; el->cs[col] = ep_i[u]; el->is[col] = ep_is[u]; el->zz[col] = ep_zz[u]; el->off4[col] = ep_off[u]; }
+    else { el->bias[col] = ep_f[u]; el->dw[col] = ep_i[u]; }
+  }
   __syncthreads();
   if (OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE) {
-    float* stage = reinterpret_cast<float*>(ring + 4096 + wave * (32 * 68 * 4));
-    if (m0 + BM <= (int)p.M) epilogue_rows_f32<TM, TN, false>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
-    else epilogue_rows_f32<TM, TN, true>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
-  } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
-  else epilogue_wide<TM, TN, ACT, OUT, true>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+    float* stage = reinterpret_cast<float*>(ring + EPI_BYTES + wave * (32 * 68 * 4));
+    if (m0 + BM <= (int)p.M) epilogue_rows_f32<TM, TN, false, EL>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
+    else epilogue_rows_f32<TM, TN, true, EL>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
+  } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  else epilogue_wide<TM, TN, ACT, OUT, true, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
   RQ_TS(3);
 }
 
 
 // host side: one instantiation set per weight format lives in its own translation unit
-template <bool W4, int S, int ACT, int OUT, int TM>
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2>
 rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
+  constexpr int BN = 64 * TN;
   p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
-  p.tiles_n = (p.N + 127) / 128;
+  p.tiles_n = (p.N + BN - 1) / BN;
   const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
-  constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? 128 * 32 : 128 * 64));
+  constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? BN * 32 : BN * 64));
   constexpr bool row_staging = OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE;
-  static_assert(sizeof(EpiLds) <= 4096 && lds_bytes >= 4096 + (row_staging ? 4 * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
+  constexpr int epi_bytes = TN == 2 ? 4096 : 8192;
+  static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 4 * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static bool attr_set = false;
   if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM>),
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const int64_t blocks = (ntiles + 7) / 8 * 8;
-  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
   return RQ_OK;
 }
 
@@ -588,9 +623,28 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
   return c320 < c256 ? 5 : 4;
 }
 
+// 256 x 256 tiles (one workgroup per CU, wavefront tile 128 x 128): per MFMA they move 192 bytes through the CU's load path
+// and the LDS instead of the 320 of a 256 x 128 tile.  They pay for products that give every CU at least two such tiles
+// and have a long K loop (8192^3: 1.57 -> 1.75 POP/s; 8192 x 4096 x 11008 with float output: 1.42 -> 1.66); with fewer
+// tiles or rows the coarser grid costs more than it saves (2048 x 12288 x 4096: 1.68 -> 1.42; 2048 x 22016 x 4096 with the
+// gated epilogue: 0.198 -> 0.205 ms).  Packed 4-bit weights only.
+template <bool W4>
+inline bool wide_tiles(const rq_ctx* ctx, const GemmParams& p) {
+  if (!W4) return false;
+  if (p.force_rows) return p.force_rows == 6;
+  const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+  return p.K >= 2048 && p.M >= 4096 && ((p.M + 255) / 256) * (int64_t)((p.N + 255) / 256) >= 2 * cu;
+}
+
 template <bool W4, int S, int ACT>
 rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
+  if constexpr (W4) {
+    if (wide_tiles<W4>(ctx, p)) {
+      if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 4>(ctx, p);
+      if (ACT == RQ_ACT_NONE && f && r && !q && !a) return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 4, 4>(ctx, p);
+    }
+  }
   if (q && !f && !r && !a) {
     // Re-quantized codes only (QKV, FC1).  With a short K loop the prologue and the epilogue weigh as much as the loop
     // itself, and more, smaller workgroups per CU (three of 192 rows, four of 128 rows) overlap those phases better than

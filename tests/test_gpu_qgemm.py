@@ -67,10 +67,12 @@ def test_accumulator_extremes(rq):
 
 
 @pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4)])
-@pytest.mark.parametrize("M,tile", [(515, 0), (515, 4), (963, 4), (320, 4), (515, 5), (192, 5), (770, 5)])
+@pytest.mark.parametrize("M,tile", [(515, 0), (515, 4), (963, 4), (320, 4), (515, 5), (192, 5), (770, 5), (515, 8), (770, 8),
+                                    (256, 8)])
 def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
     """tile 4 takes the 320-row tiles (one workgroup per CU) that large single-wave launches use, tile 5 the 192-row
-    tiles (two per CU) that launches with a short K loop use."""
+    tiles (two per CU) that launches with a short K loop use, tile 8 the 256 x 256 tiles of large products with packed
+    4-bit weights."""
     b, ctx = rq
     N, K = 384, 256
     print("case", bits_a, bits_w, M, tile, flush=True)
@@ -97,9 +99,10 @@ def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
 @pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
 @pytest.mark.parametrize("act,tile", [("none3", 0), ("gelu", 0), ("gated", 0), ("gelu_q_only", 0), ("gated_q_only", 0),
                                       ("none3", 5), ("none3", 6), ("none3", 7), ("gelu_q_only", 5), ("gelu_q_only", 6),
-                                      ("gated_q_only", 5), ("gated_q_only", 6), ("gated_q_only", 7)])
+                                      ("gated_q_only", 5), ("gated_q_only", 6), ("gated_q_only", 7),
+                                      ("none3", 8), ("gelu_q_only", 8), ("gated_q_only", 8)])
 def test_requantized_output(rq, bits_a, bits_w, bits_o, act, tile):
-    """tile 5 / 6 / 7: the 192- / 128- / 256-row tiles of the kernel that writes re-quantized codes only."""
+    """tile 5 / 6 / 7: the 192- / 128- / 256-row tiles of the kernel that writes re-quantized codes only; 8: 256 x 256 tiles."""
     b, ctx = rq
     q_only = act.endswith("_q_only")      # the block's launches: re-quantized codes are the only output
     act = act.replace("_q_only", "")
