@@ -190,6 +190,57 @@ def bench_gptq(args, cfg, rq, synth, np, torch):
     print(json.dumps(out))
 
 
+def bench_gemm(args, rq, np, torch):
+    """One step = one large quantized linear layer, 8192 x 8192 x 8192: int8 activation codes times packed 4-bit weights
+    on the int8 matrix cores, re-quantized to int8 codes in the epilogue (rq_qgemm, weight mode)."""
+    torch.cuda.set_device(0)
+    ctx = rq.Context(0)
+    M = N = K = 8192
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    A = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda", generator=g)
+    W = torch.randn((N, K), device="cuda", generator=g) * 0.02
+    lin = rq.rq_weight_quant_pack(ctx, W, torch.zeros(N, device="cuda"), 4)
+    out = torch.empty((M, N), dtype=torch.int8, device="cuda")
+    rs = torch.zeros(M, dtype=torch.int32, device="cuda")
+    rq.set_gemm_tile(args.tile)
+    run = lambda: rq.rq_qgemm(ctx, A, 8, 8, 0.01, lin, rowsum_a=rs, out_q=out, bits_o=4, s_o=[0.1], z_o=[8], off_o=[8], seg_len=N)
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    s.record()
+    for _ in range(steps):
+        run()
+    e.record()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    kernel_ms = s.elapsed_time(e) / steps
+    ops = 2.0 * M * N * K
+    achieved = ops / (kernel_ms * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import repquant_oracle as orc
+        rows = M       # the whole product, against a weight matrix of the same shape
+        a = A[:rows].cpu().numpy().astype(np.int64)
+        wq = np.random.default_rng(3).integers(-8, 8, size=(N, K), dtype=np.int64)
+        c0 = time.perf_counter()
+        orc.int_matmul_nt(a, wq)
+        c1 = time.perf_counter()
+        cpu = dict(value=2.0 * rows * N * K / (c1 - c0) / 1e12, unit="TOP/s", cores=torch.get_num_threads(), kind="oracle",
+                   sample="%d of %d output rows: the oracle's exact integer product (float64 BLAS on integers) against %d x %d weights; %.1f s"
+                          % (rows, M, N, K, c1 - c0))
+    out_d = dict(metric="quantized GEMM int8 TOP/s on 1 MI355X", value=ops / sec / 1e12, unit="TOP/s", n_gpus=1, steps=steps, warmup=warmup,
+                 ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
+                 config=dict(workload="qgemm_w4a8_8192", M=M, N=N, K=K, bits_w=4, output="re-quantized int8 codes"),
+                 roofline=dict(bound="mfma", kernel="qgemm_pipe_kernel (256 x 256 tiles)", achieved=achieved, peak=PEAK_INT8_TOPS, unit="TFLOP/s",
+                               frac=achieved / PEAK_INT8_TOPS, traffic=None, avg_launch_ms=kernel_ms, ops_per_launch=ops),
+                 cpu_baseline=cpu)
+    print(json.dumps(out_d))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,9 +252,10 @@ def main():
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true", help="append three 256 MiB elementwise copies (counter calibration)")
-    ap.add_argument("--workload", default="block", choices=["block", "dual_clip", "gptq"],
+    ap.add_argument("--workload", default="block", choices=["block", "dual_clip", "gptq", "gemm"],
                     help="block: the quantized block forward (the headline metric); dual_clip: the calibration-side learner of "
-                         "the per-channel clipping factors on the same activations; gptq: GPTQ of the QKV weights against them")
+                         "the per-channel clipping factors on the same activations; gptq: GPTQ of the QKV weights against them; "
+                         "gemm: one large quantized linear layer (8192^3, packed 4-bit weights)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (batch items never interact, so more GPUs "
@@ -222,6 +274,8 @@ def main():
         return bench_dual_clip(args, cfg, rq, synth, np, torch)
     if args.workload == "gptq":
         return bench_gptq(args, cfg, rq, synth, np, torch)
+    if args.workload == "gemm":
+        return bench_gemm(args, rq, np, torch)
     if args.chunk_mb:
         rq.set_attn_chunk_bytes(args.chunk_mb << 20)
     if args.tile:
