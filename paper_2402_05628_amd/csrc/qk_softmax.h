@@ -238,6 +238,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     }
     // ---- softmax statistics of row qi: this lane holds keys jt*32 + 8*(e/4) + 4*half + e%4 ----
     const int limit = MASKALL ? (qi_ld + 1 < p.N ? qi_ld + 1 : p.N) : p.N;     // valid keys: j < limit
+    const int rem_last = p.N - (NT - 1) * 32;                                  // keys of the row in the last key tile (1 .. 32)
     const float c1f = (float)p.c1;
     const float qmaxf = (float)p.qmax;
     float ssum = 0.f;
@@ -289,16 +290,22 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
             ssum += __builtin_amdgcn_exp2f((float)(fma((double)acc[jt][e], p.c1, (double)brow[j] * 1.4426950408889634) - tmax));
         }
     } else {
-      // only the tile that holds the row's last valid key (and, with a causal mask, every tile) needs per-element masking
+      // only the tile that holds the row's last valid key (and, with a causal mask, every tile) needs per-element masking;
+      // in that last tile the groups of 8 keys that lie wholly beyond the row's end are skipped altogether (197 keys:
+      // three of the four groups of the seventh tile)
 #pragma unroll
       for (int jt = 0; jt < NT; ++jt) {
         const bool partial = MASKALL || jt == NT - 1;      // a constant once the loop is unrolled
         if (partial) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-            acc[jt][e] = j < limit ? acc[jt][e] : INT32_MIN;        // masked and padding keys
-            amax = max(amax, acc[jt][e]);
+          for (int gq = 0; gq < 4; ++gq) {
+            if (jt == NT - 1 && gq * 8 >= rem_last) continue;      // wavefront-uniform
+#pragma unroll
+            for (int e = 4 * gq; e < 4 * gq + 4; ++e) {
+              const int j = jt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+              acc[jt][e] = j < limit ? acc[jt][e] : INT32_MIN;        // masked and padding keys
+              amax = max(amax, acc[jt][e]);
+            }
           }
         } else {
 #pragma unroll
@@ -310,16 +317,20 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
       for (int jt = 0; jt < NT; ++jt) {
         const bool partial = MASKALL || jt == NT - 1;      // a constant once the loop is unrolled
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          // acc - amax <= 0; INT32_MIN - amax would wrap, so masked keys get a fixed huge negative distance
-          const int d = (partial && acc[jt][e] == INT32_MIN) ? -0x40000000 : acc[jt][e] - amax;
-          if (F64CODE) {
-            acc[jt][e] = d;
-            ssum += __builtin_amdgcn_exp2f((float)d * c1f);     // exp2(-huge) = 0
-          } else {
-            const float df = (float)d;                          // kept as float bits: the code below needs no second convert
-            acc[jt][e] = __float_as_int(df);
-            ssum += __builtin_amdgcn_exp2f(df * c1f);
+        for (int gq = 0; gq < 4; ++gq) {
+          if (jt == NT - 1 && gq * 8 >= rem_last) continue;
+#pragma unroll
+          for (int e = 4 * gq; e < 4 * gq + 4; ++e) {
+            // acc - amax <= 0; INT32_MIN - amax would wrap, so masked keys get a fixed huge negative distance
+            const int d = (partial && acc[jt][e] == INT32_MIN) ? -0x40000000 : acc[jt][e] - amax;
+            if (F64CODE) {
+              acc[jt][e] = d;
+              ssum += __builtin_amdgcn_exp2f((float)d * c1f);     // exp2(-huge) = 0
+            } else {
+              const float df = (float)d;                          // kept as float bits: the code below needs no second convert
+              acc[jt][e] = __float_as_int(df);
+              ssum += __builtin_amdgcn_exp2f(df * c1f);
+            }
           }
         }
       }
@@ -419,6 +430,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
         unsigned pk[4];
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
+          if (!HAS_BIAS && jt == NT - 1 && gq * 8 >= rem_last) { pk[gq] = (unsigned)p.qmax * 0x01010101u; continue; }   // keys past the row's end
           unsigned w = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
