@@ -625,7 +625,7 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
 
 // 256 x 256 tiles (one workgroup per CU, wavefront tile 128 x 128): per MFMA they move 192 bytes through the CU's load path
 // and the LDS instead of the 320 of a 256 x 128 tile.  They pay for products that give every CU at least two such tiles
-// and have a long K loop (8192^3: 1.57 -> 1.75 POP/s; 8192 x 4096 x 11008 with float output: 1.42 -> 1.66); with fewer
+// and have a long K loop (8192^3 with re-quantized output: 1.57 -> 1.75 POP/s); with fewer
 // tiles or rows the coarser grid costs more than it saves (2048 x 12288 x 4096: 1.68 -> 1.42; 2048 x 22016 x 4096 with the
 // gated epilogue: 0.198 -> 0.205 ms).  Packed 4-bit weights only.
 template <bool W4>
@@ -642,7 +642,10 @@ rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   if constexpr (W4) {
     if (wide_tiles<W4>(ctx, p)) {
       if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 4>(ctx, p);
-      if (ACT == RQ_ACT_NONE && f && r && !q && !a) return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 4, 4>(ctx, p);
+      // float output + residual: only on request -- the 320 x 128 tile measures faster there (32896 x 1024 x 4096: 0.187 ms
+      // against 0.224 ms)
+      if (p.force_rows == 6 && ACT == RQ_ACT_NONE && f && r && !q && !a)
+        return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 4, 4>(ctx, p);
     }
   }
   if (q && !f && !r && !a) {
