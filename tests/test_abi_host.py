@@ -293,7 +293,8 @@ def test_block_forward_validation(b, host_ctx):
     assert "rq_block_forward" in b.lib.rq_last_error(host_ctx.handle).decode()
     assert b.lib.rq_block_forward(None, C.byref(p), None, None, 1, 8, None, 0) == 1
     assert b.lib.rq_set_attn_chunk_bytes(10) == 1
-    assert b.lib.rq_set_gemm_tile(99) == 1
+    assert b.lib.rq_set_gemm_tile(99) == 1 and b.lib.rq_set_gemm_tile(9) == 1
+    assert b.lib.rq_set_gemm_tile(8) == 0 and b.lib.rq_set_gemm_tile(0) == 0      # 8: the 256 x 256 tiles
 
 
 def test_workspace_bytes_grow_with_the_problem(b):
