@@ -27,6 +27,7 @@ struct QksParams {
   int H, N;                    // heads, tokens per group (Nq == Nk)
   int dq, dk;                  // storage offset minus zero-point of Q and of K
   const float* bias;           // [H, N, N] or NULL
+  int bias_lds;                // the bias planes of this workgroup's group slots are kept in LDS (set by the launcher)
   int causal;
   double c1, log2s;            // logit_scale * log2(e), log2(s_log)
   int qmax;
@@ -142,6 +143,17 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   };
   int gq = (int)blockIdx.x * GPB;
   if (gq < Gi) request(gq);
+  // Bias planes in LDS: a workgroup's group slot s always meets head (blockIdx.x * GPB + s) % H (the launcher checks that
+  // the stride between passes is a multiple of H), so its GPB planes are copied once and every bias read of every pass is
+  // an LDS read instead of a 4-byte gather from the L2.
+  float* const bias_lds = reinterpret_cast<float*>(lds + GPB * SLOT_BYTES);
+  if (HAS_BIAS && p.bias_lds) {
+    const int nn = p.N * p.N;
+    for (int s2 = 0; s2 < GPB; ++s2) {
+      const float* src = p.bias + (int64_t)((gq + s2) % p.H) * nn;
+      for (int i = tid; i < nn; i += 512) bias_lds[s2 * nn + i] = src[i];
+    }
+  }
   for (; gq < Gi; gq += (int)gridDim.x * GPB) {
   // ---- stage the keys of this pass in LDS (every wavefront has finished with the previous pass) ----
 #pragma unroll
@@ -245,7 +257,9 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
     double C0;
     double tmax = -1e300;
     int amax = INT32_MIN;
-    const float* brow = HAS_BIAS ? p.bias + ((int64_t)h * p.N + qi_ld) * p.N : nullptr;
+    const float* brow = !HAS_BIAS ? nullptr
+                        : (p.bias_lds ? static_cast<const float*>(bias_lds) + ((int64_t)ws * p.N + qi_ld) * p.N
+                                      : p.bias + ((int64_t)h * p.N + qi_ld) * p.N);
     if (HAS_BIAS && !F64CODE) {
       // Codes of at most 6 bits: t = acc * c1 + bias * log2(e) in float32 (c1 split into two floats, so the product is
       // as good as exact), every bias read once; the accumulator registers then hold t, later t - t_max.
@@ -532,20 +546,28 @@ rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
   if (groups > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %lld groups exceed 2^30", (long long)groups);
   const bool pv = p.V != nullptr;
   const int GPB = groups_per_pass(KSTEPS, NT, pv);      // groups per workgroup pass (as in the kernel)
-  const int lds = GPB * slot_bytes(KSTEPS, NT, pv);
+  const int lds_kv = GPB * slot_bytes(KSTEPS, NT, pv);
   const int64_t cap = (int64_t)(ctx->num_cu > 0 ? ctx->num_cu : 256);      // one 8-wavefront workgroup per CU
   const int64_t passes = (groups + GPB - 1) / GPB;
   const dim3 grid((unsigned)(passes < cap ? passes : cap));
   const bool f64 = p.qmax > 63;
+  // float32 bias path: the workgroup's GPB bias planes go to LDS where they fit and every pass of a workgroup meets the
+  // same heads (stride between passes a multiple of H, or a single pass)
+  QksParams pp = p;
+  const int64_t bias_bytes = (int64_t)GPB * p.N * p.N * 4;
+  pp.bias_lds = p.bias && !f64 && !p.causal && lds_kv + bias_bytes <= 160 * 1024 &&
+                (passes <= cap || ((int64_t)grid.x * GPB) % p.H == 0);
+  const int lds = lds_kv + (pp.bias_lds ? (int)bias_bytes : 0);
+  constexpr int lds_max = 160 * 1024;
 #define RQ_QKS_LAUNCH(B, F, C, P)                                                                                        \
   do {                                                                                                                \
     static bool attr_set = false;                                                                                     \
     if (!attr_set) {                                                                                                  \
       RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F, C, P>),           \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));                                   \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_max));                               \
       attr_set = true;                                                                                                \
     }                                                                                                                 \
-    hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F, C, P>), grid, dim3(512), lds, ctx->stream, p);            \
+    hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F, C, P>), grid, dim3(512), lds, ctx->stream, pp);           \
   } while (0)
   // the float64 code path also serves every masked or biased case; the lean variant is the common one
   if (pv) {
