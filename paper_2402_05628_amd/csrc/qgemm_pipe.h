@@ -47,6 +47,7 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
   const int64_t ldacc = p.ldacc, ldf = p.ldf, ldr = p.ldr, ldq = p.ldq;
   const int Mi = (int)p.M;
   const float qm = p.qmaxf;
+  const bool wide_codes = qm > 127.f;      // 8-bit output codes
   const bool wide_q = has_q && (ldq & 15) == 0 && (reinterpret_cast<uintptr_t>(out_q) & 15) == 0;
   const bool corr = p.da != 0 || p.centered;
   // row bases of this lane's TM tokens
@@ -130,8 +131,9 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[1], is, zz), qm), 1, w);
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[2], is, zz), qm), 2, w);
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[3], is, zz), qm), 3, w);
-          // stored = code - off per byte, no borrow across bytes, any offset: ((w | H) - (o & ~H)) ^ ((w ^ ~o) & H)
-          w = ((w | 0x80808080u) - (o4 & 0x7F7F7F7Fu)) ^ ((w ^ ~o4) & 0x80808080u);
+          // stored = code - off per byte.  Codes of 8 bits are stored with offset 128 (nothing else fits int8): flip the sign
+          // bits.  Narrower codes leave bit 7 free: with it set no byte borrows from its neighbour (off <= 128).
+          w = wide_codes ? w ^ 0x80808080u : ((w | 0x80808080u) - o4) ^ 0x80808080u;
           pk[i][g] = w;
           if (!wide_q && live) *reinterpret_cast<unsigned*>(rq[i] + no) = w;
         }
