@@ -86,6 +86,34 @@ def test_softmax_log2_codes(rq, G, H, N, bits, bias, causal):
     assert np.all(got[:, :, N:] == 2 ** bits - 1)
 
 
+@pytest.mark.parametrize("G,H,nq,nk,bits,bias", [(4, 2, 50, 197, 4, True), (3, 3, 197, 40, 6, False), (2, 2, 7, 1500, 8, True),
+                                                 (2, 1, 300, 33, 4, False)])
+def test_softmax_log2_codes_rectangular(rq, G, H, nq, nk, bits, bias):
+    """Rows of nk keys for nq queries with nq != nk (accumulators [G, nq, ld], bias planes [H, nq, nk])."""
+    b, ctx = rq
+    print("case", G, H, nq, nk, bits, bias, flush=True)
+    g = np.random.default_rng(G + nq * 3 + nk + bits)
+    acc = np.rint(g.normal(size=(G, nq, nk)) * 8000).astype(np.int64)
+    scale = 1.0 / 2048
+    ld = _ld(nk)
+    accp = np.full((G, nq, ld), -31337, np.int32)
+    accp[:, :, :nk] = acc
+    bias_a = g.normal(0, 0.7, size=(H, nq, nk)).astype(np.float32) if bias else None
+    s_log = np.float32(1.0)
+    want = np.empty((G, nq, nk), np.int64)
+    for gi in range(G):
+        L = acc[gi].astype(np.float64) * scale
+        if bias:
+            L = L + bias_a[gi % H].astype(np.float64)
+        want[gi] = orc.softmax_log_quant(L, s_log, bits)
+    codes = torch.full((G, nq, ld), 99, dtype=torch.uint8, device="cuda")
+    b.rq_softmax_log2_quant(ctx, dev(accp), G, H, nq, nk, ld, scale, codes, bits, s_log=float(s_log),
+                            bias=None if bias_a is None else dev(bias_a))
+    got = codes.cpu().numpy()
+    assert_codes_close(got[:, :, :nk], want, "softmax codes %d x %d b=%d" % (nq, nk, bits))
+    assert np.all(got[:, :, nk:] == 2 ** bits - 1)
+
+
 @pytest.mark.parametrize("batch,H,seq,dh,bits_p,bits_v,causal", [(2, 3, 197, 64, 4, 4, False), (2, 2, 49, 32, 6, 6, False),
                                                                  (1, 2, 257, 64, 4, 4, False), (1, 2, 600, 128, 8, 8, True),
                                                                  (2, 2, 64, 64, 8, 8, False), (1, 1, 1, 32, 4, 8, False),
@@ -128,6 +156,36 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
     # matrix cores: n terms of magnitude <= |v| p_j each round to 2^-24 of the running sum
     assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-4 if (bits_p > 4 and seq > 256) else 1e-5)
     assert_codes_close(outq.cpu().numpy().astype(np.int64) + off_o, orc.uniform_quant(want, s_o, z_o, bits_v), "attn_pv codes")
+
+
+@pytest.mark.parametrize("batch,H,nq,nk,dh,bits_p,bits_v", [(2, 2, 50, 197, 64, 4, 4), (1, 3, 197, 40, 32, 4, 8), (2, 1, 70, 300, 64, 8, 8),
+                                                           (1, 2, 330, 100, 128, 6, 6), (1, 1, 1, 513, 64, 8, 4), (1, 2, 290, 270, 64, 4, 4)])
+def test_attn_pv_rectangular(rq, batch, H, nq, nk, dh, bits_p, bits_v):
+    """Query and key counts that differ (the codes of one group are [nq, nk]; V has batch * nk rows, the output batch * nq)."""
+    b, ctx = rq
+    print("case", batch, H, nq, nk, dh, bits_p, bits_v, flush=True)
+    g = np.random.default_rng(nq * 7 + nk + dh + bits_p)
+    D = H * dh
+    ld = _ld(nk)
+    codes = orc.logsqrt2_quant_base2(orc.softmax_rows(g.normal(size=(batch * H, nq, nk)) * 3), 1.0, bits_p)
+    cp = np.full((batch * H, nq, ld), 2, np.uint8)
+    cp[:, :, :nk] = codes
+    qv = g.integers(0, 2 ** bits_v, size=(batch * nk, D))
+    z_v = int(g.integers(0, 2 ** bits_v))
+    offv = b.store_offset(bits_v, z_v)
+    s_log, s_v = np.float32(1.1), np.float32(0.021)
+    want = np.empty((batch * nq, D))
+    for bi in range(batch):
+        for h in range(H):
+            want[bi * nq:(bi + 1) * nq, h * dh:(h + 1) * dh] = orc.attn_pv(codes[bi * H + h], qv[bi * nk:(bi + 1) * nk, h * dh:(h + 1) * dh],
+                                                                         s_log, s_v, z_v)
+    vd = dev((qv - offv).astype(np.int8))
+    outf = torch.zeros((batch * nq, D), dtype=torch.float32, device="cuda")
+    b.rq_attn_pv(ctx, dev(cp), ld, vd.data_ptr(), D, batch, H, nq, nk, dh, float(s_log), float(s_v), z_v, offv, bits_p, out_f32=outf)
+    # narrow codes: exact integer sums, rounded once.  Wide codes: float32 sums (the per-window integer sums of short rows
+    # are each rounded to 2^-24 of themselves before they are added; long rows accumulate in float32 on the bfloat16
+    # matrix cores), so an output that cancels to nearly zero keeps an error of ~1e-7 of the row's magnitude
+    assert_float_close(outf.cpu().numpy(), want, "attn_pv rectangular", rtol=1e-4 if bits_p > 4 else 1e-5)
 
 
 @pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p,bias,causal", [(2, 3, 197, 64, 4, 4, False, False), (3, 2, 49, 32, 6, 6, True, False),
