@@ -200,7 +200,8 @@ def bench_gemm(args, rq, np, torch):
     g.manual_seed(3)
     A = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda", generator=g)
     W = torch.randn((N, K), device="cuda", generator=g) * 0.02
-    lin = rq.rq_weight_quant_pack(ctx, W, torch.zeros(N, device="cuda"), 4)
+    fmt = rq.W_I8_BAKED if args.wfmt == "i8" else rq.W_U4
+    lin = rq.rq_weight_quant_pack(ctx, W, torch.zeros(N, device="cuda"), 4, fmt=fmt)
     out = torch.empty((M, N), dtype=torch.int8, device="cuda")
     rs = torch.zeros(M, dtype=torch.int32, device="cuda")
     rq.set_gemm_tile(args.tile)
@@ -234,7 +235,8 @@ def bench_gemm(args, rq, np, torch):
                           % (rows, M, N, K, c1 - c0))
     out_d = dict(metric="quantized GEMM int8 TOP/s on 1 MI355X", value=ops / sec / 1e12, unit="TOP/s", n_gpus=1, steps=steps, warmup=warmup,
                  ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
-                 config=dict(workload="qgemm_w4a8_8192", M=M, N=N, K=K, bits_w=4, output="re-quantized int8 codes"),
+                 config=dict(workload="qgemm_w4a8_8192", M=M, N=N, K=K, bits_w=4, weight_storage=args.wfmt,
+                             output="re-quantized int8 codes"),
                  roofline=dict(bound="mfma", kernel="qgemm_pipe_kernel (256 x 256 tiles)", achieved=achieved, peak=PEAK_INT8_TOPS, unit="TFLOP/s",
                                frac=achieved / PEAK_INT8_TOPS, traffic=None, avg_launch_ms=kernel_ms, ops_per_launch=ops),
                  cpu_baseline=cpu)
@@ -251,6 +253,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--wfmt", default="u4", choices=["u4", "i8"],
+                    help="gemm workload: storage of the 4-bit weight codes -- u4: two codes per byte; i8: one int8 per code "
+                         "with the zero-point already subtracted (twice the weight bytes, no unpacking in the kernel)")
     ap.add_argument("--copy-probe", action="store_true", help="append three 256 MiB elementwise copies (counter calibration)")
     ap.add_argument("--workload", default="block", choices=["block", "dual_clip", "gptq", "gemm"],
                     help="block: the quantized block forward (the headline metric); dual_clip: the calibration-side learner of "

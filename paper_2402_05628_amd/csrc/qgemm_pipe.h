@@ -282,7 +282,16 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
   const unsigned per_xcd = (ntiles + 7u) / 8u;
   const unsigned t = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   if ((blockIdx.x >> 3) >= per_xcd || t >= ntiles) return;
-  const int tm = (int)(t / tiles_n), tn = (int)(t - (unsigned)tm * tiles_n);
+  // Within that range the tiles are walked in bands of group_m tile rows, down a band's rows first: the tiles that are
+  // in flight on an XCD at one time then cover a block of rows x columns instead of one long row of tiles, and the
+  // operand bytes its L2 has to pull in per k-step shrink accordingly.
+  const unsigned band = (unsigned)p.group_m * tiles_n;
+  const unsigned bi = t / band, br = t - bi * band;
+  const unsigned first_m = bi * (unsigned)p.group_m;
+  const unsigned left_m = (unsigned)p.tiles_m - first_m;
+  const unsigned gm = left_m < (unsigned)p.group_m ? left_m : (unsigned)p.group_m;
+  const unsigned tcol = br / gm;
+  const int tm = (int)(first_m + (br - tcol * gm)), tn = (int)tcol;
   const int m0 = tm * BM, n0 = tn * BN;
   const int nk = p.K / 64;
 
@@ -592,6 +601,22 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
   p.tiles_n = (p.N + BN - 1) / BN;
   const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
+  {
+    // tiles in flight on one XCD (an eighth of the CUs, OCC workgroups each) as g rows x (inflight / g) columns:
+    // pick the g that needs the fewest operand bytes per k-step
+    constexpr int OCC = TN == 4 ? 1 : pipe_occupancy(TM, OUT);
+    const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+    const int inflight = (cu / 8 > 0 ? cu / 8 : 1) * OCC;
+    int64_t best = -1;
+    p.group_m = 1;
+    for (int g = 1; g <= 16; g *= 2) {
+      if (g > p.tiles_m && g > 1) break;
+      int cols = (inflight + g - 1) / g;
+      cols = cols < p.tiles_n ? cols : p.tiles_n;
+      const int64_t bytes = (int64_t)g * (64 * TM * 64) + (int64_t)cols * (W4 ? BN * 32 : BN * 64);
+      if (best < 0 || bytes < best) { best = bytes; p.group_m = g; }
+    }
+  }
   constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? BN * 32 : BN * 64));
   constexpr bool row_staging = OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE;
   constexpr int epi_bytes = TN == 2 ? 4096 : 8192;
@@ -629,10 +654,11 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
 // and the LDS instead of the 320 of a 256 x 128 tile.  They pay for products that give every CU at least two such tiles
 // and have a long K loop (8192^3 with re-quantized output: 1.57 -> 1.75 POP/s); with fewer
 // tiles or rows the coarser grid costs more than it saves (2048 x 12288 x 4096: 1.68 -> 1.42; 2048 x 22016 x 4096 with the
-// gated epilogue: 0.198 -> 0.205 ms).  Packed 4-bit weights only.
+// gated epilogue: 0.198 -> 0.205 ms).  int8 weight storage gains as much (8192^3: 0.677 -> 0.612 ms) and ends up no faster
+// than the packed format: without the unpacking its wavefronts wait for operands instead (32 KB per k-step through the
+// CU's load path against 24 KB).
 template <bool W4>
 inline bool wide_tiles(const rq_ctx* ctx, const GemmParams& p) {
-  if (!W4) return false;
   if (p.force_rows) return p.force_rows == 6;
   const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   return p.K >= 2048 && p.M >= 4096 && ((p.M + 255) / 256) * (int64_t)((p.N + 255) / 256) >= 2 * cu;
@@ -641,11 +667,11 @@ inline bool wide_tiles(const rq_ctx* ctx, const GemmParams& p) {
 template <bool W4, int S, int ACT>
 rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
-  if constexpr (W4) {
-    if (wide_tiles<W4>(ctx, p)) {
-      if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 4>(ctx, p);
-      // float output + residual: only on request -- the 320 x 128 tile measures faster there (32896 x 1024 x 4096: 0.187 ms
-      // against 0.224 ms)
+  if (wide_tiles<W4>(ctx, p)) {
+    if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 4>(ctx, p);
+    // float output + residual: only on request -- the 320 x 128 tile measures faster there (32896 x 1024 x 4096: 0.187 ms
+    // against 0.224 ms)
+    if constexpr (W4) {
       if (p.force_rows == 6 && ACT == RQ_ACT_NONE && f && r && !q && !a)
         return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 4, 4>(ctx, p);
     }
