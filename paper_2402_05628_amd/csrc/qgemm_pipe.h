@@ -256,16 +256,21 @@ constexpr int pipe_occupancy(int TM, int OUT) {
 
 // TN = 2: tiles 128 columns wide (wavefront tile 32 TM x 64); TN = 4: 256 columns (wavefront tile 32 TM x 128, one workgroup
 // per CU): per MFMA half the bytes through the CU's load path and the LDS, for large products with a long K loop.
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2>
-__global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;           // TM = 4: 256-row tiles, two workgroups per CU; TM = 5: 320 rows, one
+// WN = 4: eight wavefronts in a 2 x 4 grid (two per SIMD, each with the 32 TM x 32 TN tile) on a tile 32 TN * 4 columns wide:
+// the operand bytes per MFMA of the 256 x 256 tile, with a second wavefront on every SIMD to cover the first one's waits.
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2>
+__global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
+  constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
+  constexpr int BM = 64 * TM, BN = 32 * TN * WN;      // TM = 4: 256-row tiles, two workgroups per CU; TM = 5: 320 rows, one
   constexpr int A_BYTES = BM * 64;
   constexpr int B_BYTES = W4 ? BN * 32 : BN * 64;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int BL = W4 ? TN / 2 : TN;                // weight loads per thread and stage
-  constexpr int LPS = TM + BL;                        // loads per thread and stage
+  constexpr int AL = BM * 4 / NT;                     // activation loads per thread and stage (16 bytes each)
+  constexpr int BL = (W4 ? BN * 2 : BN * 4) / NT;     // weight loads per thread and stage
+  static_assert(AL * NT == BM * 4 && BL >= 1, "the loads of a stage divide evenly over the threads");
+  constexpr int LPS = AL + BL;                        // loads per thread and stage
   typedef EpiLdsT<BN> EL;
-  constexpr int EPI_BYTES = TN == 2 ? 4096 : 8192;    // the epilogue constants at the start of the idle ring
+  constexpr int EPI_BYTES = BN == 128 ? 4096 : 8192;  // the epilogue constants at the start of the idle ring
   static_assert(sizeof(EL) <= EPI_BYTES, "epilogue constants");
   static_assert(S >= 2 && (S - 1) * LPS <= 63, "ring depth (the load counter holds 63)");
   extern __shared__ __align__(16) int8_t ring[];
@@ -273,7 +278,7 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 1) * (32 * TM), wn0 = (wave & 1) * (32 * TN);
+  const int wm0 = (wave / WN) * (32 * TM), wn0 = (wave % WN) * (32 * TN);
   const int l32 = lane & 31, half = lane >> 5;
 
   // tile of this workgroup: XCD b % 8 gets the contiguous range [xcd * per_xcd, ...) of the tile list (n fastest)
@@ -298,21 +303,21 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
   // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
   // lane l lands at 16-byte slot l of a 1 KB block = 16 tile rows of 64 B; the chunk that belongs at position
   // (lane & 3) of row (lane >> 2) is chunk ((lane & 3) - (row >> 2)) & 3
-  unsigned aofs[TM], bofs[BL];
+  unsigned aofs[AL], bofs[BL];
   {
     const int dl_row = lane >> 2;
     const int dl_c = ((lane & 3) - (dl_row >> 2)) & 3;
     const int Mi = (int)p.M;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      int m = m0 + (wave * TM + i) * 16 + dl_row;
+    for (int i = 0; i < AL; ++i) {
+      int m = m0 + (wave * AL + i) * 16 + dl_row;
       m = m < Mi ? m : Mi - 1;
       aofs[i] = (unsigned)m * (unsigned)p.lda + (unsigned)(dl_c * 16);
     }
     if (W4) {
 #pragma unroll
-      for (int u = 0; u < BL; ++u) {       // 128 weight rows (32 bytes each) per load of the workgroup
-        const int row = u * 128 + (tid >> 1);
+      for (int u = 0; u < BL; ++u) {       // NT / 2 weight rows (32 bytes each) per load of the workgroup
+        const int row = u * (NT / 2) + (tid >> 1);
         int n = n0 + row;
         n = n < p.N ? n : p.N - 1;
         bofs[u] = (unsigned)n * (unsigned)p.ldb + (unsigned)(((tid & 1) ^ ((row >> 3) & 1)) * 16);
@@ -332,14 +337,14 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
     int8_t* la = ring + slot * STAGE;
     int8_t* lb = la + A_BYTES;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < AL; ++i)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gA + (aofs[i] + (unsigned)kt * 64u)),
-                                       (__attribute__((address_space(3))) void*)(la + (wave * TM + i) * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(la + (wave * AL + i) * 1024), 16, 0, 0);
     if (W4) {
 #pragma unroll
       for (int u = 0; u < BL; ++u)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gB + (bofs[u] + (unsigned)kt * 32u)),
-                                         (__attribute__((address_space(3))) void*)(lb + u * 4096 + wave * 1024), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)(lb + u * (NT * 16) + wave * 1024), 16, 0, 0);
     } else {
 #pragma unroll
       for (int i = 0; i < BL; ++i)
@@ -436,7 +441,7 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0;
   // per-column epilogue constants: one column per thread pair, fetched now, parked in two registers over the main loop
   // (wide tiles: CPT columns per thread, 128 apart)
-  constexpr int CPT = BN / 128;
+  constexpr int CPT = BN / 128;      // (threads beyond the first 256 repeat the second 128's columns)
   float ep_f[CPT], ep_is[CPT], ep_zz[CPT]; int ep_i[CPT], ep_off[CPT];
 #pragma unroll
   for (int u = 0; u < CPT; ++u) {
@@ -595,16 +600,16 @@ __global__ __launch_bounds__(256, TN == 4 ? 1 : pipe_occupancy(TM, OUT)) void qg
 
 
 // host side: one instantiation set per weight format lives in its own translation unit
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2>
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2>
 rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
-  constexpr int BN = 64 * TN;
+  constexpr int BN = 32 * TN * WN;
   p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
   p.tiles_n = (p.N + BN - 1) / BN;
   const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
   {
     // tiles in flight on one XCD (an eighth of the CUs, OCC workgroups each) as g rows x (inflight / g) columns:
     // pick the g that needs the fewest operand bytes per k-step
-    constexpr int OCC = TN == 4 ? 1 : pipe_occupancy(TM, OUT);
+    constexpr int OCC = (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT);
     const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
     const int inflight = (cu / 8 > 0 ? cu / 8 : 1) * OCC;
     int64_t best = -1;
@@ -619,17 +624,17 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   }
   constexpr int lds_bytes = S * (64 * TM * 64 + (W4 ? BN * 32 : BN * 64));
   constexpr bool row_staging = OUT == (OUT_F32 | OUT_RES) && ACT == RQ_ACT_NONE;
-  constexpr int epi_bytes = TN == 2 ? 4096 : 8192;
-  static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 4 * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
+  constexpr int epi_bytes = BN == 128 ? 4096 : 8192;
+  static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 2 * WN * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static bool attr_set = false;
   if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN>),
+    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
     attr_set = true;
   }
   const int64_t blocks = (ntiles + 7) / 8 * 8;
-  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN>), dim3((unsigned)blocks), dim3(256), lds_bytes, ctx->stream, p);
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
   return RQ_OK;
 }
 
@@ -650,25 +655,27 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
   return c320 < c256 ? 5 : 4;
 }
 
-// 256 x 256 tiles (one workgroup per CU, wavefront tile 128 x 128): per MFMA they move 192 bytes through the CU's load path
-// and the LDS instead of the 320 of a 256 x 128 tile.  They pay for products that give every CU at least two such tiles
-// and have a long K loop (8192^3 with re-quantized output: 1.57 -> 1.75 POP/s); with fewer
-// tiles or rows the coarser grid costs more than it saves (2048 x 12288 x 4096: 1.68 -> 1.42; 2048 x 22016 x 4096 with the
-// gated epilogue: 0.198 -> 0.205 ms).  int8 weight storage gains as much (8192^3: 0.677 -> 0.612 ms) and ends up no faster
-// than the packed format: without the unpacking its wavefronts wait for operands instead (32 KB per k-step through the
-// CU's load path against 24 KB).
+// 256 x 256 tiles (one workgroup per CU): per MFMA they move 192 bytes through the CU's load path instead of the 320 of a
+// 256 x 128 tile.  They pay for products that give every CU at least two such tiles
+// and have a long K loop (8192^3 with re-quantized output: 1.57 -> 2.04 POP/s); with fewer
+// tiles the coarser grid costs more than it saves (2048 x 12288 x 4096, 384 tiles: 0.103 -> 0.105 ms; 2048 x 22016 x 4096 with
+// the gated epilogue, 688 tiles: 0.191 -> 0.173 ms).  int8 weight storage gains as much (8192^3: 0.677 -> 0.54 ms) and ends up hardly
+// faster than the packed format: without the unpacking its wavefronts wait for operands instead (32 KB per k-step through
+// the CU's load path against 24 KB).
 template <bool W4>
 inline bool wide_tiles(const rq_ctx* ctx, const GemmParams& p) {
   if (p.force_rows) return p.force_rows == 6;
   const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
-  return p.K >= 2048 && p.M >= 4096 && ((p.M + 255) / 256) * (int64_t)((p.N + 255) / 256) >= 2 * cu;
+  return p.K >= 2048 && p.M >= 2048 && ((p.M + 255) / 256) * (int64_t)((p.N + 255) / 256) >= 2 * cu;
 }
 
 template <bool W4, int S, int ACT>
 rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   const bool q = p.out_q, f = p.out_f32, r = p.residual, a = p.out_acc;
   if (wide_tiles<W4>(ctx, p)) {
-    if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 4>(ctx, p);
+    // re-quantized codes: eight wavefronts (2 x 4, each 128 x 64), two per SIMD -- 8192^3: 0.555 ms against 0.587 ms with four
+    // wavefronts of 128 x 128 (a deeper ring changes nothing: 6 stages 0.556 ms)
+    if (q && !f && !r && !a) return launch_pipe_one<W4, 4, ACT, OUT_Q, 4, 2, 4>(ctx, p);
     // float output + residual: only on request -- the 320 x 128 tile measures faster there (32896 x 1024 x 4096: 0.187 ms
     // against 0.224 ms)
     if constexpr (W4) {
