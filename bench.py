@@ -195,7 +195,8 @@ def bench_gemm(args, rq, np, torch):
     on the int8 matrix cores, re-quantized to int8 codes in the epilogue (rq_qgemm, weight mode)."""
     torch.cuda.set_device(0)
     ctx = rq.Context(0)
-    M = N = K = 8192
+    M = N = 8192
+    K = args.gemm_k
     g = torch.Generator(device="cuda")
     g.manual_seed(3)
     A = torch.randint(-8, 8, (M, K), dtype=torch.int8, device="cuda", generator=g)
@@ -235,7 +236,7 @@ def bench_gemm(args, rq, np, torch):
                           % (rows, M, N, K, c1 - c0))
     out_d = dict(metric="quantized GEMM int8 TOP/s on 1 MI355X", value=ops / sec / 1e12, unit="TOP/s", n_gpus=1, steps=steps, warmup=warmup,
                  ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
-                 config=dict(workload="qgemm_w4a8_8192", M=M, N=N, K=K, bits_w=4, weight_storage=args.wfmt,
+                 config=dict(workload="qgemm_w4a8_8192" if K == 8192 else "qgemm_w4a8_8192x8192x%d" % K, M=M, N=N, K=K, bits_w=4, weight_storage=args.wfmt,
                              output="re-quantized int8 codes"),
                  roofline=dict(bound="mfma", kernel="qgemm_pipe_kernel (256 x 256 tiles)", achieved=achieved, peak=PEAK_INT8_TOPS, unit="TFLOP/s",
                                frac=achieved / PEAK_INT8_TOPS, traffic=None, avg_launch_ms=kernel_ms, ops_per_launch=ops),
@@ -253,6 +254,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--gemm-k", type=int, default=8192, help="gemm workload: inner dimension (a multiple of 64)")
     ap.add_argument("--wfmt", default="u4", choices=["u4", "i8"],
                     help="gemm workload: storage of the 4-bit weight codes -- u4: two codes per byte; i8: one int8 per code "
                          "with the zero-point already subtracted (twice the weight bytes, no unpacking in the kernel)")

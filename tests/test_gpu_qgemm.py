@@ -114,6 +114,19 @@ def test_requantized_output(rq, bits_a, bits_w, bits_o, act, tile):
         b.set_gemm_tile(0)
 
 
+@pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
+@pytest.mark.parametrize("act,M,K", [("none3", 520, 1024), ("gelu_q_only", 301, 896), ("gated_q_only", 700, 768), ("none3", 257, 384)])
+def test_requantized_output_wide_tiles_long_k(rq, bits_a, bits_w, bits_o, act, M, K):
+    """The 256 x 256 tiles with a K loop long enough for the ring to be refilled (in pairs of stages) several times."""
+    b, ctx = rq
+    q_only = act.endswith("_q_only")
+    b.set_gemm_tile(8)
+    try:
+        _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act.replace("_q_only", ""), q_only, M, K)
+    finally:
+        b.set_gemm_tile(0)
+
+
 def _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act, q_only, M, K):
     N = 384 if act != "gated" else 512
     g = np.random.default_rng(5 + bits_a + len(act))
