@@ -217,8 +217,8 @@ rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
  * its 320x128 tile instead of 256x128 for float+residual outputs when that finishes the busiest CU sooner),
  * 1 = simple 128x128, 2 = simple 256x128, 3 = pipelined; 4 .. 7 = pipelined with the 320- / 192- / 128- / 256-row tile
  * wherever the kernel has that tile (320: float + residual output; 192: both outputs; 128 and 256: re-quantized output);
- * 8 = pipelined with 256 x 256 tiles (packed 4-bit weights; chosen by shape for products that fill the chip with such
- * tiles and have K >= 2048). */
+ * 8 = pipelined with 256 x 256 tiles (re-quantized output: any weight storage; float + residual output: packed 4-bit
+ * weights; chosen by shape for re-quantized products with M >= 2048 and K >= 2048 that give every CU two such tiles). */
 rq_status rq_set_gemm_tile(int32_t tile);
 
 /* rq_qgemm (weight mode, float output + residual) and rq_ln_quant of that output in ONE kernel whose workgroups own whole
