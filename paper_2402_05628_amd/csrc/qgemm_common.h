@@ -54,15 +54,18 @@ __device__ __forceinline__ int swz(int row, int c) {
 // GELU(y) = y Phi(y) = max(y, 0) - |y| erfc(|y| / sqrt 2) / 2.  log2(erfc(a / sqrt 2) / 2) is smooth and close to a parabola;
 // a degree-6 polynomial (weighted least squares on [0, 6.5], where the product with |y| matters) reproduces GELU to 2.6e-7
 // absolute in float32 -- the same as a rational erf, with one exp2 and no reciprocal.  Beyond 6.5 the term is below 1e-9 |y|.
+#define RQ_FMAAK(d, s0, s1, HEX) asm("v_fmaak_f32 %0, %1, %2, " HEX : "=v"(d) : "v"(s0), "v"(s1))
 __device__ __forceinline__ float gelu_f(float y) {
   const float ay = fabsf(y);
   const float a = fminf(ay, 6.5f);
   float p = fmaf(3.204148336e-05f, a, -7.530309838e-04f);
-  p = fmaf(p, a, 8.004287203e-03f);
-  p = fmaf(p, a, -5.325607760e-02f);
-  p = fmaf(p, a, -4.589186652e-01f);
-  p = fmaf(p, a, -1.151141279e+00f);
-  p = fmaf(p, a, -1.000001008e+00f);
+  // Horner steps as v_fmaak_f32 (d = s0 * s1 + literal), one instruction each: left to itself the compiler turns about a
+  // third of them into a v_mov of the constant plus a v_fmac.  Same fused multiply-add, same rounding.
+  RQ_FMAAK(p, p, a, "0x3c03246a");     //  8.004287203e-03
+  RQ_FMAAK(p, p, a, "0xbd5a230b");     // -5.325607760e-02
+  RQ_FMAAK(p, p, a, "0xbeeaf763");     // -4.589186652e-01
+  RQ_FMAAK(p, p, a, "0xbf935899");     // -1.151141279e+00
+  RQ_FMAAK(p, p, a, "0xbf800008");     // -1.000001008e+00
   return fmaf(-ay, __builtin_amdgcn_exp2f(p), fmaxf(y, 0.f));
 }
 

@@ -76,12 +76,9 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
       const float4 sc = *reinterpret_cast<const float4*>(&el->scale[nl]);
       const float4 bi = *reinterpret_cast<const float4*>(&el->bias[nl]);
       float4 sc2 = sc, bi2 = bi;
-      v4i cs = {0, 0, 0, 0}, dw = {0, 0, 0, 0}, cs2 = {0, 0, 0, 0}, dw2 = {0, 0, 0, 0};
-      if (corr) { cs = *reinterpret_cast<const v4i*>(&el->cs[nl]); dw = *reinterpret_cast<const v4i*>(&el->dw[nl]); }
       if (gated) {
         sc2 = *reinterpret_cast<const float4*>(&el->scale[nl + 32]);
         bi2 = *reinterpret_cast<const float4*>(&el->bias[nl + 32]);
-        if (corr) { cs2 = *reinterpret_cast<const v4i*>(&el->cs[nl + 32]); dw2 = *reinterpret_cast<const v4i*>(&el->dw[nl + 32]); }
       }
       float is = 0.f, zz = 0.f;
       unsigned o4 = 0;
@@ -93,7 +90,8 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
         int t[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) t[e] = acc[j][i][4 * g + e];
-        if (corr) {
+        if (corr) {      // the correction constants are read inside the branch: no registers, no zeroing without it
+          const v4i cs = *reinterpret_cast<const v4i*>(&el->cs[nl]), dw = *reinterpret_cast<const v4i*>(&el->dw[nl]);
 #pragma unroll
           for (int e = 0; e < 4; ++e) t[e] += cs[e] + dw[e] * rs[i];
         }
@@ -114,7 +112,12 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
           const int ju = (j + J1) < TN ? (j + J1) : j;
           int u[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) u[e] = acc[ju][i][4 * g + e] + (corr ? cs2[e] + dw2[e] * rs[i] : 0);
+          for (int e = 0; e < 4; ++e) u[e] = acc[ju][i][4 * g + e];
+          if (corr) {
+            const v4i cs2 = *reinterpret_cast<const v4i*>(&el->cs[nl + 32]), dw2 = *reinterpret_cast<const v4i*>(&el->dw[nl + 32]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] += cs2[e] + dw2[e] * rs[i];
+          }
           y[0] = silu_f(y[0]) * fmaf((float)u[0], sc2.x, bi2.x);
           y[1] = silu_f(y[1]) * fmaf((float)u[1], sc2.y, bi2.y);
           y[2] = silu_f(y[2]) * fmaf((float)u[2], sc2.z, bi2.z);
