@@ -102,7 +102,6 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
   const int it0 = wave - ws0 * NT;                          // and query tile
   const int Gi = (int)p.G;
   const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
-  const bool corr = p.dq != 0 || p.dk != 0;
   // Workgroups are persistent over the (batch item, head) groups.  The keys (and values) and this wavefront's first query
   // fragments of the NEXT pass are requested into registers before the current pass's arithmetic, so their latency hides.
   v4i kreg[KCH], qreg[KSTEPS];
@@ -214,20 +213,14 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s)
       fq[s] = task == wave ? fq0[s] : *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
-    int base = 0;
-    if (corr) {
-      v16i rq;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) rq[e] = 0;
-#pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) rq = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, fq[s], rq, 0, 0, 0);
-      base = p.dk * rq[0] + DH * p.dq * p.dk;   // every element of rq holds rowsum(q'[i, :]) of this lane's query row
-    }
+    // Zero-point corrections: sum (q' + dq)(k' + dk) = sum q'k' + dq colsum(k'[j, :]) + dk rowsum(q'[i, :]) + d_head dq dk.  The last
+    // two terms are the same for every key of a row and cancel in the softmax (only differences to the row's maximum enter
+    // the codes), so they are left out; the accumulators start at zero (the first MFMA of a tile takes the constant 0 as C).
     v16i acc[NT];
 #pragma unroll
     for (int jt = 0; jt < NT; ++jt) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[jt][e] = base;
+      for (int e = 0; e < 16; ++e) acc[jt][e] = 0;
       if (jt < nt) {
         v4i fk[KSTEPS];
         const int r = jt * 32 + l32;
@@ -241,7 +234,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
           for (int s = 0; s < KSTEPS; ++s) ck = __builtin_amdgcn_mfma_i32_32x32x32_i8(fk[s], ones, ck, 0, 0, 0);
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[jt][e] += p.dq * ck[e];
+          for (int e = 0; e < 16; ++e) acc[jt][e] = p.dq * ck[e];
         }
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) acc[jt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fk[s], fq[s], acc[jt], 0, 0, 0);
