@@ -127,6 +127,39 @@ def test_requantized_output_wide_tiles_long_k(rq, bits_a, bits_w, bits_o, act, M
         b.set_gemm_tile(0)
 
 
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("bits_a,bits_w,bits_o", [(4, 4, 4), (8, 6, 8)])
+def test_requantized_output_large_product(rq, bits_a, bits_w, bits_o):
+    """A product large enough for the launcher to pick the 256 x 256 tiles by itself and to walk them in bands of several
+    tile rows (9 tile rows: the last band is a partial one, and the last tile row is ragged).  Sampled rows of every band
+    against the oracle; a sentinel shows that every tile was written."""
+    b, ctx = rq
+    M, N, K = 2264, 14592, 2048
+    g = np.random.default_rng(11 + bits_w)
+    qa, z_a = _act_codes(g, M, K, bits_a)
+    lin = random_linear(g, N, K, bits_w)
+    s_a = np.float32(1.5 / (np.sqrt(K) * (2 ** bits_a / 3.46) * (2 ** bits_w / 3.46) * 3e-3))
+    rows = np.concatenate([np.arange(0, 24), np.arange(1000, 1024), np.arange(1530, 1546), np.arange(2040, 2064), np.arange(M - 24, M)])
+    y = orc.qlinear(qa[rows], s_a, z_a, lin)
+    s_o = np.float32((y.max() - y.min()) / (2 ** bits_o - 1))
+    z_o = int(np.rint(-y.min() / np.float64(s_o)))
+    want = orc.uniform_quant(y, s_o, z_o, bits_o)
+    off_o = b.store_offset(bits_o, z_o)
+    a_off = b.store_offset(bits_a, z_a)
+    A = dev((qa - a_off).astype(np.int8))
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    b.rq_rowsum_i8(ctx, A, rs)
+    sentinel = 99 if bits_o < 8 else None      # stored codes of fewer than 8 bits lie in [-off, 2^bits - 1 - off], off <= 2^bits - 1
+    out = torch.full((M, N), 99, dtype=torch.int8, device="cuda")
+    print("case large", bits_a, bits_w, bits_o, flush=True)
+    b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), out_q=out, bits_o=bits_o, s_o=[float(s_o)], z_o=[z_o],
+               off_o=[off_o], seg_len=N, rowsum_a=rs)
+    if sentinel is not None:
+        assert not bool((out == sentinel).any()), "some output tile was never written"
+    got = out[torch.as_tensor(rows, device="cuda")].cpu().numpy().astype(np.int64) + off_o
+    assert_codes_close(got, want, "large product, sampled rows")
+
+
 def _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act, q_only, M, K):
     N = 384 if act != "gated" else 512
     g = np.random.default_rng(5 + bits_a + len(act))
