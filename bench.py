@@ -205,7 +205,7 @@ def bench_gemm(args, rq, np, torch):
     lin = rq.rq_weight_quant_pack(ctx, W, torch.zeros(N, device="cuda"), 4, fmt=fmt)
     out = torch.empty((M, N), dtype=torch.int8, device="cuda")
     rs = torch.zeros(M, dtype=torch.int32, device="cuda")
-    rq.set_gemm_tile(args.tile)
+    rq.set_gemm_tile(ctx, args.tile)
     run = lambda: rq.rq_qgemm(ctx, A, 8, 8, 0.01, lin, rowsum_a=rs, out_q=out, bits_o=4, s_o=[0.1], z_o=[8], off_o=[8], seg_len=N)
     steps, warmup = min(args.steps, 20), min(args.warmup, 3)
     for _ in range(warmup):
@@ -283,16 +283,16 @@ def main():
         return bench_gptq(args, cfg, rq, synth, np, torch)
     if args.workload == "gemm":
         return bench_gemm(args, rq, np, torch)
-    if args.chunk_mb:
-        rq.set_attn_chunk_bytes(args.chunk_mb << 20)
-    if args.tile:
-        rq.set_gemm_tile(args.tile)
     torch.cuda.set_device(0)
     ctx = rq.Context(0)
+    if args.tile:
+        rq.set_gemm_tile(ctx, args.tile)
     raw = synth.make_block(cfg, args.config, 0)
     x = torch.from_numpy(raw["x"]).cuda()
     rawd = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in raw.items() if k != "x"}
     blk = rq.calibrate_block(ctx, cfg, rawd, x, cfg.batch, cfg.seq)       # untimed preparation, on the GPU
+    if args.chunk_mb:
+        blk.bp.attn_chunk_bytes = args.chunk_mb << 20
     y = torch.empty_like(x)
 
     for _ in range(args.warmup):

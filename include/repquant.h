@@ -59,6 +59,12 @@ enum { RQ_NORM_LAYERNORM = 0, RQ_NORM_RMSNORM = 1 };
 enum { RQ_ACT_NONE = 0, RQ_ACT_GELU = 1, RQ_ACT_SILU_GATED = 2 };
 enum { RQ_MASK_NONE = 0, RQ_MASK_CAUSAL = 1 };
 enum { RQ_W_I8_BAKED = 0, RQ_W_I8_CENTERED = 1, RQ_W_U4 = 2, RQ_B_ACT_I8 = 3 };
+/* `flags` of the attention descriptors and of rq_block_params / rq_block_raw.
+ * RQ_LOG_ZERO_AT_MAX_CODE: the log quantizer's de-quantizer (Section "Efficient quantizers", x^ = s 2^-q; Eq. (3.3-2)) is
+ * silent on whether the saturated code 2^b - 1, which collects every probability below the grid, still carries mass.  By
+ * default it is de-quantized literally like any other code; with this flag it de-quantizes to exactly 0 (every other code
+ * unchanged).  The codes themselves do not depend on the flag. */
+enum { RQ_LOG_ZERO_AT_MAX_CODE = 1 };
 
 /* ---- context ---------------------------------------------------------------------------------- */
 
@@ -213,13 +219,14 @@ typedef struct {
   int32_t causal;
 } rq_gemm_desc;
 rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
-/* Tuning knob (process-wide): kernel of the weight mode. 0 = choose by shape (the pipelined kernel whenever N % 32 == 0;
+/* Tuning knob of one context (host call; not to be changed while another thread issues calls on the same context):
+ * kernel of the weight mode. 0 = choose by shape (the pipelined kernel whenever N % 32 == 0;
  * its 320x128 tile instead of 256x128 for float+residual outputs when that finishes the busiest CU sooner),
  * 1 = simple 128x128, 2 = simple 256x128, 3 = pipelined; 4 .. 7 = pipelined with the 320- / 192- / 128- / 256-row tile
  * wherever the kernel has that tile (320: float + residual output; 192: both outputs; 128 and 256: re-quantized output);
  * 8 = pipelined with 256 x 256 tiles (re-quantized output: any weight storage; float + residual output: packed 4-bit
  * weights; chosen by shape for re-quantized products with M >= 2048 and K >= 2048 that give every CU two such tiles). */
-rq_status rq_set_gemm_tile(int32_t tile);
+rq_status rq_set_gemm_tile(rq_ctx* ctx, int32_t tile);
 
 /* rq_qgemm (weight mode, float output + residual) and rq_ln_quant of that output in ONE kernel whose workgroups own whole
  * output rows: xbar = GEMM + residual is written to d->out_f32 as usual and its normalized, quantized codes to ln->q
@@ -250,6 +257,7 @@ typedef struct {
   float s_log;
   int32_t bits;           /* 2..8 */
   uint8_t* codes;         /* [G, Nq, ld] out */
+  int32_t flags;          /* RQ_LOG_*: accepted for symmetry with rq_attn_pv; the codes do not depend on them */
 } rq_softmax_desc;
 rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d);
 
@@ -307,7 +315,8 @@ typedef struct {
   float* out_f32; int64_t ldf;
   int8_t* out_q; int64_t ldq;
   float s_o; int32_t z_o, off_o, bits_o;
-  const float* bias;      /* [H, N, N] dense, or NULL (last member: a zero-filled descriptor of the earlier layout reads as NULL) */
+  const float* bias;      /* [H, N, N] dense, or NULL */
+  int32_t flags;          /* RQ_LOG_ZERO_AT_MAX_CODE or 0 */
 } rq_attn_fused_desc;
 rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d);
 /* 1 if rq_attn_fused supports the shape (host, no context needed). */
@@ -344,6 +353,7 @@ typedef struct {
   int64_t ldq;
   float s_o;
   int32_t z_o, off_o, bits_o;
+  int32_t flags;          /* RQ_LOG_ZERO_AT_MAX_CODE or 0 */
 } rq_pv_desc;
 rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d);
 
@@ -440,12 +450,11 @@ typedef struct {
   double* loss;
   void* workspace;
   size_t workspace_bytes;
+  int32_t waves;         /* tuning: wavefronts per channel workgroup, 1..16; 0 chooses by shape.  The result does not
+                            depend on it beyond the order of the sums. */
 } rq_dual_clip_desc;
 size_t rq_dual_clip_workspace_bytes(int64_t T);
 rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d);
-/* Tuning knob (process-wide): wavefronts per channel workgroup of rq_dual_clip_learn, 1..16; 0 (default) chooses by
- * shape.  The result does not depend on it beyond the order of the sums. */
-rq_status rq_set_dual_clip_waves(int n);
 
 typedef struct {
   int32_t D, H, Dm;
@@ -465,26 +474,38 @@ typedef struct {
   rq_qlinear fc1;         /* N = Dm (GELU) or 2*Dm interleaved gate/up (SiLU gated) */
   float s_h; int32_t z_h;
   rq_qlinear fc2;         /* N = D, K = Dm */
+  /* ---- options of the plan; 0 (a zero-filled struct) selects the default of each.  rq_block_workspace_bytes and
+   * rq_block_forward read the same fields, so a workspace sized for these parameters fits their forward pass. ---- */
+  int32_t attn_path;      /* RQ_ATTN_*: how attention runs */
+  int32_t proj_ln_fused;  /* != 0: rq_qgemm_ln_quant for the output projection + second LayerNorm where it applies,
+                             instead of rq_qgemm followed by rq_ln_quant.  Same float32 residual stream and same codes up
+                             to the summation order of the row statistics; saves one read of the residual stream but runs
+                             one 64-row tile per compute unit, and measures no faster on the ViT-B shape. */
+  int64_t attn_chunk_bytes; /* where codes (and logits) travel through memory, attention runs in chunks of batch items so
+                             that one chunk's scratch stays in the last-level cache between its kernels: the chunk budget
+                             in bytes, at least 1 MiB; 0 = 64 MiB */
+  int32_t flags;          /* RQ_LOG_ZERO_AT_MAX_CODE or 0 */
 } rq_block_params;
-
-/* Attention runs in chunks of batch items so that the int32 logits and the codes of one chunk stay in the
- * last-level cache between Q.K^T, Softmax and P.V.  Sets the chunk budget in bytes (process-wide, default
- * 64 MiB); call before rq_block_workspace_bytes. */
-rq_status rq_set_attn_chunk_bytes(int64_t bytes);
-/* How rq_block_forward runs attention (process-wide; call before rq_block_workspace_bytes):
- *   1 (default): rq_attn_fused where it applies (no mask, short rows; see there), else as 2;
- *   2: rq_qk_softmax_log2_quant + rq_attn_pv wherever that call applies, else as 0;
- *   0: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length.
- * All three compute the same integers and the same codes (rows beyond 288 keys in mode 2: up to the order in which the
- * float32 row sum is accumulated). */
-rq_status rq_set_attn_fused(int on);
-/* 1: rq_block_forward takes rq_qgemm_ln_quant for the output projection + second LayerNorm where it applies
- * (process-wide); 0 (default): rq_qgemm followed by rq_ln_quant.  Both give the same float32 residual stream and the
- * same codes up to the summation order of the row statistics; the fused kernel saves one read of the residual stream
- * but runs one 64-row tile per compute unit with nothing to overlap its memory phase, and measures no faster on the
- * ViT-B shape. */
-rq_status rq_set_proj_ln_fused(int on);
+/* rq_block_params.attn_path.  All three compute the same integers and the same codes (rows beyond 288 keys with
+ * RQ_ATTN_QK_SOFTMAX_PV: up to the order in which the float32 row sum is accumulated).
+ *   RQ_ATTN_AUTO:          rq_attn_fused where it applies (no mask, short rows; see there), else as RQ_ATTN_QK_SOFTMAX_PV;
+ *   RQ_ATTN_QK_SOFTMAX_PV: rq_qk_softmax_log2_quant + rq_attn_pv wherever that call applies, else as RQ_ATTN_THREE_KERNELS;
+ *   RQ_ATTN_THREE_KERNELS: rq_qgemm (activation mode) + rq_softmax_log2_quant + rq_attn_pv for every length. */
+enum { RQ_ATTN_AUTO = 0, RQ_ATTN_QK_SOFTMAX_PV = 1, RQ_ATTN_THREE_KERNELS = 2 };
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq);
+/* Where the intermediates of rq_block_forward live inside the workspace (byte offsets from its start; host call, no
+ * context).  After a forward pass (and a synchronization of the stream) the regions hold: a = the codes of the second
+ * LayerNorm [T, D] (the first LayerNorm's codes were there before), qkv = the Q | K | V codes [T, 3D], o = the codes of the
+ * attention output [T, D], xbar = the float32 residual stream after attention [T, D], hidden = the codes of the MLP hidden
+ * layer [T, Dm], all stored as code - offset; logits (int32 [chunk*H, seq, ld]) and codes (uint8, same shape) hold the last
+ * attention chunk and are empty (0 bytes) on the paths that keep them in registers.  batch_chunk = batch items per
+ * attention chunk.  rq_block_calibrate_workspace_layout: the same for the calibration's own passes, which always run the
+ * three separate attention kernels; `total` then includes the calibration's further scratch. */
+typedef struct {
+  int64_t batch_chunk, ld;
+  size_t a, rowsum, qkv, logits, logits_bytes, codes, codes_bytes, o, xbar, hidden, total;
+} rq_block_layout;
+rq_status rq_block_workspace_layout(const rq_block_params* p, int64_t batch, int64_t seq, rq_block_layout* out);
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);
 
@@ -546,9 +567,13 @@ typedef struct {
   double learn_clip_alpha0;
   int32_t gptq;
   double gptq_percdamp;
+  int64_t attn_chunk_bytes; /* chunk budget of the calibration's own attention passes, as in rq_block_params; 0 = 64 MiB */
+  int32_t flags;            /* RQ_LOG_ZERO_AT_MAX_CODE or 0: enters the static scale of the attention output and is
+                               copied to out->flags */
 } rq_block_raw;
 
 size_t rq_block_calibrate_workspace_bytes(const rq_block_raw* raw, int64_t batch, int64_t seq);
+rq_status rq_block_calibrate_workspace_layout(const rq_block_raw* raw, int64_t batch, int64_t seq, rq_block_layout* out);
 /* `out` arrives with every array pointer set to caller-allocated device memory of the documented size
  * (ln*_gamma_t/beta_t [D]; each rq_qlinear: w, s_w, z_w, colsum_w, bias); scalar fields are written.
  * Synchronizes the stream (scalars are read back to the host). */

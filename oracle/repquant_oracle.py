@@ -28,7 +28,10 @@ Conventions the paper leaves open:
   * a Softmax value <= 0 takes the largest code; masked positions take no
     part in P.V;
   * every code, including the saturated one, dequantizes by the printed
-    formula (no "largest code means zero" rule);
+    formula; the other reading of the saturated code (the paper is silent: it
+    collects every probability below the grid, so it may be meant as "no mass")
+    is the option `zero_at_max`, under which the largest code dequantizes to
+    exactly 0 and every other code is unchanged;
   * stored scales are float32 numbers; all arithmetic on them is float64.
 
 Parity unpinned by the paper (conventions fixed here, not checked against a
@@ -119,9 +122,14 @@ def logsqrt2_quant_base2(A, s, bits):
     return np.clip(q, 0, qmax).astype(np.int64)
 
 
-def logsqrt2_dequant(q, s):
-    """log-sqrt2 de-quantizer, the definition: s * sqrt2^(-q)."""
-    return F64(s) * np.power(SQRT2, -np.asarray(q, dtype=F64))
+def logsqrt2_dequant(q, s, bits=None, zero_at_max=False):
+    """log-sqrt2 de-quantizer, the definition: s * sqrt2^(-q).
+    zero_at_max (needs bits): the saturated code 2^bits - 1 de-quantizes to 0 instead."""
+    q = np.asarray(q)
+    out = F64(s) * np.power(SQRT2, -q.astype(F64))
+    if zero_at_max:
+        out = np.where(q == 2 ** bits - 1, 0.0, out)
+    return out
 
 
 def parity_scale(q, s):
@@ -130,12 +138,16 @@ def parity_scale(q, s):
     return F64(s) * ((q & 1).astype(F64) * (SQRT2 - 1.0) + 1.0)
 
 
-def logsqrt2_dequant_shift(q, s):
+def logsqrt2_dequant_shift(q, s, bits=None, zero_at_max=False):
     """De-quantizer in shift form (last line of the case analysis before Eq. (3.3-2)):
-    s~(q) * 2^floor(-q / 2): an integer power of two times a scale picked by the code's parity."""
+    s~(q) * 2^floor(-q / 2): an integer power of two times a scale picked by the code's parity.
+    zero_at_max (needs bits): the saturated code 2^bits - 1 de-quantizes to 0 instead."""
     q = np.asarray(q, dtype=np.int64)
     shift = np.floor(-q.astype(F64) / 2.0)
-    return parity_scale(q, s) * np.exp2(shift)
+    out = parity_scale(q, s) * np.exp2(shift)
+    if zero_at_max:
+        out = np.where(q == 2 ** bits - 1, 0.0, out)
+    return out
 
 
 # --------------------------------------------------------------------------
@@ -319,10 +331,10 @@ def softmax_log_quant(L, s_log, bits):
     return logsqrt2_quant_base2(softmax_rows(L), s_log, bits)
 
 
-def attn_pv(codes, qv, s_log, s_v, z_v, causal=False):
+def attn_pv(codes, qv, s_log, s_v, z_v, causal=False, bits=None, zero_at_max=False):
     """P.V with shift-form de-quantized probabilities:
     out[i, c] = sum_j s~(code_ij) 2^floor(-code_ij / 2) * s_v (v[j, c] - z_v); masked j excluded."""
-    P = logsqrt2_dequant_shift(codes, s_log)
+    P = logsqrt2_dequant_shift(codes, s_log, bits, zero_at_max)
     if causal:
         n_q, n_k = P.shape
         P = np.where(np.arange(n_k)[None, :] > np.arange(n_q)[:, None], 0.0, P)
@@ -330,9 +342,9 @@ def attn_pv(codes, qv, s_log, s_v, z_v, causal=False):
     return P @ V
 
 
-def attn_pv_sqrt2(codes, qv, s_log, s_v, z_v, causal=False):
+def attn_pv_sqrt2(codes, qv, s_log, s_v, z_v, causal=False, bits=None, zero_at_max=False):
     """Definition tier of the same product: probabilities de-quantized as s * sqrt2^(-q)."""
-    P = logsqrt2_dequant(codes, s_log)
+    P = logsqrt2_dequant(codes, s_log, bits, zero_at_max)
     if causal:
         n_q, n_k = P.shape
         P = np.where(np.arange(n_k)[None, :] > np.arange(n_q)[:, None], 0.0, P)
@@ -353,6 +365,7 @@ def block_forward(P, x, keep=False):
     dh = D // H
     ba, bp = c["bits_a"], c["bits_p"]
     causal = c["mask"] == MASK_CAUSAL
+    zero_max = bool(c.get("log_zero_at_max_code", False))
     X = np.asarray(x, dtype=F64)
     T = X.shape[0]
     assert T == batch * seq
@@ -376,7 +389,7 @@ def block_forward(P, x, keep=False):
             L, acc = attention_logits(qq[r, cs], P["z_q"], P["s_q"], qk[r, cs], P["z_k"], P["s_k"],
                                       dh, bias, causal)
             codes = softmax_log_quant(L, P["s_log"], bp)
-            attn[r, cs] = attn_pv(codes, qv[r, cs], P["s_log"], P["s_v"], P["z_v"], causal)
+            attn[r, cs] = attn_pv(codes, qv[r, cs], P["s_log"], P["s_v"], P["z_v"], causal, bp, zero_max)
             if keep:
                 codes_all[b, h] = codes
                 acc_all[b, h] = acc
@@ -453,7 +466,7 @@ def _fold_ln(Xin, gamma, beta, W, b, clip_up, clip_lo, c, learn_clip=None):
 def calibrate_block(raw, cfg, learn_clip=None, gptq=False):
     """raw: dict of float32 arrays (x, ln1_gamma, ln1_beta, w_qkv, b_qkv, w_proj, b_proj, ln2_*, w_fc1,
     b_fc1, w_fc2, b_fc2, rel_bias, ln*_clip_up/lo); cfg: dict (batch, seq, D, H, Dm, bits_w, bits_a,
-    bits_p, norm, act, mask, eps).  Returns the parameter dict block_forward consumes.
+    bits_p, norm, act, mask, eps; optional log_zero_at_max_code).  Returns the parameter dict block_forward consumes.
     learn_clip: None (use the given clip factors) or dict(iters, lr, alpha0) -- learn them per LayerNorm (Algorithm 1);
     gptq: quantize every Linear with GPTQ against the codes it is fed, instead of round-to-nearest."""
     c = dict(cfg)
@@ -461,6 +474,7 @@ def calibrate_block(raw, cfg, learn_clip=None, gptq=False):
     dh = D // H
     ba, bw, bp = c["bits_a"], c["bits_w"], c["bits_p"]
     causal = c["mask"] == MASK_CAUSAL
+    zero_max = bool(c.get("log_zero_at_max_code", False))
     X = np.asarray(raw["x"], dtype=F64)
     P = dict(cfg=c, s_log=np.float32(1.0), rel_bias=raw.get("rel_bias"))
 
@@ -483,7 +497,7 @@ def calibrate_block(raw, cfg, learn_clip=None, gptq=False):
             bias = None if P["rel_bias"] is None else P["rel_bias"][h]
             L, _ = attention_logits(qq[r, cs], P["z_q"], P["s_q"], qk[r, cs], P["z_k"], P["s_k"], dh, bias, causal)
             codes = softmax_log_quant(L, P["s_log"], bp)
-            attn[r, cs] = attn_pv(codes, qv[r, cs], P["s_log"], P["s_v"], P["z_v"], causal)
+            attn[r, cs] = attn_pv(codes, qv[r, cs], P["s_log"], P["s_v"], P["z_v"], causal, bp, zero_max)
     P["s_o"], P["z_o"] = _tensor_qparams(attn, ba)
     qo = uniform_quant(attn, P["s_o"], P["z_o"], ba)
     P["proj"] = _lin(raw["w_proj"], raw["b_proj"], bw, qo - P["z_o"] if gptq else None)

@@ -24,6 +24,8 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 RQ_OK = 0
+LOG_ZERO_AT_MAX_CODE = 1
+ATTN_AUTO, ATTN_QK_SOFTMAX_PV, ATTN_THREE_KERNELS = 0, 1, 2
 NORM_LAYERNORM, NORM_RMSNORM = 0, 1
 ACT_NONE, ACT_GELU, ACT_SILU_GATED = 0, 1, 2
 MASK_NONE, MASK_CAUSAL = 0, 1
@@ -60,7 +62,7 @@ class DualClipDesc(C.Structure):
     _fields_ = [("T", i64), ("D", i32), ("ldx", i64), ("x", vp), ("norm_kind", i32), ("eps", f64), ("gamma", vp),
                 ("beta", vp), ("bits", i32), ("iters", i32), ("lr", f64), ("alpha0", f64), ("alpha1", vp), ("alpha2", vp),
                 ("clip_up", vp), ("clip_lo", vp), ("up", vp), ("lo", vp), ("loss0", vp), ("loss", vp),
-                ("workspace", vp), ("workspace_bytes", C.c_size_t)]
+                ("workspace", vp), ("workspace_bytes", C.c_size_t), ("waves", i32)]
 
 
 class GemmDesc(C.Structure):
@@ -76,7 +78,8 @@ class GemmDesc(C.Structure):
 
 class SoftmaxDesc(C.Structure):
     _fields_ = [("G", i64), ("H", i32), ("Nq", i32), ("Nk", i32), ("ld", i64), ("acc", vp),
-                ("logit_scale", f64), ("bias", vp), ("mask", i32), ("s_log", f32), ("bits", i32), ("codes", vp)]
+                ("logit_scale", f64), ("bias", vp), ("mask", i32), ("s_log", f32), ("bits", i32), ("codes", vp),
+                ("flags", i32)]
 
 
 class QkSoftmaxDesc(C.Structure):
@@ -90,14 +93,14 @@ class AttnFusedDesc(C.Structure):
                 ("q_off", i32), ("z_q", i32), ("k_off", i32), ("z_k", i32), ("v_off", i32), ("z_v", i32),
                 ("logit_scale", f64), ("s_log", f32), ("s_v", f32), ("bits_p", i32), ("codes", vp), ("ld", i64),
                 ("out_f32", vp), ("ldf", i64), ("out_q", vp), ("ldq", i64), ("s_o", f32), ("z_o", i32), ("off_o", i32),
-                ("bits_o", i32), ("bias", vp)]
+                ("bits_o", i32), ("bias", vp), ("flags", i32)]
 
 
 class PvDesc(C.Structure):
     _fields_ = [("batch", i64), ("H", i32), ("Nq", i32), ("Nk", i32), ("d_head", i32), ("ld", i64), ("codes", vp),
                 ("V", vp), ("ldv", i64), ("s_log", f32), ("s_v", f32), ("z_v", i32), ("v_off", i32),
                 ("bits_p", i32), ("mask", i32), ("out_f32", vp), ("ldf", i64), ("out_q", vp), ("ldq", i64),
-                ("s_o", f32), ("z_o", i32), ("off_o", i32), ("bits_o", i32)]
+                ("s_o", f32), ("z_o", i32), ("off_o", i32), ("bits_o", i32), ("flags", i32)]
 
 
 class QLinear(C.Structure):
@@ -114,7 +117,8 @@ class BlockParams(C.Structure):
                 ("rel_bias", vp), ("s_log", f32), ("s_o", f32), ("z_o", i32),
                 ("proj", QLinear),
                 ("ln2_gamma_t", vp), ("ln2_beta_t", vp), ("ln2_s", f32), ("ln2_z", i32),
-                ("fc1", QLinear), ("s_h", f32), ("z_h", i32), ("fc2", QLinear)]
+                ("fc1", QLinear), ("s_h", f32), ("z_h", i32), ("fc2", QLinear),
+                ("attn_path", i32), ("proj_ln_fused", i32), ("attn_chunk_bytes", i64), ("flags", i32)]
 
 
 class BlockRaw(C.Structure):
@@ -125,7 +129,13 @@ class BlockRaw(C.Structure):
                 ("w_fc2", vp), ("b_fc2", vp),
                 ("ln1_clip_up", vp), ("ln1_clip_lo", vp), ("ln2_clip_up", vp), ("ln2_clip_lo", vp),
                 ("rel_bias", vp), ("s_log", f32),
-                ("learn_clip_iters", i32), ("learn_clip_lr", f64), ("learn_clip_alpha0", f64), ("gptq", i32), ("gptq_percdamp", f64)]
+                ("learn_clip_iters", i32), ("learn_clip_lr", f64), ("learn_clip_alpha0", f64), ("gptq", i32), ("gptq_percdamp", f64),
+                ("attn_chunk_bytes", i64), ("flags", i32)]
+
+
+class BlockLayout(C.Structure):
+    _fields_ = [("batch_chunk", i64), ("ld", i64)] + [(k, C.c_size_t) for k in (
+        "a", "rowsum", "qkv", "logits", "logits_bytes", "codes", "codes_bytes", "o", "xbar", "hidden", "total")]
 
 
 def _sig(name, restype, argtypes):
@@ -211,10 +221,8 @@ _rq_qk_softmax = _sig("rq_qk_softmax_log2_quant", i32, [vp, C.POINTER(QkSoftmaxD
 _rq_attn_fused = _sig("rq_attn_fused", i32, [vp, C.POINTER(AttnFusedDesc)])
 _rq_attn_fused_supported = _sig("rq_attn_fused_supported", i32, [i32, i32, i32, i32])
 _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
+_rq_block_layout = _sig("rq_block_workspace_layout", i32, [C.POINTER(BlockParams), i64, i64, C.POINTER(BlockLayout)])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
-_rq_set_chunk = _sig("rq_set_attn_chunk_bytes", i32, [i64])
-_rq_set_fused = _sig("rq_set_attn_fused", i32, [i32])
-_rq_set_proj_ln = _sig("rq_set_proj_ln_fused", i32, [i32])
 _rq_qgemm_ln = _sig("rq_qgemm_ln_quant", i32, [vp, C.POINTER(GemmDesc), C.POINTER(LnDesc)])
 _rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
 _rq_profile_reset = _sig("rq_profile_reset", i32, [vp])
@@ -227,7 +235,6 @@ _rq_gptq_ws = _sig("rq_gptq_workspace_bytes", C.c_size_t, [i32, i32, i64])
 _rq_gptq = _sig("rq_gptq_quant_pack", i32, [vp, C.POINTER(GptqDesc)])
 _rq_dual_clip_ws = _sig("rq_dual_clip_workspace_bytes", C.c_size_t, [i64])
 _rq_dual_clip = _sig("rq_dual_clip_learn", i32, [vp, C.POINTER(DualClipDesc)])
-_rq_dual_clip_waves = _sig("rq_set_dual_clip_waves", i32, [i32])
 
 
 def rq_reparam_fold(ctx, s_ch, z_ch, gamma, beta, W, b, s_log=1.0):
@@ -366,12 +373,12 @@ def attn_fused_supported(N: int, d_head: int, bits_p: int, has_bias: bool = Fals
 
 
 def rq_attn_fused(ctx, qkv, batch, seq, H, d_head, q_off, z_q, k_off, z_k, v_off, z_v, logit_scale, s_log, s_v, bits_p, *,
-                  codes=None, ld=0, out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8, bias=None):
+                  codes=None, ld=0, out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8, bias=None, flags=0):
     """Whole attention of a [T, 3D] int8 tensor (Q | K | V column blocks) in one kernel."""
     base, D = qkv.data_ptr(), H * d_head
     d = AttnFusedDesc(batch=batch, H=H, N=seq, d_head=d_head, Q=base, K=base + D, V=base + 2 * D, ld_tok=qkv.stride(0),
                       q_off=q_off, z_q=z_q, k_off=k_off, z_k=z_k, v_off=v_off, z_v=z_v, logit_scale=logit_scale, s_log=s_log,
-                      s_v=s_v, bits_p=bits_p, codes=_p(codes), ld=ld, bias=_p(bias))
+                      s_v=s_v, bits_p=bits_p, codes=_p(codes), ld=ld, bias=_p(bias), flags=flags)
     if out_f32 is not None:
         d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
     if out_q is not None:
@@ -380,9 +387,9 @@ def rq_attn_fused(ctx, qkv, batch, seq, H, d_head, q_off, z_q, k_off, z_k, v_off
 
 
 def rq_attn_pv(ctx, codes, ld, V_ptr, ldv, batch, H, Nq, Nk, d_head, s_log, s_v, z_v, v_off, bits_p, *, mask=MASK_NONE,
-               out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8):
+               out_f32=None, out_q=None, s_o=1.0, z_o=0, off_o=0, bits_o=8, flags=0):
     d = PvDesc(batch=batch, H=H, Nq=Nq, Nk=Nk, d_head=d_head, ld=ld, codes=_p(codes), V=V_ptr, ldv=ldv, s_log=s_log,
-               s_v=s_v, z_v=z_v, v_off=v_off, bits_p=bits_p, mask=mask)
+               s_v=s_v, z_v=z_v, v_off=v_off, bits_p=bits_p, mask=mask, flags=flags)
     if out_f32 is not None:
         d.out_f32, d.ldf = _p(out_f32), out_f32.stride(0)
     if out_q is not None:
@@ -402,7 +409,8 @@ def rq_ln_channel_minmax(ctx, x, gamma, beta, norm_kind=NORM_LAYERNORM, eps=1e-6
     return cmin, cmax
 
 
-def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYERNORM, eps=1e-6, iters=100, lr=0.01, alpha0=4.0):
+def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYERNORM, eps=1e-6, iters=100, lr=0.01, alpha0=4.0,
+                       waves=0):
     """Learn the per-channel clipping factors of X' = norm(x) * gamma + beta (or of x itself when gamma is None).
     Returns a dict of device tensors: alpha1, alpha2, up, lo, loss0, loss (float64 [D]), clip_up, clip_lo (float32 [D])."""
     T, D = x.shape
@@ -415,7 +423,7 @@ def rq_dual_clip_learn(ctx, x, bits, gamma=None, beta=None, norm_kind=NORM_LAYER
     d = DualClipDesc(T=T, D=D, ldx=x.stride(0), x=_p(x), norm_kind=norm_kind, eps=eps, gamma=_p(gamma), beta=_p(beta), bits=bits,
                      iters=iters, lr=lr, alpha0=alpha0, alpha1=_p(out["alpha1"]), alpha2=_p(out["alpha2"]),
                      clip_up=_p(out["clip_up"]), clip_lo=_p(out["clip_lo"]), up=_p(out["up"]), lo=_p(out["lo"]),
-                     loss0=_p(out["loss0"]), loss=_p(out["loss"]), workspace=_p(ws), workspace_bytes=nbytes)
+                     loss0=_p(out["loss0"]), loss=_p(out["loss"]), workspace=_p(ws), workspace_bytes=nbytes, waves=waves)
     ctx.check(_rq_dual_clip(ctx.handle, C.byref(d)))
     out["_workspace"] = ws                      # keeps the scratch alive until the caller drops the result
     return out
@@ -433,34 +441,10 @@ def rq_ln_channel_percentile(ctx, x, q_lo, q_hi, gamma=None, beta=None, norm_kin
     return lo, hi, ws
 
 
-def set_dual_clip_waves(n: int):
-    if _rq_dual_clip_waves(int(n)) != 0:
-        raise ValueError("rq_set_dual_clip_waves(%r)" % (n,))
-
-
 def rq_minmax_f32(ctx, v):
     out = torch.empty(2, dtype=torch.float64, device=v.device)
     ctx.check(_rq_minmax(ctx.handle, _p(v), v.shape[0], v.shape[1], v.stride(0), _p(out)))
     return out
-
-
-def set_attn_chunk_bytes(nbytes: int):
-    rc = _rq_set_chunk(nbytes)
-    if rc != RQ_OK:
-        raise RqError(rc, _rq_last_error(None).decode())
-
-
-def set_proj_ln_fused(on: bool):
-    rc = _rq_set_proj_ln(1 if on else 0)
-    if rc != RQ_OK:
-        raise RqError(rc, _rq_last_error(None).decode())
-
-
-def set_attn_fused(on):
-    """0: three kernels, 2: fused Q.K^T + softmax then P.V, 1 / True: whole attention in one kernel where it applies."""
-    rc = _rq_set_fused(int(on))
-    if rc != RQ_OK:
-        raise RqError(rc, _rq_last_error(None).decode())
 
 
 def _qlinear_struct(lin) -> QLinear:
@@ -471,12 +455,13 @@ def _qlinear_struct(lin) -> QLinear:
 class Block:
     """Device-resident quantized block parameters + workspace; forward() calls rq_block_forward."""
 
-    def __init__(self, ctx: Context, cfg, P):
+    def __init__(self, ctx: Context, cfg, P, attn_path=ATTN_AUTO, attn_chunk_bytes=0, proj_ln_fused=False, flags=0):
         """cfg: object with D, H, Dm, norm, act, mask, bits_a, bits_p, eps.  P: dict of device tensors / scalars:
         ln1/ln2 {gamma_t, beta_t, s, z}; qkv/proj/fc1/fc2 dicts as produced by rq_weight_quant_pack;
-        s_q.., z_q.., s_o, z_o, s_h, z_h, s_log, rel_bias."""
+        s_q.., z_q.., s_o, z_o, s_h, z_h, s_log, rel_bias.  The keyword arguments are the plan options of rq_block_params."""
         self.ctx, self.cfg, self.P = ctx, cfg, P
         bp = BlockParams()
+        bp.attn_path, bp.attn_chunk_bytes, bp.proj_ln_fused, bp.flags = attn_path, attn_chunk_bytes, int(proj_ln_fused), flags
         bp.D, bp.H, bp.Dm = cfg.D, cfg.H, cfg.Dm
         bp.norm_kind, bp.mask = cfg.norm, cfg.mask
         bp.act = ACT_GELU if cfg.act == 0 else ACT_SILU_GATED
@@ -498,7 +483,7 @@ class Block:
         self._ws_key = None
 
     def workspace(self, batch, seq):
-        key = (batch, seq)
+        key = (batch, seq, self.bp.attn_path, self.bp.attn_chunk_bytes, self.bp.proj_ln_fused)
         if self._ws_key != key:
             n = int(_rq_block_ws(C.byref(self.bp), batch, seq))
             self._ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
@@ -506,6 +491,24 @@ class Block:
             self._ws_n = n
         off = (-self._ws.data_ptr()) % 256
         return self._ws.data_ptr() + off, self._ws_n
+
+    def layout(self, batch, seq) -> BlockLayout:
+        lay = BlockLayout()
+        rc = _rq_block_layout(C.byref(self.bp), batch, seq, C.byref(lay))
+        if rc != RQ_OK:
+            raise RqError(rc, _rq_last_error(None).decode())
+        return lay
+
+    def intermediates(self, batch, seq):
+        """Views (torch, no copy) of the workspace regions a finished forward pass leaves behind: a2, qkv, o, xbar, hidden."""
+        lay, T, D, Dm = self.layout(batch, seq), batch * seq, self.bp.D, self.bp.Dm
+        ptr, _ = self.workspace(batch, seq)
+        base = ptr - self._ws.data_ptr()
+        i8 = self._ws.view(torch.int8)
+        return dict(a2=i8[base + lay.a: base + lay.a + T * D].view(T, D), qkv=i8[base + lay.qkv: base + lay.qkv + 3 * T * D].view(T, 3 * D),
+                    o=i8[base + lay.o: base + lay.o + T * D].view(T, D),
+                    xbar=self._ws[base + lay.xbar: base + lay.xbar + 4 * T * D].view(torch.float32).view(T, D),
+                    hidden=i8[base + lay.hidden: base + lay.hidden + T * Dm].view(T, Dm))
 
     def forward(self, x: torch.Tensor, y: torch.Tensor, batch: int, seq: int):
         ptr, n = self.workspace(batch, seq)
@@ -528,20 +531,20 @@ def profile_read(ctx: Context):
     return {STEP_NAMES[i]: (ms[i], n[i]) for i in range(len(STEP_NAMES))}
 
 
-_rq_set_tile = _sig("rq_set_gemm_tile", i32, [i32])
+_rq_set_tile = _sig("rq_set_gemm_tile", i32, [vp, i32])
 
 
-def set_gemm_tile(tile: int):
-    rc = _rq_set_tile(tile)
-    if rc != RQ_OK:
-        raise RqError(rc, _rq_last_error(None).decode())
+def set_gemm_tile(ctx: Context, tile: int):
+    ctx.check(_rq_set_tile(ctx.handle, tile))
 
 
 _rq_cal_ws = _sig("rq_block_calibrate_workspace_bytes", C.c_size_t, [C.POINTER(BlockRaw), i64, i64])
+_rq_cal_layout = _sig("rq_block_calibrate_workspace_layout", i32, [C.POINTER(BlockRaw), i64, i64, C.POINTER(BlockLayout)])
 _rq_calibrate = _sig("rq_block_calibrate", i32, [vp, C.POINTER(BlockRaw), vp, i64, i64, C.POINTER(BlockParams), vp, C.c_size_t])
 
 
-def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: int, learn_clip=None, gptq=False) -> "Block":
+def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: int, learn_clip=None, gptq=False,
+                    attn_chunk_bytes=0, flags=0) -> "Block":
     """Allocates the quantized-parameter arrays, runs rq_block_calibrate on the batch x and returns a Block.
     raw: dict of device float32 tensors named as in synth.make_block (None allowed where the C struct allows NULL).
     learn_clip: None or dict(iters, lr, alpha0) -- learn the LayerNorm clip factors; gptq: GPTQ instead of round-to-nearest."""
@@ -557,6 +560,7 @@ def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: in
         br.learn_clip_iters, br.learn_clip_lr, br.learn_clip_alpha0 = learn_clip["iters"], learn_clip["lr"], learn_clip["alpha0"]
     if gptq:
         br.gptq, br.gptq_percdamp = 1, 0.01
+    br.attn_chunk_bytes, br.flags = attn_chunk_bytes, flags
     for k in ("ln1_gamma", "ln1_beta", "ln2_gamma", "ln2_beta", "w_qkv", "b_qkv", "w_proj", "b_proj", "w_fc1", "b_fc1",
               "w_fc2", "b_fc2", "ln1_clip_up", "ln1_clip_lo", "ln2_clip_up", "ln2_clip_lo", "rel_bias"):
         setattr(br, k, _p(raw.get(k)))
@@ -577,7 +581,7 @@ def calibrate_block(ctx: Context, cfg, raw, x: torch.Tensor, batch: int, seq: in
         P[k] = 1.0
     for k in ("z_q", "z_k", "z_v", "z_o", "z_h"):
         P[k] = 0
-    blk = Block(ctx, cfg, P)
+    blk = Block(ctx, cfg, P, flags=flags)
     n = int(_rq_cal_ws(C.byref(br), batch, seq))
     ws = torch.empty(n + 256, dtype=torch.uint8, device=dev)
     ptr = ws.data_ptr() + (-ws.data_ptr()) % 256

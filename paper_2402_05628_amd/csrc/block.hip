@@ -15,22 +15,32 @@ size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Plan {
   int64_t T, batch, seq, ld, bchunk;
   size_t o_a, o_rowsum, o_qkv, o_acc, o_codes, o_o, o_xbar, o_hid, total;
+  size_t acc_bytes, codes_bytes;
 };
 
-int64_t g_attn_chunk_bytes = 64ll << 20;
-int g_attn_fused = 1;
-int g_proj_ln_fused = 0;
+void export_layout(const Plan& pl, rq_block_layout* out) {
+  out->batch_chunk = pl.bchunk; out->ld = pl.ld;
+  out->a = pl.o_a; out->rowsum = pl.o_rowsum; out->qkv = pl.o_qkv; out->logits = pl.o_acc; out->logits_bytes = pl.acc_bytes;
+  out->codes = pl.o_codes; out->codes_bytes = pl.codes_bytes; out->o = pl.o_o; out->xbar = pl.o_xbar; out->hidden = pl.o_hid;
+  out->total = pl.total;
+}
 
+constexpr int64_t DEFAULT_CHUNK_BYTES = 64ll << 20;
+
+// Q.K^T + Softmax-log2 in one kernel (no int32 logits in memory)
 bool use_fused(const rq_block_params* p, int64_t seq) {
-  return g_attn_fused && p->H > 0 && p->D % p->H == 0 && rq_qk_softmax_supported((int)seq, p->D / p->H, p->rel_bias != nullptr);
+  return p->attn_path != RQ_ATTN_THREE_KERNELS && p->H > 0 && p->D % p->H == 0 &&
+         rq_qk_softmax_supported((int)seq, p->D / p->H, p->rel_bias != nullptr);
 }
 
 // the whole attention in one kernel: neither logits nor codes reach memory
 bool use_whole(const rq_block_params* p, int64_t seq) {
-  return g_attn_fused == 1 && p->H > 0 && p->D % p->H == 0 && p->mask == RQ_MASK_NONE &&
+  return p->attn_path == RQ_ATTN_AUTO && p->H > 0 && p->D % p->H == 0 && p->mask == RQ_MASK_NONE &&
          rq_attn_fused_preferred((int)seq, p->D / p->H, p->bits_p, p->rel_bias != nullptr);
 }
 
+// The workspace layout follows the attention path the parameters select; the forward pass and the workspace query
+// read the same fields, so the two cannot disagree.
 Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   Plan pl;
   pl.batch = batch; pl.seq = seq; pl.T = batch * seq;
@@ -38,7 +48,8 @@ Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   const bool fused = use_fused(p, seq);       // no int32 logits in memory: only the codes count
   const bool whole = use_whole(p, seq);      // nothing to keep cache-resident between kernels: one chunk
   const int64_t per_item = (int64_t)p->H * seq * pl.ld * (fused ? 1 : 5);
-  pl.bchunk = whole ? batch : g_attn_chunk_bytes / (per_item > 0 ? per_item : 1);
+  const int64_t chunk_bytes = p->attn_chunk_bytes > 0 ? p->attn_chunk_bytes : DEFAULT_CHUNK_BYTES;
+  pl.bchunk = whole ? batch : chunk_bytes / (per_item > 0 ? per_item : 1);
   if (pl.bchunk < 1) pl.bchunk = 1;
   if (pl.bchunk > batch) pl.bchunk = batch;
   if (batch > 0) {      // equal chunks: a small last chunk would run its kernels on a nearly empty chip
@@ -50,8 +61,10 @@ Plan make_plan(const rq_block_params* p, int64_t batch, int64_t seq) {
   pl.o_a = o; o += up((size_t)pl.T * p->D);
   pl.o_rowsum = o; o += up((size_t)pl.T * 4);
   pl.o_qkv = o; o += up((size_t)pl.T * 3 * p->D);
-  pl.o_acc = o; o += fused ? 0 : up((size_t)gch * seq * pl.ld * 4);
-  pl.o_codes = o; o += whole ? 0 : up((size_t)gch * seq * pl.ld);
+  pl.acc_bytes = fused ? 0 : up((size_t)gch * seq * pl.ld * 4);
+  pl.codes_bytes = whole ? 0 : up((size_t)gch * seq * pl.ld);
+  pl.o_acc = o; o += pl.acc_bytes;
+  pl.o_codes = o; o += pl.codes_bytes;
   pl.o_o = o; o += up((size_t)pl.T * p->D);
   pl.o_xbar = o; o += up((size_t)pl.T * p->D * 4);
   pl.o_hid = o; o += up((size_t)pl.T * p->Dm);
@@ -81,26 +94,16 @@ rq_status check_linear(rq_ctx* ctx, const char* name, const rq_qlinear& l, int N
 
 extern "C" {
 
-rq_status rq_set_attn_fused(int on) {
-  if (on < 0 || on > 2) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_attn_fused: %d not in 0..2", on);
-  g_attn_fused = on;
-  return RQ_OK;
-}
-
-rq_status rq_set_proj_ln_fused(int on) {
-  g_proj_ln_fused = on != 0;
-  return RQ_OK;
-}
-
-rq_status rq_set_attn_chunk_bytes(int64_t bytes) {
-  if (bytes < (1 << 20)) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_attn_chunk_bytes: at least 1 MiB");
-  g_attn_chunk_bytes = bytes;
-  return RQ_OK;
-}
-
 size_t rq_block_workspace_bytes(const rq_block_params* p, int64_t batch, int64_t seq) {
   if (!p || batch <= 0 || seq <= 0 || p->D <= 0 || p->H <= 0 || p->Dm <= 0) return 0;
   return make_plan(p, batch, seq).total;
+}
+
+rq_status rq_block_workspace_layout(const rq_block_params* p, int64_t batch, int64_t seq, rq_block_layout* out) {
+  if (!p || !out || batch <= 0 || seq <= 0 || p->D <= 0 || p->H <= 0 || p->Dm <= 0)
+    return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_block_workspace_layout: NULL argument or non-positive size");
+  export_layout(make_plan(p, batch, seq), out);
+  return RQ_OK;
 }
 
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y, int64_t batch, int64_t seq,
@@ -118,6 +121,11 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   RQ_REQUIRE(p->bits_a >= 2 && p->bits_a <= 8 && p->bits_p >= 2 && p->bits_p <= 8, RQ_ERR_INVALID_ARG,
              "rq_block_forward: bits_a = %d, bits_p = %d", p->bits_a, p->bits_p);
   RQ_REQUIRE(p->ln1_gamma_t && p->ln2_gamma_t, RQ_ERR_INVALID_ARG, "rq_block_forward: LayerNorm gammas must be non-NULL");
+  RQ_REQUIRE(p->attn_path >= RQ_ATTN_AUTO && p->attn_path <= RQ_ATTN_THREE_KERNELS, RQ_ERR_INVALID_ARG,
+             "rq_block_forward: attn_path = %d", p->attn_path);
+  RQ_REQUIRE(p->attn_chunk_bytes == 0 || p->attn_chunk_bytes >= (1 << 20), RQ_ERR_INVALID_ARG,
+             "rq_block_forward: attn_chunk_bytes must be 0 (default) or at least 1 MiB");
+  RQ_REQUIRE((p->flags & ~RQ_LOG_ZERO_AT_MAX_CODE) == 0, RQ_ERR_INVALID_ARG, "rq_block_forward: flags = %d", p->flags);
   const bool gated = p->act == RQ_ACT_SILU_GATED;
   rq_status st;
   if ((st = check_linear(ctx, "qkv", p->qkv, 3 * D, D)) != RQ_OK) return st;
@@ -186,7 +194,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
       d.batch = nb; d.H = H; d.N = (int)seq; d.d_head = dh; d.Q = qkv_c; d.K = qkv_c + D; d.V = qkv_c + 2 * D; d.ld_tok = 3 * D;
       d.q_off = offq; d.z_q = p->z_q; d.k_off = offk; d.z_k = p->z_k; d.v_off = offv; d.z_v = p->z_v;
       d.logit_scale = (double)p->s_q * (double)p->s_k / std::sqrt((double)dh);
-      d.s_log = p->s_log; d.s_v = p->s_v; d.bits_p = p->bits_p; d.bias = p->rel_bias;
+      d.s_log = p->s_log; d.s_v = p->s_v; d.bits_p = p->bits_p; d.bias = p->rel_bias; d.flags = p->flags;
       d.out_q = o + b0 * seq * D; d.ldq = D; d.s_o = p->s_o; d.z_o = p->z_o; d.off_o = offo; d.bits_o = ba;
       rq_prof_begin(ctx, RQ_STEP_QK);
       st = rq_launch_attn_fused(ctx, &d);
@@ -234,7 +242,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
       std::memset(&d, 0, sizeof d);
       d.batch = nb; d.H = H; d.Nq = (int)seq; d.Nk = (int)seq; d.d_head = dh; d.ld = pl.ld; d.codes = codes;
       d.V = qkv_c + 2 * D; d.ldv = 3 * D; d.s_log = p->s_log; d.s_v = p->s_v; d.z_v = p->z_v; d.v_off = offv;
-      d.bits_p = p->bits_p; d.mask = p->mask;
+      d.bits_p = p->bits_p; d.mask = p->mask; d.flags = p->flags;
       d.out_q = o + b0 * seq * D; d.ldq = D; d.s_o = p->s_o; d.z_o = p->z_o; d.off_o = offo; d.bits_o = ba;
       rq_prof_begin(ctx, RQ_STEP_PV);
       st = rq_attn_pv(ctx, &d);
@@ -261,7 +269,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
     d.T = T; d.D = D; d.norm_kind = p->norm_kind; d.eps = p->eps; d.x = xbar; d.ldx = D;
     d.gamma_t = p->ln2_gamma_t; d.beta_t = p->ln2_beta_t; d.s_tilde = p->ln2_s; d.z_tilde = p->ln2_z; d.bits = ba;
     d.store_off = off2; d.q = a; d.ldq = D; d.rowsum = need_rowsum(p->fc1) ? rowsum : nullptr;
-    if (g_proj_ln_fused && rq_qgemm_rowln_applies(&g, &d)) {
+    if (p->proj_ln_fused && rq_qgemm_rowln_applies(&g, &d)) {
       rq_prof_begin(ctx, RQ_STEP_PROJ);
       st = rq_qgemm_ln_quant(ctx, &g, &d);
       rq_prof_end(ctx);
@@ -322,9 +330,14 @@ struct CalPlan {
 };
 
 CalPlan make_cal_plan(const rq_block_raw* raw, int64_t batch, int64_t seq) {
+  // The calibration walks attention with the three separate kernels (it needs the float P.V output of the first pass),
+  // so its plan is the three-kernel one whatever the forward pass would choose: int32 logits and codes in regions of
+  // their own, sized for one chunk.
   rq_block_params tmp;
   std::memset(&tmp, 0, sizeof tmp);
   tmp.D = raw->D; tmp.H = raw->H; tmp.Dm = raw->Dm;
+  tmp.attn_path = RQ_ATTN_THREE_KERNELS;
+  tmp.attn_chunk_bytes = raw->attn_chunk_bytes;
   CalPlan c;
   c.fwd = make_plan(&tmp, batch, seq);
   const int D = raw->D, Dm = raw->Dm;
@@ -370,6 +383,15 @@ size_t rq_block_calibrate_workspace_bytes(const rq_block_raw* raw, int64_t batch
   return make_cal_plan(raw, batch, seq).total;
 }
 
+rq_status rq_block_calibrate_workspace_layout(const rq_block_raw* raw, int64_t batch, int64_t seq, rq_block_layout* out) {
+  if (!raw || !out || batch <= 0 || seq <= 0 || raw->D <= 0 || raw->H <= 0 || raw->Dm <= 0)
+    return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_block_calibrate_workspace_layout: NULL argument or non-positive size");
+  const CalPlan cp = make_cal_plan(raw, batch, seq);
+  export_layout(cp.fwd, out);
+  out->total = cp.total;
+  return RQ_OK;
+}
+
 rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* x, int64_t batch, int64_t seq,
                              rq_block_params* out, void* workspace, size_t workspace_bytes) {
   if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_block_calibrate: ctx is NULL");
@@ -382,6 +404,9 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
   RQ_REQUIRE(raw->s_log > 0.f, RQ_ERR_INVALID_ARG, "rq_block_calibrate: s_log must be > 0");
   RQ_REQUIRE(raw->learn_clip_iters >= 0 && raw->learn_clip_iters <= 100000, RQ_ERR_INVALID_ARG,
              "rq_block_calibrate: learn_clip_iters = %d", raw->learn_clip_iters);
+  RQ_REQUIRE(raw->attn_chunk_bytes == 0 || raw->attn_chunk_bytes >= (1 << 20), RQ_ERR_INVALID_ARG,
+             "rq_block_calibrate: attn_chunk_bytes must be 0 (default) or at least 1 MiB");
+  RQ_REQUIRE((raw->flags & ~RQ_LOG_ZERO_AT_MAX_CODE) == 0, RQ_ERR_INVALID_ARG, "rq_block_calibrate: flags = %d", raw->flags);
   if (raw->gptq)
     RQ_REQUIRE(raw->D % 64 == 0 && raw->Dm % 64 == 0 && raw->D <= 8192 && raw->Dm <= 8192 && batch * seq <= 131071,
                RQ_ERR_UNSUPPORTED, "rq_block_calibrate: GPTQ needs D and Dm multiples of 64, at most 8192, and at most 131071 tokens");
@@ -424,6 +449,7 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
 
   out->D = D; out->H = H; out->Dm = Dm; out->norm_kind = raw->norm_kind; out->act = raw->act; out->mask = raw->mask;
   out->bits_a = ba; out->bits_p = raw->bits_p; out->eps = raw->eps; out->rel_bias = raw->rel_bias; out->s_log = raw->s_log;
+  out->flags = raw->flags;
 
   auto minmax_host = [&](const float* v, int64_t rows, int64_t cols, int64_t ld, double* lo, double* hi) -> rq_status {
     double* d2 = reinterpret_cast<double*>(scal + 16);
@@ -545,7 +571,7 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
       std::memset(&pd, 0, sizeof pd);
       pd.batch = nb; pd.H = H; pd.Nq = (int)seq; pd.Nk = (int)seq; pd.d_head = dh; pd.ld = pl.ld; pd.codes = codes;
       pd.V = qkv_c + 2 * D; pd.ldv = 3 * D; pd.s_log = raw->s_log; pd.s_v = out->s_v; pd.z_v = out->z_v; pd.v_off = offv;
-      pd.bits_p = raw->bits_p; pd.mask = raw->mask;
+      pd.bits_p = raw->bits_p; pd.mask = raw->mask; pd.flags = raw->flags;
       if (pass == 0) {
         pd.out_f32 = f32 + b0 * seq * D; pd.ldf = D;
       } else {

@@ -324,13 +324,6 @@ rq_status launch_learner(rq_ctx* ctx, const LearnParams& p, int nw, int lds_rows
 
 }  // namespace
 
-static int g_dual_clip_waves = 0;       // 0: chosen by shape
-extern "C" rq_status rq_set_dual_clip_waves(int n) {
-  if (n < 0 || n > 16) return RQ_ERR_INVALID_ARG;
-  g_dual_clip_waves = n;
-  return RQ_OK;
-}
-
 rq_status rq_launch_row_stats(rq_ctx* ctx, const float* x, int64_t T, int32_t D, int64_t ldx, int32_t norm_kind, double eps,
                               double* stats) {
   hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, ctx->stream, x, T, D, ldx, norm_kind, eps, stats);
@@ -355,8 +348,8 @@ rq_status rq_launch_dual_clip(rq_ctx* ctx, const rq_dual_clip_desc* d) {
     p.stats = stats;
   }
   Shape sh = choose_shape(d->T, d->D, ctx->num_cu);
-  if (g_dual_clip_waves > 0) {
-    sh.nw = g_dual_clip_waves;
+  if (d->waves > 0) {
+    sh.nw = d->waves;
     const int64_t rpt = (d->T + 64 * sh.nw - 1) / (64 * sh.nw);
     const int64_t cap = lds_row_cap(sh.nw);
     sh.lds_rows = (int)(rpt > MAX_RPT ? (rpt - MAX_RPT < cap ? rpt - MAX_RPT : cap) : 0);

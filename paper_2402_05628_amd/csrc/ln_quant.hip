@@ -165,12 +165,8 @@ __global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_
 
 template <int LPR, int NV, bool F32Q, bool PERSIST>
 rq_status launch_one(rq_ctx* ctx, const rq_ln_desc* d, int64_t blocks, int lds, double inv_s, double zcode, float qmaxf, unsigned off4) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV, F32Q, PERSIST>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 16));
-    attr_set = true;
-  }
+  static rq_once_per_device lds_attr;
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV, F32Q, PERSIST>), 8192 * 16));
   hipLaunchKernelGGL((ln_quant_kernel<LPR, NV, F32Q, PERSIST>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T,
                      d->D, d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);
   RQ_HIP(hipGetLastError());

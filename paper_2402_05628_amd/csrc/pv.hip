@@ -39,6 +39,8 @@ struct PvParams {
   int zo, lo, hi;      // z_o - off_o, clamp bounds of the stored code
   int tiles_i;
   int num_cu;          // causal: every second round of workgroups walks its group's query tiles backwards
+  int zero_max;        // RQ_LOG_ZERO_AT_MAX_CODE: keys whose code is the largest one contribute nothing
+  unsigned qmax4;      // the largest code in each of the four bytes
 };
 
 constexpr int JB = 256;          // keys staged per LDS block (288 for rows of 257 .. 288 keys)
@@ -218,6 +220,7 @@ __global__ __launch_bounds__(256) void pv_kernel(const PvParams p) {
           unsigned pall = __builtin_amdgcn_perm(TAB_HI, TAB_LO, sel);
           if (WIDE) pall &= byte_eq_mask((kr >> 3) & 0x1F1F1F1Fu, wref);
           pall &= vm;
+          if (p.zero_max) pall &= ~rq_byte_eq_mask(c, p.qmax4);      // uniform branch
           const unsigned odd = (c & 0x01010101u) * 0xFFu;
           po[d4] = (int)(pall & odd);
           pe[d4] = (int)(pall & ~odd);
@@ -432,6 +435,7 @@ __global__ __launch_bounds__(512) void pv_long_kernel(const PvParams p, const in
             nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
             c |= nv == 4 ? 0u : ~((1u << (8 * nv)) - 1u);
           }
+          if (p.zero_max) c |= rq_byte_eq_mask(c, p.qmax4);      // the largest code reads as 255 as well (uniform branch)
 #pragma unroll
           for (int pr = 0; pr < 2; ++pr) {
             // two codes as halfwords; bfloat16 bits of 2^-k are (127 - k) << 7 = 0x3F80 - ((code & 0xFE) << 6)
@@ -489,11 +493,8 @@ rq_status launch_long(rq_ctx* ctx, const PvParams& p, int64_t groups) {
   const int64_t blocks = groups * wgs_per_group;
   if (blocks > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "rq_attn_pv: %lld workgroups exceed 2^30", (long long)blocks);
   constexpr int lds = pv_long_lds<DH>();
-  static bool attr_set = false;
-  if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pv_long_kernel<DH>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
+  static rq_once_per_device lds_attr;
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&pv_long_kernel<DH>), lds));
   hipLaunchKernelGGL((pv_long_kernel<DH>), dim3((unsigned)blocks), dim3(512), lds, ctx->stream, p, wgs_per_group);
   return RQ_OK;
 }
@@ -524,6 +525,8 @@ rq_status rq_launch_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
   p.tiles_i = (d->Nq + 31) / 32;
   p.num_cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
+  p.zero_max = (d->flags & RQ_LOG_ZERO_AT_MAX_CODE) != 0;
+  p.qmax4 = (unsigned)((1 << d->bits_p) - 1) * 0x01010101u;
   const bool wide = d->bits_p > 4;
   const int64_t groups = d->batch * d->H;
   if (wide && d->Nk > JB) {

@@ -16,10 +16,6 @@
 rq_status rq_launch_qgemm_pipe_w4(rq_ctx* ctx, rqg::GemmParams& p);
 bool rq_qgemv_applies(const rqg::GemmParams& p, bool w4);
 rq_status rq_launch_qgemv_w4(rq_ctx* ctx, const rqg::GemmParams& p);
-#ifdef RQ_GEMM_TS
-static long long* g_debug_ts = nullptr;
-extern "C" void rq_debug_gemm_ts(void* ptr) { g_debug_ts = static_cast<long long*>(ptr); }
-#endif
 rq_status rq_launch_qgemm_pipe_i8(rq_ctx* ctx, rqg::GemmParams& p);
 
 namespace {
@@ -148,19 +144,18 @@ void launch_tile(rq_ctx* ctx, GemmParams& p) {
 
 }  // namespace
 
-static int g_gemm_tile = 0;   // 0: choose by shape, 1: 128x128 simple, 2: 256x128 simple, 3: pipelined; 4 .. 7: pipelined with 320- / 192- / 128- / 256-row tiles where they exist; 8: 256 x 256 tiles
-
-extern "C" rq_status rq_set_gemm_tile(int32_t tile) {
-  if (tile < 0 || tile > 8) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: %d not in 0..8", tile);
-  g_gemm_tile = tile;
+// ctx->gemm_tile: 0: choose by shape, 1: 128x128 simple, 2: 256x128 simple, 3: pipelined; 4 .. 7: pipelined with 320- / 192- /
+// 128- / 256-row tiles where they exist; 8: 256 x 256 tiles
+extern "C" rq_status rq_set_gemm_tile(rq_ctx* ctx, int32_t tile) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: ctx is NULL");
+  RQ_REQUIRE(tile >= 0 && tile <= 8, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: %d not in 0..8", tile);
+  ctx->gemm_tile = tile;
   return RQ_OK;
 }
 
 rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   GemmParams p;
-#ifdef RQ_GEMM_TS
-  p.ts = g_debug_ts;
-#endif
+  const int g_gemm_tile = ctx->gemm_tile;
   p.M = d->M; p.N = d->N; p.K = d->K;
   p.A = d->A; p.lda = d->lda;
   p.B = static_cast<const uint8_t*>(d->B); p.ldb = d->ldb;

@@ -42,9 +42,6 @@ struct GemmParams {
   int tiles_m, tiles_n;
   int group_m;      // tile rows walked together: consecutive tiles go down group_m rows before they move to the next column
   int force_rows;   // host only: 64-row groups per tile to take wherever that tile exists (0: choose by shape)
-#ifdef RQ_GEMM_TS
-  long long* ts;
-#endif
 };
 
 __device__ __forceinline__ int swz(int row, int c) {

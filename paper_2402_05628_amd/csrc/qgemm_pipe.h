@@ -355,19 +355,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
                                          (__attribute__((address_space(3))) void*)(lb + (wave * BL + i) * 1024), 16, 0, 0);
     }
   };
-#ifdef RQ_GEMM_TS   // development builds only: per-workgroup cycle stamps of the kernel's phases
-#define RQ_TS(k) do { if (p.ts && tid == 0) p.ts[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
-  if (p.ts && tid == 0) {
-    unsigned xcc, hw;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-    p.ts[(size_t)blockIdx.x * 8 + 6] = xcc;
-    p.ts[(size_t)blockIdx.x * 8 + 7] = hw;
-  }
-#else
-#define RQ_TS(k) do { } while (0)
-#endif
-  RQ_TS(0);
   // The weight zero-points are needed by the first unpack.  Loads return in order, so they are requested BEFORE the ring
   // loads (and first used after them): their wait then does not include the ring's first stages.
   int zraw[TN] = {};
@@ -389,7 +376,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
   for (int s = 0; s < S; ++s)
     if (s < nk && (s < 2 || !ramp)) issue(s, s);
   __builtin_amdgcn_sched_barrier(0);
-  RQ_TS(4);
 
   // ---- MFMA operand fragments ----
   int a_off[2];                                                    // MFMA tile i adds i * 2048
@@ -476,7 +462,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     }
   }
 
-  RQ_TS(5);
   // stage 0 has landed when at most the loads of stages 1 .. S-1 are outstanding
   {
     const int later = ramp ? 1 : (nk - 1 < S - 1 ? nk - 1 : S - 1);
@@ -486,7 +471,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     });
   }
   asm volatile("s_barrier" ::: "memory");
-  RQ_TS(1);
   fetch_b(0, 0, fb);
 #pragma unroll
   for (int i = 0; i < TM; ++i) load_a(0, 0, i);
@@ -583,7 +567,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
   });
   // the ring is idle now: hand the per-column constants over through its first bytes
   EL* el = reinterpret_cast<EL*>(ring);
-  RQ_TS(2);
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < CPT; ++u) {
@@ -598,7 +581,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     else epilogue_rows_f32<TM, TN, true, EL>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
   } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
   else epilogue_wide<TM, TN, ACT, OUT, true, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
-  RQ_TS(3);
 }
 
 
@@ -630,12 +612,8 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   constexpr int epi_bytes = BN == 128 ? 4096 : 8192;
   static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 2 * WN * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
-  static bool attr_set = false;
-  if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-    attr_set = true;
-  }
+  static rq_once_per_device lds_attr;
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>), lds_bytes));
   const int64_t blocks = (ntiles + 7) / 8 * 8;
   hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
   return RQ_OK;

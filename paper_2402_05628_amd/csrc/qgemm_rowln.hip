@@ -42,18 +42,9 @@ __device__ __forceinline__ int sum16_i(int v) {
   return v;
 }
 
-#ifdef RQ_GEMM_TS
-static long long* g_rowln_ts = nullptr;
-extern "C" void rq_debug_rowln_ts(void* ptr) { g_rowln_ts = static_cast<long long*>(ptr); }
-#define RL_TS(k) do { if (p.ts && threadIdx.x == 0) p.ts[(size_t)blockIdx.x * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define RL_TS(k) do { } while (0)
-#endif
-
 template <int TN, int S>
 __global__ __launch_bounds__(256, 1) void qgemm_rowln_kernel(const RowLnParams P) {
   const GemmParams& p = P.g;
-  RL_TS(0);
   constexpr int TM = 2, BM = 64, BN = 128 * TN;
   constexpr int A_BYTES = BM * 64, B_BYTES = BN * 32, STAGE = A_BYTES + B_BYTES;
   constexpr int LPS = 1 + TN;                               // loads per thread and stage
@@ -145,7 +136,6 @@ __global__ __launch_bounds__(256, 1) void qgemm_rowln_kernel(const RowLnParams P
     });
   }
   asm volatile("s_barrier" ::: "memory");
-  RL_TS(1);
   fetch_b(0);
 #pragma unroll
   for (int i = 0; i < TM; ++i) load_a(0, 0, i);
@@ -212,7 +202,6 @@ __global__ __launch_bounds__(256, 1) void qgemm_rowln_kernel(const RowLnParams P
     }
   });
 
-  RL_TS(2);
   // ================= epilogue: the ring is idle =================
   float* const c_scale = reinterpret_cast<float*>(ring);              // [BN] s_a * s_w
   float* const c_bias = c_scale + BN;                                  // [BN]
@@ -291,7 +280,6 @@ __global__ __launch_bounds__(256, 1) void qgemm_rowln_kernel(const RowLnParams P
 #pragma unroll
     for (int r = 0; r < 8; ++r) res_cur[r] = res_nxt[r];
   }
-  RL_TS(3);
   // ---- row statistics: the 16 lanes of a DPP row share a token (float32 partial sums of 12 .. 48 values each), the four
   //      wavefronts meet in LDS, and wavefront 0 finishes one token per lane in float64 ----
   auto sum16f = [](float v) {
@@ -366,7 +354,6 @@ __global__ __launch_bounds__(256, 1) void qgemm_rowln_kernel(const RowLnParams P
         if ((lane & 15) == 0 && m < Mi) atomicAdd(P.rowsum + m, rsum);       // four wavefronts per token; the caller zeroes rowsum
       }
     }
-  RL_TS(4);
 }
 
 template <int TN>
@@ -374,12 +361,8 @@ rq_status launch(rq_ctx* ctx, const RowLnParams& P) {
   constexpr int S = TN <= 2 ? 6 : (TN <= 4 ? 5 : 4);
   constexpr int lds_bytes = S * (64 * 64 + 128 * TN * 32);
   static_assert(lds_bytes <= 160 * 1024, "one workgroup per CU");
-  static bool attr_set = false;
-  if (!attr_set) {
-    RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_rowln_kernel<TN, S>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               lds_bytes));
-    attr_set = true;
-  }
+  static rq_once_per_device lds_attr;
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_rowln_kernel<TN, S>), lds_bytes));
   const unsigned blocks = (unsigned)((P.g.M + 63) / 64);
   hipLaunchKernelGGL((qgemm_rowln_kernel<TN, S>), dim3(blocks), dim3(256), lds_bytes, ctx->stream, P);
   RQ_HIP(hipGetLastError());
@@ -410,9 +393,6 @@ rq_status rq_launch_qgemm_rowln(rq_ctx* ctx, const rq_gemm_desc* d, const rq_ln_
   P.off4 = (unsigned)(ln->store_off & 0xFF) * 0x01010101u;
   P.norm_kind = ln->norm_kind;
   P.q = ln->q; P.ldq2 = ln->ldq; P.rowsum = ln->rowsum;
-#ifdef RQ_GEMM_TS
-  p.ts = g_rowln_ts;
-#endif
   switch (d->N / 128) {
     case 2: return launch<2>(ctx, P);
     case 4: return launch<4>(ctx, P);

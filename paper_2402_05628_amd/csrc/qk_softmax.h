@@ -45,6 +45,7 @@ struct QksParams {
   int64_t ldo;
   double inv_so;
   int zo, lo, hi;              // z_o - off_o and the clamp bounds of the stored code
+  int zero_max;                // RQ_LOG_ZERO_AT_MAX_CODE: keys whose code is the largest one contribute nothing to P.V
 };
 
 // table of -(128 >> k), k = 0..7, as the two dwords of a byte permute: 2^-k = -(entry) / 128
@@ -365,6 +366,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
           nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
           pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
         }
+        if (p.zero_max) pall &= ~rq_byte_eq_mask(c, (unsigned)p.qmax * 0x01010101u);      // uniform branch
         const unsigned lsb = c & 0x01010101u;
         const unsigned odd = (lsb << 8) - lsb;        // 0xFF in the bytes that hold odd codes
         po[d4] = (int)(pall & odd);
@@ -398,6 +400,7 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
           nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
           c |= nv == 4 ? 0u : ~((1u << (8 * nv)) - 1u);
         }
+        if (p.zero_max) c |= rq_byte_eq_mask(c, (unsigned)p.qmax * 0x01010101u);      // reads as 255 as well (uniform branch)
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
           // two codes as halfwords; bfloat16 bits of 2^-k are (127 - k) << 7 = 0x3F80 - ((code & 0xFE) << 6)
@@ -554,12 +557,9 @@ rq_status launch(rq_ctx* ctx, const QksParams& p, int64_t groups) {
   constexpr int lds_max = 160 * 1024;
 #define RQ_QKS_LAUNCH(B, F, C, P)                                                                                        \
   do {                                                                                                                \
-    static bool attr_set = false;                                                                                     \
-    if (!attr_set) {                                                                                                  \
-      RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F, C, P>),           \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_max));                               \
-      attr_set = true;                                                                                                \
-    }                                                                                                                 \
+    static rq_once_per_device lds_attr;                                                                               \
+    RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qk_softmax_kernel<KSTEPS, NT, B, F, C, P>), \
+                                lds_max));                                                                            \
     hipLaunchKernelGGL((qk_softmax_kernel<KSTEPS, NT, B, F, C, P>), grid, dim3(512), lds, ctx->stream, pp);           \
   } while (0)
   // the float64 code path also serves every masked or biased case; the lean variant is the common one

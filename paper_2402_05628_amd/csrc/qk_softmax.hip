@@ -38,6 +38,7 @@ rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   p.inv_so = d->out_q ? 1.0 / (double)d->s_o : 0.0;
   p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
   p.G = d->batch * d->H;
+  p.zero_max = (d->flags & RQ_LOG_ZERO_AT_MAX_CODE) != 0;
   const int ks = d->d_head / 32;
   if (ks == 1) return rq_launch_qk_softmax_d32(ctx, p, p.G);
   if (ks == 2) return rq_launch_qk_softmax_d64(ctx, p, p.G);
@@ -55,7 +56,7 @@ rq_status rq_launch_qk_softmax(rq_ctx* ctx, const int8_t* Q, const int8_t* K, in
                                int d_head, int q_off, int z_q, int k_off, int z_k, double logit_scale, const float* bias,
                                int mask, float s_log, int bits, uint8_t* codes, int64_t ld) {
   QksParams p;
-  p.V = nullptr; p.dv = 0; p.out_f32 = nullptr; p.out_q = nullptr;
+  p.V = nullptr; p.dv = 0; p.out_f32 = nullptr; p.out_q = nullptr; p.zero_max = 0;
   p.Q = Q; p.K = K; p.ldq = ld_tok; p.ldk = ld_tok; p.so = (int64_t)N * ld_tok; p.si = d_head;
   p.H = H; p.N = N; p.dq = q_off - z_q; p.dk = k_off - z_k; p.bias = bias; p.causal = mask == RQ_MASK_CAUSAL;
   p.c1 = logit_scale * 1.4426950408889634; p.log2s = log2((double)s_log); p.qmax = (1 << bits) - 1;

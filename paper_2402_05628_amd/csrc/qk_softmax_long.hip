@@ -318,12 +318,8 @@ rq_status launch(rq_ctx* ctx, const QksParams& p) {
   constexpr int lds = lds_bytes(KSTEPS * 32);
 #define RQ_QKL_LAUNCH(F)                                                                                                  \
   do {                                                                                                                    \
-    static bool attr_set = false;                                                                                         \
-    if (!attr_set) {                                                                                                      \
-      RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&qk_softmax_long_kernel<KSTEPS, F>),                       \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));                                       \
-      attr_set = true;                                                                                                    \
-    }                                                                                                                     \
+    static rq_once_per_device lds_attr;                                                                                   \
+    RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qk_softmax_long_kernel<KSTEPS, F>), lds));  \
     hipLaunchKernelGGL((qk_softmax_long_kernel<KSTEPS, F>), dim3((unsigned)blocks), dim3(512), lds, ctx->stream, p, wgs_per_group); \
   } while (0)
   // float64 code arithmetic beyond 6 bits (as in rq_softmax_log2_quant)

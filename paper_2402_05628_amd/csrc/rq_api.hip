@@ -327,6 +327,7 @@ rq_status rq_softmax_log2_quant(rq_ctx* ctx, const rq_softmax_desc* d) {
              "rq_softmax_log2_quant: logit_scale must be > 0");
   RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: mask %d", d->mask);
   RQ_REQUIRE(d->mask != RQ_MASK_CAUSAL || d->Nq == d->Nk, RQ_ERR_SHAPE, "rq_softmax_log2_quant: causal needs Nq == Nk");
+  RQ_REQUIRE((d->flags & ~RQ_LOG_ZERO_AT_MAX_CODE) == 0, RQ_ERR_INVALID_ARG, "rq_softmax_log2_quant: flags = %d", d->flags);
   RQ_NEED_DEVICE();
   if (d->G == 0) return RQ_OK;
   return rq_launch_softmax(ctx, d);
@@ -369,6 +370,7 @@ rq_status rq_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   RQ_REQUIRE(d->batch >= 0 && d->H > 0 && d->N > 0, RQ_ERR_SHAPE, "rq_attn_fused: batch = %lld, H = %d, N = %d", (long long)d->batch,
              d->H, d->N);
   RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_fused: bits_p = %d not in 2..8", d->bits_p);
+  RQ_REQUIRE((d->flags & ~RQ_LOG_ZERO_AT_MAX_CODE) == 0, RQ_ERR_INVALID_ARG, "rq_attn_fused: flags = %d", d->flags);
   RQ_REQUIRE(rq_attn_fused_supported(d->N, d->d_head, d->bits_p, d->bias != nullptr), RQ_ERR_SHAPE,
              "rq_attn_fused: N = %d, d_head = %d, bits_p = %d%s outside the fused kernel's range; use the separate calls", d->N,
              d->d_head, d->bits_p, d->bias ? " with a bias" : "");
@@ -411,6 +413,7 @@ rq_status rq_attn_pv(rq_ctx* ctx, const rq_pv_desc* d) {
   RQ_REQUIRE(rq_aligned(d->codes, 16) && rq_aligned(d->V, 16), RQ_ERR_INVALID_ARG, "rq_attn_pv: codes and V need 16-byte alignment");
   RQ_REQUIRE(d->ldv >= (int64_t)d->H * d->d_head && d->ldv % 16 == 0, RQ_ERR_SHAPE, "rq_attn_pv: ldv must be >= H*d_head and a multiple of 16");
   RQ_REQUIRE(d->bits_p >= 2 && d->bits_p <= 8, RQ_ERR_INVALID_ARG, "rq_attn_pv: bits_p = %d not in 2..8", d->bits_p);
+  RQ_REQUIRE((d->flags & ~RQ_LOG_ZERO_AT_MAX_CODE) == 0, RQ_ERR_INVALID_ARG, "rq_attn_pv: flags = %d", d->flags);
   RQ_REQUIRE(d->s_log > 0.f && d->s_v > 0.f, RQ_ERR_INVALID_ARG, "rq_attn_pv: s_log and s_v must be > 0");
   RQ_REQUIRE(d->mask == RQ_MASK_NONE || d->mask == RQ_MASK_CAUSAL, RQ_ERR_INVALID_ARG, "rq_attn_pv: mask %d", d->mask);
   RQ_REQUIRE(d->mask != RQ_MASK_CAUSAL || d->Nq == d->Nk, RQ_ERR_SHAPE, "rq_attn_pv: causal needs Nq == Nk");
@@ -467,6 +470,7 @@ rq_status rq_dual_clip_learn(rq_ctx* ctx, const rq_dual_clip_desc* d) {
              RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: float32 arrays need 4-byte, float64 arrays 8-byte alignment");
   RQ_REQUIRE(d->bits >= 2 && d->bits <= 16, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: bits = %d not in 2..16", d->bits);
   RQ_REQUIRE(d->iters >= 0 && d->iters <= 100000, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: iters = %d", d->iters);
+  RQ_REQUIRE(d->waves >= 0 && d->waves <= 16, RQ_ERR_INVALID_ARG, "rq_dual_clip_learn: waves = %d not in 0..16", d->waves);
   RQ_REQUIRE(d->lr > 0.0 && std::isfinite(d->lr) && std::isfinite(d->alpha0), RQ_ERR_INVALID_ARG,
              "rq_dual_clip_learn: lr must be positive and finite, alpha0 finite");
   if (d->gamma) {

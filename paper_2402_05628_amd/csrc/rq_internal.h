@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -14,6 +15,7 @@ struct rq_ctx {
   int device = -1;            // < 0: host-only (validation) context
   hipStream_t stream = nullptr;
   int num_cu = 256;
+  int gemm_tile = 0;          // rq_set_gemm_tile: 0 = kernel and tile of the weight-mode GEMM chosen by shape
   std::string err;
   // per-kernel profiling of rq_block_forward
   bool profiling = false;
@@ -37,6 +39,22 @@ rq_status rq_fail(rq_ctx* ctx, rq_status st, const char* fmt, ...);
     if (e__ != hipSuccess)                                                                    \
       return rq_fail(ctx, RQ_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e__));        \
   } while (0)
+
+// A kernel that takes more than 64 KB of dynamic LDS needs hipFuncAttributeMaxDynamicSharedMemorySize raised, once per
+// device: `once` is a function-local static of the launcher (one per kernel instantiation) that remembers the devices done.
+struct rq_once_per_device {
+  std::mutex mu;
+  uint64_t done[2] = {0, 0};   // devices 0..127
+};
+inline hipError_t rq_allow_dynamic_lds(const rq_ctx* ctx, rq_once_per_device& once, const void* kernel, int bytes) {
+  const int dev = ctx->device;
+  if (dev < 0 || dev >= 128) return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  std::lock_guard<std::mutex> lock(once.mu);
+  if ((once.done[dev >> 6] >> (dev & 63)) & 1u) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) once.done[dev >> 6] |= 1ull << (dev & 63);
+  return e;
+}
 
 static inline bool rq_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -90,6 +108,13 @@ __device__ __forceinline__ double rq_wave_sum_xor(double v, int width) {
   for (int m = 1; m < 64; m <<= 1)
     if (m < width) v += __shfl_xor(v, m, 64);
   return v;
+}
+// 0xFF in every byte of x that equals the matching byte of ref4, 0 elsewhere (any byte values)
+__device__ __forceinline__ unsigned rq_byte_eq_mask(unsigned x, unsigned ref4) {
+  const unsigned d = x ^ ref4;
+  const unsigned nz = (((d & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d) & 0x80808080u;   // 0x80 where the byte differs
+  const unsigned z = nz ^ 0x80808080u;                                          // 0x80 where it is equal
+  return (z << 1) - (z >> 7);
 }
 __device__ __forceinline__ int rq_pack4(int c0, int c1, int c2, int c3) {
   return (c0 & 0xFF) | ((c1 & 0xFF) << 8) | ((c2 & 0xFF) << 16) | (c3 << 24);

@@ -50,7 +50,8 @@ def test_structures_have_the_c_layout(b, tmp_path):
     pairs = [("rq_fold_desc", b.FoldDesc), ("rq_wq_desc", b.WqDesc), ("rq_ln_desc", b.LnDesc), ("rq_gemm_desc", b.GemmDesc),
              ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_attn_fused_desc", b.AttnFusedDesc),
              ("rq_pv_desc", b.PvDesc), ("rq_dual_clip_desc", b.DualClipDesc), ("rq_gptq_desc", b.GptqDesc),
-             ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw)]
+             ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw),
+             ("rq_block_layout", b.BlockLayout)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
     for cname, cls in pairs:
         last = cls._fields_[-1][0]
@@ -292,9 +293,9 @@ def test_block_forward_validation(b, host_ctx):
     assert rc in (1, 2)
     assert "rq_block_forward" in b.lib.rq_last_error(host_ctx.handle).decode()
     assert b.lib.rq_block_forward(None, C.byref(p), None, None, 1, 8, None, 0) == 1
-    assert b.lib.rq_set_attn_chunk_bytes(10) == 1
-    assert b.lib.rq_set_gemm_tile(99) == 1 and b.lib.rq_set_gemm_tile(9) == 1
-    assert b.lib.rq_set_gemm_tile(8) == 0 and b.lib.rq_set_gemm_tile(0) == 0      # 8: the 256 x 256 tiles
+    h = host_ctx.handle
+    assert b.lib.rq_set_gemm_tile(h, 99) == 1 and b.lib.rq_set_gemm_tile(h, 9) == 1 and b.lib.rq_set_gemm_tile(None, 0) == 1
+    assert b.lib.rq_set_gemm_tile(h, 8) == 0 and b.lib.rq_set_gemm_tile(h, 0) == 0      # 8: the 256 x 256 tiles
 
 
 def test_workspace_bytes_grow_with_the_problem(b):
@@ -307,6 +308,45 @@ def test_workspace_bytes_grow_with_the_problem(b):
     assert 0 < small < big
     # ViT-B at batch 64: int8 activations, the float residual stream and the attention scratch stay far below HBM size
     assert big < (1 << 30)
+
+
+def test_calibration_plan_keeps_logits_and_codes_apart(b):
+    """The calibration always runs the three separate attention kernels: its plan must hold int32 logits AND codes for one
+    chunk, in regions of their own and inside the workspace it asks for, whatever the forward pass would choose for the
+    shape (short unmasked rows take the one-kernel attention there and need neither).  Includes small-head long-row shapes
+    and a chunk budget that splits the batch."""
+    cases = [(768, 12, 3072, 64, 197, 0), (1024, 16, 4096, 128, 257, 0), (1024, 16, 4096, 128, 257, 1 << 20), (512, 4, 1024, 1, 2048, 0),
+             (512, 4, 1024, 1, 4096, 0), (128, 4, 512, 64, 49, 1 << 20), (384, 6, 1536, 1, 197, 0)]
+    for D, H, Dm, batch, seq, chunk in cases:
+        raw = b.BlockRaw()
+        raw.D, raw.H, raw.Dm, raw.attn_chunk_bytes = D, H, Dm, chunk
+        lay = b.BlockLayout()
+        assert b.lib.rq_block_calibrate_workspace_layout(C.byref(raw), batch, seq, C.byref(lay)) == 0
+        ld = (seq + 15) // 16 * 16
+        assert lay.ld == ld and 1 <= lay.batch_chunk <= batch
+        need_logits, need_codes = 4 * lay.batch_chunk * H * seq * ld, lay.batch_chunk * H * seq * ld
+        assert lay.logits_bytes >= need_logits and lay.codes_bytes >= need_codes, (D, H, batch, seq)
+        assert lay.codes - lay.logits >= need_logits                      # the codes start after the last logit
+        assert lay.o - lay.codes >= need_codes                            # and end before the attention output
+        regions = sorted([(lay.a, batch * seq * D), (lay.rowsum, 4 * batch * seq), (lay.qkv, 3 * batch * seq * D),
+                          (lay.logits, need_logits), (lay.codes, need_codes), (lay.o, batch * seq * D),
+                          (lay.xbar, 4 * batch * seq * D), (lay.hidden, batch * seq * Dm)])
+        for (o0, n0), (o1, _) in zip(regions, regions[1:]):
+            assert o0 + n0 <= o1, (D, H, batch, seq)
+        total = b.lib.rq_block_calibrate_workspace_bytes(C.byref(raw), batch, seq)
+        assert total == lay.total and regions[-1][0] + regions[-1][1] <= total
+        if chunk:
+            assert lay.batch_chunk < batch                                # the budget splits this batch
+    # the forward plan of a short unmasked row keeps neither logits nor codes in memory
+    p = b.BlockParams()
+    p.D, p.H, p.Dm, p.bits_p = 768, 12, 3072, 4
+    lay = b.BlockLayout()
+    assert b.lib.rq_block_workspace_layout(C.byref(p), 64, 197, C.byref(lay)) == 0
+    assert lay.logits_bytes == 0 and lay.codes_bytes == 0 and lay.batch_chunk == 64
+    p.attn_path = b.ATTN_THREE_KERNELS
+    assert b.lib.rq_block_workspace_layout(C.byref(p), 64, 197, C.byref(lay)) == 0
+    assert lay.logits_bytes >= 4 * lay.batch_chunk * 12 * 197 * 208 and lay.codes - lay.logits >= lay.logits_bytes
+    assert b.lib.rq_block_workspace_layout(None, 64, 197, C.byref(lay)) == 1
 
 
 def test_synthetic_inputs_are_seeded_and_shaped():

@@ -1,4 +1,5 @@
 """rq_block_forward against the oracle block, with the oracle's calibrated parameters handed to both sides."""
+import ctypes
 import dataclasses
 
 import numpy as np
@@ -36,19 +37,12 @@ def test_block_forward_matches_oracle(rq, name, chunk_mb, fused, rowln):
     raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
     P = orc.calibrate_block(raw, cfg_dict(cfg))
     want, t = orc.block_forward(P, raw["x"], keep=True)
-    b.set_attn_chunk_bytes(chunk_mb << 20)
-    b.set_attn_fused(fused)
-    b.set_proj_ln_fused(rowln)
-    try:
-        blk = b.Block(ctx, cfg, block_to_device(P))
-        x = dev(raw["x"])
-        y = torch.zeros_like(x)
-        blk.forward(x, y, cfg.batch, cfg.seq)
-        torch.cuda.synchronize()
-    finally:
-        b.set_attn_chunk_bytes(64 << 20)
-        b.set_attn_fused(1)
-        b.set_proj_ln_fused(False)
+    path = {1: b.ATTN_AUTO, 2: b.ATTN_QK_SOFTMAX_PV, 0: b.ATTN_THREE_KERNELS}[fused]
+    blk = b.Block(ctx, cfg, block_to_device(P), attn_path=path, attn_chunk_bytes=chunk_mb << 20, proj_ln_fused=bool(rowln))
+    x = dev(raw["x"])
+    y = torch.zeros_like(x)
+    blk.forward(x, y, cfg.batch, cfg.seq)
+    torch.cuda.synchronize()
     got = y.cpu().numpy().astype(np.float64)
     ref = np.abs(want).max()
     err = np.abs(got - want).max()
@@ -65,16 +59,25 @@ def _raw_to_device(raw):
     return {k: (None if v is None else dev(v)) for k, v in raw.items() if k != "x"}
 
 
-@pytest.mark.parametrize("name", list(SMALL))
-def test_block_calibrate_matches_oracle(rq, name):
-    """The library's own calibration (min/max bounds, fold, weight packing) reproduces the oracle's parameters."""
+@pytest.mark.parametrize("name,chunk_mb", [(n, 0) for n in SMALL] + [("vit_b_w4a4_b2", 1), ("clip_vit_l14_w4a4_b2", 1),
+                                                                      ("llama_like_w4a8", 1)])
+def test_block_calibrate_matches_oracle(rq, name, chunk_mb):
+    """The library's own calibration (min/max bounds, fold, weight packing) reproduces the oracle's parameters.
+    chunk_mb = 1 splits the batch of the calibration's attention passes into several chunks: the attention output of an
+    earlier chunk must survive the later chunks' logits (proj, LayerNorm-2 and the MLP are calibrated on it)."""
     b, ctx = rq
     cfg = SMALL[name]
-    print("case", name, flush=True)
+    print("case", name, chunk_mb, flush=True)
     raw = synth.make_block(cfg, cfg_id=list(SMALL).index(name), seed=0)
     P = orc.calibrate_block(raw, cfg_dict(cfg))
     x = dev(raw["x"])
-    blk = b.calibrate_block(ctx, cfg, _raw_to_device(raw), x, cfg.batch, cfg.seq)
+    blk = b.calibrate_block(ctx, cfg, _raw_to_device(raw), x, cfg.batch, cfg.seq, attn_chunk_bytes=chunk_mb << 20)
+    if chunk_mb and cfg.batch > 1:
+        br = b.BlockRaw()
+        br.D, br.H, br.Dm, br.attn_chunk_bytes = cfg.D, cfg.H, cfg.Dm, chunk_mb << 20
+        lay = b.BlockLayout()
+        assert b.lib.rq_block_calibrate_workspace_layout(ctypes.byref(br), ctypes.c_int64(cfg.batch), ctypes.c_int64(cfg.seq), ctypes.byref(lay)) == 0
+        assert lay.batch_chunk < cfg.batch
     Q = blk.P
     # the LayerNorm folds see the same float inputs on both sides: equal up to the last float32 place
     for k in ("ln1",):
@@ -94,6 +97,10 @@ def test_block_calibrate_matches_oracle(rq, name):
         assert abs(Q[k] - P[k]) <= 1, (k, Q[k], P[k])
     assert abs(Q["ln2"]["z"] - P["ln2"]["z"]) <= 1
     assert abs(Q["ln2"]["s"] - float(P["ln2"]["s"])) <= 1e-3 * float(P["ln2"]["s"])
+    assert np.allclose(Q["ln2"]["gamma_t"].cpu().numpy(), P["ln2"]["gamma_t"], rtol=2e-3, atol=0)
+    # proj is quantized from the raw weights (no fold): its codes do not depend on activations at all
+    want_proj = lin_to_device(P["proj"], cfg.bits_w)
+    assert np.array_equal(Q["proj"]["w"].cpu().numpy(), want_proj["w"].cpu().numpy())
     # and the block it produces tracks the oracle block built from the oracle's own calibration
     want_y = orc.block_forward(P, raw["x"])
     y = torch.zeros_like(x)

@@ -29,7 +29,7 @@ def _act_codes(g, M, K, bits):
 def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
     b, ctx = rq
     print("case", M, N, K, bits_a, bits_w, tile, flush=True)
-    b.set_gemm_tile(tile)
+    b.set_gemm_tile(ctx, tile)
     try:
         g = np.random.default_rng(M + N + K + bits_a)
         qa, z_a = _act_codes(g, M, K, bits_a)
@@ -44,7 +44,7 @@ def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
         torch.cuda.synchronize()
         assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
     finally:
-        b.set_gemm_tile(0)
+        b.set_gemm_tile(ctx, 0)
 
 
 def test_accumulator_extremes(rq):
@@ -87,12 +87,12 @@ def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
     rs = torch.empty(M, dtype=torch.int32, device="cuda")
     b.rq_rowsum_i8(ctx, A, rs)
     out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
-    b.set_gemm_tile(tile)
+    b.set_gemm_tile(ctx, tile)
     try:
         b.rq_qgemm(ctx, A, a_off, z_a, float(s_a), lin_to_device(lin, bits_w), residual=dev(res), out_f32=out, rowsum_a=rs)
         torch.cuda.synchronize()
     finally:
-        b.set_gemm_tile(0)
+        b.set_gemm_tile(ctx, 0)
     assert_float_close(out.cpu().numpy(), want, "qgemm f32")
 
 
@@ -107,11 +107,11 @@ def test_requantized_output(rq, bits_a, bits_w, bits_o, act, tile):
     q_only = act.endswith("_q_only")      # the block's launches: re-quantized codes are the only output
     act = act.replace("_q_only", "")
     M, K = 301, 256
-    b.set_gemm_tile(tile)
+    b.set_gemm_tile(ctx, tile)
     try:
         _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act, q_only, M, K)
     finally:
-        b.set_gemm_tile(0)
+        b.set_gemm_tile(ctx, 0)
 
 
 @pytest.mark.parametrize("bits_a,bits_w,bits_o", [(8, 8, 8), (4, 4, 4), (6, 6, 6), (8, 4, 8)])
@@ -120,11 +120,11 @@ def test_requantized_output_wide_tiles_long_k(rq, bits_a, bits_w, bits_o, act, M
     """The 256 x 256 tiles with a K loop long enough for the ring to be refilled (in pairs of stages) several times."""
     b, ctx = rq
     q_only = act.endswith("_q_only")
-    b.set_gemm_tile(8)
+    b.set_gemm_tile(ctx, 8)
     try:
         _requantized_output_case(b, ctx, bits_a, bits_w, bits_o, act.replace("_q_only", ""), q_only, M, K)
     finally:
-        b.set_gemm_tile(0)
+        b.set_gemm_tile(ctx, 0)
 
 
 @pytest.mark.timeout(300)

@@ -452,3 +452,149 @@ def test_percentile_bounds_against_sorting_and_closed_forms():
     lo, hi = orc.channel_percentile_bounds(ramp, 0.1, 0.9)
     np.testing.assert_allclose(lo, [10.0, -180.0], rtol=1e-14)
     np.testing.assert_allclose(hi, [90.0, -20.0], rtol=1e-14)
+
+
+# ---------------------------------------------------------------- saturated log code: the "means zero" reading
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_zero_at_max_code_changes_only_the_saturated_code(bits):
+    """Log de-quantizer of Section 'Efficient quantizers' / Eq. (3.3-2) under the second reading of the saturated code:
+    the largest code de-quantizes to exactly 0, every other code to the printed formula; both forms agree."""
+    qmax = 2 ** bits - 1
+    q = np.arange(qmax + 1)
+    for s in (1.0, 0.37):
+        lit_def, lit_shift = orc.logsqrt2_dequant(q, s), orc.logsqrt2_dequant_shift(q, s)
+        z_def, z_shift = orc.logsqrt2_dequant(q, s, bits, True), orc.logsqrt2_dequant_shift(q, s, bits, True)
+        assert z_def[qmax] == 0.0 and z_shift[qmax] == 0.0
+        assert np.array_equal(z_def[:qmax], lit_def[:qmax]) and np.array_equal(z_shift[:qmax], lit_shift[:qmax])
+        assert lit_def[qmax] > 0 and lit_shift[qmax] > 0
+        for k in range(qmax):                     # the printed formula, typed out: s * sqrt2^-q
+            assert z_shift[k] == pytest.approx(s * 2.0 ** (-k / 2.0), rel=1e-15)
+
+
+def test_attn_pv_zero_at_max_code_is_a_sum_without_the_saturated_keys():
+    g = np.random.default_rng(5)
+    bits, n, dh = 4, 23, 8
+    codes = g.integers(0, 16, size=(n, n))
+    codes[:, ::3] = 15                            # many saturated keys
+    qv = g.integers(0, 16, size=(n, dh))
+    s_log, s_v, z_v = 1.0, 0.07, 6
+    got = orc.attn_pv(codes, qv, s_log, s_v, z_v, False, bits, True)
+    got_def = orc.attn_pv_sqrt2(codes, qv, s_log, s_v, z_v, False, bits, True)
+    want = np.zeros((n, dh))
+    for i in range(n):
+        for j in range(n):
+            if codes[i, j] != 15:
+                want[i] += s_log * math.sqrt(2.0) ** -int(codes[i, j]) * s_v * (qv[j] - z_v)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(got_def, want, rtol=1e-13, atol=1e-15)
+    lit = orc.attn_pv(codes, qv, s_log, s_v, z_v)
+    assert np.abs(lit - got).max() > 1e-3         # the literal reading keeps the tail's mass
+    # causal: masked keys stay excluded, saturated ones too
+    gc = orc.attn_pv(codes, qv, s_log, s_v, z_v, True, bits, True)
+    np.testing.assert_allclose(gc[0], 0.0 if codes[0, 0] == 15 else want[0] * 0 + s_log * math.sqrt(2.0) ** -int(codes[0, 0]) * s_v * (qv[0] - z_v),
+                               rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------- dual-clipped channel bounds, typed out per channel
+def test_channel_bounds_with_asymmetric_clip_factors():
+    """Eqs. for X'_up and X'_low (Section 'Per-channel dual clipping'): the channel MAXIMUM is multiplied by the upper
+    factor and the channel MINIMUM by the lower one, channel by channel; a swap of the two factors, or a factor applied
+    to the wrong extreme, fails on the one-sided channels."""
+    g = np.random.default_rng(3)
+    X = g.standard_normal((50, 6)) * np.array([1.0, 4.0, 0.2, 1.0, 1.0, 3.0])
+    X[:, 3] = np.abs(X[:, 3]) + 0.5               # all-positive channel: min > 0
+    X[:, 4] = -np.abs(X[:, 4]) - 0.5              # all-negative channel: max < 0
+    cu = np.array([0.9, 0.5, 1.0, 0.8, 0.6, 0.95])
+    cl = np.array([0.7, 1.0, 0.55, 0.9, 0.85, 0.5])
+    lo, up = orc.channel_bounds(X, cu, cl)
+    for d in range(X.shape[1]):
+        col = [float(v) for v in X[:, d]]
+        assert up[d] == max(col) * cu[d]
+        assert lo[d] == min(col) * cl[d]
+    # a contraction factor moves an extreme toward 0, also when that widens the range (one-sided channels)
+    assert up[3] < X[:, 3].max() and lo[3] < X[:, 3].min() and lo[3] > 0
+    assert lo[4] > X[:, 4].min() and up[4] > X[:, 4].max() and up[4] < 0
+    # one factor given, the other not
+    lo1, up1 = orc.channel_bounds(X, cu, None)
+    assert np.array_equal(lo1, X.min(axis=0)) and np.array_equal(up1, X.max(axis=0) * cu)
+    lo2, up2 = orc.channel_bounds(X, None, cl)
+    assert np.array_equal(up2, X.max(axis=0)) and np.array_equal(lo2, X.min(axis=0) * cl)
+    lo0, up0 = orc.channel_bounds(X)
+    assert np.array_equal(lo0, X.min(axis=0)) and np.array_equal(up0, X.max(axis=0))
+
+
+# ---------------------------------------------------------------- static layer-wise (s, z) of a tensor
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_tensor_qparams_against_the_bounds_formula_and_end_codes(bits):
+    """Eq. for s and z on the tensor's min / max: the minimum takes code 0 and the maximum code 2^b - 1, 0 de-quantizes to
+    within half a step of 0, and (s, z) equal qparams_from_bounds up to the float32 storage of s."""
+    g = np.random.default_rng(bits)
+    qmax = 2 ** bits - 1
+    for shift in (0.0, 0.8, -2.5, 7.0):
+        v = g.standard_normal((40, 12)) * 1.7 + shift
+        s, z = orc._tensor_qparams(v, bits)
+        assert isinstance(z, int) and np.asarray(s).dtype == np.float32
+        s_ref, z_ref = orc.qparams_from_bounds(v.min(), v.max(), bits)
+        assert abs(float(s) - float(s_ref)) <= 1e-7 * float(s_ref)
+        assert abs(z - int(z_ref)) <= 1
+        assert float(s) == pytest.approx((v.max() - v.min()) / qmax, rel=1e-7)
+        assert z == round(-v.min() / float(s))                          # the formula typed out (python round: half to even)
+        q = orc.uniform_quant(v, s, z, bits)
+        i_min, i_max = np.unravel_index(v.argmin(), v.shape), np.unravel_index(v.argmax(), v.shape)
+        if 0 <= z <= qmax:                                              # the range straddles 0: nothing is clipped
+            assert q[i_min] == 0 and q[i_max] == qmax
+            assert np.abs(orc.uniform_dequant(q, s, z) - v).max() <= 0.5 * float(s) * (1 + 1e-6) + abs(z + v.min() / float(s)) * float(s)
+        assert q.min() >= 0 and q.max() <= qmax
+
+
+def test_calibrate_block_gives_q_k_v_their_own_scale_and_zero_point_at_4_bits():
+    """Static quantizers of Q, K and V (Algorithm 1: every activation gets its own quantizer): with the three weight
+    blocks of very different magnitude and offset, each of (s_q, z_q), (s_k, z_k), (s_v, z_v) must come from its OWN
+    column block of the QKV output, and the block's Q / K / V codes must be that block's own uniform quantization.  At 4
+    bits a zero-point off by one, or a swapped pair, moves every de-quantized value by a whole step."""
+    cfg = synth.BlockConfig("t", batch=2, seq=21, D=32, H=4, Dm=64, bits_w=8, bits_a=4, bits_p=4)
+    raw = synth.make_block(cfg, cfg_id=3, seed=2)
+    D = cfg.D
+    raw["w_qkv"] = raw["w_qkv"].copy()
+    raw["b_qkv"] = raw["b_qkv"].copy()
+    raw["w_qkv"][0:D] *= 1.0
+    raw["w_qkv"][D:2 * D] *= 6.0
+    raw["w_qkv"][2 * D:3 * D] *= 0.25
+    raw["b_qkv"][D:2 * D] += 1.5                   # K offset upwards, V downwards: distinct zero-points
+    raw["b_qkv"][2 * D:3 * D] -= 0.1
+    P = orc.calibrate_block(raw, _cfg_dict(cfg))
+    y, t = orc.block_forward(P, raw["x"], keep=True)
+    qkv = t["qkv"]
+    pairs = {}
+    for i, nm in enumerate("qkv"):
+        blk = qkv[:, i * D:(i + 1) * D]
+        s, z = float(P["s_" + nm]), int(P["z_" + nm])
+        pairs[nm] = (s, z)
+        # its own min / max, by the printed formula
+        assert s == pytest.approx((blk.max() - blk.min()) / 15.0, rel=1e-6)
+        assert z == round(-blk.min() / s)
+        codes = t["q" + nm]
+        assert codes.min() == 0 and codes.max() == 15
+        want = np.clip(np.rint(blk / s) + z, 0, 15)
+        assert np.array_equal(codes, want)
+        # de-quantized with its own pair the block is reproduced to half a step; with a neighbour's pair it is not
+        assert np.abs(s * (codes - z) - blk).max() <= 0.5 * s * (1 + 1e-9) + s * abs(z + blk.min() / s)
+    assert pairs["k"][0] > 3 * pairs["q"][0] > 3 * pairs["v"][0]
+    assert len({pairs[n][1] for n in "qkv"}) == 3
+    for nm, other in (("q", "k"), ("k", "v"), ("v", "q")):
+        i = "qkv".index(nm)
+        blk = qkv[:, i * D:(i + 1) * D]
+        so, zo = pairs[other]
+        wrong = so * (np.clip(np.rint(blk / so) + zo, 0, 15) - zo)
+        s, z = pairs[nm]
+        assert np.abs(wrong - blk).max() > 0.5 * s * 1.5
+    # the attention logits use s_q * s_k and the values s_v: recompute one head of one batch item by hand
+    dh = D // cfg.H
+    r, cs = slice(0, cfg.seq), slice(dh, 2 * dh)
+    L = (pairs["q"][0] * (t["qq"][r, cs] - pairs["q"][1])) @ (pairs["k"][0] * (t["qk"][r, cs] - pairs["k"][1])).T / math.sqrt(dh)
+    A = np.exp(L - L.max(axis=1, keepdims=True))
+    A /= A.sum(axis=1, keepdims=True)
+    codes = np.clip(np.rint(-2.0 * np.log2(A)), 0, 15)
+    assert np.mean(codes != t["codes"][0, 1]) < 5e-3
+    out = (math.sqrt(2.0) ** -t["codes"][0, 1].astype(np.float64)) @ (pairs["v"][0] * (t["qv"][r, cs] - pairs["v"][1]))
+    np.testing.assert_allclose(t["attn"][r, cs], out, rtol=1e-12, atol=1e-14)
