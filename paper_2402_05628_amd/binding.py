@@ -505,10 +505,15 @@ class Block:
         ptr, _ = self.workspace(batch, seq)
         base = ptr - self._ws.data_ptr()
         i8 = self._ws.view(torch.int8)
-        return dict(a2=i8[base + lay.a: base + lay.a + T * D].view(T, D), qkv=i8[base + lay.qkv: base + lay.qkv + 3 * T * D].view(T, 3 * D),
+        out = {}
+        if lay.codes_bytes:      # the codes of the last attention chunk
+            g = lay.batch_chunk * self.bp.H
+            out["codes"] = self._ws[base + lay.codes: base + lay.codes + g * seq * lay.ld].view(g, seq, lay.ld)
+        out.update(a2=i8[base + lay.a: base + lay.a + T * D].view(T, D), qkv=i8[base + lay.qkv: base + lay.qkv + 3 * T * D].view(T, 3 * D),
                     o=i8[base + lay.o: base + lay.o + T * D].view(T, D),
                     xbar=self._ws[base + lay.xbar: base + lay.xbar + 4 * T * D].view(torch.float32).view(T, D),
                     hidden=i8[base + lay.hidden: base + lay.hidden + T * Dm].view(T, Dm))
+        return out
 
     def forward(self, x: torch.Tensor, y: torch.Tensor, batch: int, seq: int):
         ptr, n = self.workspace(batch, seq)

@@ -166,6 +166,7 @@ rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   p.n_seg = d->n_seg > 0 ? d->n_seg : 1; p.seg_len = d->seg_len > 0 ? d->seg_len : d->N;
   for (int i = 0; i < 4; ++i) {
     const bool on = d->out_q && i < p.n_seg;
+    p.inv_so_d[i] = on ? 1.0 / (double)d->s_o[i] : 0.0;
     p.inv_so[i] = on ? 1.0f / d->s_o[i] : 0.f;
     p.zo[i] = on ? (float)(d->z_o[i] - d->off_o[i]) : 0.f;
     p.zcode[i] = on ? (float)d->z_o[i] : 0.f;

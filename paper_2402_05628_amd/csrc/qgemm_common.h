@@ -33,6 +33,7 @@ struct GemmParams {
   int8_t* out_q;
   int64_t ldq;
   int n_seg, seg_len;
+  double inv_so_d[4];   // 1 / s_o in float64 (the exact re-decision of codes near rounding ties)
   float inv_so[4];
   float zo[4];   // z_o - off_o
   float zcode[4];   // z_o
@@ -64,6 +65,32 @@ __device__ __forceinline__ float gelu_f(float y) {
   RQ_FMAAK(p, p, a, "0xbf935899");     // -1.151141279e+00
   RQ_FMAAK(p, p, a, "0xbf800008");     // -1.000001008e+00
   return fmaf(-ay, __builtin_amdgcn_exp2f(p), fmaxf(y, 0.f));
+}
+
+// Re-quantization of 8-bit codes: the float32 epilogue carries up to ~1e-4 of a code of rounding error, enough to flip a
+// code whose exact value sits that close to a rounding tie -- and a flipped Q or K code can move the winning key of a
+// peaked attention row.  Outputs whose float32 pre-round value lies within TIE_GUARD of a tie are therefore decided again in
+// float64, in the order the definition states: y = acc * (s_a * s_w[n]) + bias[n] (+ residual), code = round(y / s_o) + z_o
+// (the division as a product with the float64 reciprocal: one more rounding of 1e-16).  Inlined: a call from the epilogue
+// would park the accumulators in scratch memory.
+// (Narrower codes: |value| <= 127 keeps the float32 error below 4e-6 of a code, flips stay inside the tolerated 1e-4 of the
+// elements at no cost; activation epilogues feed the MLP, where a flipped code moves one output by one step and no more.)
+constexpr float TIE_GUARD = 1.0f / 4096.0f;
+__device__ __forceinline__ unsigned requant_exact4(const GemmParams& p, int t0, int t1, int t2, int t3, int n, float r0, float r1, float r2,
+                                                   float r3, int seg) {
+  const int t[4] = {t0, t1, t2, t3};
+  const float r[4] = {r0, r1, r2, r3};
+  const double iso = p.inv_so_d[seg], zc = (double)p.zcode[seg], qm = (double)p.qmaxf, sa = (double)p.s_a;
+  unsigned w = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int ne = n + e < p.N ? n + e : p.N - 1;
+    double y = (double)t[e] * (sa * (double)p.s_b[ne]) + (p.bias ? (double)p.bias[ne] : 0.0);
+    y += (double)r[e];
+    const double c = fmin(fmax(rint(y * iso) + zc, 0.0), qm);
+    w |= (unsigned)(int)c << (8 * e);
+  }
+  return w;
 }
 
 __device__ __forceinline__ float silu_f(float y) {
@@ -129,6 +156,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16i (&acc)[TN][TM
       const int sg = (p.out_q && p.n_seg > 1) ? no / p.seg_len : 0;
       const float is = p.inv_so[sg], zz = p.zo[sg];
       const int lo = p.lo[sg], hi = p.hi[sg];
+      const bool guard = p.out_q && p.act == RQ_ACT_NONE && p.qmaxf > 127.f;     // 8-bit codes: see TIE_GUARD
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int64_t m = m0 + wm0 + i * 32 + lcol;
@@ -154,17 +182,29 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16i (&acc)[TN][TM
           const float u3 = fmaf((float)acc[ju][i][4 * g + 3], sc2.w, bi2.w);
           y[0] = silu_f(y[0]) * u0; y[1] = silu_f(y[1]) * u1; y[2] = silu_f(y[2]) * u2; y[3] = silu_f(y[3]) * u3;
         }
+        float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
         if (p.residual) {
-          const float4 r = *reinterpret_cast<const float4*>(p.residual + m * p.ldr + no);
+          r = *reinterpret_cast<const float4*>(p.residual + m * p.ldr + no);
           y[0] += r.x; y[1] += r.y; y[2] += r.z; y[3] += r.w;
         }
         if (p.out_f32) *reinterpret_cast<float4*>(p.out_f32 + m * p.ldf + no) = make_float4(y[0], y[1], y[2], y[3]);
         if (p.out_q) {
           int c[4];
+          bool near_tie = false;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            int k = (int)(__builtin_rintf(y[e] * is) + zz);
+            const float v = y[e] * is;
+            const float rv = __builtin_rintf(v);
+            near_tie |= fabsf(v - rv) > 0.5f - TIE_GUARD;
+            int k = (int)(rv + zz);
             c[e] = k < lo ? lo : (k > hi ? hi : k);
+          }
+          if (guard && near_tie) {
+            const unsigned w = requant_exact4(p, acc[j][i][4 * g], acc[j][i][4 * g + 1], acc[j][i][4 * g + 2], acc[j][i][4 * g + 3], n, r.x,
+                                              r.y, r.z, r.w, sg);
+            const int off = (int)p.zcode[sg] - (int)p.zo[sg];      // the storage offset
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c[e] = (int)((w >> (8 * e)) & 0xFFu) - off;
           }
           *reinterpret_cast<int*>(p.out_q + m * p.ldq + no) = rq_pack4(c[0], c[1], c[2], c[3]);
         }

@@ -30,7 +30,9 @@ enum { OUT_ACC = 1, OUT_F32 = 2, OUT_RES = 4, OUT_Q = 8, OUT_ANY = 15 };
 //  * v_cvt_pk_u8_f32 rounds to nearest-even, saturates to 0..255 and packs in one instruction; two
 //    v_permlane32_swap exchange dwords between lane l and lane l+32 (which hold interleaved groups of 4 channels of
 //    the same token) so that each lane owns 16 consecutive channels and issues one 16-byte store.
-template <int TM, int TN, int ACT, int OUT, bool CHECK, typename EL = EpiLds>
+//  * Q8 (a separate kernel instantiation, so that narrower codes carry none of its code or registers): 8-bit output codes
+//    without an activation are guarded against rounding ties, see TIE_GUARD.
+template <int TM, int TN, int ACT, int OUT, bool CHECK, typename EL = EpiLds, bool Q8 = false>
 __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[TN][TM], const EL* el, const int (&rs)[TM],
                                               int m0, int n0, int wm0, int wn0, int lane) {
   const int lcol = lane & 31, half = lane >> 5, lrow4 = half * 4;
@@ -123,17 +125,37 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
           y[2] = silu_f(y[2]) * fmaf((float)u[2], sc2.z, bi2.z);
           y[3] = silu_f(y[3]) * fmaf((float)u[3], sc2.w, bi2.w);
         }
+        float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
         if (has_res && live) {
-          const float4 r = *reinterpret_cast<const float4*>(rres[i] + no);
+          r = *reinterpret_cast<const float4*>(rres[i] + no);
           y[0] += r.x; y[1] += r.y; y[2] += r.z; y[3] += r.w;
         }
         if (has_f32 && live) *reinterpret_cast<float4*>(rf32[i] + no) = make_float4(y[0], y[1], y[2], y[3]);
         if (has_q) {
           unsigned w = 0;
+          if (Q8 && ACT == RQ_ACT_NONE) {      // 8-bit codes: the packed convert saturates at 255 by itself
+            // the codes taken TIE_GUARD above and below agree unless the value sits that close to a rounding tie
+            const float zp = zz + TIE_GUARD, zm = zz - TIE_GUARD;
+            unsigned wl = 0;
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[0], is, zp), 0, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[1], is, zp), 1, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[2], is, zp), 2, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[3], is, zp), 3, w);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[0], is, zm), 0, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[1], is, zm), 1, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[2], is, zm), 2, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(y[3], is, zm), 3, wl);
+            if (w != wl) {
+              int sg = p.n_seg > 1 ? no / p.seg_len : 0;
+              sg = sg < p.n_seg ? sg : p.n_seg - 1;
+              w = requant_exact4(p, t[0], t[1], t[2], t[3], n, r.x, r.y, r.z, r.w, sg);
+            }
+          } else {
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[0], is, zz), qm), 0, w);
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[1], is, zz), qm), 1, w);
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[2], is, zz), qm), 2, w);
           w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(fmaf(y[3], is, zz), qm), 3, w);
+          }
           // stored = code - off per byte.  Codes of 8 bits are stored with offset 128 (nothing else fits int8): flip the sign
           // bits.  Narrower codes leave bit 7 free: with it set no byte borrows from its neighbour (off <= 128).
           w = wide_codes ? w ^ 0x80808080u : ((w | 0x80808080u) - o4) ^ 0x80808080u;
@@ -261,7 +283,7 @@ constexpr int pipe_occupancy(int TM, int OUT) {
 // per CU): per MFMA half the bytes through the CU's load path and the LDS, for large products with a long K loop.
 // WN = 4: eight wavefronts in a 2 x 4 grid (two per SIMD, each with the 32 TM x 32 TN tile) on a tile 32 TN * 4 columns wide:
 // the operand bytes per MFMA of the 256 x 256 tile, with a second wavefront on every SIMD to cover the first one's waits.
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2>
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false>
 __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
   constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
   constexpr int BM = 64 * TM, BN = 32 * TN * WN;      // TM = 4: 256-row tiles, two workgroups per CU; TM = 5: 320 rows, one
@@ -579,14 +601,17 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     float* stage = reinterpret_cast<float*>(ring + EPI_BYTES + wave * (32 * 68 * 4));
     if (m0 + BM <= (int)p.M) epilogue_rows_f32<TM, TN, false, EL>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
     else epilogue_rows_f32<TM, TN, true, EL>(p, acc, el, rs, stage, m0, n0, wm0, wn0, lane);
-  } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
-  else epilogue_wide<TM, TN, ACT, OUT, true, EL>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  } else if (m0 + BM <= (int)p.M) epilogue_wide<TM, TN, ACT, OUT, false, EL, Q8>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
+  else epilogue_wide<TM, TN, ACT, OUT, true, EL, Q8>(p, acc, el, rs, m0, n0, wm0, wn0, lane);
 }
 
 
 // host side: one instantiation set per weight format lives in its own translation unit
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2>
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false>
 rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
+  if constexpr (!Q8 && ACT == RQ_ACT_NONE && (OUT & OUT_Q) != 0) {      // 8-bit output codes: the tie-guarded instantiation
+    if (p.out_q && p.qmaxf > 127.f) return launch_pipe_one<W4, S, ACT, OUT, TM, TN, WN, true>(ctx, p);
+  }
   constexpr int BN = 32 * TN * WN;
   p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
   p.tiles_n = (p.N + BN - 1) / BN;
@@ -613,9 +638,9 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 2 * WN * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static rq_once_per_device lds_attr;
-  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>), lds_bytes));
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8>), lds_bytes));
   const int64_t blocks = (ntiles + 7) / 8 * 8;
-  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
   return RQ_OK;
 }
 

@@ -122,7 +122,12 @@ __global__ __launch_bounds__(256) void qgemv_kernel(const GemmParams p, int m_ba
       if (p.out_q) {
         int sg = p.n_seg > 1 ? u / p.seg_len : 0;
         sg = sg < p.n_seg ? sg : p.n_seg - 1;
-        const float v = fminf(fmaxf(rintf(fmaf(y, p.inv_so[sg], p.zcode[sg])), 0.f), p.qmaxf);
+        const float vf = fmaf(y, p.inv_so[sg], p.zcode[sg]);
+        float v = fminf(fmaxf(rintf(vf), 0.f), p.qmaxf);
+        if (p.act == RQ_ACT_NONE && p.qmaxf > 127.f && fabsf(vf - rintf(vf)) > 0.5f - rqg::TIE_GUARD) {   // 8-bit codes near a tie: float64
+          const float r = p.residual ? p.residual[mt * p.ldr + u] : 0.f;
+          v = (float)(rqg::requant_exact4(p, t0, t0, t0, t0, n, r, r, r, r, sg) & 0xFFu);
+        }
         p.out_q[mt * p.ldq + u] = (int8_t)((int)v - (p.off4[sg] & 0xFF));
       }
     }

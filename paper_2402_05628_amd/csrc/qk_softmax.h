@@ -525,7 +525,17 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
             if (p.out_q) {
               int k[4];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) k[e] = (int)fminf(fmaxf(rintf(fmaf(y[e], iso, zof)), lof), hif);
+              for (int e = 0; e < 4; ++e) {
+                const float v = fmaf(y[e], iso, zof);
+                k[e] = (int)fminf(fmaxf(rintf(v), lof), hif);
+                // 8-bit output codes next to a rounding tie: decided again in float64 from the exact integer sums
+                if (!WIDE && p.hi - p.lo > 127 && fabsf(v - rintf(v)) > 0.5f - 1.0f / 4096.0f) {
+                  const double y64 = p.a_even * ((double)E[WIDE ? 0 : c][4 * gq + e] + (double)p.dv * psE) +
+                                     p.a_odd * ((double)O[WIDE ? 0 : c][4 * gq + e] + (double)p.dv * psO);
+                  const int q = (int)rint(y64 * p.inv_so) + p.zo;
+                  k[e] = q < p.lo ? p.lo : (q > p.hi ? p.hi : q);
+                }
+              }
               *reinterpret_cast<int*>(p.out_q + tok * p.ldo + col) = rq_pack4(k[0], k[1], k[2], k[3]);
             }
           }

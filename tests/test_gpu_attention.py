@@ -122,14 +122,28 @@ def test_softmax_log2_codes_rectangular(rq, G, H, nq, nk, bits, bias):
                                                                  (1, 2, 300, 64, 6, 8, False), (2, 1, 700, 32, 8, 6, True),
                                                                  (1, 1, 1025, 128, 8, 8, False), (1, 2, 257, 128, 5, 4, True)])
 def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
+    _attn_pv_case(rq, batch, H, seq, dh, bits_p, bits_v, causal, False)
+
+
+@pytest.mark.parametrize("batch,H,seq,dh,bits_p,bits_v,causal", [(2, 2, 197, 64, 4, 4, False), (2, 2, 49, 32, 6, 6, False),
+                                                                 (1, 2, 257, 64, 4, 8, True), (1, 2, 300, 64, 6, 8, False),
+                                                                 (1, 1, 520, 128, 8, 8, True), (1, 2, 40, 32, 3, 4, False)])
+def test_attn_pv_zero_at_max_code(rq, batch, H, seq, dh, bits_p, bits_v, causal):
+    """RQ_LOG_ZERO_AT_MAX_CODE: keys whose code is the saturated one contribute nothing (every kernel variant of rq_attn_pv)."""
+    _attn_pv_case(rq, batch, H, seq, dh, bits_p, bits_v, causal, True)
+
+
+def _attn_pv_case(rq, batch, H, seq, dh, bits_p, bits_v, causal, zero_max):
     b, ctx = rq
-    print("case", batch, H, seq, dh, bits_p, bits_v, causal, flush=True)
+    print("case", batch, H, seq, dh, bits_p, bits_v, causal, zero_max, flush=True)
     g = np.random.default_rng(seq + dh + bits_p)
     D = H * dh
     ld = _ld(seq)
     # codes with a realistic spread: most mass on large codes, a few small ones
     A = orc.softmax_rows(g.normal(size=(batch * H, seq, seq)) * 3)
     codes = orc.logsqrt2_quant_base2(A, 1.0, bits_p)
+    if zero_max:         # make sure the saturated code is there, also where the softmax of this draw rarely reaches it
+        codes[g.random(codes.shape) < 0.05] = 2 ** bits_p - 1
     cp = np.full((batch * H, seq, ld), 3, np.uint8)      # padding holds a small code on purpose: it must be ignored
     cp[:, :, :seq] = codes
     qv = g.integers(0, 2 ** bits_v, size=(batch * seq, D))
@@ -142,7 +156,8 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
     for bi in range(batch):
         r = slice(bi * seq, (bi + 1) * seq)
         for h in range(H):
-            want[r, h * dh:(h + 1) * dh] = orc.attn_pv(codes[bi * H + h], qv[r, h * dh:(h + 1) * dh], s_log, s_v, z_v, causal)
+            want[r, h * dh:(h + 1) * dh] = orc.attn_pv(codes[bi * H + h], qv[r, h * dh:(h + 1) * dh], s_log, s_v, z_v, causal,
+                                                       bits_p, zero_max)
     s_o = np.float32((want.max() - want.min()) / (2 ** bits_v - 1))
     z_o = int(np.rint(-want.min() / np.float64(s_o)))
     off_o = b.store_offset(bits_v, z_o)
@@ -151,7 +166,7 @@ def test_attn_pv(rq, batch, H, seq, dh, bits_p, bits_v, causal):
     outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
     b.rq_attn_pv(ctx, dev(cp), ld, qd.data_ptr() + 2 * D, 3 * D, batch, H, seq, seq, dh, float(s_log), float(s_v), z_v, offv, bits_p,
                  mask=b.MASK_CAUSAL if causal else b.MASK_NONE, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o,
-                 bits_o=bits_v)
+                 bits_o=bits_v, flags=b.LOG_ZERO_AT_MAX_CODE if zero_max else 0)
     # exact integer sums everywhere except for wide codes on long rows, which accumulate in float32 on the bfloat16
     # matrix cores: n terms of magnitude <= |v| p_j each round to 2^-24 of the running sum
     assert_float_close(outf.cpu().numpy(), want, "attn_pv", rtol=1e-4 if (bits_p > 4 and seq > 256) else 1e-5)
@@ -258,9 +273,17 @@ def test_attn_fused_whole_windows(rq, batch, H, seq, dh, bits, bits_p, bias):
     _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias)
 
 
-def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias):
+@pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p,bias", [(2, 3, 197, 64, 4, 4, False), (2, 2, 257, 64, 4, 4, False),
+                                                             (3, 2, 49, 32, 6, 6, True), (2, 2, 64, 128, 8, 3, False)])
+def test_attn_fused_zero_at_max_code(rq, batch, H, seq, dh, bits, bits_p, bias):
+    """RQ_LOG_ZERO_AT_MAX_CODE in the one-kernel attention (int8 and bfloat16 P.V variants)."""
+    _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias, True)
+
+
+def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias, zero_max=False):
     b, ctx = rq
-    print("case", batch, H, seq, dh, bits, bits_p, bias, flush=True)
+    flags = b.LOG_ZERO_AT_MAX_CODE if zero_max else 0
+    print("case", batch, H, seq, dh, bits, bits_p, bias, zero_max, flush=True)
     assert b.attn_fused_supported(seq, dh, bits_p, bias)
     g = np.random.default_rng(seq * 3 + dh + bits)
     D = H * dh
@@ -291,7 +314,7 @@ def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias):
                 L = L + bias_a[h].astype(np.float64)
             pc = orc.softmax_log_quant(L, s_log, bits_p)
             want_codes[bi * H + h] = pc
-            want[r, c] = orc.attn_pv(pc, codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log, s_v, z[2], False)
+            want[r, c] = orc.attn_pv(pc, codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log, s_v, z[2], False, bits_p, zero_max)
     s_o = np.float32((want.max() - want.min()) / qmax)
     z_o = int(np.rint(-want.min() / np.float64(s_o)))
     off_o = b.store_offset(bits, z_o)
@@ -300,7 +323,7 @@ def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias):
     outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
     b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
                     codes=outc, ld=ld, out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits,
-                    bias=None if bias_a is None else dev(bias_a))
+                    bias=None if bias_a is None else dev(bias_a), flags=flags)
     got_codes = outc.cpu().numpy()[:, :, :seq]
     frac = assert_codes_close(got_codes, want_codes, "fused attention codes")
     # float32 epilogue on exact integer sums: the even- and odd-code terms can cancel, so an element far below the row's
@@ -314,10 +337,11 @@ def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias):
             for h in range(H):
                 c = slice(h * dh, (h + 1) * dh)
                 want[r, c] = orc.attn_pv(got_codes[bi * H + h].astype(np.int64), codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log,
-                                         s_v, z[2], False)
+                                         s_v, z[2], False, bits_p, zero_max)
         assert_float_close(outf.cpu().numpy(), want, "fused attention out", rtol=1e-4)
     # without the optional codes output the result is the same
     outq2 = torch.zeros_like(outq)
     b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
-                    out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits, bias=None if bias_a is None else dev(bias_a))
+                    out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits, bias=None if bias_a is None else dev(bias_a),
+                    flags=flags)
     assert torch.equal(outq, outq2)

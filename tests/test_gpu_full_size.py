@@ -60,10 +60,12 @@ def test_llama_shape_full_size_stage_by_stage(rq):
     """The LLaMA-7B-shaped block (one 2048-token sequence, hidden 4096, causal, gated MLP, W4/A8) at full size.
 
     With ~1 % of the channels scaled 50-200x the attention logits span hundreds of units, so Softmax is close to an argmax
-    and ONE rounding-tie flip in a Q or K code can move a row's winning key: end-to-end element-wise agreement is not a
-    property of this workload (a float64 and a float32 evaluation of the same formulas disagree the same way).  Every
-    stage is therefore checked teacher-forced on the oracle's own intermediates (integer accumulators bit-exact, codes
-    within the tie budget, floats to 1e-3), and end to end the rows that no flip reached must agree."""
+    and ONE rounding-tie flip in a Q or K code can move a row's winning key.  The 8-bit re-quantization of Q, K, V is
+    therefore guarded against ties (float64 re-decision), and this test holds the block to the stated bar: every stage
+    teacher-forced on the oracle's own intermediates (integer accumulators bit-exact, codes within the tie budget, floats to
+    1e-3); every code tensor of the whole pass read back from the workspace and compared; the oracle's stages fed with the
+    GPU's own codes must reproduce the GPU's floats to 1e-3; and end to end max|d| <= 1e-3 max|ref| on every row that no
+    differing code upstream of P.V reaches (all rows when none differs; the differing codes are within the tie budget)."""
     import math
     from tests.helpers import assert_codes_close, assert_float_close, lin_to_device
     b, ctx = rq
@@ -148,10 +150,61 @@ def test_llama_shape_full_size_stage_by_stage(rq):
     yb = torch.zeros_like(xd)
     blk.forward(xd, yb, cfg.batch, cfg.seq)
     torch.cuda.synchronize()
-    e = np.abs(yb.cpu().numpy().astype(np.float64) - y_ref).max(axis=1)
+    got_y = yb.cpu().numpy().astype(np.float64)
     ref = np.abs(y_ref).max()
-    bad = float(np.mean(e > 1e-3 * ref))
-    print("  rows beyond 1e-3 of max|ref| (reached by a tie flip through the near-argmax Softmax): %.3g; median row error %.3g"
-          % (bad, float(np.median(e)) / ref), flush=True)
-    assert bad < 0.05
+    e = np.abs(got_y - y_ref).max(axis=1)
+    print("  end to end: max|d| / max|ref| = %.3g, rows beyond 1e-3: %.3g, median row error %.3g"
+          % (e.max() / ref, float(np.mean(e > 1e-3 * ref)), float(np.median(e)) / ref), flush=True)
+    # ---- what the kernels left in the workspace: every code tensor of the pass ----
+    lay = blk.layout(cfg.batch, cfg.seq)
+    assert lay.codes_bytes >= H * N * lay.ld and lay.batch_chunk == 1
+    inter = blk.intermediates(cfg.batch, cfg.seq)
+    g_qkv = inter["qkv"].cpu().numpy().astype(np.int64)
+    g_q, g_k, g_v = (g_qkv[:, i * D:(i + 1) * D] + offs[i] for i in range(3))
+    g_codes = inter["codes"].cpu().numpy()[:, :, :N].astype(np.int64)
+    g_o = inter["o"].cpu().numpy().astype(np.int64) + offo
+    g_xbar = inter["xbar"].cpu().numpy()
+    g_a2 = inter["a2"].cpu().numpy().astype(np.int64) + off2
+    g_h = inter["hidden"].cpu().numpy().astype(np.int64) + offh
+    flips = {k: int(np.count_nonzero(a != w)) for k, a, w in (("q", g_q, t["qq"]), ("k", g_k, t["qk"]), ("v", g_v, t["qv"]))}
+    print("  Q / K / V codes that differ from the oracle's: %s of %d each" % (flips, T * D), flush=True)
+    for k, a, w in (("q", g_q, t["qq"]), ("k", g_k, t["qk"]), ("v", g_v, t["qv"])):
+        assert_codes_close(a, w, "block " + k)
+    # ---- the oracle's stages fed with the codes the kernels produced (every code the GPU chose differently sits on a
+    # rounding tie and is inside the 1e-4 budget; given the same codes, the floats must agree to 1e-3) ----
+    attn = np.empty((T, D))
+    code_flips = 0
+    reached = np.zeros(T, bool)               # rows that a differing code upstream of the Softmax output can reach
+    reached |= (g_q != t["qq"]).any(axis=1)
+    for arr, w in ((g_k, t["qk"]), (g_v, t["qv"])):
+        rows_kv = np.flatnonzero((arr != w).any(axis=1))
+        if rows_kv.size:
+            reached[rows_kv.min():] = True    # causal: a key / value row is seen by the queries after it
+    for h in range(H):
+        cs = slice(h * dh, (h + 1) * dh)
+        L, _ = orc.attention_logits(g_q[:, cs], P["z_q"], P["s_q"], g_k[:, cs], P["z_k"], P["s_k"], dh, None, True)
+        want_codes = orc.softmax_log_quant(L, P["s_log"], bp)
+        d = np.abs(want_codes - g_codes[h])[m]
+        assert d.max() <= 1
+        code_flips += int(np.count_nonzero(d))
+        reached |= ((g_codes[h] != t["codes"][0][h].astype(np.int64)) & m).any(axis=1)
+        attn[:, cs] = orc.attn_pv(g_codes[h], g_v[:, cs], P["s_log"], P["s_v"], P["z_v"], True)
+    print("  Softmax codes that differ from the oracle's on the GPU's own Q, K: %d of %d" % (code_flips, H * N * (N + 1) // 2), flush=True)
+    assert code_flips <= 1e-4 * H * N * (N + 1) // 2
+    assert_codes_close(g_o, orc.uniform_quant(attn, P["s_o"], P["z_o"], ba), "block attention output codes")
+    xbar_w = orc.qlinear(g_o, P["s_o"], P["z_o"], P["proj"]) + x.astype(np.float64)
+    assert_float_close(g_xbar, xbar_w, "block xbar")
+    assert_codes_close(g_a2, orc.ln_quant(g_xbar.astype(np.float64), ln2["gamma_t"], ln2["beta_t"], ln2["s"], ln2["z"], ba, cfg.eps, cfg.norm),
+                       "block ln2 codes")
+    hid_w = orc.mlp_activation(orc.qlinear(g_a2, ln2["s"], ln2["z"], P["fc1"]), cfg.act, Dm)
+    assert_codes_close(g_h, orc.uniform_quant(hid_w, P["s_h"], P["z_h"], ba), "block hidden codes")
+    y_w = orc.qlinear(g_h, P["s_h"], P["z_h"], P["fc2"]) + g_xbar.astype(np.float64)
+    assert_float_close(got_y, y_w, "block y from the GPU's own codes")
+    # ---- and end to end against the oracle's own pass: the stated bar, unless a tie flip upstream of the near-argmax
+    # Softmax was found above (then the rows it reached are explained by it and everything else must still agree) ----
+    print("  rows reached by a differing code upstream of P.V: %d of %d" % (int(reached.sum()), T), flush=True)
+    assert reached.mean() <= 0.1
+    assert e[~reached].max() <= 1e-3 * ref                  # every row no tie flip reached: the stated bar
+    if not reached.any():
+        assert e.max() <= 1e-3 * ref
     assert np.median(e) <= 1e-4 * ref
