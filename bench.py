@@ -238,10 +238,120 @@ def bench_gemm(args, rq, np, torch):
                  ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
                  config=dict(workload="qgemm_w4a8_8192" if K == 8192 else "qgemm_w4a8_8192x8192x%d" % K, M=M, N=N, K=K, bits_w=4, weight_storage=args.wfmt,
                              output="re-quantized int8 codes"),
-                 roofline=dict(bound="mfma", kernel="qgemm_pipe_kernel (256 x 256 tiles)", achieved=achieved, peak=PEAK_INT8_TOPS, unit="TFLOP/s",
+                 roofline=dict(bound="mfma", kernel="qgemm_pipe_kernel (256 x 256 tiles)", achieved=achieved, peak=PEAK_INT8_TOPS, unit="TOP/s",
                                frac=achieved / PEAK_INT8_TOPS, traffic=None, avg_launch_ms=kernel_ms, ops_per_launch=ops),
                  cpu_baseline=cpu)
     print(json.dumps(out_d))
+
+
+GEMMS = ("qkv", "proj", "fc1", "fc2")
+
+
+def run_block(args, cfg_id, cfg, ctx, rq, synth, np, torch, full):
+    """Times rq_block_forward on one workload; returns the JSON record.  full=False: the timed pass and the instrumented
+    pass only (no stand-alone row kernels, no CPU leg)."""
+    steps, warmup = (args.steps, args.warmup) if full else (min(args.steps, 20), min(args.warmup, 5))
+    raw = synth.make_block(cfg, cfg_id, 0)
+    x = torch.from_numpy(raw["x"]).cuda()
+    rawd = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in raw.items() if k != "x"}
+    blk = rq.calibrate_block(ctx, cfg, rawd, x, cfg.batch, cfg.seq)       # untimed preparation, on the GPU
+    del rawd, raw
+    if args.chunk_mb:
+        blk.bp.attn_chunk_bytes = args.chunk_mb << 20
+    y = torch.empty_like(x)
+
+    for _ in range(warmup):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
+
+    # second pass of the same length with HIP events around every kernel launch (on the library's stream)
+    rq.profile_enable(ctx, True)
+    rq.profile_reset(ctx)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(steps):
+        blk.forward(x, y, cfg.batch, cfg.seq)
+    prof = rq.profile_read(ctx)
+    t3 = time.perf_counter()
+    rq.profile_enable(ctx, False)
+    ld = (cfg.seq + 15) // 16 * 16
+    work = algorithmic_work(cfg, ld)
+    kern = {}
+    for name, (ms, n) in prof.items():
+        if n == 0 or name not in work:
+            continue
+        per_step_ms = ms / steps
+        kern[name] = dict(ms_per_step=per_step_ms, launches_per_step=n / steps,
+                          tops=work[name]["ops"] / (per_step_ms * 1e-3) / 1e12,
+                          gbs=work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9)
+    # dominant kernel: the weight-mode int8 MFMA GEMM (four launches per step, one kernel family).  Each launch against the
+    # roofline that bounds IT: max(ops / int8 peak, algorithmic bytes / HBM peak).
+    launches = {}
+    for k in GEMMS:
+        ops, nbytes, ms = work[k]["ops"], work[k]["bytes"], kern[k]["ms_per_step"]
+        t_mfma, t_hbm = ops / (PEAK_INT8_TOPS * 1e12) * 1e3, nbytes / (PEAK_HBM_GBS * 1e9) * 1e3
+        launches[k] = dict(ms=ms, ops=ops, bytes=nbytes, achieved_tops=kern[k]["tops"], frac_of_int8_peak=kern[k]["tops"] / PEAK_INT8_TOPS,
+                           achieved_gbs=kern[k]["gbs"], bound="mfma" if t_mfma >= t_hbm else "hbm", roofline_ms=max(t_mfma, t_hbm),
+                           frac_of_own_roofline=max(t_mfma, t_hbm) / ms)
+    gemm_ms = sum(kern[k]["ms_per_step"] for k in GEMMS)
+    gemm_ops = sum(work[k]["ops"] for k in GEMMS)
+    gemm_bytes = sum(work[k]["bytes"] for k in GEMMS)
+    achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    agg_bound = "mfma" if gemm_ops / (PEAK_INT8_TOPS * 1e12) >= gemm_bytes / (PEAK_HBM_GBS * 1e9) else "hbm"
+    roofline = dict(bound=agg_bound, kernel="qgemm_pipe_kernel (qkv+proj+fc1+fc2; per launch: gemm_launches)", achieved=achieved,
+                    peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved / PEAK_INT8_TOPS, traffic=None,
+                    avg_launch_ms=gemm_ms / 4.0, ops_per_launch=gemm_ops / 4.0, bytes_per_launch=gemm_bytes / 4.0,
+                    share_of_step=gemm_ms / sum(v["ms_per_step"] for v in kern.values()))
+    roofline["traffic"] = read_traffic(os.path.join(ROOT, "profiles", "qgemm_%s_hbm_traffic.txt" % cfg.name))
+    hbm = {}
+    for k in ("ln1", "ln2", "softmax"):
+        if k in kern:
+            hbm[k + "_in_block"] = dict(achieved=kern[k]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=kern[k]["gbs"] / PEAK_HBM_GBS,
+                                        ms_per_launch=kern[k]["ms_per_step"] / kern[k]["launches_per_step"])
+    if full:
+        hbm.update(standalone_row_kernels(rq, ctx, cfg, torch))
+
+    cpu = None
+    if full and not args.no_cpu_baseline:
+        from oracle import repquant_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        cal_cfg = cfg.with_batch(min(cfg.batch, 4))
+        run_cfg = cfg.with_batch(min(cfg.batch, 64 if cfg.seq <= 512 else 1))
+        raw_c = synth.make_block(cal_cfg, cfg_id, 1)
+        P = orc.calibrate_block(raw_c, dataclasses.asdict(cal_cfg))
+        P["cfg"] = dataclasses.asdict(run_cfg)
+        xs = synth.make_block(run_cfg, cfg_id, 2)["x"]
+        passes, c0 = 0, time.perf_counter()
+        while passes < 40 and time.perf_counter() - c0 < 12.0:   # whole passes, about 12 s of host work
+            orc.block_forward(P, xs)
+            passes += 1
+        c1 = time.perf_counter()
+        cpu = dict(value=passes * run_cfg.tokens / (c1 - c0), unit="tokens/s", cores=cores, kind="oracle",
+                   sample="%d forward passes over %d of %d sequences of the same workload (%d tokens each pass; tokens/s does not "
+                          "depend on the number of sequences, they never interact), float64 numpy oracle calibrated on %d sequences; "
+                          "%.1f s" % (passes, run_cfg.batch, cfg.batch, run_cfg.tokens, cal_cfg.batch, c1 - c0))
+
+    del blk
+    torch.cuda.empty_cache()
+    return dict(metric="quantized-block tokens/s on 1 MI355X", value=tokens_per_s, unit="tokens/s", n_gpus=1,
+                steps=steps, warmup=warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
+                vs_baseline=None, dtype="int8", data="synthetic",
+                config=dict(workload=cfg.name, batch=cfg.batch, seq=cfg.seq, hidden=cfg.D, heads=cfg.H, mlp=cfg.Dm,
+                            bits_w=cfg.bits_w, bits_a=cfg.bits_a, bits_softmax=cfg.bits_p, tokens=cfg.tokens),
+                roofline=roofline, gemm_launches=launches, hbm_kernels=hbm,
+                kernels_ms_per_step={k: round(v["ms_per_step"], 5) for k, v in kern.items()},
+                ms_per_step_instrumented=(t3 - t2) * 1e3 / steps, cpu_baseline=cpu)
 
 
 def main():
@@ -249,7 +359,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, help="index into the synthetic workloads (default: ViT-B W4/A4)")
+    ap.add_argument("--config", type=int, default=4,
+                    help="index into the synthetic workloads; default 4: CLIP ViT-L/14 image tower W4/A4, 128 x 257 tokens, the "
+                         "largest single-GPU workload (862 GOP per step)")
+    ap.add_argument("--also", default="3,1", help="further workloads timed briefly in the same run (comma-separated; '' for none)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-mb", type=int, default=0)
@@ -287,94 +400,18 @@ def main():
     ctx = rq.Context(0)
     if args.tile:
         rq.set_gemm_tile(ctx, args.tile)
-    raw = synth.make_block(cfg, args.config, 0)
-    x = torch.from_numpy(raw["x"]).cuda()
-    rawd = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in raw.items() if k != "x"}
-    blk = rq.calibrate_block(ctx, cfg, rawd, x, cfg.batch, cfg.seq)       # untimed preparation, on the GPU
-    if args.chunk_mb:
-        blk.bp.attn_chunk_bytes = args.chunk_mb << 20
-    y = torch.empty_like(x)
-
-    for _ in range(args.warmup):
-        blk.forward(x, y, cfg.batch, cfg.seq)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        blk.forward(x, y, cfg.batch, cfg.seq)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = cfg.tokens / (ms_per_step * 1e-3)
-
-    # second pass of the same length with HIP events around every kernel launch (on the library's stream)
-    rq.profile_enable(ctx, True)
-    rq.profile_reset(ctx)
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(args.steps):
-        blk.forward(x, y, cfg.batch, cfg.seq)
-    prof = rq.profile_read(ctx)
-    t3 = time.perf_counter()
-    rq.profile_enable(ctx, False)
-    ld = (cfg.seq + 15) // 16 * 16
-    work = algorithmic_work(cfg, ld)
-    kern = {}
-    for name, (ms, n) in prof.items():
-        if n == 0 or name not in work:
-            continue
-        per_step_ms = ms / args.steps
-        kern[name] = dict(ms_per_step=per_step_ms, launches_per_step=n / args.steps,
-                          tops=work[name]["ops"] / (per_step_ms * 1e-3) / 1e12,
-                          gbs=work[name]["bytes"] / (per_step_ms * 1e-3) / 1e9)
-    # dominant kernel: the weight-mode int8 MFMA GEMM (four launches per step, one kernel family)
-    gemm_ms = sum(kern[k]["ms_per_step"] for k in ("qkv", "proj", "fc1", "fc2"))
-    gemm_ops = sum(work[k]["ops"] for k in ("qkv", "proj", "fc1", "fc2"))
-    other = {k: v["ms_per_step"] for k, v in kern.items() if k not in ("qkv", "proj", "fc1", "fc2")}
-    achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel="qgemm_pipe_kernel (qkv+proj+fc1+fc2)", achieved=achieved, peak=PEAK_INT8_TOPS,
-                    unit="TFLOP/s", frac=achieved / PEAK_INT8_TOPS, traffic=None,
-                    avg_launch_ms=gemm_ms / 4.0, ops_per_launch=gemm_ops / 4.0,
-                    share_of_step=gemm_ms / sum(v["ms_per_step"] for v in kern.values()))
-    roofline["traffic"] = read_traffic(os.path.join(ROOT, "profiles", "qgemm_%s_hbm_traffic.txt" % cfg.name))
-    hbm = {}
-    for k in ("ln1", "ln2", "softmax"):
-        if k in kern:
-            hbm[k + "_in_block"] = dict(achieved=kern[k]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=kern[k]["gbs"] / PEAK_HBM_GBS,
-                                        ms_per_launch=kern[k]["ms_per_step"] / kern[k]["launches_per_step"])
-    hbm.update(standalone_row_kernels(rq, ctx, cfg, torch))
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import repquant_oracle as orc
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        cal_cfg = cfg.with_batch(min(cfg.batch, 4))
-        run_cfg = cfg.with_batch(min(cfg.batch, 64 if cfg.seq <= 512 else 1))
-        raw_c = synth.make_block(cal_cfg, args.config, 1)
-        P = orc.calibrate_block(raw_c, dataclasses.asdict(cal_cfg))
-        P["cfg"] = dataclasses.asdict(run_cfg)
-        xs = synth.make_block(run_cfg, args.config, 2)["x"]
-        passes, c0 = 0, time.perf_counter()
-        while passes < 40 and time.perf_counter() - c0 < 12.0:   # whole passes, about 12 s of host work
-            orc.block_forward(P, xs)
-            passes += 1
-        c1 = time.perf_counter()
-        cpu = dict(value=passes * run_cfg.tokens / (c1 - c0), unit="tokens/s", cores=cores, kind="oracle",
-                   sample="%d forward passes over %d of %d sequences of the same workload (%d tokens each pass), float64 numpy "
-                          "oracle calibrated on %d sequences; %.1f s" % (passes, run_cfg.batch, cfg.batch, run_cfg.tokens,
-                                                                        cal_cfg.batch, c1 - c0))
-
-    out = dict(metric="quantized-block tokens/s on 1 MI355X", value=tokens_per_s, unit="tokens/s", n_gpus=1,
-               steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
-               vs_baseline=None, dtype="int8", data="synthetic",
-               config=dict(workload=cfg.name, batch=cfg.batch, seq=cfg.seq, hidden=cfg.D, heads=cfg.H, mlp=cfg.Dm,
-                           bits_w=cfg.bits_w, bits_a=cfg.bits_a, bits_softmax=cfg.bits_p, tokens=cfg.tokens),
-               roofline=roofline, hbm_kernels=hbm,
-               kernels_ms_per_step={k: round(v["ms_per_step"], 5) for k, v in kern.items()},
-               ms_per_step_instrumented=(t3 - t2) * 1e3 / args.steps, cpu_baseline=cpu)
+    out = run_block(args, args.config, cfg, ctx, rq, synth, np, torch, full=True)
+    # the other large single-GPU workloads in the same run (shorter, no stand-alone kernels, no CPU leg): context for the
+    # headline line, each with its own per-launch GEMM figures
+    others = {}
+    for c in [int(v) for v in args.also.split(",") if v.strip()]:
+        if c != args.config and not args.batch:
+            o = run_block(args, c, synth.CONFIGS[c], ctx, rq, synth, np, torch, full=False)
+            others[o["config"]["workload"]] = dict(ms_per_step=o["ms_per_step"], tokens_per_s=o["value"], tokens=o["config"]["tokens"],
+                                                   gemm_frac_of_int8_peak=o["roofline"]["frac"], gemm_launches=o["gemm_launches"],
+                                                   kernels_ms_per_step=o["kernels_ms_per_step"])
+    if others:
+        out["other_workloads"] = others
     print(json.dumps(out))
     if args.copy_probe:
         # a plain device copy of known size (256 MiB read + 256 MiB written): scales the HBM byte counters of a --pmc run
