@@ -509,6 +509,18 @@ rq_status rq_block_workspace_layout(const rq_block_params* p, int64_t batch, int
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);
 
+/* rq_block_forward for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same pass, same kernels and same results, with the scratch in a fixed device array
+ * inside the library instead of a caller workspace.  The array holds RQ_NOALLOC_SCRATCH_BYTES on every GPU the library is
+ * loaded on, until the process ends; its per-device address is resolved in rq_create.  The call allocates nothing and
+ * frees nothing.  A shape whose plan (rq_block_workspace_bytes) exceeds the array is refused with RQ_ERR_WORKSPACE and a
+ * message that names both sizes.  All calls on one GPU share that GPU's array: two calls that overlap in time on the same
+ * GPU (different streams or threads) race; calls on one stream are ordered and need nothing cleared between them (every
+ * byte a pass reads, it wrote before).  x and y stay caller buffers as in rq_block_forward. */
+#define RQ_NOALLOC_SCRATCH_BYTES (32u << 20)
+size_t rq_block_noalloc_scratch_bytes(void);
+rq_status rq_block_forward_noalloc(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y, int64_t batch, int64_t seq);
+
 /* Per-kernel timing of rq_block_forward: when enabled, every kernel launch inside rq_block_forward is
  * bracketed by HIP events on the context's stream.  rq_profile_read synchronizes the stream, writes up to
  * `cap` records (host arrays) accumulated since the last rq_profile_reset and returns their number.

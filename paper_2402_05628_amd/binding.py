@@ -222,6 +222,8 @@ _rq_attn_fused = _sig("rq_attn_fused", i32, [vp, C.POINTER(AttnFusedDesc)])
 _rq_attn_fused_supported = _sig("rq_attn_fused_supported", i32, [i32, i32, i32, i32])
 _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockParams), i64, i64])
 _rq_block_layout = _sig("rq_block_workspace_layout", i32, [C.POINTER(BlockParams), i64, i64, C.POINTER(BlockLayout)])
+_rq_block_forward_noalloc = _sig("rq_block_forward_noalloc", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64])
+_rq_noalloc_bytes = _sig("rq_block_noalloc_scratch_bytes", C.c_size_t, [])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_qgemm_ln = _sig("rq_qgemm_ln_quant", i32, [vp, C.POINTER(GemmDesc), C.POINTER(LnDesc)])
 _rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
@@ -519,6 +521,16 @@ class Block:
         ptr, n = self.workspace(batch, seq)
         self.ctx.check(_rq_block_forward(self.ctx.handle, C.byref(self.bp), _p(x), _p(y), batch, seq, ptr, n))
         return y
+
+
+def noalloc_scratch_bytes() -> int:
+    return int(_rq_noalloc_bytes())
+
+
+def rq_block_forward_noalloc(blk: "Block", x: torch.Tensor, y: torch.Tensor, batch: int, seq: int):
+    """rq_block_forward_noalloc with the parameters of `blk`: no workspace argument, nothing allocated."""
+    blk.ctx.check(_rq_block_forward_noalloc(blk.ctx.handle, C.byref(blk.bp), _p(x), _p(y), batch, seq))
+    return y
 
 
 def profile_enable(ctx: Context, on: bool):

@@ -4,6 +4,7 @@
 // stay resident in the 256 MB last-level cache between Q.K^T, Softmax-log2 and P.V.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "rq_internal.h"
 
@@ -314,6 +315,63 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
     if (st != RQ_OK) return st;
   }
   return RQ_OK;
+}
+
+// ---- rq_block_forward_noalloc: the same pass with its scratch in a fixed device array of this library ----------------
+}  // extern "C"
+
+// Scratch of rq_block_forward_noalloc.  One copy of the array exists on every GPU the library is loaded on, at an address of
+// its own; host code never uses the array's name as an address: the per-device address comes from hipGetSymbolAddress,
+// taken once per device with that device current, and is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[RQ_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+}  // namespace
+
+// Called by rq_create for a device context (and again, harmlessly, by the entry point): resolves this device's copy.
+rq_status rq_noalloc_scratch_init(rq_ctx* ctx, void** out) {
+  const int dev = ctx->device;
+  if (dev < 0 || dev >= MAX_DEVICES) return rq_fail(ctx, RQ_ERR_UNSUPPORTED, "rq_block_forward_noalloc: device %d outside 0..%d", dev, MAX_DEVICES - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    int prev = -1;
+    RQ_HIP(hipGetDevice(&prev));
+    if (prev != dev) RQ_HIP(hipSetDevice(dev));
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (prev != dev) (void)hipSetDevice(prev);
+    if (e != hipSuccess || !ptr)
+      return rq_fail(ctx, RQ_ERR_HIP, "rq_block_forward_noalloc: hipGetSymbolAddress(scratch) on device %d failed: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  if (out) *out = g_scratch_ptr[dev];
+  return RQ_OK;
+}
+
+extern "C" {
+
+size_t rq_block_noalloc_scratch_bytes(void) { return (size_t)RQ_NOALLOC_SCRATCH_BYTES; }
+
+rq_status rq_block_forward_noalloc(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y, int64_t batch, int64_t seq) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_block_forward_noalloc: ctx is NULL");
+  RQ_REQUIRE(p && x && y, RQ_ERR_INVALID_ARG, "rq_block_forward_noalloc: params, x, y must be non-NULL");
+  RQ_REQUIRE(batch > 0 && seq > 0 && p->D > 0 && p->H > 0 && p->Dm > 0, RQ_ERR_SHAPE,
+             "rq_block_forward_noalloc: batch = %lld, seq = %lld, D = %d, H = %d, Dm = %d", (long long)batch, (long long)seq, p->D, p->H,
+             p->Dm);
+  const size_t need = make_plan(p, batch, seq).total;
+  RQ_REQUIRE(need <= (size_t)RQ_NOALLOC_SCRATCH_BYTES, RQ_ERR_WORKSPACE,
+             "rq_block_forward_noalloc: this shape needs %zu bytes of scratch, the fixed array holds %zu; use rq_block_forward with a "
+             "caller workspace", need, (size_t)RQ_NOALLOC_SCRATCH_BYTES);
+  if (ctx->device < 0)      // host-only context: let the shared path finish the validation and refuse
+    return rq_block_forward(ctx, p, x, y, batch, seq, reinterpret_cast<void*>(uintptr_t(256)), need);
+  void* ptr = nullptr;
+  const rq_status st = rq_noalloc_scratch_init(ctx, &ptr);
+  if (st != RQ_OK) return st;
+  // No region has to start at zero: every byte a kernel of the pass reads was written earlier in the same pass.
+  return rq_block_forward(ctx, p, x, y, batch, seq, ptr, (size_t)RQ_NOALLOC_SCRATCH_BYTES);
 }
 
 }  // extern "C"

@@ -46,6 +46,14 @@ rq_status rq_create(rq_ctx** out, int device, void* hip_stream) {
   }
   c->pending = new std::vector<rq_ctx::EvPair>();
   c->pool = new std::vector<hipEvent_t>();
+  if (device >= 0) {      // set-up work that must not happen inside rq_block_forward_noalloc's callers' hot loops
+    const rq_status st = rq_noalloc_scratch_init(c, nullptr);
+    if (st != RQ_OK) {
+      g_last_error = c->err;
+      rq_destroy(c);
+      return st;
+    }
+  }
   *out = c;
   return RQ_OK;
 }

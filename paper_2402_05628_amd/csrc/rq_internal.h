@@ -97,6 +97,9 @@ rq_status rq_launch_ln_channel_percentile(rq_ctx* ctx, const float* x, int64_t T
 rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d);
 rq_status rq_launch_dual_clip(rq_ctx* ctx, const rq_dual_clip_desc* d);
 
+// resolves (once per device) the address of the fixed scratch array of rq_block_forward_noalloc; out may be NULL
+rq_status rq_noalloc_scratch_init(rq_ctx* ctx, void** out);
+
 // profiling hooks used by rq_block_forward
 void rq_prof_begin(rq_ctx* ctx, int step);
 void rq_prof_end(rq_ctx* ctx);
