@@ -204,7 +204,8 @@ def bench_gemm(args, rq, np, torch):
     fmt = rq.W_I8_BAKED if args.wfmt == "i8" else rq.W_U4
     lin = rq.rq_weight_quant_pack(ctx, W, torch.zeros(N, device="cuda"), 4, fmt=fmt)
     out = torch.empty((M, N), dtype=torch.int8, device="cuda")
-    rs = torch.zeros(M, dtype=torch.int32, device="cuda")
+    rs = torch.empty(M, dtype=torch.int32, device="cuda")
+    rq.rq_rowsum_i8(ctx, A, rs)      # with the row sums at hand the kernel multiplies the raw 4-bit codes
     rq.set_gemm_tile(ctx, args.tile)
     run = lambda: rq.rq_qgemm(ctx, A, 8, 8, 0.01, lin, rowsum_a=rs, out_q=out, bits_o=4, s_o=[0.1], z_o=[8], off_o=[8], seg_len=N)
     steps, warmup = min(args.steps, 20), min(args.warmup, 3)

@@ -140,7 +140,9 @@ rq_status rq_weight_quant_pack(rq_ctx* ctx, const rq_wq_desc* d);
  * LayerNorm (Eq. for X'_{n,:}) with the folded affine, fused with the layer-wise uniform quantizer:
  *    code = clip(round((xhat * gamma~ + beta~) / s~) + z~, 0, 2^b - 1),  stored as int8 code - store_off.
  * xhat = (x - mean) / sqrt(var + eps) (population variance) or x / sqrt(mean(x^2) + eps) for RMSNorm.
- * Statistics and the affine are evaluated in float64.  rowsum[t] = sum_d stored[t, d] (optional).
+ * The row statistics are float64; the affine and the quantizer are float32 (pre-round error ~1e-5 of a code at up to 6
+ * bits), and at 7 or 8 bits every value within 2^-11 of a rounding tie is decided again in float64, so such codes differ from
+ * a float64 evaluation only at exact ties.  rowsum[t] = sum_d stored[t, d] (optional).
  * x and q must be 16-byte aligned, D a multiple of 4, ldx a multiple of 4, ldq a multiple of 4.
  */
 typedef struct {
@@ -178,7 +180,10 @@ rq_status rq_ln_quant(rq_ctx* ctx, const rq_ln_desc* d);
  * have N/2 columns: SiLU(y_gate) * y_up.
  * Requant segments: column n (output column) uses entry n / seg_len of s_o/z_o/off_o (n_seg <= 4);
  * this is how one GEMM emits Q, K and V with their own static scales.
- * rowsum_a[m] = sum_k stored_a[m, k] is required for RQ_W_I8_CENTERED.
+ * rowsum_a[m] = sum_k stored_a[m, k] is required for RQ_W_I8_CENTERED.  With RQ_W_U4 it is optional and, when given, must
+ * be those sums as well: the kernel then multiplies the raw 4-bit codes and takes the zero-point term
+ * -z_b[n] * rowsum_a[m] from it where that is faster (K >= 2048; same exact accumulators, fewer instructions per weight;
+ * rq_ln_quant can emit the sums).
  * A, B 16-byte aligned; lda % 16 == 0; weight mode: K % 64 == 0, N % 4 == 0.
  */
 typedef struct {
@@ -194,7 +199,7 @@ typedef struct {
   const float* s_b;          /* [N] (weight mode) */
   const int32_t* z_b;        /* [N] (weight mode; may be NULL for RQ_W_I8_BAKED) */
   const int32_t* colsum_b;   /* [N] (weight mode; required when a_off != z_a) */
-  const int32_t* rowsum_a;   /* [M] (required for RQ_W_I8_CENTERED) */
+  const int32_t* rowsum_a;   /* [M] (required for RQ_W_I8_CENTERED; optional for RQ_W_U4, see above) */
   int32_t b_off, z_b_scalar; /* activation mode */
   const float* bias;         /* [N] or NULL */
   int32_t act;               /* RQ_ACT_* */
@@ -225,7 +230,9 @@ rq_status rq_qgemm(rq_ctx* ctx, const rq_gemm_desc* d);
  * 1 = simple 128x128, 2 = simple 256x128, 3 = pipelined; 4 .. 7 = pipelined with the 320- / 192- / 128- / 256-row tile
  * wherever the kernel has that tile (320: float + residual output; 192: both outputs; 128 and 256: re-quantized output);
  * 8 = pipelined with 256 x 256 tiles (re-quantized output: any weight storage; float + residual output: packed 4-bit
- * weights; chosen by shape for re-quantized products with M >= 2048 and K >= 2048 that give every CU two such tiles). */
+ * weights; chosen by shape for re-quantized products with M >= 2048 and K >= 2048 that give every CU two such tiles).
+ * Adding 256 keeps the zero-point subtraction in the 4-bit unpack even when rowsum_a is given, adding 512 takes the raw
+ * nibbles whenever it is given (by default only for K >= 2048, where it pays); same results either way. */
 rq_status rq_set_gemm_tile(rq_ctx* ctx, int32_t tile);
 
 /* rq_qgemm (weight mode, float output + residual) and rq_ln_quant of that output in ONE kernel whose workgroups own whole

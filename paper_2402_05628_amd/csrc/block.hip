@@ -152,7 +152,11 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   const int64_t T = pl.T;
   const int ba = p->bits_a;
 
+  // Row sums of the stored activation codes: required by centered 8-bit weights; with packed 4-bit weights they let the
+  // GEMM multiply raw nibbles.  The LayerNorm kernel emits them for free; computing them for the attention output and the
+  // MLP hidden layer would cost a pass of its own, so there only the weights that need them get them.
   auto need_rowsum = [](const rq_qlinear& l) { return l.format == RQ_W_I8_CENTERED; };
+  auto ln_rowsum = [](const rq_qlinear& l) { return l.format == RQ_W_I8_CENTERED || l.format == RQ_W_U4; };
 
   // ---- LN1 + layer-wise quant -------------------------------------------------------------------------
   const int off1 = rq_store_offset(ba, p->ln1_z);
@@ -161,7 +165,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
     std::memset(&d, 0, sizeof d);
     d.T = T; d.D = D; d.norm_kind = p->norm_kind; d.eps = p->eps; d.x = x; d.ldx = D;
     d.gamma_t = p->ln1_gamma_t; d.beta_t = p->ln1_beta_t; d.s_tilde = p->ln1_s; d.z_tilde = p->ln1_z; d.bits = ba;
-    d.store_off = off1; d.q = a; d.ldq = D; d.rowsum = need_rowsum(p->qkv) ? rowsum : nullptr;
+    d.store_off = off1; d.q = a; d.ldq = D; d.rowsum = ln_rowsum(p->qkv) ? rowsum : nullptr;
     rq_prof_begin(ctx, RQ_STEP_LN1);
     st = rq_ln_quant(ctx, &d);
     rq_prof_end(ctx);
@@ -171,7 +175,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   const int offq = rq_store_offset(ba, p->z_q), offk = rq_store_offset(ba, p->z_k), offv = rq_store_offset(ba, p->z_v);
   {
     rq_gemm_desc g;
-    fill_linear(g, p->qkv, a, T, D, p->ln1_s, p->ln1_z, off1, rowsum);
+    fill_linear(g, p->qkv, a, T, D, p->ln1_s, p->ln1_z, off1, ln_rowsum(p->qkv) ? rowsum : nullptr);
     g.out_q = qkv; g.ldq = 3 * D; g.bits_o = ba; g.n_seg = 3; g.seg_len = D;
     g.s_o[0] = p->s_q; g.s_o[1] = p->s_k; g.s_o[2] = p->s_v;
     g.z_o[0] = p->z_q; g.z_o[1] = p->z_k; g.z_o[2] = p->z_v;
@@ -263,13 +267,13 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   const int off2 = rq_store_offset(ba, p->ln2_z);
   {
     rq_gemm_desc g;
-    fill_linear(g, p->proj, o, T, D, p->s_o, p->z_o, offo, rowsum);
+    fill_linear(g, p->proj, o, T, D, p->s_o, p->z_o, offo, need_rowsum(p->proj) ? rowsum : nullptr);
     g.residual = x; g.ldr = D; g.out_f32 = xbar; g.ldf = D;
     rq_ln_desc d;
     std::memset(&d, 0, sizeof d);
     d.T = T; d.D = D; d.norm_kind = p->norm_kind; d.eps = p->eps; d.x = xbar; d.ldx = D;
     d.gamma_t = p->ln2_gamma_t; d.beta_t = p->ln2_beta_t; d.s_tilde = p->ln2_s; d.z_tilde = p->ln2_z; d.bits = ba;
-    d.store_off = off2; d.q = a; d.ldq = D; d.rowsum = need_rowsum(p->fc1) ? rowsum : nullptr;
+    d.store_off = off2; d.q = a; d.ldq = D; d.rowsum = ln_rowsum(p->fc1) ? rowsum : nullptr;
     if (p->proj_ln_fused && rq_qgemm_rowln_applies(&g, &d)) {
       rq_prof_begin(ctx, RQ_STEP_PROJ);
       st = rq_qgemm_ln_quant(ctx, &g, &d);
@@ -290,7 +294,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   const int offh = rq_store_offset(ba, p->z_h);
   {
     rq_gemm_desc g;
-    fill_linear(g, p->fc1, a, T, D, p->ln2_s, p->ln2_z, off2, rowsum);
+    fill_linear(g, p->fc1, a, T, D, p->ln2_s, p->ln2_z, off2, ln_rowsum(p->fc1) ? rowsum : nullptr);
     g.act = p->act; g.out_q = hid; g.ldq = Dm; g.bits_o = ba; g.n_seg = 1; g.seg_len = Dm;
     g.s_o[0] = p->s_h; g.z_o[0] = p->z_h; g.off_o[0] = offh;
     rq_prof_begin(ctx, RQ_STEP_FC1);
@@ -307,7 +311,7 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   }
   {
     rq_gemm_desc g;
-    fill_linear(g, p->fc2, hid, T, Dm, p->s_h, p->z_h, offh, rowsum);
+    fill_linear(g, p->fc2, hid, T, Dm, p->s_h, p->z_h, offh, need_rowsum(p->fc2) ? rowsum : nullptr);
     g.residual = xbar; g.ldr = D; g.out_f32 = y; g.ldf = D;
     rq_prof_begin(ctx, RQ_STEP_FC2);
     st = rq_qgemm(ctx, &g);
@@ -588,7 +592,8 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
   const int off1 = rq_store_offset(ba, out->ln1_z);
   if ((st = quant_linear(&out->qkv, wt, bt, 3 * D, D, 0, a, off1, out->ln1_z)) != RQ_OK) return st;
   rq_gemm_desc g;
-  fill_linear(g, out->qkv, a, T, D, out->ln1_s, out->ln1_z, off1, rowsum);
+  const int32_t* const rs_c = wfmt == RQ_W_I8_CENTERED ? rowsum : nullptr;      // the calibration computes row sums only where required
+  fill_linear(g, out->qkv, a, T, D, out->ln1_s, out->ln1_z, off1, rs_c);
   g.out_f32 = f32; g.ldf = 3 * D;
   if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
   float* s3[3] = {&out->s_q, &out->s_k, &out->s_v};
@@ -647,7 +652,7 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
   // ---- proj (plain channel-wise weight quantization), residual ----
   if ((st = quant_linear(&out->proj, raw->w_proj, raw->b_proj, D, D, 0, o, offo, out->z_o)) != RQ_OK) return st;
   if (out->proj.format == RQ_W_I8_CENTERED && (st = rq_rowsum_i8(ctx, o, T, D, D, rowsum)) != RQ_OK) return st;
-  fill_linear(g, out->proj, o, T, D, out->s_o, out->z_o, offo, rowsum);
+  fill_linear(g, out->proj, o, T, D, out->s_o, out->z_o, offo, rs_c);
   g.residual = x; g.ldr = D; g.out_f32 = xbar; g.ldf = D;
   if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
   // ---- LN2 -> FC1 ----
@@ -657,7 +662,7 @@ rq_status rq_block_calibrate(rq_ctx* ctx, const rq_block_raw* raw, const float* 
   if ((st = ln_q(xbar, out->ln2_gamma_t, out->ln2_beta_t, out->ln2_s, out->ln2_z)) != RQ_OK) return st;
   const int off2 = rq_store_offset(ba, out->ln2_z);
   if ((st = quant_linear(&out->fc1, wt, bt, n1, D, gated ? Dm : 0, a, off2, out->ln2_z)) != RQ_OK) return st;
-  fill_linear(g, out->fc1, a, T, D, out->ln2_s, out->ln2_z, off2, rowsum);
+  fill_linear(g, out->fc1, a, T, D, out->ln2_s, out->ln2_z, off2, rs_c);
   g.act = raw->act; g.out_f32 = f32; g.ldf = Dm;
   if ((st = rq_qgemm(ctx, &g)) != RQ_OK) return st;
   {

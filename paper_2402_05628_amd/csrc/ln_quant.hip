@@ -5,9 +5,10 @@
 // a 64-wide wavefront, so that narrow rows still fill the wavefront); the row statistics are reduced with DPP lane
 // exchanges inside 16-lane rows and one or two shuffles across them; the codes leave as one dword (4 codes) per
 // lane, contiguous across lanes.  The per-channel constants g = gamma~/s~ and h = beta~/s~ + z~ are computed once
-// per workgroup in float64 and staged in LDS.  The row statistics are float64; for 8-bit codes so is the quantizer
-// (codes agree with a float64 reference except at exact ties), for narrower codes it is two float32 fma; rounding,
-// saturation to 0..255 and byte packing are one v_cvt_pk_u8_f32 per code.  Small launches run one pass per workgroup with
+// per workgroup in float64 and staged in LDS as float32.  The row statistics are float64; the quantizer is two float32 fma
+// per element; codes of 7 or 8 bits, whose float32 pre-round value carries up to ~5e-5 of a code of error, are decided
+// again in float64 wherever that value lies within 2^-11 of a rounding tie (codes then agree with a float64 reference
+// except at exact ties); rounding, saturation to 0..255 and byte packing are one v_cvt_pk_u8_f32 per code.  Small launches run one pass per workgroup with
 // all workgroups resident; large ones use persistent workgroups that fetch their next rows while quantizing.
 #include <vector>
 
@@ -54,21 +55,23 @@ __device__ __forceinline__ double rsqrt_f64(double a) {
 }
 
 // wavefronts per SIMD the kernel is built for (bounds its registers): rows held in registers grow with NV
-constexpr int ln_waves_per_simd(int nv, bool f32q, bool persist) {
-  return persist ? (nv <= 8 ? 2 : 1) : (nv <= 6 && f32q ? 7 : nv <= 8 ? 4 : nv <= 16 ? 2 : 1);
+constexpr int ln_waves_per_simd(int nv, bool guard, bool persist) {
+  return persist ? (nv <= 8 ? 2 : 1) : (nv <= 6 && !guard ? 7 : nv <= 8 ? 4 : nv <= 16 ? 2 : 1);
 }
+constexpr float TIE_GUARD = 1.0f / 2048.0f;
 
-// F32Q: the normalization and the quantizer run in float32 (codes of at most 6 bits: the pre-round value is below 64, so its
-// float32 error, ~1e-5 of a code, flips far fewer than 1e-4 of the codes); the row statistics stay float64 either way.
+// The normalization and the quantizer run in float32, the row statistics in float64.  GUARD = false (codes of at most 6
+// bits): the pre-round value is below 64, so its float32 error, ~1e-5 of a code, flips far fewer than 1e-4 of the codes.
+// GUARD = true (7 or 8 bits): values within TIE_GUARD of a rounding tie are re-evaluated in float64, in the order of the
+// definition (normalize, folded affine, divide by the scale as a product with g = gamma~ / s~, add z~).
 // PERSIST: workgroups loop over rows and fetch the next rows early; otherwise one pass, fewer registers, more wavefronts.
-template <int LPR, int NV, bool F32Q, bool PERSIST>
-__global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
+template <int LPR, int NV, bool GUARD, bool PERSIST>
+__global__ __launch_bounds__(256, ln_waves_per_simd(NV, GUARD, PERSIST)) void ln_quant_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
                                                        double eps, const float* __restrict__ gamma_t,
                                                        const float* __restrict__ beta_t, double inv_s, double zcode, float qmaxf,
                                                        unsigned off4, int8_t* __restrict__ q, int64_t ldq,
                                                        int32_t* __restrict__ rowsum) {
-  extern __shared__ __align__(16) char gh_raw[];  // [D]: {gamma~ / s~, beta~ / s~ + z~} as double2, or float2 with F32Q
-  double2* const gh = reinterpret_cast<double2*>(gh_raw);
+  extern __shared__ __align__(16) char gh_raw[];  // [D]: {gamma~ / s~, beta~ / s~ + z~} as float2
   float2* const ghf = reinterpret_cast<float2*>(gh_raw);
   constexpr int RPW = 64 / LPR;                   // rows per wavefront
   const int lane = threadIdx.x & 63;
@@ -80,8 +83,7 @@ __global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_
 
   for (int ch = threadIdx.x; ch < D; ch += 256) {
     const double g = (double)gamma_t[ch] * inv_s, h = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode;
-    if (F32Q) ghf[ch] = make_float2((float)g, (float)h);
-    else gh[ch] = make_double2(g, h);
+    ghf[ch] = make_float2((float)g, (float)h);
   }
 
   float4 cur[NV], nxt[PERSIST ? NV : 1];
@@ -131,16 +133,14 @@ __global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_
           unsigned w = 0;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            float vf;
-            if (F32Q) {
-              const float2 g = ghf[c * 4 + e];
-              vf = fminf(fmaf(fmaf(xv[e], rstd_f, nmr_f), g.x, g.y), qmaxf);   // the packed convert below rounds to nearest-even
-            } else {
-              const double2 g = gh[c * 4 + e];
-              const double xh = fma((double)xv[e], rstd, nmr);
-              const double v = rint(fma(xh, g.x, g.y));               // exact integer in float64 ...
-              vf = fminf((float)v, qmaxf);                             // ... so the float32 conversion is exact too
+            const float2 g = ghf[c * 4 + e];
+            float vf = fmaf(fmaf(xv[e], rstd_f, nmr_f), g.x, g.y);    // the packed convert below rounds to nearest-even
+            if (GUARD && fabsf(vf - __builtin_rintf(vf)) > 0.5f - TIE_GUARD) {      // next to a tie: float64 decides
+              const int ch = c * 4 + e;
+              const double gd = (double)gamma_t[ch] * inv_s, hd = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode;
+              vf = (float)rint(fma(fma((double)xv[e], rstd, nmr), gd, hd));      // an exact integer: the float32 conversion is exact too
             }
+            vf = fminf(vf, qmaxf);
             if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);  // saturates below at 0 and packs the byte
             if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
             if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
@@ -163,11 +163,11 @@ __global__ __launch_bounds__(256, ln_waves_per_simd(NV, F32Q, PERSIST)) void ln_
   }
 }
 
-template <int LPR, int NV, bool F32Q, bool PERSIST>
+template <int LPR, int NV, bool GUARD, bool PERSIST>
 rq_status launch_one(rq_ctx* ctx, const rq_ln_desc* d, int64_t blocks, int lds, double inv_s, double zcode, float qmaxf, unsigned off4) {
   static rq_once_per_device lds_attr;
-  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV, F32Q, PERSIST>), 8192 * 16));
-  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV, F32Q, PERSIST>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T,
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&ln_quant_kernel<LPR, NV, GUARD, PERSIST>), 8192 * 8));
+  hipLaunchKernelGGL((ln_quant_kernel<LPR, NV, GUARD, PERSIST>), dim3((unsigned)blocks), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T,
                      d->D, d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);
   RQ_HIP(hipGetLastError());
   return RQ_OK;
@@ -178,22 +178,22 @@ rq_status launch(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcode, f
   constexpr int RPW = 64 / LPR;
   const int64_t rows_per_block = 4 * RPW;
   const int64_t blocks = (d->T + rows_per_block - 1) / rows_per_block;
-  const bool f32q = d->bits <= 6;
-  const int lds = d->D * (f32q ? 8 : 16);
+  const bool guard = d->bits > 6;
+  const int lds = d->D * 8;
   // one pass per workgroup while every workgroup can be resident at once (7 per CU: the kernel is built for 7 wavefronts
   // per SIMD; LDS permitting);
   // beyond that, persistent workgroups that prefetch their next rows
   const int by_lds = lds > 0 ? (160 * 1024) / lds : 8;
-  const int by_regs = ln_waves_per_simd(NV, f32q, false);
+  const int by_regs = ln_waves_per_simd(NV, guard, false);
   const int64_t one_pass_slots = (int64_t)ctx->num_cu * (by_lds < by_regs ? by_lds : by_regs);
   if (blocks <= one_pass_slots) {
-    return f32q ? launch_one<LPR, NV, true, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4)
-                : launch_one<LPR, NV, false, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4);
+    return guard ? launch_one<LPR, NV, true, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4)
+                 : launch_one<LPR, NV, false, false>(ctx, d, blocks, lds, inv_s, zcode, qmaxf, off4);
   }
   const int per_cu = by_lds < 4 ? (by_lds < 1 ? 1 : by_lds) : 4;
   const int64_t cap = (int64_t)ctx->num_cu * per_cu;
-  return f32q ? launch_one<LPR, NV, true, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4)
-              : launch_one<LPR, NV, false, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4);
+  return guard ? launch_one<LPR, NV, true, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4)
+               : launch_one<LPR, NV, false, true>(ctx, d, cap, lds, inv_s, zcode, qmaxf, off4);
 }
 
 }  // namespace

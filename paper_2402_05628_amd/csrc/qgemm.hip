@@ -148,8 +148,10 @@ void launch_tile(rq_ctx* ctx, GemmParams& p) {
 // 128- / 256-row tiles where they exist; 8: 256 x 256 tiles
 extern "C" rq_status rq_set_gemm_tile(rq_ctx* ctx, int32_t tile) {
   if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: ctx is NULL");
-  RQ_REQUIRE(tile >= 0 && tile <= 8, RQ_ERR_INVALID_ARG, "rq_set_gemm_tile: %d not in 0..8", tile);
-  ctx->gemm_tile = tile;
+  RQ_REQUIRE(tile >= 0 && (tile & 0xFF) <= 8 && (tile & ~0x3FF) == 0 && (tile >> 8) != 3, RQ_ERR_INVALID_ARG,
+             "rq_set_gemm_tile: %d not in 0..8 (+ 256 or + 512)", tile);
+  ctx->gemm_tile = tile & 0xFF;
+  ctx->gemm_no_raw = (tile >> 8) == 1 ? 1 : ((tile >> 8) == 2 ? -1 : 0);
   return RQ_OK;
 }
 
@@ -180,6 +182,7 @@ rq_status rq_launch_qgemm_weight(rq_ctx* ctx, const rq_gemm_desc* d) {
   const int64_t big_tiles = ((d->M + 255) / 256) * ((d->N + 127) / 128);
   const bool big = g_gemm_tile ? g_gemm_tile == 2 : big_tiles >= 2 * (int64_t)ctx->num_cu;
   const bool fits32 = (double)d->M * (double)d->lda < 4.0e9 && (double)d->N * (double)d->ldb < 4.0e9;
+  p.no_raw = ctx->gemm_no_raw;
   p.force_rows = g_gemm_tile == 4 ? 5 : (g_gemm_tile == 5 ? 3 : (g_gemm_tile == 6 ? 2 : (g_gemm_tile == 7 ? 4 : (g_gemm_tile == 8 ? 6 : 0))));
   if (g_gemm_tile == 0 && rq_qgemv_applies(p, w4)) return rq_launch_qgemv_w4(ctx, p);   // a few tokens: weight-bandwidth bound
   if ((g_gemm_tile == 3 || g_gemm_tile == 0 || g_gemm_tile >= 4) && d->N % 32 == 0 && fits32) {

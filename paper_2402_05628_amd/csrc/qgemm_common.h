@@ -43,6 +43,8 @@ struct GemmParams {
   int tiles_m, tiles_n;
   int group_m;      // tile rows walked together: consecutive tiles go down group_m rows before they move to the next column
   int force_rows;   // host only: 64-row groups per tile to take wherever that tile exists (0: choose by shape)
+  int no_raw;       // host only: 1 = packed 4-bit weights keep the zero-point subtraction in the unpack even when row sums are
+                    // given, -1 = raw nibbles whenever they are given (default: only with a long K loop)
 };
 
 __device__ __forceinline__ int swz(int row, int c) {

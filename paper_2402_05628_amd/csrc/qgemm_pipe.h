@@ -278,13 +278,23 @@ template <int N> __device__ __forceinline__ void wait_vm() {
 constexpr int pipe_occupancy(int TM, int OUT) {
   return TM <= 2 ? 4 : (TM == 3 ? (OUT == OUT_Q ? 3 : 2) : (TM == 4 ? 2 : 1));
 }
+// the same for every tile shape: 256-column tiles and the eight-wavefront grid own their CU
+constexpr int pipe_wgs_per_cu(int TM, int TN, int WN, int OUT) {
+  return (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT);
+}
 
 // TN = 2: tiles 128 columns wide (wavefront tile 32 TM x 64); TN = 4: 256 columns (wavefront tile 32 TM x 128, one workgroup
 // per CU): per MFMA half the bytes through the CU's load path and the LDS, for large products with a long K loop.
 // WN = 4: eight wavefronts in a 2 x 4 grid (two per SIMD, each with the 32 TM x 32 TN tile) on a tile 32 TN * 4 columns wide:
 // the operand bytes per MFMA of the 256 x 256 tile, with a second wavefront on every SIMD to cover the first one's waits.
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false>
-__global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
+// RAW (packed 4-bit weights with the row sums of the stored activations given): the nibbles enter the MFMA as the raw codes
+// 0 .. 15 -- one AND per operand dword, one shift more for the high nibbles, instead of the byte-wise zero-point
+// subtraction -- and the zero-point term -z_w[n] * rowsum_a[m] is what the accumulators START from:
+//   sum_k a'[m,k] (code[n,k] - z_w[n]) = sum_k a'[m,k] code[n,k] - z_w[n] sum_k a'[m,k],
+// the same exact integers.  It more than halves the vector instructions of the K loop.
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false, bool RAW = false>
+__global__ __launch_bounds__(128 * WN, pipe_wgs_per_cu(TM, TN, WN, OUT)) void qgemm_pipe_kernel(const GemmParams p) {
+  static_assert(!RAW || (W4 && TN == 2), "raw nibbles: packed weights, two column tiles per wavefront");
   constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
   constexpr int BM = 64 * TM, BN = 32 * TN * WN;      // TM = 4: 256-row tiles, two workgroups per CU; TM = 5: 320 rows, one
   constexpr int A_BYTES = BM * 64;
@@ -324,7 +334,6 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
   const int tm = (int)(first_m + (br - tcol * gm)), tn = (int)tcol;
   const int m0 = tm * BM, n0 = tn * BN;
   const int nk = p.K / 64;
-
   // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
   // lane l lands at 16-byte slot l of a 1 KB block = 16 tile rows of 64 B; the chunk that belongs at position
   // (lane & 3) of row (lane >> 2) is chunk ((lane & 3) - (row >> 2)) & 3
@@ -380,12 +389,32 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
   // The weight zero-points are needed by the first unpack.  Loads return in order, so they are requested BEFORE the ring
   // loads (and first used after them): their wait then does not include the ring's first stages.
   int zraw[TN] = {};
-  if (W4) {
+  if (W4 && !RAW) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       int n = n0 + wn0 + j * 32 + l32;
       n = n < p.N ? n : p.N - 1;
       zraw[j] = p.z_b[n];
+    }
+  }
+  // RAW: the zero-points of this lane's 16 output columns per column tile and the row sums of its TM rows, for the
+  // accumulators' start values (requested ahead of the ring like the zero-points above)
+  v4i zcol[RAW ? TN : 1][4];
+  int rsa[RAW ? TM : 1];
+  if (RAW) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int n = n0 + wn0 + j * 32 + 8 * g + 4 * half;
+        n = n + 4 <= p.N ? n : p.N - 4;
+        zcol[RAW ? j : 0][g] = *reinterpret_cast<const v4i*>(p.z_b + n);
+      }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int m = m0 + wm0 + i * 32 + l32;
+      m = m < (int)p.M ? m : (int)p.M - 1;
+      rsa[RAW ? i : 0] = p.rowsum_a[m];
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -424,6 +453,11 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int d0 = bpk[j][2 * s], d1 = bpk[j][2 * s + 1], z4 = zb4[j];
+      if (RAW) {
+        dst[j][0] = d0 & 0x0F0F0F0F; dst[j][1] = (d0 >> 4) & 0x0F0F0F0F;
+        dst[j][2] = d1 & 0x0F0F0F0F; dst[j][3] = (d1 >> 4) & 0x0F0F0F0F;
+        continue;
+      }
       dst[j][0] = (int)((unsigned)(d0 & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
       dst[j][1] = (int)((unsigned)((d0 >> 4) & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
       dst[j][2] = (int)((unsigned)(d1 & 0x0F0F0F0F) - (unsigned)z4) ^ 0x80808080;
@@ -434,7 +468,8 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     const int j = idx >> 2, c = idx & 3;
     const int d = bpk[j][2 * s + (c >> 1)];
     // per byte: code - z without borrow across bytes = ((code | 0x80) - z) ^ 0x80, with 0x80 - z folded into zb4
-    dst[j][c] = (int)((unsigned)(((c & 1) ? (d >> 4) : d) & 0x0F0F0F0F) - (unsigned)zb4[j]) ^ 0x80808080;
+    if (RAW) dst[j][c] = ((c & 1) ? (d >> 4) : d) & 0x0F0F0F0F;
+    else dst[j][c] = (int)((unsigned)(((c & 1) ? (d >> 4) : d) & 0x0F0F0F0F) - (unsigned)zb4[j]) ^ 0x80808080;
   };
   auto fetch_b = [&](int slot, int s, v4i (&dst)[TN]) {   // int8 weights: fragments straight from LDS; W4: the packet (s == 0 only)
 #pragma unroll
@@ -449,7 +484,8 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0;
+      for (int e = 0; e < 16; ++e)      // RAW: |z_w| <= 15 and |rowsum_a| <= 128 K fit the 24-bit multiply (K <= 32768: launcher)
+        acc[j][i][e] = RAW ? -__mul24(zcol[RAW ? j : 0][e >> 2][e & 3], rsa[RAW ? i : 0]) : 0;
   // per-column epilogue constants: one column per thread pair, fetched now, parked in two registers over the main loop
   // (wide tiles: CPT columns per thread, 128 apart)
   constexpr int CPT = BN / 128;      // (threads beyond the first 256 repeat the second 128's columns)
@@ -475,7 +511,7 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
     }
   }
   int rs[TM] = {};
-  if (p.centered) {
+  if (!W4 && p.centered) {      // (packed 4-bit weights are never stored centered: no registers parked for them)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       int m = m0 + wm0 + i * 32 + l32;
@@ -607,10 +643,17 @@ __global__ __launch_bounds__(128 * WN, (TN == 4 || WN == 4) ? 1 : pipe_occupancy
 
 
 // host side: one instantiation set per weight format lives in its own translation unit
-template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false>
+template <bool W4, int S, int ACT, int OUT, int TM, int TN = 2, int WN = 2, bool Q8 = false, bool RAW = false>
 rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   if constexpr (!Q8 && ACT == RQ_ACT_NONE && (OUT & OUT_Q) != 0) {      // 8-bit output codes: the tie-guarded instantiation
-    if (p.out_q && p.qmaxf > 127.f) return launch_pipe_one<W4, S, ACT, OUT, TM, TN, WN, true>(ctx, p);
+    if (p.out_q && p.qmaxf > 127.f) return launch_pipe_one<W4, S, ACT, OUT, TM, TN, WN, true, RAW>(ctx, p);
+  }
+  // Row sums of the activations at hand and a K loop long enough for the cheaper unpack (25 vector instructions per k-step)
+  // to outweigh the start values (about 250 per tile): raw nibbles, see the kernel.  Measured: 8192^3 0.544 -> 0.500 ms; with
+  // K <= 1024 it gains nothing, the K loop there is not bound by its vector instructions.
+  if constexpr (!RAW && W4 && TN == 2) {
+    if (p.rowsum_a && !p.no_raw && (p.K >= 2048 || p.no_raw < 0) && p.K <= 32768 && (reinterpret_cast<uintptr_t>(p.z_b) & 15) == 0 && p.N >= 4)
+      return launch_pipe_one<W4, S, ACT, OUT, TM, TN, WN, Q8, true>(ctx, p);
   }
   constexpr int BN = 32 * TN * WN;
   p.tiles_m = (int)((p.M + 64 * TM - 1) / (64 * TM));
@@ -619,7 +662,7 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   {
     // tiles in flight on one XCD (an eighth of the CUs, OCC workgroups each) as g rows x (inflight / g) columns:
     // pick the g that needs the fewest operand bytes per k-step
-    constexpr int OCC = (TN == 4 || WN == 4) ? 1 : pipe_occupancy(TM, OUT);
+    constexpr int OCC = pipe_wgs_per_cu(TM, TN, WN, OUT);
     const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
     const int inflight = (cu / 8 > 0 ? cu / 8 : 1) * OCC;
     int64_t best = -1;
@@ -638,9 +681,9 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   static_assert(sizeof(EpiLdsT<BN>) <= epi_bytes && lds_bytes >= epi_bytes + (row_staging ? 2 * WN * 32 * 68 * 4 : 0) && lds_bytes <= 160 * 1024,
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static rq_once_per_device lds_attr;
-  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8>), lds_bytes));
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8, RAW>), lds_bytes));
   const int64_t blocks = (ntiles + 7) / 8 * 8;
-  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
+  hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8, RAW>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
   return RQ_OK;
 }
 
@@ -657,7 +700,8 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
   const double c192 = t192 <= cu ? 0.75 : 1.125 * (double)((t192 + 2 * cu - 1) / (2 * cu));
   const double c256 = t256 <= cu ? 1.0 : 1.5 * (double)((t256 + 2 * cu - 1) / (2 * cu));
   const double c320 = 1.25 * (double)((t320 + cu - 1) / cu);
-  if (p.K <= 1024 && c192 < c256 && c192 < c320) return 3;
+  const double other = c320 < c256 ? c320 : c256;
+  if (c192 < other && (p.K <= 1024 || c192 < 0.8 * other)) return 3;      // (a long loop: only where the tile count clearly favours it)
   return c320 < c256 ? 5 : 4;
 }
 

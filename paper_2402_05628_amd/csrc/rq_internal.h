@@ -16,6 +16,7 @@ struct rq_ctx {
   hipStream_t stream = nullptr;
   int num_cu = 256;
   int gemm_tile = 0;          // rq_set_gemm_tile: 0 = kernel and tile of the weight-mode GEMM chosen by shape
+  int gemm_no_raw = 0;        // rq_set_gemm_tile + 256: packed 4-bit weights never take the raw-nibble variant (1); + 512: whenever row sums are given (-1)
   std::string err;
   // per-kernel profiling of rq_block_forward
   bool profiling = false;

@@ -25,7 +25,7 @@ def _act_codes(g, M, K, bits):
 @pytest.mark.parametrize("M,N,K", [(333, 192, 128), (128, 128, 64), (1000, 768, 768), (2049, 1536, 384), (77, 2304, 768),
                                    (513, 260, 3072)])
 @pytest.mark.parametrize("bits_a,bits_w", [(8, 8), (4, 4), (8, 4), (6, 6)])
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 259, 515])      # 259: pipelined, zero-points subtracted in the 4-bit unpack; 515: raw nibbles
 def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
     b, ctx = rq
     print("case", M, N, K, bits_a, bits_w, tile, flush=True)
@@ -100,9 +100,12 @@ def test_float_output_bias_residual(rq, bits_a, bits_w, M, tile):
 @pytest.mark.parametrize("act,tile", [("none3", 0), ("gelu", 0), ("gated", 0), ("gelu_q_only", 0), ("gated_q_only", 0),
                                       ("none3", 5), ("none3", 6), ("none3", 7), ("gelu_q_only", 5), ("gelu_q_only", 6),
                                       ("gated_q_only", 5), ("gated_q_only", 6), ("gated_q_only", 7),
-                                      ("none3", 8), ("gelu_q_only", 8), ("gated_q_only", 8)])
+                                      ("none3", 8), ("gelu_q_only", 8), ("gated_q_only", 8),
+                                      ("none3", 512), ("none3", 517), ("gelu_q_only", 518), ("gated_q_only", 519), ("none3", 520)])
 def test_requantized_output(rq, bits_a, bits_w, bits_o, act, tile):
-    """tile 5 / 6 / 7: the 192- / 128- / 256-row tiles of the kernel that writes re-quantized codes only; 8: 256 x 256 tiles."""
+    """tile 5 / 6 / 7: the 192- / 128- / 256-row tiles of the kernel that writes re-quantized codes only; 8: 256 x 256 tiles;
+    + 512: the same with the raw-nibble variant of the packed 4-bit weights at this short K (the row sums are passed either way; by
+    default the variant is taken for K >= 2048, as in the large-product and long-K tests below)."""
     b, ctx = rq
     q_only = act.endswith("_q_only")      # the block's launches: re-quantized codes are the only output
     act = act.replace("_q_only", "")
