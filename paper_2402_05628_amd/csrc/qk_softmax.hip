@@ -6,6 +6,8 @@ rq_status rq_launch_qk_softmax_d32(rq_ctx* ctx, const rqks::QksParams& p, int64_
 rq_status rq_launch_qk_softmax_d64(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 rq_status rq_launch_qk_softmax_d128(rq_ctx* ctx, const rqks::QksParams& p, int64_t groups);
 rq_status rq_launch_qk_softmax_long(rq_ctx* ctx, const rqks::QksParams& p, int d_head);
+bool rq_attn_stream_supported(int N, int d_head, int bits_p, bool has_bias);
+rq_status rq_launch_attn_stream(rq_ctx* ctx, const rqks::QksParams& p, int d_head);
 
 
 extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bits_p, int32_t has_bias) {
@@ -16,12 +18,13 @@ extern "C" int32_t rq_attn_fused_supported(int32_t N, int32_t d_head, int32_t bi
   return bits_p <= 6 && nt <= rqks::FUSED_EXT_TILES ? 1 : 0;      // with a bias and / or codes of 5 or 6 bits
 }
 
-// Where the one-kernel attention is also the faster choice: up to 8 key tiles.  Nine tiles (257 .. 288 keys) on the 8
-// wavefronts of a workgroup take two rounds per group; rq_qk_softmax_log2_quant + rq_attn_pv are then as fast or faster
-// (257 keys, d_head 64, 1024 groups: 117 us against 53 + 51 us).
+// Where the one-kernel attention is also the faster choice: up to 8 key tiles, and nine where the streamed kernel
+// serves them.  (Nine tiles on the 8 wavefronts of the register-resident kernel take two rounds per group;
+// rq_qk_softmax_log2_quant + rq_attn_pv are then as fast or faster: 257 keys, d_head 64, 1024 groups: 117 us against
+// 53 + 51 us.)
 bool rq_attn_fused_preferred(int N, int d_head, int bits_p, bool has_bias) {
   if (!rq_attn_fused_supported(N, d_head, bits_p, has_bias)) return false;
-  return (N + 31) / 32 <= 8;
+  return (N + 31) / 32 <= 8 || rq_attn_stream_supported(N, d_head, bits_p, has_bias);
 }
 
 rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
@@ -39,6 +42,7 @@ rq_status rq_launch_attn_fused(rq_ctx* ctx, const rq_attn_fused_desc* d) {
   p.zo = d->z_o - d->off_o; p.lo = -d->off_o; p.hi = (1 << d->bits_o) - 1 - d->off_o;
   p.G = d->batch * d->H;
   p.zero_max = (d->flags & RQ_LOG_ZERO_AT_MAX_CODE) != 0;
+  if (rq_attn_stream_supported(d->N, d->d_head, d->bits_p, d->bias != nullptr)) return rq_launch_attn_stream(ctx, p, d->d_head);
   const int ks = d->d_head / 32;
   if (ks == 1) return rq_launch_qk_softmax_d32(ctx, p, p.G);
   if (ks == 2) return rq_launch_qk_softmax_d64(ctx, p, p.G);

@@ -259,7 +259,8 @@ def test_fused_qk_softmax_codes(rq, batch, H, seq, dh, bits, bits_p, bias, causa
 @pytest.mark.parametrize("batch,H,seq,dh,bits,bits_p", [(2, 3, 197, 64, 4, 4), (3, 2, 49, 32, 6, 4), (1, 2, 224, 64, 4, 4),
                                                         (2, 2, 64, 128, 8, 4), (1, 1, 1, 32, 8, 3), (2, 1, 288, 32, 4, 4),
                                                         (5, 2, 100, 64, 8, 2), (2, 2, 257, 64, 4, 4), (1, 3, 256, 64, 8, 4),
-                                                        (2, 1, 288, 64, 4, 4), (1, 2, 160, 128, 4, 4), (1, 2, 288, 128, 8, 4)])
+                                                        (2, 1, 288, 64, 4, 4), (1, 2, 160, 128, 4, 4), (1, 2, 288, 128, 8, 4),
+                                                        (3, 3, 270, 64, 8, 4), (2, 3, 259, 32, 8, 3), (5, 1, 257, 64, 8, 2)])
 def test_attn_fused_whole(rq, batch, H, seq, dh, bits, bits_p):
     """rq_attn_fused (one kernel) against the oracle's logits -> log-sqrt2 codes -> shift de-quantized P.V -> uniform codes."""
     _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, False)
@@ -345,3 +346,56 @@ def _attn_fused_case(rq, batch, H, seq, dh, bits, bits_p, bias, zero_max=False):
                     out_q=outq2, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits, bias=None if bias_a is None else dev(bias_a),
                     flags=flags)
     assert torch.equal(outq, outq2)
+
+
+def test_attn_fused_many_passes(rq):
+    """257 keys, more groups than one pass of every workgroup takes (the persistent workgroups of the streamed kernel refill
+    their LDS slots while they compute, and the last pass is partial): sampled batch items against the oracle, and every item
+    bit-equal to a call on that item alone."""
+    b, ctx = rq
+    batch, H, seq, dh, bits, bits_p = 515, 2, 257, 32, 8, 4
+    assert b.attn_fused_supported(seq, dh, bits_p, False)
+    g = np.random.default_rng(77)
+    D = H * dh
+    qmax = 2 ** bits - 1
+    s_qk = 8.0 / qmax
+    z = [int(g.integers(qmax // 3, 2 * qmax // 3 + 1)) for _ in range(3)]
+    codes = np.empty((batch * seq, 3 * D), np.int64)
+    for i in range(3):
+        codes[:, i * D:(i + 1) * D] = np.clip(np.rint(g.normal(size=(batch * seq, D)) / s_qk) + z[i], 0, qmax)
+    off = [b.store_offset(bits, zz) for zz in z]
+    st = codes.copy()
+    for i in range(3):
+        st[:, i * D:(i + 1) * D] -= off[i]
+    qkv = dev(st.astype(np.int8))
+    scale = s_qk * s_qk / math.sqrt(dh)
+    s_log, s_v = np.float32(0.8), np.float32(s_qk)
+    s_o, z_o = np.float32(0.004), 120
+    off_o = b.store_offset(bits, z_o)
+    outq = torch.zeros((batch * seq, D), dtype=torch.int8, device="cuda")
+    outf = torch.zeros((batch * seq, D), dtype=torch.float32, device="cuda")
+    print("case many passes", batch, H, seq, dh, flush=True)
+    b.rq_attn_fused(ctx, qkv, batch, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log), float(s_v), bits_p,
+                    out_f32=outf, out_q=outq, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+    torch.cuda.synchronize()
+    gotf = outf.cpu().numpy()
+    for bi in (0, 1, 255, 256, 511, 512, 513, 514):
+        r = slice(bi * seq, (bi + 1) * seq)
+        one_q = torch.zeros((seq, D), dtype=torch.int8, device="cuda")
+        b.rq_attn_fused(ctx, qkv[bi * seq:(bi + 1) * seq], 1, seq, H, dh, off[0], z[0], off[1], z[1], off[2], z[2], scale, float(s_log),
+                        float(s_v), bits_p, out_q=one_q, s_o=float(s_o), z_o=z_o, off_o=off_o, bits_o=bits)
+        assert torch.equal(one_q, outq[r]), "batch item %d differs from its own call" % bi
+        want = np.empty((seq, D))
+        flips = 0
+        for h in range(H):
+            c = slice(h * dh, (h + 1) * dh)
+            acc = orc.int_matmul_nt(codes[r, c] - z[0], codes[r, D + h * dh:D + (h + 1) * dh] - z[1])
+            pc = orc.softmax_log_quant(acc.astype(np.float64) * scale, s_log, bits_p)
+            want[:, c] = orc.attn_pv(pc, codes[r, 2 * D + h * dh:2 * D + (h + 1) * dh], s_log, s_v, z[2], False, bits_p)
+        # a code next to a rounding tie may differ (float32 against float64 sum); rows without one meet the float bar
+        e = np.abs(gotf[r] - want).max(axis=1)
+        ref = np.abs(want).max()
+        assert np.mean(e > 1e-4 * ref) < 0.02, "batch item %d: %g of the rows off" % (bi, np.mean(e > 1e-4 * ref))
+        assert e.max() < 0.05 * ref
+    # every item, not only the sampled ones, was written
+    assert int((outq.view(batch, seq * D) == 0).all(dim=1).sum()) == 0
