@@ -33,7 +33,7 @@ constexpr int NTHR = W * 64;
 
 constexpr int slot_bytes(int ksteps, int nt) { return nt * 32 * ksteps * 32 + ksteps * 32 * (nt * 32 + 16); }
 
-template <int KSTEPS, int NT, int GPB, bool DQ>
+template <int KSTEPS, int NT, int GPB, bool DQ, bool ZM>
 __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
   constexpr int DH = KSTEPS * 32;
   constexpr int TC = DH / 32;
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
         for (int c = 0; c < TC; ++c)
 #pragma unroll
           for (int e = 0; e < 16; ++e) { E[c][e] = 0; O[c][e] = 0; }
-        int se = 0, so = 0;
+        int sa = 0, so = 0;
         auto code_tile = [&](int jt, auto last) {
           const v16i d16 = qk_tile(jt, cneg);
           unsigned pk[4];
@@ -300,7 +300,9 @@ __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
           const int j0 = jt * 32 + half * 16;
           const v4i tv = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
           if (crow && qi < p.N && j0 < p.ld) *reinterpret_cast<v4i*>(crow + j0) = tv;
-          v4i pe, po;
+          // A accumulates -(128 >> (code / 2)) v of ALL keys, O that of the keys with odd codes only (the even-code sum is
+          // their difference, taken in the epilogue): one byte mask per four codes instead of two
+          v4i pa, po;
 #pragma unroll
           for (int d4 = 0; d4 < 4; ++d4) {
             const unsigned c = (unsigned)tv[d4];
@@ -310,23 +312,23 @@ __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
               nv = nv < 0 ? 0 : (nv > 4 ? 4 : nv);
               pall &= nv == 4 ? 0xFFFFFFFFu : ((1u << (8 * nv)) - 1u);
             }
-            if (p.zero_max) pall &= ~rq_byte_eq_mask(c, qmax4);      // uniform branch
-            const unsigned lsb = c & 0x01010101u;
-            const unsigned odd = (lsb << 8) - lsb;        // 0xFF in the bytes that hold odd codes
+            if (ZM) pall &= ~rq_byte_eq_mask(c, qmax4);
+            // byte selectors 0x0C / 0x0D of a byte permute read as the constants 0x00 / 0xFF: 0xFF in the bytes that hold odd codes
+            const unsigned odd = __builtin_amdgcn_perm(0u, 0u, (c & 0x01010101u) | 0x0C0C0C0Cu);
+            pa[d4] = (int)pall;
             po[d4] = (int)(pall & odd);
-            pe[d4] = (int)(pall & ~odd);
           }
           if (p.dv != 0) {
 #pragma unroll
             for (int d4 = 0; d4 < 4; ++d4) {
-              se = __builtin_amdgcn_sdot4(pe[d4], 0x01010101, se, false);
+              sa = __builtin_amdgcn_sdot4(pa[d4], 0x01010101, sa, false);
               so = __builtin_amdgcn_sdot4(po[d4], 0x01010101, so, false);
             }
           }
 #pragma unroll
           for (int c = 0; c < TC; ++c) {
             const v4i fv = *reinterpret_cast<const v4i*>(vt + (c * 32 + l32) * VTP + j0);
-            E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pe, E[c], 0, 0, 0);
+            E[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, pa, E[c], 0, 0, 0);
             O[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fv, po, O[c], 0, 0, 0);
           }
         };
@@ -340,7 +342,10 @@ __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
         if (r + 1 < R) request_q(gq, (r + 1) * W + wave);
         else if (gq + stride < Gi) request_q(gq + stride, wave);
         // ---- output: lane holds channels c*32 + 8*(e/4) + 4*half + e%4 of row qi ----
-        double psE = (double)se, psO = (double)so;
+        // from here on E holds the even-code sums
+#pragma unroll
+        for (int c = 0; c < TC; ++c) E[c] -= O[c];
+        double psE = (double)(sa - so), psO = (double)so;
         if (p.dv != 0) {   // the two halves of the wavefront saw different keys of the same row
           psE += __shfl_xor(psE, 32, 64);
           psO += __shfl_xor(psO, 32, 64);
@@ -394,7 +399,7 @@ __global__ __launch_bounds__(NTHR) void attn_stream_kernel(const QksParams p) {
   }
 }
 
-template <int KSTEPS, int NT, int GPB, bool DQ>
+template <int KSTEPS, int NT, int GPB, bool DQ, bool ZM>
 rq_status launch(rq_ctx* ctx, const QksParams& p) {
   if (p.G > (int64_t)1 << 30) return rq_fail(ctx, RQ_ERR_SHAPE, "fused attention: %lld groups exceed 2^30", (long long)p.G);
   if (p.ldk <= 0 || p.ldk * (int64_t)(NT * 32) >= (int64_t)1 << 31)
@@ -405,8 +410,8 @@ rq_status launch(rq_ctx* ctx, const QksParams& p) {
   const int64_t passes = (p.G + GPB - 1) / GPB;
   const dim3 grid((unsigned)(passes < cap ? passes : cap));
   static rq_once_per_device lds_attr;
-  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&attn_stream_kernel<KSTEPS, NT, GPB, DQ>), lds));
-  hipLaunchKernelGGL((attn_stream_kernel<KSTEPS, NT, GPB, DQ>), grid, dim3(NTHR), lds, ctx->stream, p);
+  RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&attn_stream_kernel<KSTEPS, NT, GPB, DQ, ZM>), lds));
+  hipLaunchKernelGGL((attn_stream_kernel<KSTEPS, NT, GPB, DQ, ZM>), grid, dim3(NTHR), lds, ctx->stream, p);
   RQ_HIP(hipGetLastError());
   return RQ_OK;
 }
@@ -420,7 +425,16 @@ bool rq_attn_stream_supported(int N, int d_head, int bits_p, bool has_bias) {
 }
 
 rq_status rq_launch_attn_stream(rq_ctx* ctx, const rqks::QksParams& p, int d_head) {
-  if (p.tiles == 9 && d_head == 64) return p.dq ? launch<2, 9, 4, true>(ctx, p) : launch<2, 9, 4, false>(ctx, p);
-  if (p.tiles == 9 && d_head == 32) return p.dq ? launch<1, 9, 4, true>(ctx, p) : launch<1, 9, 4, false>(ctx, p);
+  // variants: with the dq colsum(k') term (DQ), with RQ_LOG_ZERO_AT_MAX_CODE (ZM)
+#define RQ_STREAM_PICK(KS)                                                                       \
+  do {                                                                                           \
+    if (p.dq && p.zero_max) return launch<KS, 9, 4, true, true>(ctx, p);                         \
+    if (p.dq) return launch<KS, 9, 4, true, false>(ctx, p);                                      \
+    if (p.zero_max) return launch<KS, 9, 4, false, true>(ctx, p);                                \
+    return launch<KS, 9, 4, false, false>(ctx, p);                                               \
+  } while (0)
+  if (p.tiles == 9 && d_head == 64) RQ_STREAM_PICK(2);
+  if (p.tiles == 9 && d_head == 32) RQ_STREAM_PICK(1);
+#undef RQ_STREAM_PICK
   return rq_fail(ctx, RQ_ERR_SHAPE, "streamed attention: %d key tiles at d_head = %d not supported", p.tiles, d_head);
 }
