@@ -528,6 +528,49 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
 size_t rq_block_noalloc_scratch_bytes(void);
 rq_status rq_block_forward_noalloc(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y, int64_t batch, int64_t seq);
 
+/* ---- block parameters as one flat blob ------------------------------------------------------------------------------
+ * The folded and quantized parameters of a block (the result of rq_block_calibrate, or of the caller's own
+ * preparation: the output of the reparameterization of Section "Scale reparameterization" and of the weight
+ * quantizers) are checkpointed as ONE little-endian byte string, so that the preparation need not run again:
+ *    rq_blob_header | arrays, each at the 256-byte aligned offset the header records
+ * Array i of RQ_BLOB_ARRAYS: 0..3 = ln1_gamma_t, ln1_beta_t, ln2_gamma_t, ln2_beta_t (float32 [D]); then for each of
+ * qkv, proj, fc1, fc2 (k = 0..3): 4+5k = w (int8 [N, K] or packed 4-bit [N, K/2]), 5+5k = s_w (float32 [N]),
+ * 6+5k = z_w (int32 [N]), 7+5k = colsum_w (int32 [N]), 8+5k = bias (float32 [N]); 24 = rel_bias (float32, rel_bias_elems).
+ * An absent (NULL) array has offset 0 and length 0.  Pointers inside rq_block_params never enter the blob.
+ *
+ * rq_block_blob_bytes: size of the blob of these parameters (host arithmetic only); 0 if p is NULL or inconsistent.
+ * rq_block_blob_save:  copies the device arrays into blob_host (host memory of at least that size; pageable is fine) on
+ *                      the context's stream and synchronizes it.  RQ_ERR_WORKSPACE if blob_bytes is too small.
+ * rq_block_blob_check: validates a blob in host memory (magic, version, sizes, every offset and length against the shapes
+ *                      in the header and against blob_bytes) without touching a device; *arena_bytes receives the device
+ *                      memory rq_block_blob_load needs.  RQ_ERR_INVALID_ARG / RQ_ERR_SHAPE with text in rq_last_error(NULL).
+ * rq_block_blob_load:  validates likewise, copies the blob to `arena_device` (caller-owned device memory, 256-byte
+ *                      aligned, at least *arena_bytes; it must outlive every use of `out`), synchronizes, and fills `out`
+ *                      with the scalars of the header and pointers into the arena.
+ */
+enum { RQ_BLOB_ARRAYS = 25, RQ_BLOB_VERSION = 1 };
+typedef struct {
+  char magic[8];                 /* "RQBLOCK\0" */
+  uint32_t header_bytes;         /* sizeof(rq_blob_header) */
+  uint32_t version;              /* RQ_BLOB_VERSION */
+  uint64_t total_bytes;          /* header + arrays + padding */
+  int32_t D, H, Dm, norm_kind, act, mask, bits_a, bits_p;
+  double eps;
+  float ln1_s, ln2_s, s_q, s_k, s_v, s_log, s_o, s_h;
+  int32_t ln1_z, ln2_z, z_q, z_k, z_v, z_o, z_h;
+  int32_t attn_path, proj_ln_fused, flags;
+  int64_t attn_chunk_bytes;
+  int32_t lin[4][4];             /* N, K, bits, format of qkv, proj, fc1, fc2 */
+  int64_t rel_bias_elems;
+  uint64_t off[RQ_BLOB_ARRAYS];  /* from the start of the blob */
+  uint64_t len[RQ_BLOB_ARRAYS];  /* bytes */
+} rq_blob_header;
+size_t rq_block_blob_bytes(const rq_block_params* p, int64_t rel_bias_elems);
+rq_status rq_block_blob_save(rq_ctx* ctx, const rq_block_params* p, int64_t rel_bias_elems, void* blob_host, size_t blob_bytes);
+rq_status rq_block_blob_check(const void* blob_host, size_t blob_bytes, size_t* arena_bytes);
+rq_status rq_block_blob_load(rq_ctx* ctx, const void* blob_host, size_t blob_bytes, void* arena_device, size_t arena_bytes,
+                             rq_block_params* out);
+
 /* Per-kernel timing of rq_block_forward: when enabled, every kernel launch inside rq_block_forward is
  * bracketed by HIP events on the context's stream.  rq_profile_read synchronizes the stream, writes up to
  * `cap` records (host arrays) accumulated since the last rq_profile_reset and returns their number.

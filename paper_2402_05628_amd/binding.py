@@ -24,6 +24,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 RQ_OK = 0
+RQ_ERR_INVALID_ARG = 1
 LOG_ZERO_AT_MAX_CODE = 1
 ATTN_AUTO, ATTN_QK_SOFTMAX_PV, ATTN_THREE_KERNELS = 0, 1, 2
 NORM_LAYERNORM, NORM_RMSNORM = 0, 1
@@ -138,6 +139,18 @@ class BlockLayout(C.Structure):
         "a", "rowsum", "qkv", "logits", "logits_bytes", "codes", "codes_bytes", "o", "xbar", "hidden", "total")]
 
 
+BLOB_ARRAYS = 25
+
+
+class BlobHeader(C.Structure):
+    _fields_ = ([("magic", C.c_char * 8), ("header_bytes", C.c_uint32), ("version", C.c_uint32), ("total_bytes", C.c_uint64)]
+                + [(k, i32) for k in ("D", "H", "Dm", "norm_kind", "act", "mask", "bits_a", "bits_p")] + [("eps", f64)]
+                + [(k, f32) for k in ("ln1_s", "ln2_s", "s_q", "s_k", "s_v", "s_log", "s_o", "s_h")]
+                + [(k, i32) for k in ("ln1_z", "ln2_z", "z_q", "z_k", "z_v", "z_o", "z_h", "attn_path", "proj_ln_fused", "flags")]
+                + [("attn_chunk_bytes", i64), ("lin", (i32 * 4) * 4), ("rel_bias_elems", i64),
+                   ("off", C.c_uint64 * BLOB_ARRAYS), ("len", C.c_uint64 * BLOB_ARRAYS)])
+
+
 def _sig(name, restype, argtypes):
     fn = getattr(lib, name)
     fn.restype = restype
@@ -224,6 +237,10 @@ _rq_block_ws = _sig("rq_block_workspace_bytes", C.c_size_t, [C.POINTER(BlockPara
 _rq_block_layout = _sig("rq_block_workspace_layout", i32, [C.POINTER(BlockParams), i64, i64, C.POINTER(BlockLayout)])
 _rq_block_forward_noalloc = _sig("rq_block_forward_noalloc", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64])
 _rq_noalloc_bytes = _sig("rq_block_noalloc_scratch_bytes", C.c_size_t, [])
+_rq_blob_bytes = _sig("rq_block_blob_bytes", C.c_size_t, [C.POINTER(BlockParams), i64])
+_rq_blob_save = _sig("rq_block_blob_save", i32, [vp, C.POINTER(BlockParams), i64, vp, C.c_size_t])
+_rq_blob_check = _sig("rq_block_blob_check", i32, [vp, C.c_size_t, C.POINTER(C.c_size_t)])
+_rq_blob_load = _sig("rq_block_blob_load", i32, [vp, vp, C.c_size_t, vp, C.c_size_t, C.POINTER(BlockParams)])
 _rq_block_forward = _sig("rq_block_forward", i32, [vp, C.POINTER(BlockParams), vp, vp, i64, i64, vp, C.c_size_t])
 _rq_qgemm_ln = _sig("rq_qgemm_ln_quant", i32, [vp, C.POINTER(GemmDesc), C.POINTER(LnDesc)])
 _rq_profile_enable = _sig("rq_profile_enable", i32, [vp, i32])
@@ -484,6 +501,10 @@ class Block:
         self._ws = None
         self._ws_key = None
 
+    def rel_bias_elems(self) -> int:
+        rb = self.P.get("rel_bias") if isinstance(self.P, dict) else None
+        return 0 if rb is None else int(rb.numel())
+
     def workspace(self, batch, seq):
         key = (batch, seq, self.bp.attn_path, self.bp.attn_chunk_bytes, self.bp.proj_ln_fused)
         if self._ws_key != key:
@@ -525,6 +546,48 @@ class Block:
 
 def noalloc_scratch_bytes() -> int:
     return int(_rq_noalloc_bytes())
+
+
+def block_blob_bytes(blk: "Block") -> int:
+    return int(_rq_blob_bytes(C.byref(blk.bp), blk.rel_bias_elems()))
+
+
+def save_block(blk: "Block", path: str) -> int:
+    """rq_block_blob_save: the block's folded and quantized parameters as one file; returns its size."""
+    n = block_blob_bytes(blk)
+    if n == 0:
+        raise RqError(RQ_ERR_INVALID_ARG, "block parameters are inconsistent: no blob")
+    buf = (C.c_char * n)()
+    blk.ctx.check(_rq_blob_save(blk.ctx.handle, C.byref(blk.bp), blk.rel_bias_elems(), C.cast(buf, vp), n))
+    with open(path, "wb") as fh:
+        fh.write(bytes(buf))
+    return n
+
+
+def check_block_blob(data: bytes) -> int:
+    """rq_block_blob_check on bytes in host memory: the device arena size, or RqError."""
+    need = C.c_size_t(0)
+    buf = C.create_string_buffer(data, len(data))
+    rc = _rq_blob_check(C.cast(buf, vp), len(data), C.byref(need))
+    if rc != RQ_OK:
+        raise RqError(rc, _rq_last_error(None).decode())
+    return int(need.value)
+
+
+def load_block(ctx: Context, path: str) -> "Block":
+    """rq_block_blob_load: a Block whose arrays live in one device arena; the preparation does not run again."""
+    with open(path, "rb") as fh:
+        data = fh.read()
+    need = check_block_blob(data)
+    arena = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    ptr = arena.data_ptr() + (-arena.data_ptr()) % 256
+    bp = BlockParams()
+    buf = C.create_string_buffer(data, len(data))
+    ctx.check(_rq_blob_load(ctx.handle, C.cast(buf, vp), len(data), ptr, need, C.byref(bp)))
+    blk = Block.__new__(Block)
+    blk.ctx, blk.cfg, blk.P, blk.bp = ctx, None, {"arena": arena}, bp
+    blk._ws, blk._ws_key = None, None
+    return blk
 
 
 def rq_block_forward_noalloc(blk: "Block", x: torch.Tensor, y: torch.Tensor, batch: int, seq: int):

@@ -51,7 +51,7 @@ def test_structures_have_the_c_layout(b, tmp_path):
              ("rq_softmax_desc", b.SoftmaxDesc), ("rq_qk_softmax_desc", b.QkSoftmaxDesc), ("rq_attn_fused_desc", b.AttnFusedDesc),
              ("rq_pv_desc", b.PvDesc), ("rq_dual_clip_desc", b.DualClipDesc), ("rq_gptq_desc", b.GptqDesc),
              ("rq_qlinear", b.QLinear), ("rq_block_params", b.BlockParams), ("rq_block_raw", b.BlockRaw),
-             ("rq_block_layout", b.BlockLayout)]
+             ("rq_block_layout", b.BlockLayout), ("rq_blob_header", b.BlobHeader)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "repquant.h"', "int main(void) {"]
     for cname, cls in pairs:
         last = cls._fields_[-1][0]
@@ -386,3 +386,116 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr or "one GPU" in r.stderr
+
+
+def _fake_block_params(b, rel_bias=False, rms=False):
+    bp = b.BlockParams()
+    bp.D, bp.H, bp.Dm, bp.bits_a, bp.bits_p, bp.eps = 64, 2, 128, 4, 4, 1e-6
+    for k in ("ln1_gamma_t", "ln2_gamma_t"):
+        setattr(bp, k, FAKE)
+    if not rms:
+        bp.ln1_beta_t, bp.ln2_beta_t = FAKE, FAKE
+
+    def lin(N, K, fmt):
+        q = b.QLinear()
+        q.N, q.K, q.bits, q.format = N, K, 4, fmt
+        q.w, q.s_w, q.z_w, q.colsum_w, q.bias = FAKE, FAKE, FAKE, FAKE, FAKE
+        return q
+    bp.qkv, bp.proj, bp.fc1, bp.fc2 = lin(192, 64, b.W_U4), lin(64, 64, b.W_I8_BAKED), lin(128, 64, b.W_U4), lin(64, 128, b.W_I8_CENTERED)
+    if rel_bias:
+        bp.rel_bias = FAKE
+    return bp
+
+
+def _up(n):
+    return (n + 255) // 256 * 256
+
+
+def test_block_blob_size_is_the_header_plus_the_aligned_arrays(b):
+    bp = _fake_block_params(b)
+    want = _up(C.sizeof(b.BlobHeader)) + 4 * _up(64 * 4)
+    for N, K, packed in ((192, 64, True), (64, 64, False), (128, 64, True), (64, 128, False)):
+        want += _up(N * K // 2 if packed else N * K) + 4 * _up(N * 4)
+    assert b._rq_blob_bytes(C.byref(bp), 0) == want
+    # a relative-position bias adds its elements; it needs a positive count
+    bpr = _fake_block_params(b, rel_bias=True)
+    assert b._rq_blob_bytes(C.byref(bpr), 2 * 49 * 49) == want + _up(2 * 49 * 49 * 4)
+    assert b._rq_blob_bytes(C.byref(bpr), 0) == 0
+    # RMSNorm blocks have no beta~: two arrays fewer
+    assert b._rq_blob_bytes(C.byref(_fake_block_params(b, rms=True)), 0) == want - 2 * _up(64 * 4)
+    # a required array missing, or no parameters at all: no blob
+    bad = _fake_block_params(b)
+    bad.qkv.s_w = None
+    assert b._rq_blob_bytes(C.byref(bad), 0) == 0
+    assert b._rq_blob_bytes(None, 0) == 0
+    odd = _fake_block_params(b)
+    odd.qkv.K = 63
+    assert b._rq_blob_bytes(C.byref(odd), 0) == 0      # packed 4-bit rows need an even K
+
+
+def _blob_image(b, **edits):
+    """A well-formed blob (zero arrays) of the fake block, built here field by field, then edited."""
+    h = b.BlobHeader()
+    h.magic, h.header_bytes, h.version = b"RQBLOCK", C.sizeof(b.BlobHeader), 1
+    h.D, h.H, h.Dm, h.bits_a, h.bits_p, h.eps = 64, 2, 128, 4, 4, 1e-6
+    shapes = ((192, 64, b.W_U4), (64, 64, b.W_I8_BAKED), (128, 64, b.W_U4), (64, 128, b.W_I8_CENTERED))
+    o = _up(C.sizeof(b.BlobHeader))
+    lens = [64 * 4] * 4
+    for k, (N, K, fmt) in enumerate(shapes):
+        h.lin[k][0], h.lin[k][1], h.lin[k][2], h.lin[k][3] = N, K, 4, fmt
+        lens += [N * K // 2 if fmt == b.W_U4 else N * K] + [N * 4] * 4
+    lens.append(0)
+    for i, n in enumerate(lens):
+        h.off[i], h.len[i] = (o, n) if n else (0, 0)
+        o += _up(n)
+    h.total_bytes = o
+    for k, v in edits.items():
+        if k.startswith("off") or k.startswith("len"):
+            getattr(h, k[:3])[int(k[3:])] = v
+        elif k.startswith("lin"):
+            h.lin[int(k[3])][int(k[4])] = v
+        else:
+            setattr(h, k, v)
+    return bytes(h) + bytes(o - C.sizeof(b.BlobHeader))
+
+
+def test_block_blob_check_accepts_a_well_formed_blob_and_names_what_is_wrong_with_others(b):
+    good = _blob_image(b)
+    assert b.check_block_blob(good) == len(good)
+    assert b.check_block_blob(good + b"tail") == len(good)          # a longer buffer is fine
+    cases = [(dict(magic=b"RQBLOCX"), 1, "magic"), (dict(version=2), 3, "version"), (dict(header_bytes=600), 2, "header"),
+             (dict(D=0), 2, "out of range"), (dict(lin00=-5), 2, "out of range"), (dict(lin03=9), 2, "format"),
+             (dict(lin01=63), 2, "even K"), (dict(len5=100), 2, "array 5"), (dict(off6=8), 2, "array 6"),
+             (dict(off7=1 << 40), 2, "array 7"), (dict(off4=0, len4=0), 2, "required array 4"),
+             (dict(rel_bias_elems=-1), 2, "rel_bias_elems")]
+    for edits, status, word in cases:
+        with pytest.raises(b.RqError) as e:
+            b.check_block_blob(_blob_image(b, **edits))
+        assert e.value.status == status and word in str(e.value), (edits, str(e.value))
+    # two arrays swapped in place: in range and aligned, but out of order (they would be allowed to overlap otherwise)
+    h = b.BlobHeader.from_buffer_copy(good)
+    with pytest.raises(b.RqError):
+        b.check_block_blob(_blob_image(b, off5=h.off[6], off6=h.off[5]))
+    with pytest.raises(b.RqError) as e:
+        b.check_block_blob(good[:len(good) - 1])
+    assert "truncated" in str(e.value)
+    with pytest.raises(b.RqError):
+        b.check_block_blob(good[:100])
+
+
+def test_block_blob_save_and_load_validate_before_any_copy(b, host_ctx):
+    bp = _fake_block_params(b)
+    n = b._rq_blob_bytes(C.byref(bp), 0)
+    buf = (C.c_char * n)()
+    assert b._rq_blob_save(host_ctx.handle, C.byref(bp), 0, C.cast(buf, C.c_void_p), n - 1) == 4       # blob too small
+    assert b._rq_blob_save(host_ctx.handle, C.byref(bp), 0, None, n) == 1
+    assert b._rq_blob_save(None, C.byref(bp), 0, C.cast(buf, C.c_void_p), n) == 1
+    assert b._rq_blob_save(host_ctx.handle, C.byref(bp), 0, C.cast(buf, C.c_void_p), n) == 3           # valid: host-only context
+    good = _blob_image(b)
+    img = C.create_string_buffer(good, len(good))
+    out = b.BlockParams()
+    assert b._rq_blob_load(host_ctx.handle, C.cast(img, C.c_void_p), len(good), FAKE, len(good), C.byref(out)) == 3
+    assert b._rq_blob_load(host_ctx.handle, C.cast(img, C.c_void_p), len(good), FAKE + 4, len(good), C.byref(out)) == 1   # misaligned arena
+    assert b._rq_blob_load(host_ctx.handle, C.cast(img, C.c_void_p), len(good), FAKE, len(good) - 1, C.byref(out)) == 4   # arena too small
+    assert b._rq_blob_load(host_ctx.handle, C.cast(img, C.c_void_p), len(good), FAKE, len(good), None) == 1
+    assert b._rq_blob_load(host_ctx.handle, C.cast(img, C.c_void_p), 50, FAKE, len(good), C.byref(out)) == 2
