@@ -29,7 +29,7 @@
  *  Weight formats (per-output-channel scale s_w[n] and zero-point z_w[n]):
  *    RQ_W_I8_BAKED     int8 [N, K], stored = code - z_w[n]          (b <= 7)
  *    RQ_W_I8_CENTERED  int8 [N, K], stored = code - 128             (b == 8); needs rowsum_a
- *    RQ_W_U4           uint8 [N, K/2], two raw 4-bit codes per byte, in the interleaved order
+ *    RQ_W_U4           uint8 [N, K/2], two raw 4-bit codes per byte (z_b[n] in 0..15), in the interleaved order
  *                      produced by rq_weight_quant_pack (see there); z_w[n] is subtracted while the
  *                      nibbles are unpacked in LDS.
  *  colsum_w[n] = sum_k (code[n, k] - z_w[n]) accompanies every format.
@@ -112,7 +112,11 @@ rq_status rq_reparam_fold(rq_ctx* ctx, const rq_fold_desc* d);
  * Channel-wise (per output channel) min/max uniform quantization of a float weight matrix
  * (Section "Efficient quantizers", Eq. for s and z; granularity paragraph):
  *    s_w[n] = float32((max_n - min_n) / (2^b - 1)),  z_w[n] = round(-min_n / s_w[n]),
- *    code = clip(round(W / s_w[n]) + z_w[n], 0, 2^b - 1).
+ *    code = clip(round(W / s_w[n]) + z_w[n], 0, 2^b - 1),
+ * where min_n = min(row n, 0) and max_n = max(row n, 0): the zero-point is itself a code in [0, 2^b - 1], which the
+ * formula gives exactly when the range contains 0, so a row whose weights all share one sign has its range extended
+ * to 0 (z_w = 0 or 2^b - 1); a row of zeros gets s_w = 1.  (rq_qgemm subtracts z_w from packed 4-bit codes byte-wise:
+ * z_w[n] outside 0..15 is not a valid RQ_W_U4 operand.)
  * bits = 8 -> RQ_W_I8_CENTERED, bits in 2..7 with format RQ_W_I8_BAKED, bits = 4 with RQ_W_U4.
  * RQ_W_U4 layout: row n holds K/2 bytes; within each aligned group of 8 codes k0..k7 the four bytes
  * are (k0 | k4<<4), (k1 | k5<<4), (k2 | k6<<4), (k3 | k7<<4), so that `dword & 0x0F0F0F0F` yields

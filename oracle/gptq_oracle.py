@@ -56,9 +56,11 @@ def damped_hessian(H, W, percdamp=0.01):
 
 
 def row_grid(W, bits):
-    """Per-output-channel min/max grid (Eq. for s and z per row of W); the scale is a float32 number."""
-    lo, hi = W.min(axis=1), W.max(axis=1)
+    """Per-output-channel min/max grid (Eq. for s and z per row of W); the scale is a float32 number.  As in the
+    round-to-nearest weight quantizer the row's range is taken to contain 0, so that z is a code in [0, 2^b - 1]."""
+    lo, hi = np.minimum(W.min(axis=1), 0.0), np.maximum(W.max(axis=1), 0.0)
     s = ((hi - lo) / (2 ** bits - 1)).astype(np.float32).astype(F64)
+    s = np.where(s > 0, s, 1.0)
     z = np.rint(-lo / s)
     return s, z
 

@@ -242,16 +242,21 @@ def ln_quant(X, gamma_t, beta_t, s_t, z_t, bits, eps, kind=NORM_LAYERNORM):
 # (Section "Efficient quantizers", granularity paragraph; "Implementation details")
 # --------------------------------------------------------------------------
 def weight_quant(W, bits):
-    """Per-output-channel min/max uniform quantization of W [D_out, K].
+    """Per-output-channel min/max uniform quantization of W [D_out, K] (Eq. for s and z, per row of W).
 
+    The zero-point of a weight row is itself a code: an integer in [0, 2^b - 1].  The formula z = round(-min / s) gives
+    that exactly when the row's range contains 0; a row whose weights all share one sign has its range extended to 0
+    (min(row, 0) .. max(row, 0)), so that z = 0 or 2^b - 1 and every weight stays inside the grid.  A row of zeros gets
+    s = 1 (any positive scale represents it exactly).
     The scale is rounded to float32 (it is stored as float32) before the codes
     are taken, so codes and stored scale are consistent.
     Returns codes [D_out, K] (int64 in [0, 2^b-1]), s_w float32 [D_out], z_w int64 [D_out].
     """
     W = np.asarray(W, dtype=F64)
-    lo = W.min(axis=1)
-    hi = W.max(axis=1)
+    lo = np.minimum(W.min(axis=1), 0.0)
+    hi = np.maximum(W.max(axis=1), 0.0)
     s = ((hi - lo) / (2 ** bits - 1)).astype(np.float32)
+    s = np.where(s > 0, s, np.float32(1.0)).astype(np.float32)
     s64 = s.astype(F64)
     z = np.rint(-lo / s64).astype(np.int64)
     codes = uniform_quant(W, s64[:, None], z[:, None], bits)

@@ -210,13 +210,14 @@ __global__ __launch_bounds__(256) void init_inverse_kernel(double* __restrict__ 
   X[idx] = (i / NB == j / NB) ? Dinv[(int64_t)(i / NB) * NB * NB + (i % NB) * NB + (j % NB)] : 0.0;
 }
 
-// ---- per output channel: grid from the row's extremes (dead columns count as 0), float64 working copy ----------------
+// ---- per output channel: grid from the row's extremes (dead columns count as 0; the range always contains 0, so the
+// zero-point is a code of the grid), float64 working copy ----------------
 __global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__ W, int K, int bits, const int32_t* __restrict__ dead,
                                                        double* __restrict__ Wc, double* __restrict__ s64, double* __restrict__ z64) {
   __shared__ float smin[256], smax[256];
   const int tid = threadIdx.x, n = blockIdx.x;
   const float* w = W + (int64_t)n * K;
-  float lo = FLT_MAX, hi = -FLT_MAX;
+  float lo = 0.f, hi = 0.f;
   for (int k = tid; k < K; k += 256) {
     const float v = dead[k] ? 0.f : w[k];
     Wc[(int64_t)n * K + k] = (double)v;
@@ -235,7 +236,8 @@ __global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__
   }
   if (tid == 0) {
     const double dlo = (double)smin[0], dhi = (double)smax[0];
-    const double s = (double)(float)((dhi - dlo) / (double)((1 << bits) - 1));      // the scale is stored as float32
+    double s = (double)(float)((dhi - dlo) / (double)((1 << bits) - 1));      // the scale is stored as float32
+    if (!(s > 0.0)) s = 1.0;                                                     // a row of zeros
     s64[n] = s;
     z64[n] = rint(-dlo / s);
   }

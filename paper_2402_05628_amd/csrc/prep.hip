@@ -65,14 +65,16 @@ __global__ __launch_bounds__(256) void fold_kernel(rq_fold_desc d) {
   }
 }
 
-// Channel-wise weight quantization, one workgroup per output channel (Eq. for s and z, per row of W).
+// Channel-wise weight quantization, one workgroup per output channel (Eq. for s and z, per row of W).  The row's range is
+// taken to contain 0 (a row whose weights share one sign is extended to 0), so that the zero-point is a code in
+// [0, 2^b - 1]: the packed 4-bit GEMM operands subtract it byte-wise without widening.  A row of zeros gets s = 1.
 __global__ __launch_bounds__(256) void weight_quant_kernel(rq_wq_desc d) {
   __shared__ float smin[256], smax[256];
   __shared__ int ssum[256];
   const int tid = threadIdx.x;
   const int n = blockIdx.x;
   const float* w = d.W + (int64_t)n * d.K;
-  float lo = FLT_MAX, hi = -FLT_MAX;
+  float lo = 0.f, hi = 0.f;
   for (int k = tid; k < d.K; k += 256) {
     const float v = w[k];
     lo = fminf(lo, v);
@@ -90,7 +92,8 @@ __global__ __launch_bounds__(256) void weight_quant_kernel(rq_wq_desc d) {
   }
   const double dlo = (double)smin[0], dhi = (double)smax[0];
   const int qmax = (1 << d.bits) - 1;
-  const float s_f = (float)((dhi - dlo) / (double)qmax);
+  float s_f = (float)((dhi - dlo) / (double)qmax);
+  if (!(s_f > 0.f)) s_f = 1.f;
   const double s = (double)s_f;
   const int z = (int)rint(-dlo / s);
   int r = n;   // output row

@@ -69,6 +69,39 @@ def test_weight_quant_pack(rq, N, K, bits):
         assert np.array_equal(w.astype(np.int64) + z_w[:, None], codes)
 
 
+@pytest.mark.parametrize("bits", [4, 6, 8])
+def test_weight_quant_pack_rows_of_one_sign(rq, bits):
+    """All-positive, all-negative and all-zero rows: the zero-point stays a code (0, 2^b - 1, 0), and a 4-bit GEMM over
+    such rows gives the exact accumulators (the packed operands subtract the zero-point byte-wise)."""
+    b, ctx = rq
+    g = np.random.default_rng(bits)
+    N, K, M = 64, 128, 96
+    W = g.normal(0, 0.02, size=(N, K)).astype(np.float32)
+    W[0::4] = np.abs(W[0::4]) + np.float32(0.01)
+    W[1::4] = -np.abs(W[1::4]) - np.float32(0.01)
+    W[2] = 0
+    codes, s_w, z_w = orc.weight_quant(W, bits)
+    qmax = 2 ** bits - 1
+    assert np.all(z_w[0::4] == 0) and np.all(z_w[1::4] == qmax) and z_w[2] == 0 and s_w[2] == 1.0
+    out = b.rq_weight_quant_pack(ctx, dev(W), None, bits)
+    assert np.array_equal(out["s_w"].cpu().numpy(), s_w)
+    assert np.array_equal(out["z_w"].cpu().numpy(), z_w)
+    assert np.array_equal(out["colsum_w"].cpu().numpy(), (codes - z_w[:, None]).sum(1))
+    if bits == 4:
+        assert np.array_equal(out["w"].cpu().numpy(), pack_u4(codes))
+    # the GEMM on these weights: true accumulators
+    bits_a = 4 if bits == 4 else 8
+    qa = 2 ** bits_a - 1
+    z_a = qa // 2
+    A = g.integers(0, qa + 1, size=(M, K))
+    off = b.store_offset(bits_a, z_a)
+    acc = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+    stored = (A - off).astype(np.int8)
+    rowsum = dev(stored.astype(np.int64).sum(axis=1).astype(np.int32)) if out["format"] == b.W_I8_CENTERED else None
+    b.rq_qgemm(ctx, dev(stored), off, z_a, 0.1, out, out_acc=acc, rowsum_a=rowsum)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), orc.int_matmul_nt(A - z_a, codes - z_w[:, None]))
+
+
 def test_weight_quant_pack_gate_up_interleave(rq):
     b, ctx = rq
     Dm, K = 64, 128

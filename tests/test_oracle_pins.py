@@ -270,6 +270,42 @@ def test_weight_quant_properties():
         assert np.allclose(s, rng / (2 ** bits - 1), rtol=1e-6)
 
 
+def test_weight_quant_zero_point_is_a_code_for_rows_of_one_sign():
+    """Rows whose weights share a sign have their range extended to 0: z is 0 (all positive) or 2^b - 1 (all negative),
+    the scale is max|w| / (2^b - 1), no weight leaves the grid (error at most s / 2), and a row whose range already contains
+    0 is quantized exactly as by the plain formula s = (max - min) / (2^b - 1), z = round(-min / s)."""
+    g = np.random.default_rng(66)
+    K = 48
+    pos = np.abs(g.normal(0.05, 0.01, size=K)).astype(np.float32) + np.float32(0.02)
+    neg = -pos[::-1].copy()
+    mixed = g.normal(0, 0.02, size=K).astype(np.float32)
+    zero = np.zeros(K, np.float32)
+    W = np.stack([pos, neg, mixed, zero])
+    for bits in (3, 4, 8):
+        qmax = 2 ** bits - 1
+        codes, s, z = orc.weight_quant(W, bits)
+        assert list(z[[0, 1, 3]]) == [0, qmax, 0]
+        assert s[0] == np.float32(float(pos.max()) / qmax) and s[1] == np.float32(float(pos.max()) / qmax) and s[3] == 1.0
+        assert 0 <= z.min() and z.max() <= qmax
+        Wh = orc.uniform_dequant(codes, s.astype(np.float64)[:, None], z[:, None])
+        assert np.all(np.abs(Wh - W) <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
+        assert codes[0].max() == qmax and codes[1].min() == 0 and np.all(codes[3] == 0)
+        # the mixed row: the plain formula, typed out
+        lo, hi = float(mixed.min()), float(mixed.max())
+        s_m = np.float32((hi - lo) / qmax)
+        z_m = int(np.rint(-lo / float(s_m)))
+        assert s[2] == s_m and z[2] == z_m
+        assert np.array_equal(codes[2], np.clip(np.rint(mixed.astype(np.float64) / float(s_m)) + z_m, 0, qmax).astype(np.int64))
+
+
+def test_gptq_grid_contains_zero():
+    from oracle import gptq_oracle as gq
+    W = np.array([[0.5, 1.0, 2.0, 1.5], [-3.0, -1.0, -2.0, -0.5], [-1.0, 2.0, 0.5, 0.0], [0.0, 0.0, 0.0, 0.0]])
+    s, z = gq.row_grid(W, 4)
+    assert np.array_equal(z, [0, 15, 5, 0])
+    assert np.allclose(s[:3], np.array([2.0, 3.0, 3.0]) / 15, rtol=1e-7) and s[3] == 1.0
+
+
 # ---------------------------------------------------------------- softmax and P.V
 def test_softmax_matches_torch_and_masks():
     g = np.random.default_rng(7)
