@@ -102,6 +102,29 @@ def standalone_row_kernels(rq, ctx, cfg, torch):
 DUAL_CLIP_FLOPS_PER_ELEMENT_PASS = 17      # mul, round, 7 add/sub, 2 compare, min, max, mul, 2 fma (4)
 
 
+def copy_reference(torch):
+    """What a kernel with nothing but memory traffic reaches on this machine: plain device-to-device copies (torch's copy_),
+    1 GiB (served from HBM) and 128 MiB (partly from the 256 MB last-level cache).  Context for the HBM-bound kernels'
+    fractions of the published peak; not a kernel of this library."""
+    out = {}
+    for name, n, reps in (("copy_1GiB", 1 << 30, 10), ("copy_128MiB", 128 << 20, 30)):
+        a = torch.empty(n // 4, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = dict(ms=ms, achieved=2 * n / (ms * 1e-3) / 1e9, unit="GB/s", frac_of_peak=2 * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS)
+        del a, b
+    return out
+
+
 def bench_dual_clip(args, cfg, rq, synth, np, torch):
     """One step = learning the clipping factors of one LayerNorm activation [T, D] (100 Adam iterations)."""
     iters, lr, alpha0 = 100, 0.01, 4.0
@@ -413,6 +436,7 @@ def main():
                                                    kernels_ms_per_step=o["kernels_ms_per_step"])
     if others:
         out["other_workloads"] = others
+    out["hbm_copy_reference"] = copy_reference(torch)
     print(json.dumps(out))
     if args.copy_probe:
         # a plain device copy of known size (256 MiB read + 256 MiB written): scales the HBM byte counters of a --pmc run
