@@ -263,6 +263,138 @@ rq_status launch_row(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcod
   return RQ_OK;
 }
 
+// ---- many rows: rows travel through LDS without holding registers --------------------------------------------------------
+// A kernel this simple is bound by how many bytes it keeps in flight.  The persistent kernel above prefetches its next
+// rows into registers, which caps a CU at 8 wavefronts x 8 KB.  Here a wavefront owns one row at a time (64 lanes, NV
+// float4 each) and a private two-slot ring in LDS: rows are requested with asynchronous global->LDS loads (each lane's 16
+// bytes land at slot + 1 KiB * i + 16 * lane, and the same lane reads them back, so the ring is a per-lane FIFO without
+// bank conflicts or barriers), two rows ahead, and cost no registers while they travel: 16 wavefronts per CU x 2 rows.
+// Waiting for a row is a count of the wavefront's own younger memory operations (loads return in issue order): the next
+// row's NV loads and the previous row's NV code stores may still be in flight, everything older has landed.
+constexpr int ring_wgs_per_cu(int nv) { return nv <= 4 ? 4 : nv <= 6 ? 3 : 2; }      // by LDS (table + 8 nv KiB) and registers
+
+template <int NV, bool GUARD>
+__global__ __launch_bounds__(256, ring_wgs_per_cu(NV)) void ln_quant_ring_kernel(const float* __restrict__ x, int64_t ldx, int64_t T, int D, int norm_kind,
+                                                               double eps, const float* __restrict__ gamma_t,
+                                                               const float* __restrict__ beta_t, double inv_s, double zcode, float qmaxf,
+                                                               unsigned off4, int8_t* __restrict__ q, int64_t ldq,
+                                                               int32_t* __restrict__ rowsum) {
+  extern __shared__ __align__(16) char ring_raw[];      // [D] float2 {gamma~ / s~, beta~ / s~ + z~}, then per wavefront 2 slots of NV KiB
+  float2* const ghf = reinterpret_cast<float2*>(ring_raw);
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chunks = D >> 2;
+  char* const slots = ring_raw + (size_t)D * 8 + (size_t)wv * (2 * NV * 1024);
+  for (int ch = threadIdx.x; ch < D; ch += 256) {
+    const double g = (double)gamma_t[ch] * inv_s, h = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode;
+    ghf[ch] = make_float2((float)g, (float)h);
+  }
+  const int64_t stride = (int64_t)gridDim.x * 4;
+  int64_t row = (int64_t)blockIdx.x * 4 + wv;
+  // request row r into slot k (rows past the end re-read the last row: every request is the same NV loads)
+  auto request = [&](int64_t r, int k) {
+    const float* src = x + (r < T ? r : T - 1) * ldx;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + i * 64;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (c < chunks ? c : 0) * 4),
+                                       (__attribute__((address_space(3))) void*)(slots + k * (NV * 1024) + i * 1024), 16, 0, 0);
+    }
+  };
+  request(row, 0);
+  request(row + stride, 1);
+  __syncthreads();      // the constant table
+  const double invD = 1.0 / (double)D;
+  bool first = true;
+  for (int k = 0; row < T; row += stride, k ^= 1) {      // wavefront-uniform
+    // younger than this row's loads: the next row's NV loads, and (from the second turn on) the last row's NV code stores
+    if (first) __builtin_amdgcn_s_waitcnt((NV & 0xF) | ((NV >> 4) << 14) | 0x0F70);
+    else __builtin_amdgcn_s_waitcnt(((2 * NV) & 0xF) | (((2 * NV) >> 4) << 14) | 0x0F70);
+    first = false;
+    float4 cur[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const float4 v = *reinterpret_cast<const float4*>(slots + k * (NV * 1024) + i * 1024 + lane * 16);
+      cur[i] = lane + i * 64 < chunks ? v : make_float4(0, 0, 0, 0);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the slot is read: it may be refilled
+    request(row + 2 * stride, k);
+    double s1 = 0.0, s2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const double a = cur[i].x, b = cur[i].y, c = cur[i].z, d = cur[i].w;
+      s1 += (a + b) + (c + d);
+      s2 = fma(a, a, s2); s2 = fma(b, b, s2); s2 = fma(c, c, s2); s2 = fma(d, d, s2);
+    }
+    s2 = group_sum<64>(s2);
+    double mean = 0.0, var = s2 * invD;
+    if (norm_kind == RQ_NORM_LAYERNORM) {
+      s1 = group_sum<64>(s1);
+      mean = s1 * invD;
+      var = fma(-mean, mean, var);
+      var = var < 0.0 ? 0.0 : var;
+    }
+    const double rstd = rsqrt_f64(var + eps);
+    const double nmr = -mean * rstd;
+    const float rstd_f = (float)rstd, nmr_f = (float)nmr;
+    int rs = 0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + i * 64;
+      const float xv[4] = {cur[i].x, cur[i].y, cur[i].z, cur[i].w};
+      unsigned w = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float2 g = ghf[(c < chunks ? c : 0) * 4 + e];
+        float vf = fmaf(fmaf(xv[e], rstd_f, nmr_f), g.x, g.y);    // the packed convert below rounds to nearest-even
+        if (GUARD && c < chunks && fabsf(vf - __builtin_rintf(vf)) > 0.5f - TIE_GUARD) {      // next to a tie: float64 decides
+          const int ch = c * 4 + e;
+          const double gd = (double)gamma_t[ch] * inv_s, hd = (beta_t ? (double)beta_t[ch] * inv_s : 0.0) + zcode;
+          vf = (float)rint(fma(fma((double)xv[e], rstd, nmr), gd, hd));
+        }
+        vf = fminf(vf, qmaxf);
+        if (e == 0) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 0, w);
+        if (e == 1) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 1, w);
+        if (e == 2) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 2, w);
+        if (e == 3) w = __builtin_amdgcn_cvt_pk_u8_f32(vf, 3, w);
+      }
+      w = ((w | 0x80808080u) - (off4 & 0x7F7F7F7Fu)) ^ ((w ^ ~off4) & 0x80808080u);      // stored = code - off per byte
+      if (c < chunks) {
+        if (rowsum) rs = __builtin_amdgcn_sdot4((int)w, 0x01010101, rs, false);
+        *reinterpret_cast<unsigned*>(q + row * ldq + c * 4) = w;      // one store instruction per i: the wait above counts on it
+      }
+    }
+    if (rowsum) {
+      rs = group_sum_i<64>(rs);
+      if (lane == 0) rowsum[row] = rs;
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // no request may outlive the workgroup's LDS
+}
+
+constexpr int ring_lds_bytes(int D, int nv) { return D * 8 + 4 * 2 * nv * 1024; }
+
+template <int NV>
+rq_status launch_ring(rq_ctx* ctx, const rq_ln_desc* d, double inv_s, double zcode, float qmaxf, unsigned off4) {
+  const int lds = ring_lds_bytes(d->D, NV);
+  int per_cu = (160 * 1024) / lds;
+  per_cu = per_cu > ring_wgs_per_cu(NV) ? ring_wgs_per_cu(NV) : (per_cu < 1 ? 1 : per_cu);
+  const int64_t blocks = (d->T + 3) / 4;
+  const int64_t cap = (int64_t)ctx->num_cu * per_cu;
+  const unsigned grid = (unsigned)(blocks < cap ? blocks : cap);
+#define RQ_LN_RING(G)                                                                                                              \
+  do {                                                                                                                             \
+    static rq_once_per_device lds_attr;                                                                                            \
+    RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&ln_quant_ring_kernel<NV, G>), 8192 * 8 + 64 * 1024)); \
+    hipLaunchKernelGGL((ln_quant_ring_kernel<NV, G>), dim3(grid), dim3(256), lds, ctx->stream, d->x, d->ldx, d->T, d->D,           \
+                       d->norm_kind, d->eps, d->gamma_t, d->beta_t, inv_s, zcode, qmaxf, off4, d->q, d->ldq, d->rowsum);          \
+  } while (0)
+  if (d->bits > 6) RQ_LN_RING(true);
+  else RQ_LN_RING(false);
+#undef RQ_LN_RING
+  RQ_HIP(hipGetLastError());
+  return RQ_OK;
+}
+
 template <int LPR, int NV, bool GUARD, bool PERSIST>
 rq_status launch_one(rq_ctx* ctx, const rq_ln_desc* d, int64_t blocks, int lds, double inv_s, double zcode, float qmaxf, unsigned off4) {
   static rq_once_per_device lds_attr;
@@ -311,6 +443,15 @@ rq_status rq_launch_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
     if (nvr <= 2) return launch_row<2>(ctx, d, inv_s, zcode, qmaxf, off4);
     if (nvr <= 4) return launch_row<4>(ctx, d, inv_s, zcode, qmaxf, off4);
     if (nvr <= 8) return launch_row<8>(ctx, d, inv_s, zcode, qmaxf, off4);
+  }
+  // many rows of 1 .. 8 KiB: the LDS-ring kernel (more rows than the one-pass form of the register kernel takes)
+  if (chunks >= 128 && chunks <= 512 && d->T > (int64_t)ctx->num_cu * 16) {
+    const int nvr = (chunks + 63) / 64;
+    if (nvr <= 2) return launch_ring<2>(ctx, d, inv_s, zcode, qmaxf, off4);
+    if (nvr <= 3) return launch_ring<3>(ctx, d, inv_s, zcode, qmaxf, off4);
+    if (nvr <= 4) return launch_ring<4>(ctx, d, inv_s, zcode, qmaxf, off4);
+    if (nvr <= 6) return launch_ring<6>(ctx, d, inv_s, zcode, qmaxf, off4);
+    return launch_ring<8>(ctx, d, inv_s, zcode, qmaxf, off4);
   }
   // lanes per row: the smallest group that keeps a row within 8 float4 per lane
   int lpr = 64;

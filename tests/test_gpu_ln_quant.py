@@ -17,7 +17,9 @@ def rq():
 
 
 @pytest.mark.parametrize("T,D", [(333, 384), (1031, 768), (517, 128), (130, 1024), (67, 4096), (45, 100), (9, 8192),
-                                 (1, 768), (700, 52)])
+                                 (1, 768), (700, 52),
+                                 # more rows than one pass takes: rows travel through the LDS ring (2, 3, 4, 6, 8 KiB rows, ragged ones)
+                                 (5001, 768), (4500, 1024), (4203, 520), (4100, 2048), (4099, 1300), (4101, 512)])
 @pytest.mark.parametrize("bits", [4, 6, 8])
 @pytest.mark.parametrize("kind", [orc.NORM_LAYERNORM, orc.NORM_RMSNORM])
 def test_ln_quant_matches_oracle(rq, T, D, bits, kind):
@@ -41,9 +43,10 @@ def test_ln_quant_matches_oracle(rq, T, D, bits, kind):
     assert np.abs(got - q_def).max() <= 1 and np.mean(got != q_def) < 2e-3
 
 
-def test_ln_quant_strided_rows_and_no_beta(rq):
+@pytest.mark.parametrize("T", [50, 4300])
+def test_ln_quant_strided_rows_and_no_beta(rq, T):
     b, ctx = rq
-    T, D = 50, 384
+    D = 384
     x = synth.make_rows(T, D + 64, seed=3)
     p = folded_ln_case(x[:, :D], seed=1, bits=8, kind=orc.NORM_RMSNORM)
     xd = dev(x)
