@@ -141,7 +141,17 @@ __global__ __launch_bounds__(512) void qk_softmax_kernel(const QksParams p) {
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) qreg[s] = *reinterpret_cast<const v4i*>(Qg + (int64_t)qi_ld * p.ldq + s * 32 + half * 16);
   };
-  int gq = (int)blockIdx.x * GPB;
+  // Which groups a workgroup starts with.  Consecutive groups are consecutive heads of one batch item, whose 64- (or
+  // 32-) byte slices of a token row share 128-byte lines.  Workgroup b runs on XCD b % 8, each XCD with its own L2: with one
+  // group per pass, neighbouring heads are dealt to the two workgroups b and b + 8 of the same XCD (same round), so that
+  // XCD fetches the shared lines once instead of two XCDs fetching them each.  (A permutation of the workgroups of the
+  // first whole multiple of 16; the rest keep their index.)
+  unsigned wg = blockIdx.x;
+  if (GPB == 1 && wg < (gridDim.x & ~15u)) {
+    const unsigned xcd = wg & 7u, slot = wg >> 3;
+    wg = (slot & 1u) + 2u * (xcd + 8u * (slot >> 1));
+  }
+  int gq = (int)wg * GPB;
   if (gq < Gi) request(gq);
   // Bias planes in LDS: a workgroup's group slot s always meets head (blockIdx.x * GPB + s) % H (the launcher checks that
   // the stride between passes is a multiple of H), so its GPB planes are copied once and every bias read of every pass is
