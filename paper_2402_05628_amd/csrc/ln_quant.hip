@@ -444,8 +444,10 @@ rq_status rq_launch_ln_quant(rq_ctx* ctx, const rq_ln_desc* d) {
     if (nvr <= 4) return launch_row<4>(ctx, d, inv_s, zcode, qmaxf, off4);
     if (nvr <= 8) return launch_row<8>(ctx, d, inv_s, zcode, qmaxf, off4);
   }
-  // many rows of 1 .. 8 KiB: the LDS-ring kernel (more rows than the one-pass form of the register kernel takes)
-  if (chunks >= 128 && chunks <= 512 && d->T > (int64_t)ctx->num_cu * 16) {
+  // many rows of 2 .. 8 KiB: the LDS-ring kernel, once its wavefronts (16 per CU) have at least six rows each -- with
+  // fewer the ring never reaches its steady state and the register kernel's all-rows-at-once pass is faster (12 608 x 768:
+  // 13.4 us against 15.6 us; 32 896 x 1024: 36.1 against 34.8 us)
+  if (chunks >= 128 && chunks <= 512 && d->T >= (int64_t)ctx->num_cu * 96) {
     const int nvr = (chunks + 63) / 64;
     if (nvr <= 2) return launch_ring<2>(ctx, d, inv_s, zcode, qmaxf, off4);
     if (nvr <= 3) return launch_ring<3>(ctx, d, inv_s, zcode, qmaxf, off4);

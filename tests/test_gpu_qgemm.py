@@ -47,6 +47,32 @@ def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
         b.set_gemm_tile(ctx, 0)
 
 
+@pytest.mark.parametrize("M,N,K,tile", [(1990, 3072, 256, 7), (1990, 3072, 2048, 7), (2048, 6144, 256, 8), (1000, 4096, 128, 5),
+                                        (700, 8192, 192, 6)])
+@pytest.mark.parametrize("bits_a,bits_w", [(4, 4), (8, 8)])
+def test_accumulators_with_one_rectangle_of_tiles_per_xcd(rq, M, N, K, tile, bits_a, bits_w):
+    """Few tile rows, many tile columns: the launcher cuts the tile grid into one rectangle per XCD (ragged last tile row
+    included).  Every output must still be written exactly once: true accumulators, no sentinel left."""
+    b, ctx = rq
+    print("case", M, N, K, tile, bits_a, bits_w, flush=True)
+    b.set_gemm_tile(ctx, tile)
+    try:
+        g = np.random.default_rng(M + N + K + tile)
+        qa, z_a = _act_codes(g, M, K, bits_a)
+        lin = random_linear(g, N, K, bits_w)
+        want = orc.qlinear_acc(qa, z_a, lin["codes"], lin["z_w"])
+        a_off = b.store_offset(bits_a, z_a)
+        A = dev((qa - a_off).astype(np.int8))
+        rs = torch.empty(M, dtype=torch.int32, device="cuda")
+        b.rq_rowsum_i8(ctx, A, rs)
+        acc = torch.full((M, N), -(2 ** 31) + 5, dtype=torch.int32, device="cuda")
+        b.rq_qgemm(ctx, A, a_off, z_a, 0.01, lin_to_device(lin, bits_w), out_acc=acc, rowsum_a=rs)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
+    finally:
+        b.set_gemm_tile(ctx, 0)
+
+
 def test_accumulator_extremes(rq):
     """All-max codes against all-min weights at K = 11008: the largest magnitudes the int32 contract allows."""
     b, ctx = rq
