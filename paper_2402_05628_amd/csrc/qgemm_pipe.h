@@ -37,6 +37,7 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
                                               int m0, int n0, int wm0, int wn0, int lane) {
   const int lcol = lane & 31, half = lane >> 5, lrow4 = half * 4;
   constexpr bool gated = ACT == RQ_ACT_SILU_GATED;
+  constexpr bool FOLD = OUT == OUT_Q && ACT == RQ_ACT_NONE;      // el->scale / el->bias hold the folded constants A, B (see the kernel)
   // everything the stores need, read from the kernel arguments once
   int32_t* const out_acc = (OUT & OUT_ACC) ? p.out_acc : nullptr;
   float* const out_f32 = (OUT & OUT_F32) ? p.out_f32 : nullptr;
@@ -133,7 +134,27 @@ __device__ __forceinline__ void epilogue_wide(const GemmParams& p, v16i (&acc)[T
         if (has_f32 && live) *reinterpret_cast<float4*>(rf32[i] + no) = make_float4(y[0], y[1], y[2], y[3]);
         if (has_q) {
           unsigned w = 0;
-          if (Q8 && ACT == RQ_ACT_NONE) {      // 8-bit codes: the packed convert saturates at 255 by itself
+          if (FOLD && Q8) {      // y is the pre-round code already; the same guard with the tie distance added to it
+            unsigned wl = 0;
+            w = __builtin_amdgcn_cvt_pk_u8_f32(y[0] + TIE_GUARD, 0, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(y[1] + TIE_GUARD, 1, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(y[2] + TIE_GUARD, 2, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(y[3] + TIE_GUARD, 3, w);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(y[0] - TIE_GUARD, 0, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(y[1] - TIE_GUARD, 1, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(y[2] - TIE_GUARD, 2, wl);
+            wl = __builtin_amdgcn_cvt_pk_u8_f32(y[3] - TIE_GUARD, 3, wl);
+            if (w != wl) {
+              int sg = p.n_seg > 1 ? no / p.seg_len : 0;
+              sg = sg < p.n_seg ? sg : p.n_seg - 1;
+              w = requant_exact4(p, t[0], t[1], t[2], t[3], n, r.x, r.y, r.z, r.w, sg);
+            }
+          } else if (FOLD) {
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(y[0], qm), 0, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(y[1], qm), 1, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(y[2], qm), 2, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(fminf(y[3], qm), 3, w);
+          } else if (Q8 && ACT == RQ_ACT_NONE) {      // 8-bit codes: the packed convert saturates at 255 by itself
             // the codes taken TIE_GUARD above and below agree unless the value sits that close to a rounding tie
             const float zp = zz + TIE_GUARD, zm = zz - TIE_GUARD;
             unsigned wl = 0;
@@ -511,17 +532,23 @@ __global__ __launch_bounds__(128 * WN, pipe_wgs_per_cu(TM, TN, WN, OUT)) void qg
     const int col = (tid & 127) + 128 * u;
     int n = n0 + col;
     n = n < p.N ? n : p.N - 1;
+    // Codes as the only output and no activation (QKV): scale and re-quantization fold into one multiply-add per output,
+    // code = rne(acc * A[n] + B[n]) with A = s_a s_w[n] / s_o and B = b[n] / s_o + z_o formed in float64 and rounded once
+    // (one rounding less than scale-then-requantize, and one instruction less per output)
+    constexpr bool FOLD = OUT == OUT_Q && ACT == RQ_ACT_NONE;
+    int sg = 0;
+    if ((OUT & OUT_Q) && p.out_q) {   // re-quantization segment of output column col of this tile
+      const int no = (ACT == RQ_ACT_SILU_GATED ? n0 / 2 : n0) + col;
+      sg = p.n_seg > 1 ? no / p.seg_len : 0;
+      sg = sg < p.n_seg ? sg : p.n_seg - 1;
+    }
     if (tid < 128) {
-      ep_f[u] = p.s_a * p.s_b[n];
+      ep_f[u] = FOLD ? (float)((double)p.s_a * (double)p.s_b[n] * p.inv_so_d[sg]) : p.s_a * p.s_b[n];
       ep_i[u] = (p.da != 0 && p.colsum_b) ? p.da * p.colsum_b[n] : 0;
-      if ((OUT & OUT_Q) && p.out_q) {   // re-quantization constants of output column col of this tile
-        const int no = (ACT == RQ_ACT_SILU_GATED ? n0 / 2 : n0) + col;
-        int sg = p.n_seg > 1 ? no / p.seg_len : 0;
-        sg = sg < p.n_seg ? sg : p.n_seg - 1;
-        ep_is[u] = p.inv_so[sg]; ep_zz[u] = p.zcode[sg]; ep_off[u] = p.off4[sg];
-      }
+      if ((OUT & OUT_Q) && p.out_q) { ep_is[u] = p.inv_so[sg]; ep_zz[u] = p.zcode[sg]; ep_off[u] = p.off4[sg]; }
     } else {
-      ep_f[u] = p.bias ? p.bias[n] : 0.f;
+      const float bn = p.bias ? p.bias[n] : 0.f;
+      ep_f[u] = FOLD ? (float)((double)bn * p.inv_so_d[sg] + (double)p.zcode[sg]) : bn;
       ep_i[u] = p.centered ? 128 - p.z_b[n] : 0;
     }
   }
