@@ -297,7 +297,7 @@ template <int N> __device__ __forceinline__ void wait_vm() {
 
 // workgroups (= wavefronts per SIMD) a CU is meant to hold: bounds the registers the compiler may take
 constexpr int pipe_occupancy(int TM, int OUT) {
-  return TM <= 2 ? 4 : (TM == 3 ? (OUT == OUT_Q ? 3 : 2) : (TM == 4 ? 2 : 1));
+  return TM <= 2 ? 4 : (TM == 3 ? 3 : (TM == 4 ? 2 : 1));
 }
 // the same for every tile shape: 256-column tiles and the eight-wavefront grid own their CU
 constexpr int pipe_wgs_per_cu(int TM, int TN, int WN, int OUT) {
@@ -760,7 +760,7 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
 }
 
 // Tile height for the float + residual outputs.  In units of the time one 256-row tile takes alone on a CU, two co-resident
-// 256-row tiles take about 1.5, a 320-row tile (which owns its CU) 1.25 and two co-resident 192-row tiles 1.125; pick what
+// 256-row tiles take about 1.5, a 320-row tile (which owns its CU) 1.25, two co-resident 192-row tiles 1.125 and three 1.7; pick what
 // finishes the busiest CU first.  The 192-row tile only pays while the K loop is short (the epilogue's memory phase then
 // weighs as much as the loop and two smaller workgroups overlap it better); with a long loop it measures no faster.
 // Returns the number of 64-row groups per tile: 3, 4 or 5.
@@ -769,7 +769,9 @@ inline int pick_rows_f32(const rq_ctx* ctx, const GemmParams& p) {
   const int64_t cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   const int64_t tn = (p.N + 127) / 128;
   const int64_t t192 = ((p.M + 191) / 192) * tn, t256 = ((p.M + 255) / 256) * tn, t320 = ((p.M + 319) / 320) * tn;
-  const double c192 = t192 <= cu ? 0.75 : 1.125 * (double)((t192 + 2 * cu - 1) / (2 * cu));
+  // (192-row tiles: up to three per CU; a round of three costs about 1.7, and the last round what its fill costs)
+  const int64_t r192 = t192 % (3 * cu);
+  const double c192 = 1.69 * (double)(t192 / (3 * cu)) + (r192 == 0 ? 0.0 : r192 <= cu ? 0.75 : r192 <= 2 * cu ? 1.125 : 1.69);
   const double c256 = t256 <= cu ? 1.0 : 1.5 * (double)((t256 + 2 * cu - 1) / (2 * cu));
   const double c320 = 1.25 * (double)((t320 + cu - 1) / cu);
   const double other = c320 < c256 ? c320 : c256;
@@ -817,7 +819,7 @@ rq_status launch_pipe_out(rq_ctx* ctx, GemmParams& p) {
   if (ACT == RQ_ACT_NONE && f && r && !q && !a) {
     constexpr int S_TALL = W4 ? 6 : 5;       // one workgroup per CU: the ring may take most of the LDS
     const int rows = pick_rows_f32(ctx, p);
-    if (rows == 3) return launch_pipe_one<W4, 4, RQ_ACT_NONE, OUT_F32 | OUT_RES, 3>(ctx, p);
+    if (rows == 3) return launch_pipe_one<W4, 3, RQ_ACT_NONE, OUT_F32 | OUT_RES, 3>(ctx, p);
     if (rows == 5) return launch_pipe_one<W4, S_TALL, RQ_ACT_NONE, OUT_F32 | OUT_RES, 5>(ctx, p);
     return launch_pipe_one<W4, S, ACT, OUT_F32 | OUT_RES, 4>(ctx, p);
   }
