@@ -42,7 +42,6 @@ struct GemmParams {
   int lo[4], hi[4];
   int tiles_m, tiles_n;
   int group_m;      // tile rows walked together: consecutive tiles go down group_m rows before they move to the next column
-  int xcd_m, xcd_rows, xcd_cols;      // xcd_m != 0: the tile grid is cut into xcd_m x (8 / xcd_m) rectangles of xcd_rows x xcd_cols tiles, one per XCD
   int force_rows;   // host only: 64-row groups per tile to take wherever that tile exists (0: choose by shape)
   int no_raw;       // host only: 1 = packed 4-bit weights keep the zero-point subtraction in the unpack even when row sums are
                     // given, -1 = raw nibbles whenever they are given (default: only with a long K loop)

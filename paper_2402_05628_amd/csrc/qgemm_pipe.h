@@ -337,37 +337,26 @@ __global__ __launch_bounds__(128 * WN, pipe_wgs_per_cu(TM, TN, WN, OUT)) void qg
   const int wm0 = (wave / WN) * (32 * TM), wn0 = (wave % WN) * (32 * TN);
   const int l32 = lane & 31, half = lane >> 5;
 
-  // tile of this workgroup.  Workgroup b runs on XCD b % 8, each XCD with its own L2.  Default: XCD x gets the contiguous
-  // range [x * per_xcd, ...) of the tile list (n fastest), i.e. a few whole tile rows and every column.  Where that makes
-  // every XCD pull (nearly) all of the weights through its L2 -- few tile rows, many tile columns -- the launcher cuts the
-  // tile grid into xcd_m x (8 / xcd_m) rectangles of xcd_rows x xcd_cols tiles instead, one per XCD.
-  const unsigned xcd = blockIdx.x & 7u, local = blockIdx.x >> 3;
-  unsigned row0 = 0, col0 = 0, nrows = (unsigned)p.tiles_m, ncols = (unsigned)p.tiles_n, t = local;
-  if (p.xcd_m == 0) {
-    const unsigned ntiles = nrows * ncols;
-    const unsigned per_xcd = (ntiles + 7u) / 8u;
-    t = xcd * per_xcd + local;
-    if (local >= per_xcd || t >= ntiles) return;
-  } else {
-    const unsigned xb = 8u / (unsigned)p.xcd_m;
-    const unsigned xm = xcd / xb, xn = xcd - xm * xb;
-    row0 = xm * (unsigned)p.xcd_rows;
-    col0 = xn * (unsigned)p.xcd_cols;
-    if (row0 >= nrows || col0 >= ncols) return;
-    nrows = nrows - row0 < (unsigned)p.xcd_rows ? nrows - row0 : (unsigned)p.xcd_rows;
-    ncols = ncols - col0 < (unsigned)p.xcd_cols ? ncols - col0 : (unsigned)p.xcd_cols;
-    if (t >= nrows * ncols) return;
-  }
-  // Within its share the tiles are walked in bands of group_m tile rows, down a band's rows first: the tiles that are
+  // tile of this workgroup: XCD b % 8 gets the contiguous range [xcd * per_xcd, ...) of the tile list (n fastest), i.e. a few
+  // whole tile rows and every column.  (Cutting the tile grid into one rectangle of tile rows x tile columns per XCD, which
+  // on paper halves the operand bytes an XCD's L2 pulls in for launches with few tile rows and many tile columns, measured
+  // no faster -- 2048 x 12288 x 4096: 0.119 ms either way, 8192^3: 0.49 - 0.51 ms either way -- and raised the counted L2
+  // fetches from 129 to 181 MB per launch at the first shape; it is not used.)
+  const unsigned tiles_n = (unsigned)p.tiles_n;
+  const unsigned ntiles = (unsigned)p.tiles_m * tiles_n;
+  const unsigned per_xcd = (ntiles + 7u) / 8u;
+  const unsigned t = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || t >= ntiles) return;
+  // Within that range the tiles are walked in bands of group_m tile rows, down a band's rows first: the tiles that are
   // in flight on an XCD at one time then cover a block of rows x columns instead of one long row of tiles, and the
   // operand bytes its L2 has to pull in per k-step shrink accordingly.
-  const unsigned band = (unsigned)p.group_m * ncols;
+  const unsigned band = (unsigned)p.group_m * tiles_n;
   const unsigned bi = t / band, br = t - bi * band;
   const unsigned first_m = bi * (unsigned)p.group_m;
-  const unsigned left_m = nrows - first_m;
+  const unsigned left_m = (unsigned)p.tiles_m - first_m;
   const unsigned gm = left_m < (unsigned)p.group_m ? left_m : (unsigned)p.group_m;
   const unsigned tcol = br / gm;
-  const int tm = (int)(row0 + first_m + (br - tcol * gm)), tn = (int)(col0 + tcol);
+  const int tm = (int)(first_m + (br - tcol * gm)), tn = (int)tcol;
   const int m0 = tm * BM, n0 = tn * BN;
   const int nk = p.K / 64;
   // ---- asynchronous loads: 32-bit byte offsets from the tensor bases (the launcher checks both are < 4 GiB) ----
@@ -724,37 +713,7 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
                 "the idle ring holds the epilogue constants and, for float rows, the row staging");
   static rq_once_per_device lds_attr;
   RQ_HIP(rq_allow_dynamic_lds(ctx, lds_attr, reinterpret_cast<const void*>(&qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8, RAW>), lds_bytes));
-  // Share of an XCD.  Bytes one XCD's L2 pulls in over the launch: its tile rows of A plus its tile columns of B.  The
-  // default (contiguous ranges of the tile list) gives every XCD ntiles / 8 / tiles_n tile rows and all columns; a cut into
-  // xa x (8 / xa) rectangles is taken where it saves at least a fifth of those bytes and pads the grid by at most 4 %.
-  int64_t blocks = (ntiles + 7) / 8 * 8;
-  p.xcd_m = 0; p.xcd_rows = 0; p.xcd_cols = 0;
-  {
-    const double a_row = 64.0 * TM * (double)p.K, b_col = (W4 ? 0.5 : 1.0) * BN * (double)p.K;
-    const double rows_now = (double)ntiles / 8.0 / (double)p.tiles_n;
-    double best = (rows_now < 1.0 ? 1.0 : rows_now + 1.0) * a_row + (rows_now < 1.0 ? rows_now * p.tiles_n + 1.0 : (double)p.tiles_n) * b_col;
-    best *= 0.8;
-    for (int xa = 1; xa <= 4; xa *= 2) {
-      const int xb = 8 / xa;
-      const int64_t r = (p.tiles_m + xa - 1) / xa, c = (p.tiles_n + xb - 1) / xb;
-      if (r * c * 8 > ntiles + ntiles / 25) continue;
-      const double bytes = (double)r * a_row + (double)c * b_col;
-      if (bytes < best) { best = bytes; p.xcd_m = xa; p.xcd_rows = (int)r; p.xcd_cols = (int)c; blocks = r * c * 8; }
-    }
-    if (p.xcd_m) {      // bands inside the rectangle
-      const int cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
-      const int inflight = (cu / 8 > 0 ? cu / 8 : 1) * pipe_wgs_per_cu(TM, TN, WN, OUT);
-      int64_t bb = -1;
-      p.group_m = 1;
-      for (int g = 1; g <= 16; g *= 2) {
-        if (g > p.xcd_rows && g > 1) break;
-        int cols = (inflight + g - 1) / g;
-        cols = cols < p.xcd_cols ? cols : p.xcd_cols;
-        const int64_t bytes = (int64_t)g * (64 * TM * 64) + (int64_t)cols * (W4 ? BN * 32 : BN * 64);
-        if (bb < 0 || bytes < bb) { bb = bytes; p.group_m = g; }
-      }
-    }
-  }
+  const int64_t blocks = (ntiles + 7) / 8 * 8;
   hipLaunchKernelGGL((qgemm_pipe_kernel<W4, S, ACT, OUT, TM, TN, WN, Q8, RAW>), dim3((unsigned)blocks), dim3(128 * WN), lds_bytes, ctx->stream, p);
   return RQ_OK;
 }

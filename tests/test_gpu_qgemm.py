@@ -50,9 +50,9 @@ def test_accumulators_bit_exact(rq, M, N, K, bits_a, bits_w, tile):
 @pytest.mark.parametrize("M,N,K,tile", [(1990, 3072, 256, 7), (1990, 3072, 2048, 7), (2048, 6144, 256, 8), (1000, 4096, 128, 5),
                                         (700, 8192, 192, 6)])
 @pytest.mark.parametrize("bits_a,bits_w", [(4, 4), (8, 8)])
-def test_accumulators_with_one_rectangle_of_tiles_per_xcd(rq, M, N, K, tile, bits_a, bits_w):
-    """Few tile rows, many tile columns: the launcher cuts the tile grid into one rectangle per XCD (ragged last tile row
-    included).  Every output must still be written exactly once: true accumulators, no sentinel left."""
+def test_accumulators_few_tile_rows_many_tile_columns(rq, M, N, K, tile, bits_a, bits_w):
+    """Few tile rows, many tile columns (every XCD's range of the tile list spans many columns; ragged last tile row):
+    every output written exactly once: true accumulators, no sentinel left."""
     b, ctx = rq
     print("case", M, N, K, tile, bits_a, bits_w, flush=True)
     b.set_gemm_tile(ctx, tile)
