@@ -8,9 +8,11 @@
 //                                            and U = J X J, because H = (J L J)(J L J)^T with J L J upper triangular
 //   for every column j (blocks of 64):       q_j = quantize(w_j) on the row's fixed min/max grid,
 //                                            err_j = (w_j - dequant(q_j)) / U_jj,  W[:, j+1:] -= err_j (x) U[j, j+1:]
-// inside a block four lanes sweep one output channel with its 64 columns in their registers; the columns after the block are
-// updated once per block by a float64 GEMM (E [N x 64] times U[block, rest]).  Everything is float64 except the Gram
-// matrix (exact integers) so that the codes agree with a float64 reference except next to rounding ties.
+// inside a block four lanes sweep one output channel with its 64 columns in their registers; the columns after the block
+// get E [16 x 64] times U[block, rest] from the other wavefronts of the workgroup that owns the 16 channels, while the
+// next block is swept (the update of a row needs nothing from other rows, so the whole sweep is one launch).  Everything is
+// float64 except the Gram matrix (exact integers) so that the codes agree with a float64 reference except next to rounding
+// ties.
 #include <cfloat>
 #include <cmath>
 
@@ -171,35 +173,137 @@ __device__ __forceinline__ double lane_value(double v, int lane) {
   const int lo = __builtin_amdgcn_readlane((int)b, lane), hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
   return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
 }
-__global__ __launch_bounds__(64) void potf2_inv_kernel(const double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
-                                                       int K, int kb) {
-  const int i = threadIdx.x;
-  const int64_t base = (int64_t)kb * NB * K + (int64_t)kb * NB;
-  double a[NB];
-#pragma unroll
-  for (int c = 0; c < NB; ++c) a[c] = H[base + (int64_t)i * K + c];          // only c <= i is used (the maintained triangle)
+// Lane i holds row i of the block in a[]; on return a[] is row i of its Cholesky factor (zeros above the diagonal), and
+// Lt (LDS, LP doubles per row) holds the factor as well.  An entry of another row comes from that LDS copy, which every
+// lane extends by its new entry after each column: the address is the same for all lanes, two entries per read.
+constexpr int LP = 66;
+__device__ __forceinline__ void diag_factor(double (&a)[NB], int i, double* __restrict__ Lt) {
   // left-looking: l_ij = (h_ij - sum_{k<j} l_ik l_jk) / l_jj
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     double sum = 0.0;
+    const double2* row = reinterpret_cast<const double2*>(Lt + j * LP);
 #pragma unroll
-    for (int k = 0; k < j; ++k) sum = fma(a[k], lane_value(a[k], j), sum);
+    for (int k = 0; k < j; k += 2) {
+      const double2 l = row[k >> 1];
+      sum = fma(a[k], l.x, sum);
+      if (k + 1 < j) sum = fma(a[k + 1], l.y, sum);
+    }
     const double v = a[j] - sum;
     const double d = sqrt(lane_value(v, j));
     a[j] = i == j ? d : (i > j ? v / d : 0.0);
+    Lt[i * LP + j] = a[j];
   }
-#pragma unroll
-  for (int c = 0; c < NB; ++c) L[base + (int64_t)i * K + c] = a[c];
-  // inverse, lane c takes column c: x(r) = (delta_rc - sum_{m<r} l_rm x(m)) / l_rr, x(m) = 0 for m < c
-  double x[NB];
+}
+// Lane c takes column c of the inverse of the factor: x(r) = (delta_rc - sum_{m<r} l_rm x(m)) / l_rr, x(m) = 0 for m < c.
+__device__ __forceinline__ void diag_inverse(double (&x)[NB], int i, const double* __restrict__ Lt) {
 #pragma unroll
   for (int r = 0; r < NB; ++r) {
     double sum = 0.0;
+    const double2* row = reinterpret_cast<const double2*>(Lt + r * LP);
 #pragma unroll
-    for (int m = 0; m < r; ++m) sum = fma(lane_value(a[m], r), x[m], sum);
-    x[r] = r < i ? 0.0 : ((r == i ? 1.0 : 0.0) - sum) / lane_value(a[r], r);
-    Dinv[(int64_t)kb * NB * NB + r * NB + i] = x[r];
+    for (int m = 0; m < r; m += 2) {
+      const double2 l = row[m >> 1];
+      sum = fma(l.x, x[m], sum);
+      if (m + 1 < r) sum = fma(l.y, x[m + 1], sum);
+    }
+    x[r] = r < i ? 0.0 : ((r == i ? 1.0 : 0.0) - sum) / Lt[r * LP + r];
   }
+}
+
+// ---- one step of the blocked right-looking factorization in one launch ----------------------------------------------
+// Step kb: L_kk = chol(H_kk), D = L_kk^-1, panel L_ik = H_ik D^T (i > kb), trailing update H_ij -= L_ik L_jk^T (i >= j > kb).
+// One workgroup per trailing tile (i, j).  Each factors and inverts the 64 x 64 diagonal block itself (its first wavefront,
+// in registers; the others fetch the tile's two panel blocks meanwhile), forms the two panel blocks it needs and then its
+// tile: nothing passes between workgroups inside the launch, at the price of the same small factorization in every one.
+// Workgroup 0 stores L_kk and D, the workgroups of the first tile column store the panel.  Sums run over k in ascending
+// order, one fma per term.
+constexpr int TP = 66;                                      // row pitch of the k-major 64 x 64 tiles in LDS (16-byte rows)
+constexpr int CHOL_LDS = (3 * NB * TP + NB * LP) * 8;
+__device__ __forceinline__ void tile_product(const double* __restrict__ As, const double* __restrict__ Bs, int ty, int tx,
+                                             double (&acc)[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+#pragma unroll 4
+  for (int kk = 0; kk < NB; ++kk) {
+    const double2* ap = reinterpret_cast<const double2*>(As + kk * TP + ty * 4);
+    const double2* bp = reinterpret_cast<const double2*>(Bs + kk * TP + tx * 4);
+    const double2 a01 = ap[0], a23 = ap[1], b01 = bp[0], b23 = bp[1];
+    const double a[4] = {a01.x, a01.y, a23.x, a23.y}, b[4] = {b01.x, b01.y, b23.x, b23.y};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+  }
+}
+__global__ __launch_bounds__(256) void chol_step_kernel(double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
+                                                        int K, int kb) {
+  extern __shared__ __attribute__((aligned(16))) double chol_lds[];
+  double* Bs = chol_lds;                                    // Bs[k][n] = D(n, k)
+  double* Ai = chol_lds + NB * TP;                          // Ai[k][m] = H_ik(m, k), later L_ik(m, k)
+  double* Aj = chol_lds + 2 * NB * TP;
+  double* Lt = chol_lds + 3 * NB * TP;                      // the diagonal block's factor
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int n = K / NB - kb - 1;                            // block rows below the diagonal block
+  int ti = 0, tj = (int)blockIdx.x;
+  while (tj > ti) { ++ti; tj -= ti; }                       // tile t of the lower triangle: t = ti (ti + 1) / 2 + tj
+  const int64_t bi = (int64_t)(kb + 1 + ti) * NB, bj = (int64_t)(kb + 1 + tj) * NB, c0 = (int64_t)kb * NB;
+  if (tid < 64) {
+    const int i = tid;
+    const int64_t base = c0 * K + c0;
+    double a[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) a[c] = H[base + (int64_t)i * K + c];        // only c <= i is used (the maintained triangle)
+    diag_factor(a, i, Lt);
+    if (blockIdx.x == 0) {
+#pragma unroll
+      for (int c = 0; c < NB; ++c) L[base + (int64_t)i * K + c] = a[c];
+    }
+    double x[NB];
+    diag_inverse(x, i, Lt);
+#pragma unroll
+    for (int r = 0; r < NB; ++r) {
+      Bs[i * TP + r] = x[r];
+      if (blockIdx.x == 0) Dinv[(int64_t)kb * NB * NB + r * NB + i] = x[r];
+    }
+  } else if (n > 0) {
+    for (int e = tid - 64; e < NB * NB; e += 192) {
+      const int k = e & 63, m = e >> 6;
+      Ai[k * TP + m] = H[(bi + m) * K + c0 + k];
+      if (ti != tj) Aj[k * TP + m] = H[(bj + m) * K + c0 + k];
+    }
+  }
+  if (n <= 0) return;
+  __syncthreads();
+  double li[4][4], lj[4][4];
+  tile_product(Ai, Bs, ty, tx, li);
+  if (ti != tj) tile_product(Aj, Bs, ty, tx, lj);
+  if (tj == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) L[(bi + ty * 4 + i) * K + c0 + tx * 4 + j] = li[i][j];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      Ai[(tx * 4 + j) * TP + ty * 4 + i] = li[i][j];
+      if (ti != tj) Aj[(tx * 4 + j) * TP + ty * 4 + i] = lj[i][j];
+    }
+  __syncthreads();
+  double acc[4][4];
+  tile_product(Ai, ti != tj ? Aj : Ai, ty, tx, acc);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      double* c = H + (bi + ty * 4 + i) * K + bj + tx * 4 + j;
+      *c = *c - acc[i][j];
+    }
 }
 
 // X = 0 with the inverted diagonal blocks in place
@@ -246,6 +350,8 @@ __global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__
 // ---- the sweep inside one block of 64 columns: four lanes per output channel -----------------------------------------
 // Lane q of a quad owns columns q, q + 4, ... of its channel's block.  Every step broadcasts the current column's
 // weight from its owner, all four lanes take the same code and error, and each updates the columns it owns.
+constexpr int SWEEP_ROWS = 16;   // output channels per workgroup of the sweep (four lanes each in its first wavefront)
+constexpr int SWEEP_WAVES = 8;
 template <int SRC>
 __device__ __forceinline__ double quad_bcast(double v) {
   const long long b = __double_as_longlong(v);
@@ -257,13 +363,13 @@ __device__ __forceinline__ double quad_bcast(double v) {
 
 template <int JJ>
 __device__ __forceinline__ void sweep_step(double (&w)[NB / 4], const double (*Ub)[NB], int q, double s, double z, double qmax,
-                                           uint8_t* code_row, double* e_row) {
+                                           uint8_t* code_row, double* e_col) {
   const double x = quad_bcast<JJ & 3>(w[JJ >> 2]);
   const double c = fmin(fmax(rint(x / s) + z, 0.0), qmax);
   const double err = (x - s * (c - z)) / Ub[JJ][JJ];
   if (q == (JJ & 3)) {
     code_row[JJ] = (uint8_t)c;
-    e_row[JJ] = err;
+    e_col[JJ * SWEEP_ROWS] = err;
   }
 #pragma unroll
   for (int t = 0; t < NB / 4; ++t) {
@@ -273,36 +379,117 @@ __device__ __forceinline__ void sweep_step(double (&w)[NB / 4], const double (*U
       if (cc > JJ) w[t] -= err * u;
     }
   }
-  if constexpr (JJ + 1 < NB) sweep_step<JJ + 1>(w, Ub, q, s, z, qmax, code_row, e_row);
+  if constexpr (JJ + 1 < NB) sweep_step<JJ + 1>(w, Ub, q, s, z, qmax, code_row, e_col);
 }
 
-__global__ __launch_bounds__(64) void sweep_block_kernel(double* __restrict__ Wc, const double* __restrict__ X, int N, int K, int j0,
-                                                         int bits, const double* __restrict__ s64, const double* __restrict__ z64,
-                                                         double* __restrict__ E, uint8_t* __restrict__ codes) {
+// The whole sweep in one launch.  A workgroup of 8 wavefronts owns 16 output channels.  Per block b of 64 columns:
+//   phase 1 (all wavefronts)   U[block b, block b] -> LDS; the block's own columns get the update of block b - 1,
+//                              W[:, b] -= E_{b-1} U[b-1, b]  (two channels per wavefront, lane = column)
+//   phase 2 (wavefront 0)      the sweep of block b: codes, errors E_b (kept in LDS, [column][channel])
+//           (six others)       meanwhile the columns after block b get the update of block b - 1,
+//                              W[:, c] -= E_{b-1} U[b-1, c]  (chunks of 64 columns dealt to the wavefronts, lane = column,
+//                              all 16 channels of a column in the lane's registers)
+// A column block c thus receives E_0 U, E_1 U, ... E_{c-1} U one after the other, each as one sum over the block's 64
+// columns in ascending order.  The working copy of the weights stays in global memory; the wavefronts of a workgroup hand
+// it to each other across the barriers (a workgroup's wavefronts share their CU's vector cache, and __syncthreads orders
+// their stores and loads at workgroup scope).
+__global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __restrict__ Wc, const double* __restrict__ X, int N, int K,
+                                                                   int bits, const double* __restrict__ s64,
+                                                                   const double* __restrict__ z64, uint8_t* __restrict__ codes) {
   __shared__ double Ub[NB][NB];                             // U[j0 + jj][j0 + cc] = X[K-1-j0-jj][K-1-j0-cc], upper triangular
-  for (int i = threadIdx.x; i < NB * NB; i += 64) {
-    const int jj = i >> 6, cc = i & 63;
-    Ub[jj][cc] = X[(int64_t)(K - 1 - j0 - jj) * K + (K - 1 - j0 - cc)];
-  }
-  __syncthreads();
-  const int q = threadIdx.x & 3;
-  int n = blockIdx.x * 16 + (threadIdx.x >> 2);
-  const bool live = n < N;
-  n = live ? n : N - 1;                                      // idle quads shadow the last channel and write nothing
-  double w[NB / 4];
-#pragma unroll
-  for (int t = 0; t < NB / 4; ++t) w[t] = Wc[(int64_t)n * K + j0 + 4 * t + q];
+  __shared__ __attribute__((aligned(16))) double Es[2][NB][SWEEP_ROWS];
+  __shared__ uint8_t code_s[SWEEP_ROWS][NB];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n0 = blockIdx.x * SWEEP_ROWS;
+  const int nrows = N - n0 < SWEEP_ROWS ? N - n0 : SWEEP_ROWS;
+  const int nb = K / NB;
+  const int q = lane & 3, rr = lane >> 2;
+  const int n = n0 + (rr < nrows ? rr : nrows - 1);         // idle quads shadow the last channel and write nothing
   const double s = s64[n], z = z64[n], qmax = (double)((1 << bits) - 1);
-  __shared__ uint8_t code_s[16][NB];
-  __shared__ double e_s[16][NB];
-  sweep_step<0>(w, Ub, q, s, z, qmax, code_s[threadIdx.x >> 2], e_s[threadIdx.x >> 2]);
-  __syncthreads();
-  if (live) {
-#pragma unroll
-    for (int t = 0; t < NB / 4; ++t) {
-      codes[(int64_t)n * K + j0 + 4 * t + q] = code_s[threadIdx.x >> 2][4 * t + q];
-      E[(int64_t)n * NB + 4 * t + q] = e_s[threadIdx.x >> 2][4 * t + q];
+  for (int b = 0; b < nb; ++b) {
+    const int j0 = b * NB;
+    const double(*Ep)[SWEEP_ROWS] = Es[(b + 1) & 1];        // errors of block b - 1
+    // ---- phase 1 ----
+    for (int i = tid; i < NB * NB; i += SWEEP_WAVES * 64) {
+      const int jj = i >> 6, cc = i & 63;
+      Ub[jj][cc] = X[(int64_t)(K - 1 - j0 - jj) * K + (K - 1 - j0 - cc)];
     }
+    if (b > 0) {
+      constexpr int RW = SWEEP_ROWS / SWEEP_WAVES;          // channels per wavefront
+      const int c = j0 + lane;
+      const double* u = X + (int64_t)(K - 1 - (j0 - NB)) * K + (K - 1 - c);   // U[j0 - 64 + k][c] = u[-k K]
+      double w[RW], acc[RW];
+#pragma unroll
+      for (int r = 0; r < RW; ++r) {
+        const int row = wave * RW + r;
+        w[r] = Wc[(int64_t)(n0 + (row < nrows ? row : nrows - 1)) * K + c];
+        acc[r] = 0.0;
+      }
+#pragma unroll 8
+      for (int k = 0; k < NB; ++k) {
+        const double uk = u[-(int64_t)k * K];
+#pragma unroll
+        for (int r = 0; r < RW; ++r) acc[r] = fma(Ep[k][wave * RW + r], uk, acc[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < RW; ++r)
+        if (wave * RW + r < nrows) Wc[(int64_t)(n0 + wave * RW + r) * K + c] = w[r] - acc[r];
+    }
+    __syncthreads();
+    // ---- phase 2 ----
+    if (wave == 0) {
+      double w[NB / 4];
+#pragma unroll
+      for (int t = 0; t < NB / 4; ++t) w[t] = Wc[(int64_t)n * K + j0 + 4 * t + q];
+      sweep_step<0>(w, Ub, q, s, z, qmax, code_s[rr], &Es[b & 1][0][rr]);
+      __builtin_amdgcn_wave_barrier();
+      if (rr < nrows) {
+#pragma unroll
+        for (int t = 0; t < NB / 4; ++t) codes[(int64_t)n * K + j0 + 4 * t + q] = code_s[rr][4 * t + q];
+      }
+    } else if (b > 0 && wave != 4) {
+      // Lane k keeps E_{b-1}[k][0..15]; a term's error reaches the fma as a scalar operand through v_readlane (LDS stays
+      // free for the sweep, whose chain of dependent steps waits on its own LDS reads).  Wavefront 4 shares its SIMD
+      // with the sweep and stays out.  Two chunks of 64 columns per pass.
+      const int fw = wave < 4 ? wave - 1 : wave - 2;        // 0..5
+      double e[SWEEP_ROWS];
+#pragma unroll
+      for (int r = 0; r < SWEEP_ROWS; ++r) e[r] = Ep[lane][r];
+      for (int c0 = j0 + NB + fw * 2 * NB; c0 < K; c0 += (SWEEP_WAVES - 2) * 2 * NB) {
+        const bool two = c0 + NB < K;
+        const int c = c0 + lane;
+        const double* u = X + (int64_t)(K - 1 - (j0 - NB)) * K + (K - 1 - c);
+        // the current values first (rows beyond the last channel re-read the last one and store nothing)
+        double w0[SWEEP_ROWS], w1[SWEEP_ROWS];
+#pragma unroll
+        for (int r = 0; r < SWEEP_ROWS; ++r) {
+          const double* w = Wc + (int64_t)(n0 + (r < nrows ? r : nrows - 1)) * K + c;
+          w0[r] = w[0];
+          w1[r] = two ? w[NB] : 0.0;
+        }
+        double acc0[SWEEP_ROWS], acc1[SWEEP_ROWS];
+#pragma unroll
+        for (int r = 0; r < SWEEP_ROWS; ++r) { acc0[r] = 0.0; acc1[r] = 0.0; }
+#pragma unroll 8
+        for (int k = 0; k < NB; ++k) {
+          const double u0 = u[-(int64_t)k * K], u1 = two ? u[-(int64_t)k * K - NB] : 0.0;
+#pragma unroll
+          for (int r = 0; r < SWEEP_ROWS; ++r) {
+            const double ek = lane_value(e[r], k);
+            acc0[r] = fma(ek, u0, acc0[r]);
+            acc1[r] = fma(ek, u1, acc1[r]);
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < SWEEP_ROWS; ++r)
+          if (r < nrows) {
+            double* w = Wc + (int64_t)(n0 + r) * K + c;
+            w[0] = w0[r] - acc0[r];
+            if (two) w[NB] = w1[r] - acc1[r];
+          }
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -356,7 +543,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t at, g, s, ones, zeros, dead, scal, h, l, x, dinv, wc, e, codes, s64, z64, total;
+  size_t at, g, s, ones, zeros, dead, scal, h, l, x, dinv, wc, codes, s64, z64, total;
 };
 Layout make_layout(int N, int K, int64_t T) {
   const size_t Tpad = (size_t)((T + 63) / 64) * 64, KK = (size_t)K * K;
@@ -375,7 +562,6 @@ Layout make_layout(int N, int K, int64_t T) {
   o.x = take(KK * 8);
   o.dinv = take((size_t)(K / NB) * NB * NB * 8);
   o.wc = take((size_t)N * K * 8);
-  o.e = take((size_t)N * NB * 8);
   o.codes = take((size_t)N * K);
   o.s64 = take((size_t)N * 8);
   o.z64 = take((size_t)N * 8);
@@ -407,7 +593,6 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
   double* X = reinterpret_cast<double*>(ws + o.x);
   double* Dinv = reinterpret_cast<double*>(ws + o.dinv);
   double* Wc = reinterpret_cast<double*>(ws + o.wc);
-  double* E = reinterpret_cast<double*>(ws + o.e);
   uint8_t* codes = reinterpret_cast<uint8_t*>(ws + o.codes);
   double* s64 = reinterpret_cast<double*>(ws + o.s64);
   double* z64 = reinterpret_cast<double*>(ws + o.z64);
@@ -433,27 +618,15 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
   hipLaunchKernelGGL(assemble_kernel, dim3((unsigned)((KK + 255) / 256)), dim3(256), 0, st, G, S, K, T, delta, dead, scal, H);
   RQ_HIP(hipGetLastError());
 
-  // ---- blocked right-looking Cholesky of the index-reversed Hessian: H = L L^T ----
+  // ---- blocked right-looking Cholesky of the index-reversed Hessian: H = L L^T, one launch per block column ----
+  {
+    static rq_once_per_device once;
+    RQ_HIP(rq_allow_dynamic_lds(ctx, once, reinterpret_cast<const void*>(&chol_step_kernel), CHOL_LDS));
+  }
   for (int kb = 0; kb < nb; ++kb) {
-    hipLaunchKernelGGL(potf2_inv_kernel, dim3(1), dim3(64), 0, st, H, L, Dinv, K, kb);
+    const int n = nb - kb - 1;
+    hipLaunchKernelGGL(chol_step_kernel, dim3((unsigned)(n > 0 ? n * (n + 1) / 2 : 1)), dim3(256), CHOL_LDS, st, H, L, Dinv, K, kb);
     RQ_HIP(hipGetLastError());
-    const int r0 = (kb + 1) * NB, rest = K - r0;
-    if (rest <= 0) break;
-    const int64_t c0 = (int64_t)kb * NB;
-    // panel: L[r0:, kb] = H[r0:, kb] Dinv_kk^T
-    GemmF64 g = {};
-    g.batch = 1; g.tri = TRI_NONE;
-    g.A = H + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
-    g.B = Dinv + (int64_t)kb * NB * NB; g.sbk = 1; g.sbn = NB;
-    g.C = L + (int64_t)r0 * K + c0; g.scm = K; g.scn = 1;
-    g.M = rest; g.N = NB; g.Kin = NB; g.alpha = 1.0; g.beta = 0.0;
-    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
-    // trailing update: H[r0:, r0:] -= L[r0:, kb] L[r0:, kb]^T
-    g.A = L + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
-    g.B = L + (int64_t)r0 * K + c0; g.sbk = 1; g.sbn = K;
-    g.C = H + (int64_t)r0 * K + r0; g.scm = K; g.scn = 1;
-    g.M = rest; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0; g.tri = TRI_C_LOWER;
-    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
   }
   // ---- X = L^-1 by doubling: the 64-blocks on the diagonal are inverted already; two neighbouring inverted diagonal
   //      blocks X11 (s x s) and X22 merge through X21 = -X22 (L21 X11).  All pairs of a level run as one batched GEMM
@@ -487,21 +660,9 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
   // ---- the sweep ----
   hipLaunchKernelGGL(row_init_kernel, dim3((unsigned)N), dim3(256), 0, st, d->W, K, d->bits, dead, Wc, s64, z64);
   RQ_HIP(hipGetLastError());
-  for (int b = 0; b < nb; ++b) {
-    const int j0 = b * NB;
-    hipLaunchKernelGGL(sweep_block_kernel, dim3((unsigned)((N + 15) / 16)), dim3(64), 0, st, Wc, X, N, K, j0, d->bits, s64, z64, E, codes);
-    RQ_HIP(hipGetLastError());
-    const int rest = K - j0 - NB;
-    if (rest <= 0) break;
-    // W[:, j0+64:] -= E U[j0:j0+64, j0+64:],  U[a][b] = X[K-1-a][K-1-b]
-    GemmF64 g = {};
-    g.batch = 1; g.tri = TRI_NONE;
-    g.A = E; g.sam = NB; g.sak = 1;
-    g.B = X + (int64_t)(K - 1 - j0) * K + (K - 1 - j0 - NB); g.sbk = -(int64_t)K; g.sbn = -1;
-    g.C = Wc + j0 + NB; g.scm = K; g.scn = 1;
-    g.M = N; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0;
-    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
-  }
+  hipLaunchKernelGGL(sweep_all_kernel, dim3((unsigned)((N + SWEEP_ROWS - 1) / SWEEP_ROWS)), dim3(SWEEP_WAVES * 64), 0, st, Wc, X, N, K,
+                     d->bits, s64, z64, codes);
+  RQ_HIP(hipGetLastError());
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)N), dim3(256), 0, st, codes, K, d->format, d->gate_up_rows, s64, z64, d->bias, d->w_out,
                      d->s_w, d->z_w, d->colsum_w, d->bias_out);
   RQ_HIP(hipGetLastError());
