@@ -175,39 +175,63 @@ __device__ __forceinline__ double lane_value(double v, int lane) {
 }
 // Lane i holds row i of the block in a[]; on return a[] is row i of its Cholesky factor (zeros above the diagonal), and
 // Lt (LDS, LP doubles per row) holds the factor as well.  An entry of another row comes from that LDS copy, which every
-// lane extends by its new entry after each column: the address is the same for all lanes, two entries per read.
+// lane extends by its new entry after each column: the address is the same for all lanes, two entries per read.  The
+// sum of column j + 1 is formed, up to its last term, while the square root and the division of column j are in flight
+// (its terms k < j need only columns that are complete); the last term takes l_{j+1, j} from its lane directly.
+// Lt is passed through a vector register the compiler cannot see through, so that the reads use one base register and
+// immediate offsets instead of a scalar address computation each.
 constexpr int LP = 66;
-__device__ __forceinline__ void diag_factor(double (&a)[NB], int i, double* __restrict__ Lt) {
+__device__ __forceinline__ const double* opaque_lds(const double* p) {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return p + z;
+}
+__device__ __forceinline__ void diag_factor(double (&a)[NB], int i, double* Lt) {
   // left-looking: l_ij = (h_ij - sum_{k<j} l_ik l_jk) / l_jj
+  const double* Lr = opaque_lds(Lt);
+  double sum = 0.0;
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
-    double sum = 0.0;
-    const double2* row = reinterpret_cast<const double2*>(Lt + j * LP);
-#pragma unroll
-    for (int k = 0; k < j; k += 2) {
-      const double2 l = row[k >> 1];
-      sum = fma(a[k], l.x, sum);
-      if (k + 1 < j) sum = fma(a[k + 1], l.y, sum);
-    }
     const double v = a[j] - sum;
     const double d = sqrt(lane_value(v, j));
+    double psum = 0.0;
+    if (j + 1 < NB) {
+      const double2* row = reinterpret_cast<const double2*>(Lr + (j + 1) * LP);
+#pragma unroll
+      for (int k = 0; k < j; k += 2) {
+        const double2 l = row[k >> 1];
+        psum = fma(a[k], l.x, psum);
+        if (k + 1 < j) psum = fma(a[k + 1], l.y, psum);
+        if ((k & 14) == 14) __builtin_amdgcn_sched_barrier(0);   // at most eight reads in flight: the registers are needed
+      }
+    }
     a[j] = i == j ? d : (i > j ? v / d : 0.0);
     Lt[i * LP + j] = a[j];
+    if (j + 1 < NB) sum = fma(a[j], lane_value(a[j], j + 1), psum);
   }
 }
 // Lane c takes column c of the inverse of the factor: x(r) = (delta_rc - sum_{m<r} l_rm x(m)) / l_rr, x(m) = 0 for m < c.
+// Same arrangement: the sum of row r + 1 without its last term stands before the division of row r.
 __device__ __forceinline__ void diag_inverse(double (&x)[NB], int i, const double* __restrict__ Lt) {
+  const double* Lr = opaque_lds(Lt);
+  double sum = 0.0;
 #pragma unroll
   for (int r = 0; r < NB; ++r) {
-    double sum = 0.0;
-    const double2* row = reinterpret_cast<const double2*>(Lt + r * LP);
+    double psum = 0.0;
+    double last = 0.0;
+    if (r + 1 < NB) {
+      const double2* row = reinterpret_cast<const double2*>(Lr + (r + 1) * LP);
 #pragma unroll
-    for (int m = 0; m < r; m += 2) {
-      const double2 l = row[m >> 1];
-      sum = fma(l.x, x[m], sum);
-      if (m + 1 < r) sum = fma(l.y, x[m + 1], sum);
+      for (int m = 0; m < r; m += 2) {
+        const double2 l = row[m >> 1];
+        psum = fma(l.x, x[m], psum);
+        if (m + 1 < r) psum = fma(l.y, x[m + 1], psum);
+        if ((m & 14) == 14) __builtin_amdgcn_sched_barrier(0);
+      }
+      last = Lr[(r + 1) * LP + r];
     }
-    x[r] = r < i ? 0.0 : ((r == i ? 1.0 : 0.0) - sum) / Lt[r * LP + r];
+    x[r] = r < i ? 0.0 : ((r == i ? 1.0 : 0.0) - sum) / Lr[r * LP + r];
+    if (r + 1 < NB) sum = fma(last, x[r], psum);
   }
 }
 
@@ -257,17 +281,10 @@ __global__ __launch_bounds__(256) void chol_step_kernel(double* __restrict__ H, 
 #pragma unroll
     for (int c = 0; c < NB; ++c) a[c] = H[base + (int64_t)i * K + c];        // only c <= i is used (the maintained triangle)
     diag_factor(a, i, Lt);
-    if (blockIdx.x == 0) {
-#pragma unroll
-      for (int c = 0; c < NB; ++c) L[base + (int64_t)i * K + c] = a[c];
-    }
     double x[NB];
     diag_inverse(x, i, Lt);
 #pragma unroll
-    for (int r = 0; r < NB; ++r) {
-      Bs[i * TP + r] = x[r];
-      if (blockIdx.x == 0) Dinv[(int64_t)kb * NB * NB + r * NB + i] = x[r];
-    }
+    for (int r = 0; r < NB; ++r) Bs[i * TP + r] = x[r];
   } else if (n > 0) {
     for (int e = tid - 64; e < NB * NB; e += 192) {
       const int k = e & 63, m = e >> 6;
@@ -275,8 +292,15 @@ __global__ __launch_bounds__(256) void chol_step_kernel(double* __restrict__ H, 
       if (ti != tj) Aj[k * TP + m] = H[(bj + m) * K + c0 + k];
     }
   }
-  if (n <= 0) return;
   __syncthreads();
+  if (blockIdx.x == 0) {                                    // L_kk and its inverse, from their LDS copies
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int r = e >> 6, c = e & 63;
+      L[c0 * K + c0 + (int64_t)r * K + c] = Lt[r * LP + c];
+      Dinv[(int64_t)kb * NB * NB + r * NB + c] = Bs[c * TP + r];
+    }
+  }
+  if (n <= 0) return;
   double li[4][4], lj[4][4];
   tile_product(Ai, Bs, ty, tx, li);
   if (ti != tj) tile_product(Aj, Bs, ty, tx, lj);
