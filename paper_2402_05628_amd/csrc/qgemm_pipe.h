@@ -681,9 +681,10 @@ rq_status launch_pipe_one(rq_ctx* ctx, GemmParams& p) {
   }
   // Row sums of the activations at hand and a K loop long enough for the cheaper unpack (25 vector instructions per k-step)
   // to outweigh the start values (about 250 per tile): raw nibbles, see the kernel.  Measured: 8192^3 0.544 -> 0.500 ms; with
-  // K <= 1024 it gains nothing, the K loop there is not bound by its vector instructions.
+  // K = 1024 it is 2 % slower (QKV 0.119 -> 0.121, FC1 0.175 -> 0.178 ms at 32896 rows): the K loop there is not bound by its
+  // vector instructions and the start values come on top.
   if constexpr (!RAW && W4 && TN == 2) {
-    if (p.rowsum_a && !p.no_raw && (p.K >= 2048 || p.no_raw < 0) && p.K <= 32768 && (reinterpret_cast<uintptr_t>(p.z_b) & 15) == 0 && p.N >= 4)
+    if (p.rowsum_a && p.no_raw <= 0 && (p.K >= 2048 || p.no_raw < 0) && p.K <= 32768 && (reinterpret_cast<uintptr_t>(p.z_b) & 15) == 0 && p.N >= 4)
       return launch_pipe_one<W4, S, ACT, OUT, TM, TN, WN, Q8, true>(ctx, p);
   }
   constexpr int BN = 32 * TN * WN;
