@@ -241,7 +241,9 @@ __device__ __forceinline__ void diag_inverse(double (&x)[NB], int i, const doubl
 // in registers; the others fetch the tile's two panel blocks meanwhile), forms the two panel blocks it needs and then its
 // tile: nothing passes between workgroups inside the launch, at the price of the same small factorization in every one.
 // Workgroup 0 stores L_kk and D, the workgroups of the first tile column store the panel.  Sums run over k in ascending
-// order, one fma per term.
+// order, one fma per term.  With more trailing tiles than CUs the repeated factorization (and the panel blocks formed once
+// per tile) would cost more than the launches saved: such steps run the kernel for the diagonal block alone (`diag_only`)
+// and take panel and trailing update as two launches of the float64 GEMM below, the same sums in the same order.
 constexpr int TP = 66;                                      // row pitch of the k-major 64 x 64 tiles in LDS (16-byte rows)
 constexpr int CHOL_LDS = (3 * NB * TP + NB * LP) * 8;
 __device__ __forceinline__ void tile_product(const double* __restrict__ As, const double* __restrict__ Bs, int ty, int tx,
@@ -263,14 +265,14 @@ __device__ __forceinline__ void tile_product(const double* __restrict__ As, cons
   }
 }
 __global__ __launch_bounds__(256) void chol_step_kernel(double* __restrict__ H, double* __restrict__ L, double* __restrict__ Dinv,
-                                                        int K, int kb) {
+                                                        int K, int kb, int diag_only) {
   extern __shared__ __attribute__((aligned(16))) double chol_lds[];
   double* Bs = chol_lds;                                    // Bs[k][n] = D(n, k)
   double* Ai = chol_lds + NB * TP;                          // Ai[k][m] = H_ik(m, k), later L_ik(m, k)
   double* Aj = chol_lds + 2 * NB * TP;
   double* Lt = chol_lds + 3 * NB * TP;                      // the diagonal block's factor
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  const int n = K / NB - kb - 1;                            // block rows below the diagonal block
+  const int n = diag_only ? 0 : K / NB - kb - 1;            // block rows below the diagonal block that this launch updates
   int ti = 0, tj = (int)blockIdx.x;
   while (tj > ti) { ++ti; tj -= ti; }                       // tile t of the lower triangle: t = ti (ti + 1) / 2 + tj
   const int64_t bi = (int64_t)(kb + 1 + ti) * NB, bj = (int64_t)(kb + 1 + tj) * NB, c0 = (int64_t)kb * NB;
@@ -374,7 +376,7 @@ __global__ __launch_bounds__(256) void row_init_kernel(const float* __restrict__
 // ---- the sweep inside one block of 64 columns: four lanes per output channel -----------------------------------------
 // Lane q of a quad owns columns q, q + 4, ... of its channel's block.  Every step broadcasts the current column's
 // weight from its owner, all four lanes take the same code and error, and each updates the columns it owns.
-constexpr int SWEEP_ROWS = 16;   // output channels per workgroup of the sweep (four lanes each in its first wavefront)
+constexpr int SWEEP_ROWS = 16;   // most output channels per workgroup of the sweep (four lanes each in its first wavefront)
 constexpr int SWEEP_WAVES = 8;
 template <int SRC>
 __device__ __forceinline__ double quad_bcast(double v) {
@@ -417,6 +419,7 @@ __device__ __forceinline__ void sweep_step(double (&w)[NB / 4], const double (*U
 // columns in ascending order.  The working copy of the weights stays in global memory; the wavefronts of a workgroup hand
 // it to each other across the barriers (a workgroup's wavefronts share their CU's vector cache, and __syncthreads orders
 // their stores and loads at workgroup scope).
+template <int ROWS>
 __global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __restrict__ Wc, const double* __restrict__ X, int N, int K,
                                                                    int bits, const double* __restrict__ s64,
                                                                    const double* __restrict__ z64, uint8_t* __restrict__ codes) {
@@ -424,8 +427,8 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __r
   __shared__ __attribute__((aligned(16))) double Es[2][NB][SWEEP_ROWS];
   __shared__ uint8_t code_s[SWEEP_ROWS][NB];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int n0 = blockIdx.x * SWEEP_ROWS;
-  const int nrows = N - n0 < SWEEP_ROWS ? N - n0 : SWEEP_ROWS;
+  const int n0 = blockIdx.x * ROWS;
+  const int nrows = N - n0 < ROWS ? N - n0 : ROWS;
   const int nb = K / NB;
   const int q = lane & 3, rr = lane >> 2;
   const int n = n0 + (rr < nrows ? rr : nrows - 1);         // idle quads shadow the last channel and write nothing
@@ -438,14 +441,14 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __r
       const int jj = i >> 6, cc = i & 63;
       Ub[jj][cc] = X[(int64_t)(K - 1 - j0 - jj) * K + (K - 1 - j0 - cc)];
     }
-    if (b > 0) {
-      constexpr int RW = SWEEP_ROWS / SWEEP_WAVES;          // channels per wavefront
+    if (b > 0 && wave < ROWS) {
+      constexpr int RW = (ROWS + SWEEP_WAVES - 1) / SWEEP_WAVES;   // channels per wavefront: wave, wave + 8
       const int c = j0 + lane;
       const double* u = X + (int64_t)(K - 1 - (j0 - NB)) * K + (K - 1 - c);   // U[j0 - 64 + k][c] = u[-k K]
       double w[RW], acc[RW];
 #pragma unroll
       for (int r = 0; r < RW; ++r) {
-        const int row = wave * RW + r;
+        const int row = wave + r * SWEEP_WAVES;
         w[r] = Wc[(int64_t)(n0 + (row < nrows ? row : nrows - 1)) * K + c];
         acc[r] = 0.0;
       }
@@ -453,11 +456,11 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __r
       for (int k = 0; k < NB; ++k) {
         const double uk = u[-(int64_t)k * K];
 #pragma unroll
-        for (int r = 0; r < RW; ++r) acc[r] = fma(Ep[k][wave * RW + r], uk, acc[r]);
+        for (int r = 0; r < RW; ++r) acc[r] = fma(Ep[k][wave + r * SWEEP_WAVES], uk, acc[r]);
       }
 #pragma unroll
       for (int r = 0; r < RW; ++r)
-        if (wave * RW + r < nrows) Wc[(int64_t)(n0 + wave * RW + r) * K + c] = w[r] - acc[r];
+        if (wave + r * SWEEP_WAVES < nrows) Wc[(int64_t)(n0 + wave + r * SWEEP_WAVES) * K + c] = w[r] - acc[r];
     }
     __syncthreads();
     // ---- phase 2 ----
@@ -472,44 +475,48 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void sweep_all_kernel(double* __r
         for (int t = 0; t < NB / 4; ++t) codes[(int64_t)n * K + j0 + 4 * t + q] = code_s[rr][4 * t + q];
       }
     } else if (b > 0 && wave != 4) {
-      // Lane k keeps E_{b-1}[k][0..15]; a term's error reaches the fma as a scalar operand through v_readlane (LDS stays
+      // Lane k keeps E_{b-1}[k][0..ROWS); a term's error reaches the fma as a scalar operand through v_readlane (LDS stays
       // free for the sweep, whose chain of dependent steps waits on its own LDS reads).  Wavefront 4 shares its SIMD
-      // with the sweep and stays out.  Two chunks of 64 columns per pass.
+      // with the sweep and stays out.  CP chunks of 64 columns per pass: 32 sums per lane whatever ROWS is, and one
+      // v_readlane pair serves CP terms.
+      constexpr int CP = 32 / ROWS;
       const int fw = wave < 4 ? wave - 1 : wave - 2;        // 0..5
-      double e[SWEEP_ROWS];
+      double e[ROWS];
 #pragma unroll
-      for (int r = 0; r < SWEEP_ROWS; ++r) e[r] = Ep[lane][r];
-      for (int c0 = j0 + NB + fw * 2 * NB; c0 < K; c0 += (SWEEP_WAVES - 2) * 2 * NB) {
-        const bool two = c0 + NB < K;
+      for (int r = 0; r < ROWS; ++r) e[r] = Ep[lane][r];
+      for (int c0 = j0 + NB + fw * CP * NB; c0 < K; c0 += (SWEEP_WAVES - 2) * CP * NB) {
         const int c = c0 + lane;
         const double* u = X + (int64_t)(K - 1 - (j0 - NB)) * K + (K - 1 - c);
         // the current values first (rows beyond the last channel re-read the last one and store nothing)
-        double w0[SWEEP_ROWS], w1[SWEEP_ROWS];
+        double w[CP][ROWS], acc[CP][ROWS];
 #pragma unroll
-        for (int r = 0; r < SWEEP_ROWS; ++r) {
-          const double* w = Wc + (int64_t)(n0 + (r < nrows ? r : nrows - 1)) * K + c;
-          w0[r] = w[0];
-          w1[r] = two ? w[NB] : 0.0;
+        for (int r = 0; r < ROWS; ++r) {
+          const double* wp = Wc + (int64_t)(n0 + (r < nrows ? r : nrows - 1)) * K + c;
+#pragma unroll
+          for (int pc = 0; pc < CP; ++pc) {
+            w[pc][r] = c0 + pc * NB < K ? wp[pc * NB] : 0.0;
+            acc[pc][r] = 0.0;
+          }
         }
-        double acc0[SWEEP_ROWS], acc1[SWEEP_ROWS];
-#pragma unroll
-        for (int r = 0; r < SWEEP_ROWS; ++r) { acc0[r] = 0.0; acc1[r] = 0.0; }
 #pragma unroll 8
         for (int k = 0; k < NB; ++k) {
-          const double u0 = u[-(int64_t)k * K], u1 = two ? u[-(int64_t)k * K - NB] : 0.0;
+          double uk[CP];
 #pragma unroll
-          for (int r = 0; r < SWEEP_ROWS; ++r) {
+          for (int pc = 0; pc < CP; ++pc) uk[pc] = c0 + pc * NB < K ? u[-(int64_t)k * K - pc * NB] : 0.0;
+#pragma unroll
+          for (int r = 0; r < ROWS; ++r) {
             const double ek = lane_value(e[r], k);
-            acc0[r] = fma(ek, u0, acc0[r]);
-            acc1[r] = fma(ek, u1, acc1[r]);
+#pragma unroll
+            for (int pc = 0; pc < CP; ++pc) acc[pc][r] = fma(ek, uk[pc], acc[pc][r]);
           }
         }
 #pragma unroll
-        for (int r = 0; r < SWEEP_ROWS; ++r)
+        for (int r = 0; r < ROWS; ++r)
           if (r < nrows) {
-            double* w = Wc + (int64_t)(n0 + r) * K + c;
-            w[0] = w0[r] - acc0[r];
-            if (two) w[NB] = w1[r] - acc1[r];
+            double* wp = Wc + (int64_t)(n0 + r) * K + c;
+#pragma unroll
+            for (int pc = 0; pc < CP; ++pc)
+              if (c0 + pc * NB < K) wp[pc * NB] = w[pc][r] - acc[pc][r];
           }
       }
     }
@@ -647,10 +654,33 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
     static rq_once_per_device once;
     RQ_HIP(rq_allow_dynamic_lds(ctx, once, reinterpret_cast<const void*>(&chol_step_kernel), CHOL_LDS));
   }
+  const int num_cu = ctx->num_cu > 0 ? ctx->num_cu : 256;
   for (int kb = 0; kb < nb; ++kb) {
     const int n = nb - kb - 1;
-    hipLaunchKernelGGL(chol_step_kernel, dim3((unsigned)(n > 0 ? n * (n + 1) / 2 : 1)), dim3(256), CHOL_LDS, st, H, L, Dinv, K, kb);
+    const int64_t tiles = (int64_t)n * (n + 1) / 2;
+    if (tiles <= num_cu) {
+      hipLaunchKernelGGL(chol_step_kernel, dim3((unsigned)(n > 0 ? tiles : 1)), dim3(256), CHOL_LDS, st, H, L, Dinv, K, kb, 0);
+      RQ_HIP(hipGetLastError());
+      continue;
+    }
+    hipLaunchKernelGGL(chol_step_kernel, dim3(1), dim3(256), CHOL_LDS, st, H, L, Dinv, K, kb, 1);
     RQ_HIP(hipGetLastError());
+    const int r0 = (kb + 1) * NB, rest = K - r0;
+    const int64_t c0 = (int64_t)kb * NB;
+    // panel: L[r0:, kb] = H[r0:, kb] Dinv_kk^T
+    GemmF64 g = {};
+    g.batch = 1; g.tri = TRI_NONE;
+    g.A = H + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
+    g.B = Dinv + (int64_t)kb * NB * NB; g.sbk = 1; g.sbn = NB;
+    g.C = L + (int64_t)r0 * K + c0; g.scm = K; g.scn = 1;
+    g.M = rest; g.N = NB; g.Kin = NB; g.alpha = 1.0; g.beta = 0.0;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
+    // trailing update: H[r0:, r0:] -= L[r0:, kb] L[r0:, kb]^T
+    g.A = L + (int64_t)r0 * K + c0; g.sam = K; g.sak = 1;
+    g.B = L + (int64_t)r0 * K + c0; g.sbk = 1; g.sbn = K;
+    g.C = H + (int64_t)r0 * K + r0; g.scm = K; g.scn = 1;
+    g.M = rest; g.N = rest; g.Kin = NB; g.alpha = -1.0; g.beta = 1.0; g.tri = TRI_C_LOWER;
+    if ((rc = gemm_f64(ctx, g)) != RQ_OK) return rc;
   }
   // ---- X = L^-1 by doubling: the 64-blocks on the diagonal are inverted already; two neighbouring inverted diagonal
   //      blocks X11 (s x s) and X22 merge through X21 = -X22 (L21 X11).  All pairs of a level run as one batched GEMM
@@ -684,8 +714,14 @@ rq_status rq_launch_gptq(rq_ctx* ctx, const rq_gptq_desc* d) {
   // ---- the sweep ----
   hipLaunchKernelGGL(row_init_kernel, dim3((unsigned)N), dim3(256), 0, st, d->W, K, d->bits, dead, Wc, s64, z64);
   RQ_HIP(hipGetLastError());
-  hipLaunchKernelGGL(sweep_all_kernel, dim3((unsigned)((N + SWEEP_ROWS - 1) / SWEEP_ROWS)), dim3(SWEEP_WAVES * 64), 0, st, Wc, X, N, K,
-                     d->bits, s64, z64, codes);
+  // Output channels per workgroup: the six wavefronts that update the later columns must keep up with the one that sweeps
+  // (about 33 us per block).  With 16 channels they do for K <= 1664; longer rows take 8 channels per workgroup (half the
+  // update's work per workgroup, a third of its time), unless that would give more workgroups than the chip holds at once.
+  const int resident = num_cu * 3;
+  if (K <= 1664 || (N + 7) / 8 > resident)
+    hipLaunchKernelGGL(sweep_all_kernel<16>, dim3((unsigned)((N + 15) / 16)), dim3(SWEEP_WAVES * 64), 0, st, Wc, X, N, K, d->bits, s64, z64, codes);
+  else
+    hipLaunchKernelGGL(sweep_all_kernel<8>, dim3((unsigned)((N + 7) / 8)), dim3(SWEEP_WAVES * 64), 0, st, Wc, X, N, K, d->bits, s64, z64, codes);
   RQ_HIP(hipGetLastError());
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)N), dim3(256), 0, st, codes, K, d->format, d->gate_up_rows, s64, z64, d->bias, d->w_out,
                      d->s_w, d->z_w, d->colsum_w, d->bias_out);

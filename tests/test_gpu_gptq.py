@@ -59,7 +59,9 @@ def _check(b, out, want, bits, max_bad_rows):
 
 @pytest.mark.parametrize("N,K,T,bits_w,bits_a", [(96, 128, 500, 4, 4), (200, 192, 1000, 4, 8), (64, 64, 100, 3, 4), (130, 256, 777, 8, 8),
                                                   (33, 320, 64, 6, 6), (1, 64, 1, 4, 4), (17, 64, 3, 2, 8),
-                                                  (40, 1152, 300, 4, 4)])   # 18 panels / sweep blocks: every wavefront of the sweep gets several column chunks
+                                                  (40, 1152, 300, 4, 4),    # 18 panels / sweep blocks: every wavefront of the sweep gets several column chunks
+                                                  (24, 1600, 200, 4, 4),    # 25 panels: the first steps have more trailing tiles than CUs (separate launches)
+                                                  (13, 2048, 150, 4, 4)])   # rows this long: 8 channels per workgroup of the sweep
 def test_gptq_matches_oracle(rq, N, K, T, bits_w, bits_a):
     b, ctx = rq
     print("case", N, K, T, bits_w, bits_a, flush=True)
