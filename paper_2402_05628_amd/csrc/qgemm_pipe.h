@@ -596,7 +596,11 @@ __global__ __launch_bounds__(128 * WN, pipe_wgs_per_cu(TM, TN, WN, OUT)) void qg
       wait_vm<WAIT * LPS>();     // stage kt+1 has landed (this wavefront's share)
       // every read of stage kt by this wavefront has been issued; once they have returned (lgkmcnt) and all wavefronts
       // are here, the slot may be refilled and stage kt+1 (landed everywhere) may be read
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      // (the wait as a builtin: the compiler's own wait-count pass cannot see into inline assembly, would take the reads
+      // above for still outstanding behind the barrier and drain the counter again -- with the next stage's weight packets
+      // just requested -- in front of the first MFMA of sub-step 1)
+      __builtin_amdgcn_s_waitcnt(0xC07F);                    // lgkmcnt(0)
+      asm volatile("s_barrier" ::: "memory");
       fetch_b(nslot, 0, fb);
       if (RAMP) {          // first k-step of a ramped start: the untouched slots 2 .. S-1 get their first stages now
 #pragma unroll
