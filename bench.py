@@ -372,7 +372,10 @@ def run_block(args, cfg_id, cfg, ctx, rq, synth, np, torch, full):
                 steps=steps, warmup=warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
                 vs_baseline=None, dtype="int8", data="synthetic",
                 config=dict(workload=cfg.name, batch=cfg.batch, seq=cfg.seq, hidden=cfg.D, heads=cfg.H, mlp=cfg.Dm,
-                            bits_w=cfg.bits_w, bits_a=cfg.bits_a, bits_softmax=cfg.bits_p, tokens=cfg.tokens),
+                            bits_w=cfg.bits_w, bits_a=cfg.bits_a, bits_softmax=cfg.bits_p, tokens=cfg.tokens,
+                            streams=("two halves of the batch side by side on two streams (library default at this size); the "
+                                     "instrumented pass behind kernels_ms_per_step and roofline runs on one"
+                                     if cfg.tokens * cfg.D >= (16 << 20) and cfg.batch >= 2 and cfg.seq <= 288 and args.streams != 1 else "one")),
                 roofline=roofline, gemm_launches=launches, hbm_kernels=hbm,
                 kernels_ms_per_step={k: round(v["ms_per_step"], 5) for k, v in kern.items()},
                 ms_per_step_instrumented=(t3 - t2) * 1e3 / steps, cpu_baseline=cpu)
@@ -391,6 +394,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-mb", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2, 3],
+                    help="rq_set_block_streams: 1 = one stream, 2 = the library's default (large batches run as two halves side by side), 3 = always two")
     ap.add_argument("--gemm-k", type=int, default=8192, help="gemm workload: inner dimension (a multiple of 64)")
     ap.add_argument("--wfmt", default="u4", choices=["u4", "i8"],
                     help="gemm workload: storage of the 4-bit weight codes -- u4: two codes per byte; i8: one int8 per code "
@@ -424,6 +429,8 @@ def main():
     ctx = rq.Context(0)
     if args.tile:
         rq.set_gemm_tile(ctx, args.tile)
+    if args.streams != 2:
+        rq.set_block_streams(ctx, args.streams)
     out = run_block(args, args.config, cfg, ctx, rq, synth, np, torch, full=True)
     # the other large single-GPU workloads in the same run (shorter, no stand-alone kernels, no CPU leg): context for the
     # headline line, each with its own per-launch GEMM figures

@@ -520,6 +520,19 @@ rq_status rq_block_workspace_layout(const rq_block_params* p, int64_t batch, int
 rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x, float* y,
                            int64_t batch, int64_t seq, void* workspace, size_t workspace_bytes);
 
+/* Streams of rq_block_forward (per context; host call, not to be changed while another thread issues calls on the same
+ * context).  The context owns a second stream besides the caller's.  Where the whole attention runs as one kernel (no
+ * attention scratch) and the batch is large (tokens x D >= 16 Mi elements, at least two batch items), the pass runs the two
+ * halves of the batch side by side, one on each stream: the second stream waits for everything enqueued on the caller's
+ * stream before the call, and the caller's stream waits for the second one before the call returns, so for the caller the
+ * pass still is one piece of work on its stream (under stream capture: a fork and a join inside the captured graph).  Every
+ * intermediate is token-major, so each half works in its own rows of the same workspace; the kernels and the output bits
+ * are those of one stream.  What it buys: the tail of one half's kernel, with the chip running empty while the last tiles
+ * finish, is filled by the other half's (CLIP ViT-L/14, batch 128: 2 - 3 % per pass; small workloads lose as much, hence
+ * the size condition).  streams: 1 = always one stream; 2 = as described (default); 3 = two halves whenever the one-kernel
+ * attention applies and batch >= 2 (tests).  Per-kernel profiling (rq_profile_enable) keeps the pass on one stream. */
+rq_status rq_set_block_streams(rq_ctx* ctx, int32_t streams);
+
 /* rq_block_forward for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc): the same pass, same kernels and same results, with the scratch in a fixed device array
  * inside the library instead of a caller workspace.  The array holds RQ_NOALLOC_SCRATCH_BYTES on every GPU the library is

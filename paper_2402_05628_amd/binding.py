@@ -612,10 +612,15 @@ def profile_read(ctx: Context):
 
 
 _rq_set_tile = _sig("rq_set_gemm_tile", i32, [vp, i32])
+_rq_set_streams = _sig("rq_set_block_streams", i32, [vp, i32])
 
 
 def set_gemm_tile(ctx: Context, tile: int):
     ctx.check(_rq_set_tile(ctx.handle, tile))
+
+
+def set_block_streams(ctx: Context, streams: int):
+    ctx.check(_rq_set_streams(ctx.handle, streams))
 
 
 _rq_cal_ws = _sig("rq_block_calibrate_workspace_bytes", C.c_size_t, [C.POINTER(BlockRaw), i64, i64])

@@ -141,15 +141,24 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   RQ_NEED_DEVICE();
 
   char* ws = static_cast<char*>(workspace);
-  int8_t* a = reinterpret_cast<int8_t*>(ws + pl.o_a);
-  int32_t* rowsum = reinterpret_cast<int32_t*>(ws + pl.o_rowsum);
-  int8_t* qkv = reinterpret_cast<int8_t*>(ws + pl.o_qkv);
+  const float* const x_all = x;
+  float* const y_all = y;
+  // the pass over the batch items [first, first + nbatch): every intermediate is token-major, so a part of the batch works in
+  // its own rows of the same workspace arrays
+  auto run_part = [&](int64_t first, int64_t nbatch) -> rq_status {
+  rq_status st;
+  const int64_t t0 = first * seq;
+  int8_t* a = reinterpret_cast<int8_t*>(ws + pl.o_a) + t0 * D;
+  int32_t* rowsum = reinterpret_cast<int32_t*>(ws + pl.o_rowsum) + t0;
+  int8_t* qkv = reinterpret_cast<int8_t*>(ws + pl.o_qkv) + t0 * 3 * D;
   int32_t* acc = reinterpret_cast<int32_t*>(ws + pl.o_acc);
   uint8_t* codes = reinterpret_cast<uint8_t*>(ws + pl.o_codes);
-  int8_t* o = reinterpret_cast<int8_t*>(ws + pl.o_o);
-  float* xbar = reinterpret_cast<float*>(ws + pl.o_xbar);
-  int8_t* hid = reinterpret_cast<int8_t*>(ws + pl.o_hid);
-  const int64_t T = pl.T;
+  int8_t* o = reinterpret_cast<int8_t*>(ws + pl.o_o) + t0 * D;
+  float* xbar = reinterpret_cast<float*>(ws + pl.o_xbar) + t0 * D;
+  int8_t* hid = reinterpret_cast<int8_t*>(ws + pl.o_hid) + t0 * Dm;
+  const int64_t T = nbatch * seq;
+  const float* x = x_all + t0 * D;
+  float* y = y_all + t0 * D;
   const int ba = p->bits_a;
 
   // Row sums of the stored activation codes: required by centered 8-bit weights; with packed 4-bit weights they let the
@@ -189,8 +198,8 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
   const int offo = rq_store_offset(ba, p->z_o);
   const bool fused = use_fused(p, seq);
   const bool whole = use_whole(p, seq);
-  for (int64_t b0 = 0; b0 < batch; b0 += pl.bchunk) {
-    const int64_t nb = (batch - b0) < pl.bchunk ? (batch - b0) : pl.bchunk;
+  for (int64_t b0 = 0; b0 < nbatch; b0 += pl.bchunk) {
+    const int64_t nb = (nbatch - b0) < pl.bchunk ? (nbatch - b0) : pl.bchunk;
     const int8_t* qkv_c = qkv + b0 * seq * 3 * D;
     if (whole) {
       // Q.K^T, Softmax-log2 codes and P.V in one kernel: neither logits nor codes reach memory
@@ -319,6 +328,24 @@ rq_status rq_block_forward(rq_ctx* ctx, const rq_block_params* p, const float* x
     if (st != RQ_OK) return st;
   }
   return RQ_OK;
+  };
+  // Two halves of the batch on two streams where neither half needs attention scratch (the one-kernel attention) and each is
+  // a launch of its own right: the tail of one half's kernel -- the chip running empty while the last tiles finish -- is
+  // filled by the other half's.  Same kernels on the same rows: the output bits do not depend on the split.
+  const bool split = ctx->block_streams >= 2 && ctx->stream2 && !ctx->profiling && use_whole(p, seq) && batch >= 2 &&
+                     (ctx->block_streams == 3 || pl.T * D >= (16ll << 20));
+  if (!split) return run_part(0, batch);
+  const int64_t b1 = (batch + 1) / 2;
+  RQ_HIP(hipEventRecord(ctx->ev_fork, ctx->stream));
+  RQ_HIP(hipStreamWaitEvent(ctx->stream2, ctx->ev_fork, 0));
+  rq_status st1 = run_part(0, b1);
+  hipStream_t main_stream = ctx->stream;
+  ctx->stream = ctx->stream2;
+  rq_status st2 = run_part(b1, batch - b1);
+  ctx->stream = main_stream;
+  RQ_HIP(hipEventRecord(ctx->ev_join, ctx->stream2));
+  RQ_HIP(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+  return st1 != RQ_OK ? st1 : st2;
 }
 
 // ---- rq_block_forward_noalloc: the same pass with its scratch in a fixed device array of this library ----------------

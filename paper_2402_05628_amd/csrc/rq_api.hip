@@ -47,6 +47,14 @@ rq_status rq_create(rq_ctx** out, int device, void* hip_stream) {
   c->pending = new std::vector<rq_ctx::EvPair>();
   c->pool = new std::vector<hipEvent_t>();
   if (device >= 0) {      // set-up work that must not happen inside rq_block_forward_noalloc's callers' hot loops
+    if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      if (c->stream2) (void)hipStreamDestroy(c->stream2);
+      c->stream2 = nullptr;      // rq_block_forward then stays on one stream
+    }
+    c->block_streams = c->stream2 ? 2 : 1;
     const rq_status st = rq_noalloc_scratch_init(c, nullptr);
     if (st != RQ_OK) {
       g_last_error = c->err;
@@ -68,7 +76,17 @@ void rq_destroy(rq_ctx* ctx) {
     for (auto e : *ctx->pool) hipEventDestroy(e);
     delete ctx->pool;
   }
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->stream2) (void)hipStreamDestroy(ctx->stream2);
   delete ctx;
+}
+
+rq_status rq_set_block_streams(rq_ctx* ctx, int32_t streams) {
+  if (!ctx) return rq_fail(nullptr, RQ_ERR_INVALID_ARG, "rq_set_block_streams: ctx is NULL");
+  RQ_REQUIRE(streams >= 1 && streams <= 3, RQ_ERR_INVALID_ARG, "rq_set_block_streams: %d not in 1..3", streams);
+  ctx->block_streams = (streams > 1 && !ctx->stream2 && ctx->device >= 0) ? 1 : streams;
+  return RQ_OK;
 }
 
 const char* rq_last_error(const rq_ctx* ctx) { return ctx ? ctx->err.c_str() : g_last_error.c_str(); }

@@ -17,6 +17,11 @@ struct rq_ctx {
   int num_cu = 256;
   int gemm_tile = 0;          // rq_set_gemm_tile: 0 = kernel and tile of the weight-mode GEMM chosen by shape
   int gemm_no_raw = 0;        // rq_set_gemm_tile + 256: packed 4-bit weights never take the raw-nibble variant (1); + 512: whenever row sums are given (-1)
+  // rq_block_forward over two halves of the batch at once: a second stream of this context and the two events that fork it
+  // from `stream` and join it again (created with the context).  block_streams: see rq_set_block_streams
+  int block_streams = 1;
+  hipStream_t stream2 = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::string err;
   // per-kernel profiling of rq_block_forward
   bool profiling = false;

@@ -297,6 +297,8 @@ def test_block_forward_validation(b, host_ctx):
     assert b.lib.rq_set_gemm_tile(h, 99) == 1 and b.lib.rq_set_gemm_tile(h, 9) == 1 and b.lib.rq_set_gemm_tile(None, 0) == 1
     assert b.lib.rq_set_gemm_tile(h, 8) == 0 and b.lib.rq_set_gemm_tile(h, 256 + 5) == 0 and b.lib.rq_set_gemm_tile(h, 512 + 3) == 0 and b.lib.rq_set_gemm_tile(h, 800) == 1
     assert b.lib.rq_set_gemm_tile(h, 0) == 0      # 8: the 256 x 256 tiles; + 256: no raw-nibble variant
+    assert b.lib.rq_set_block_streams(h, 0) == 1 and b.lib.rq_set_block_streams(h, 4) == 1 and b.lib.rq_set_block_streams(None, 1) == 1
+    assert b.lib.rq_set_block_streams(h, 1) == 0 and b.lib.rq_set_block_streams(h, 3) == 0 and b.lib.rq_set_block_streams(h, 2) == 0
 
 
 def test_workspace_bytes_grow_with_the_problem(b):

@@ -56,6 +56,21 @@ def test_block_forward_is_bitwise_repeatable(name):
     inter_b = blk2.intermediates(cfg.batch, cfg.seq)
     for k in inter_a:
         assert torch.equal(inter_a[k], inter_b[k]), "intermediate %s differs between the two contexts" % k
+    # the two halves of the batch side by side on two streams (forced here: these batches are below the size at which the
+    # pass splits by itself): same kernels on the same rows, same bits
+    if cfg.batch >= 2:
+        b.set_block_streams(ctx, 3)
+        for rep in range(2):
+            y4 = torch.full_like(x, float("nan"))
+            blk.forward(x, y4, cfg.batch, cfg.seq)
+            torch.cuda.synchronize()
+            assert torch.equal(ys[0], y4), "the split over two streams gives other bits"
+        b.set_block_streams(ctx, 1)
+        y5 = torch.zeros_like(x)
+        blk.forward(x, y5, cfg.batch, cfg.seq)
+        torch.cuda.synchronize()
+        assert torch.equal(ys[0], y5)
+        b.set_block_streams(ctx, 2)
     # the no-allocation entry point shares the kernels: same bits where the shape fits its scratch
     if blk.workspace(cfg.batch, cfg.seq)[1] <= b.noalloc_scratch_bytes():
         y3 = torch.zeros_like(x)
